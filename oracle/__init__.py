@@ -1,0 +1,165 @@
+"""CPU oracle for the KGE mini-batch step (test infrastructure only).
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import this
+package.  It is a ctypes wrapper around ``kge_oracle.c`` (plain C, fp64 arithmetic, one triple and one
+negative at a time) and contains no arithmetic of its own.  It imports nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kge_oracle.c")
+_LIB = os.path.join(_HERE, "libkge_oracle.so")
+
+TRANSE_L2, TRANSE_L1, DISTMULT, COMPLEX, ROTATE = 0, 1, 2, 3, 4
+NEG_TAIL, NEG_HEAD = 0, 1
+MODEL_IDS = {"transe_l2": TRANSE_L2, "transe_l1": TRANSE_L1, "distmult": DISTMULT, "complex": COMPLEX,
+             "rotate": ROTATE}
+
+
+def build(force: bool = False) -> str:
+    """Compile kge_oracle.c with gcc (no fast-math, no contraction) and return the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.run(["gcc", "-O2", "-Wall", "-Wextra", "-ffp-contract=off", "-shared", "-fPIC", "-o", _LIB,
+                        _SRC, "-lm"], check=True)
+    return _LIB
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [("model", ctypes.c_int32), ("ent_dim", ctypes.c_int32), ("rel_dim", ctypes.c_int32),
+                ("neg_side", ctypes.c_int32), ("tables_f64", ctypes.c_int32), ("bf16_inputs", ctypes.c_int32),
+                ("rotate_squared", ctypes.c_int32), ("split_form", ctypes.c_int32),
+                ("gamma", ctypes.c_double), ("adv_temperature", ctypes.c_double)]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        vp, i64, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double
+        lib.ko_loss_grad.restype = ctypes.c_int
+        lib.ko_loss_grad.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, vp, vp, i64, vp, i64, i64, vp,
+                                     vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
+        lib.ko_dedup.restype = i64
+        lib.ko_dedup.argtypes = [vp, i64, vp, vp]
+        lib.ko_adagrad_rows.restype = None
+        lib.ko_adagrad_rows.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, dbl, dbl]
+        lib.ko_train_step.restype = ctypes.c_int
+        lib.ko_train_step.argtypes = [ctypes.POINTER(_Params), vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
+                                      vp, i64, i64, dbl, dbl, ctypes.c_int, vp, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _ids(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int64)
+
+
+def _params(model, ent_dim, rel_dim, neg_side, gamma, adv_temperature=0.0, tables_f64=False, bf16_inputs=False,
+            rotate_squared=False, split_form=False) -> _Params:
+    m = MODEL_IDS[model] if isinstance(model, str) else int(model)
+    return _Params(m, int(ent_dim), int(rel_dim), int(neg_side), int(tables_f64), int(bf16_inputs),
+                   int(rotate_squared), int(split_form), float(gamma), float(adv_temperature))
+
+
+def loss_and_grad(model, E, R, h, r, t, neg, k, chunk, neg_side, gamma, adv_temperature=0.0, w_fixed=None,
+                  want_grad=True, bf16_inputs=False, rotate_squared=False, split_form=False):
+    """Loss, scores, weights and (dense) gradients of one mini-batch.
+
+    E, R: float32 or float64 2-D arrays.  Returns a dict with ``loss`` (float), ``pos`` [b], ``neg`` [b,k],
+    ``w`` [b,k] and, if wanted, ``dE``, ``dR`` with the shapes of E and R (float64).
+    """
+    lib = _load()
+    f64 = E.dtype == np.float64
+    assert R.dtype == E.dtype and E.dtype in (np.float32, np.float64)
+    E = np.ascontiguousarray(E)
+    R = np.ascontiguousarray(R)
+    h, r, t, neg = _ids(h), _ids(r), _ids(t), _ids(neg).reshape(-1)
+    b = h.shape[0]
+    assert neg.shape[0] == (b // chunk) * k
+    p = _params(model, E.shape[1], R.shape[1], neg_side, gamma, adv_temperature, f64, bf16_inputs, rotate_squared,
+                split_form)
+    loss = ctypes.c_double(0.0)
+    pos = np.zeros(b, np.float64)
+    negs = np.zeros((b, k), np.float64)
+    w = np.zeros((b, k), np.float64)
+    dE = np.zeros(E.shape, np.float64) if want_grad else None
+    dR = np.zeros(R.shape, np.float64) if want_grad else None
+    wf = None if w_fixed is None else np.ascontiguousarray(w_fixed, dtype=np.float64)
+    rc = lib.ko_loss_grad(ctypes.byref(p), _ptr(E), _ptr(R), _ptr(h), _ptr(r), _ptr(t), b, _ptr(neg), k, chunk,
+                          _ptr(wf), ctypes.addressof(loss), _ptr(pos), _ptr(negs), _ptr(w),
+                          None, E.shape[0], _ptr(dE), None, R.shape[0], _ptr(dR))
+    if rc != 0:
+        raise ValueError(f"ko_loss_grad failed with {rc}")
+    out = {"loss": loss.value, "pos": pos, "neg": negs, "w": w}
+    if want_grad:
+        out["dE"], out["dR"] = dE, dR
+    return out
+
+
+def scores(model, E, R, h, r, t, neg, k, chunk, neg_side, gamma, **kw):
+    """Positive scores [b] and negative scores [b,k] (float64)."""
+    o = loss_and_grad(model, E, R, h, r, t, neg, k, chunk, neg_side, gamma, want_grad=False, **kw)
+    return o["pos"], o["neg"]
+
+
+def dedup(keys):
+    """Distinct values (ascending) and their multiplicities, both int64."""
+    lib = _load()
+    keys = _ids(keys).reshape(-1)
+    n = keys.shape[0]
+    uniq = np.zeros(max(n, 1), np.int64)
+    cnt = np.zeros(max(n, 1), np.int64)
+    u = lib.ko_dedup(_ptr(keys), n, _ptr(uniq), _ptr(cnt))
+    return uniq[:u].copy(), cnt[:u].copy()
+
+
+def adagrad_rows(table, state, ids, grad, lr, eps):
+    """In-place Adagrad on rows ``ids`` (or all rows when ids is None) of float32 table/state."""
+    lib = _load()
+    assert table.dtype == np.float32 and state.dtype == np.float32 and table.flags.c_contiguous
+    grad = np.ascontiguousarray(grad, dtype=np.float64)
+    if ids is None:
+        n = table.shape[0]
+        idp = None
+    else:
+        ids = _ids(ids)
+        n = ids.shape[0]
+        idp = _ptr(ids)
+    lib.ko_adagrad_rows(_ptr(table), _ptr(state), idp, n, table.shape[1], _ptr(grad), float(lr), float(eps))
+
+
+def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr, eps=1e-10, adv_temperature=0.0,
+               dense=False, bf16_inputs=False, rotate_squared=False, want_scores=False):
+    """One step, in place on float32 E, SE, R, SR.  Returns loss (and scores when asked)."""
+    lib = _load()
+    for a in (E, SE, R, SR):
+        assert a.dtype == np.float32 and a.flags.c_contiguous
+    h, r, t, neg = _ids(h), _ids(r), _ids(t), _ids(neg).reshape(-1)
+    b = h.shape[0]
+    assert neg.shape[0] == (b // chunk) * k
+    p = _params(model, E.shape[1], R.shape[1], neg_side, gamma, adv_temperature, False, bf16_inputs, rotate_squared)
+    loss = ctypes.c_double(0.0)
+    pos = np.zeros(b, np.float64) if want_scores else None
+    negs = np.zeros((b, k), np.float64) if want_scores else None
+    rc = lib.ko_train_step(ctypes.byref(p), _ptr(E), _ptr(SE), E.shape[0], _ptr(R), _ptr(SR), R.shape[0],
+                           _ptr(h), _ptr(r), _ptr(t), b, _ptr(neg), k, chunk, float(lr), float(eps), int(dense),
+                           ctypes.addressof(loss), _ptr(pos), _ptr(negs))
+    if rc != 0:
+        raise ValueError(f"ko_train_step failed with {rc}")
+    if want_scores:
+        return loss.value, pos, negs
+    return loss.value

@@ -1,0 +1,538 @@
+/*
+ * kge_oracle.c -- plain, slow CPU oracle for one mini-batch step of knowledge-graph-embedding training.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  It exists so that the GPU library can be checked against
+ * something obviously correct.  Only the tests, the smoke check and the benchmark's cpu_baseline leg may
+ * build, load or call it.  It shares no code, header, table or helper with the GPU library.
+ *
+ * What it computes (paper sections in brackets):
+ *   - the score of a triple (h, r, t) for TransE (L1 or L2), DistMult, ComplEx and RotatE   [Table 1]
+ *   - negatives obtained by replacing the head or the tail of a positive triple              [Sec. 2]
+ *   - joint negative sampling: positives are grouped into consecutive sets of size g and all members of a
+ *     set share the same k corrupting entities                                               [Sec. 3.3]
+ *   - the logistic loss  log(1 + exp(-y f))  with y = +1 on positives and -1 on negatives    [Sec. 2]
+ *   - the gradients of that loss with respect to every embedding row that took part          [Sec. 3.1 step 3]
+ *   - the update of exactly those rows by Adagrad                                            [Sec. 3.1 step 4]
+ *
+ * How: every (positive, negative) pair is scored on its own, directly from the table rows, with the Table 1
+ * formula written out.  There is no grouping into matrix products, no splitting of the score into two
+ * parts, no blocking or fusion.  All arithmetic is fp64; embedding tables and optimizer state are stored as
+ * fp32 (one rounding when a value is written back).
+ *
+ * Readings taken where the paper is silent (each is listed with its reason in the design notes):
+ *   - distance models use  f = gamma - distance ; DistMult and ComplEx do not use gamma
+ *   - TransE-L2 uses the un-squared norm (Table 1 and Sec. 3.3 agree on that)
+ *   - RotatE uses gamma - sum_j |h_j r_j - t_j| (modulus per complex coordinate); the literally printed
+ *     squared norm is available through rotate_squared
+ *   - a row of ComplEx / RotatE entities is [real parts | imaginary parts]; a RotatE relation row holds
+ *     phases in radians
+ *   - loss = (1/b) sum_i [ softplus(-f+_i) + sum_j w_ij softplus(f-_ij) ],  w_ij = 1/k, or the softmax over
+ *     j of (adv_temperature * f-_ij) treated as a constant when adv_temperature > 0
+ *   - the optimizer is element-wise Adagrad:  S += g^2 ; theta -= lr * g / (sqrt(S) + eps), where g is the
+ *     sum of all contributions to that row within the step
+ *   - where a norm or modulus is exactly zero its sub-gradient is taken to be zero
+ *
+ * In bf16_inputs mode the score of a (positive, negative) pair is, as in Sec. 3.3, a function of
+ * o = h + r (or its analogue for the other models and the other side) and the corrupting row n; both are
+ * rounded to bfloat16 (round to nearest even) before the pair function is evaluated, and so is the
+ * per-pair backward coefficient.  Positives, loss and the update stay unrounded.
+ *
+ * parity pins (tests/test_oracle_*.py): hand-worked scores, central finite differences of the loss,
+ * equality of the per-pair scores with the split form of Sec. 3.3 evaluated by numpy matrix products,
+ * special values of the loss, the Adagrad closed form, brute-force duplicate counting.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { KO_TRANSE_L2 = 0, KO_TRANSE_L1 = 1, KO_DISTMULT = 2, KO_COMPLEX = 3, KO_ROTATE = 4 };
+enum { KO_NEG_TAIL = 0, KO_NEG_HEAD = 1 };
+
+typedef struct {
+    int32_t model;
+    int32_t ent_dim;         /* numbers per entity row   */
+    int32_t rel_dim;         /* numbers per relation row */
+    int32_t neg_side;        /* KO_NEG_TAIL: (h, r, n);  KO_NEG_HEAD: (n, r, t) */
+    int32_t tables_f64;      /* tables hold double instead of float (finite-difference tests) */
+    int32_t bf16_inputs;     /* see header comment */
+    int32_t rotate_squared;  /* RotatE as printed in Table 1: gamma - sum_j |h_j r_j - t_j|^2 */
+    int32_t split_form;      /* evaluate negatives through the Sec. 3.3 split without any rounding (tests) */
+    double gamma;
+    double adv_temperature;
+} ko_params;
+
+/* ------------------------------------------------------------------------------------------------ */
+/* helpers                                                                                            */
+
+static void fetch_row(const void *table, int is_f64, int64_t row, int dim, double *out) {
+    if (is_f64) {
+        const double *src = (const double *)table + row * (int64_t)dim;
+        for (int d = 0; d < dim; ++d) out[d] = src[d];
+    } else {
+        const float *src = (const float *)table + row * (int64_t)dim;
+        for (int d = 0; d < dim; ++d) out[d] = (double)src[d];
+    }
+}
+
+/* index of id in the ascending list ids[0..n); ids == NULL means the identity (dense tables) */
+static int64_t slot_of(const int64_t *ids, int64_t n, int64_t id) {
+    if (!ids) return id;
+    int64_t lo = 0, hi = n - 1;
+    while (lo <= hi) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (ids[mid] == id) return mid;
+        if (ids[mid] < id) lo = mid + 1; else hi = mid - 1;
+    }
+    return -1;
+}
+
+static double softplus(double x) { return (x > 0 ? x : 0) + log1p(exp(-fabs(x))); }
+static double sigmoid(double x) {
+    if (x >= 0) return 1.0 / (1.0 + exp(-x));
+    double e = exp(x);
+    return e / (1.0 + e);
+}
+
+/* bfloat16 rounding (nearest, ties to even) of a value that is first held as fp32 */
+static double round_bf16(double x) {
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (double)f; /* inf / nan unchanged */
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* ------------------------------------------------------------------------------------------------ */
+/* Table 1: score of one triple from its three rows                                                   */
+
+static double score_triple(const ko_params *p, const double *h, const double *r, const double *t) {
+    const int D = p->ent_dim;
+    double acc = 0.0;
+    switch (p->model) {
+    case KO_TRANSE_L2:
+        for (int d = 0; d < D; ++d) { double u = h[d] + r[d] - t[d]; acc += u * u; }
+        return p->gamma - sqrt(acc);
+    case KO_TRANSE_L1:
+        for (int d = 0; d < D; ++d) acc += fabs(h[d] + r[d] - t[d]);
+        return p->gamma - acc;
+    case KO_DISTMULT:
+        for (int d = 0; d < D; ++d) acc += h[d] * r[d] * t[d];
+        return acc;
+    case KO_COMPLEX: {
+        const int C = D / 2;
+        for (int j = 0; j < C; ++j) {
+            double hr_re = h[j] * r[j] - h[C + j] * r[C + j];
+            double hr_im = h[j] * r[C + j] + h[C + j] * r[j];
+            acc += hr_re * t[j] + hr_im * t[C + j]; /* Re( (h r) conj(t) ) */
+        }
+        return acc;
+    }
+    case KO_ROTATE: {
+        const int C = D / 2;
+        for (int j = 0; j < C; ++j) {
+            double c = cos(r[j]), s = sin(r[j]);
+            double q_re = h[j] * c - h[C + j] * s - t[j];
+            double q_im = h[j] * s + h[C + j] * c - t[C + j];
+            double m2 = q_re * q_re + q_im * q_im;
+            acc += p->rotate_squared ? m2 : sqrt(m2);
+        }
+        return p->gamma - acc;
+    }
+    default: return NAN;
+    }
+}
+
+/* gh += coef * df/dh, gr += coef * df/dr, gt += coef * df/dt  for one triple */
+static void grad_triple(const ko_params *p, const double *h, const double *r, const double *t, double coef,
+                        double *gh, double *gr, double *gt) {
+    const int D = p->ent_dim;
+    switch (p->model) {
+    case KO_TRANSE_L2: {
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) { double u = h[d] + r[d] - t[d]; s += u * u; }
+        double dist = sqrt(s);
+        if (dist == 0.0) return;
+        for (int d = 0; d < D; ++d) {
+            double e = (h[d] + r[d] - t[d]) / dist;  /* d(dist)/du */
+            gh[d] -= coef * e; gr[d] -= coef * e; gt[d] += coef * e;
+        }
+        return;
+    }
+    case KO_TRANSE_L1:
+        for (int d = 0; d < D; ++d) {
+            double u = h[d] + r[d] - t[d];
+            double e = (u > 0) - (u < 0);
+            gh[d] -= coef * e; gr[d] -= coef * e; gt[d] += coef * e;
+        }
+        return;
+    case KO_DISTMULT:
+        for (int d = 0; d < D; ++d) {
+            gh[d] += coef * r[d] * t[d];
+            gr[d] += coef * h[d] * t[d];
+            gt[d] += coef * h[d] * r[d];
+        }
+        return;
+    case KO_COMPLEX: {
+        const int C = D / 2;
+        for (int j = 0; j < C; ++j) {
+            double hre = h[j], him = h[C + j], rre = r[j], rim = r[C + j], tre = t[j], tim = t[C + j];
+            gh[j]     += coef * ( rre * tre + rim * tim);
+            gh[C + j] += coef * (-rim * tre + rre * tim);
+            gr[j]     += coef * ( hre * tre + him * tim);
+            gr[C + j] += coef * (-him * tre + hre * tim);
+            gt[j]     += coef * ( hre * rre - him * rim);
+            gt[C + j] += coef * ( hre * rim + him * rre);
+        }
+        return;
+    }
+    case KO_ROTATE: {
+        const int C = D / 2;
+        for (int j = 0; j < C; ++j) {
+            double c = cos(r[j]), s = sin(r[j]);
+            double p_re = h[j] * c - h[C + j] * s, p_im = h[j] * s + h[C + j] * c; /* h rotated by theta */
+            double q_re = p_re - t[j], q_im = p_im - t[C + j];
+            double e_re, e_im; /* d(term_j)/dq, term_j = |q| or |q|^2 */
+            if (p->rotate_squared) { e_re = 2 * q_re; e_im = 2 * q_im; }
+            else {
+                double m = sqrt(q_re * q_re + q_im * q_im);
+                if (m == 0.0) continue;
+                e_re = q_re / m; e_im = q_im / m;
+            }
+            /* f = gamma - sum term_j */
+            gt[j]     += coef * e_re;
+            gt[C + j] += coef * e_im;
+            gh[j]     -= coef * ( e_re * c + e_im * s);
+            gh[C + j] -= coef * (-e_re * s + e_im * c);
+            gr[j]     -= coef * (-e_re * p_im + e_im * p_re);
+        }
+        return;
+    }
+    default: return;
+    }
+}
+
+/* ------------------------------------------------------------------------------------------------ */
+/* bf16_inputs mode: the Sec. 3.3 split.  o depends on the uncorrupted entity a and the relation only. */
+
+/* o for a positive: tail side a = h, head side a = t */
+static void split_o(const ko_params *p, const double *a, const double *r, double *o) {
+    const int D = p->ent_dim, C = D / 2;
+    const int head = p->neg_side == KO_NEG_HEAD;
+    switch (p->model) {
+    case KO_TRANSE_L2: case KO_TRANSE_L1:
+        for (int d = 0; d < D; ++d) o[d] = head ? a[d] - r[d] : a[d] + r[d];
+        break;
+    case KO_DISTMULT:
+        for (int d = 0; d < D; ++d) o[d] = a[d] * r[d];
+        break;
+    case KO_COMPLEX: case KO_ROTATE:
+        for (int j = 0; j < C; ++j) {
+            double rre, rim;
+            if (p->model == KO_ROTATE) { rre = cos(r[j]); rim = sin(r[j]); } else { rre = r[j]; rim = r[C + j]; }
+            if (head) rim = -rim; /* a * conj(r) */
+            o[j]     = a[j] * rre - a[C + j] * rim;
+            o[C + j] = a[j] * rim + a[C + j] * rre;
+        }
+        break;
+    }
+}
+
+/* score of a pair from o and the corrupting row x */
+static double pair_score(const ko_params *p, const double *o, const double *x) {
+    const int D = p->ent_dim, C = D / 2;
+    double acc = 0.0;
+    switch (p->model) {
+    case KO_TRANSE_L2:
+        for (int d = 0; d < D; ++d) { double u = o[d] - x[d]; acc += u * u; }
+        return p->gamma - sqrt(acc);
+    case KO_TRANSE_L1:
+        for (int d = 0; d < D; ++d) acc += fabs(o[d] - x[d]);
+        return p->gamma - acc;
+    case KO_DISTMULT: case KO_COMPLEX:
+        for (int d = 0; d < D; ++d) acc += o[d] * x[d];
+        return acc;
+    case KO_ROTATE:
+        for (int j = 0; j < C; ++j) {
+            double q_re = o[j] - x[j], q_im = o[C + j] - x[C + j];
+            double m2 = q_re * q_re + q_im * q_im;
+            acc += p->rotate_squared ? m2 : sqrt(m2);
+        }
+        return p->gamma - acc;
+    }
+    return NAN;
+}
+
+/* go += coef * dpsi/do, gx += coef * dpsi/dx */
+static void pair_grad(const ko_params *p, const double *o, const double *x, double coef, double *go, double *gx) {
+    const int D = p->ent_dim, C = D / 2;
+    switch (p->model) {
+    case KO_TRANSE_L2: {
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) { double u = o[d] - x[d]; s += u * u; }
+        double dist = sqrt(s);
+        if (dist == 0.0) return;
+        for (int d = 0; d < D; ++d) { double e = (o[d] - x[d]) / dist; go[d] -= coef * e; gx[d] += coef * e; }
+        return;
+    }
+    case KO_TRANSE_L1:
+        for (int d = 0; d < D; ++d) { double u = o[d] - x[d]; double e = (u > 0) - (u < 0); go[d] -= coef * e; gx[d] += coef * e; }
+        return;
+    case KO_DISTMULT: case KO_COMPLEX:
+        for (int d = 0; d < D; ++d) { go[d] += coef * x[d]; gx[d] += coef * o[d]; }
+        return;
+    case KO_ROTATE:
+        for (int j = 0; j < C; ++j) {
+            double q_re = o[j] - x[j], q_im = o[C + j] - x[C + j], e_re, e_im;
+            if (p->rotate_squared) { e_re = 2 * q_re; e_im = 2 * q_im; }
+            else {
+                double m = sqrt(q_re * q_re + q_im * q_im);
+                if (m == 0.0) continue;
+                e_re = q_re / m; e_im = q_im / m;
+            }
+            go[j] -= coef * e_re; go[C + j] -= coef * e_im;
+            gx[j] += coef * e_re; gx[C + j] += coef * e_im;
+        }
+        return;
+    }
+}
+
+/* ga += J_a^T go, gr += J_r^T go for o = split_o(a, r) */
+static void split_o_backward(const ko_params *p, const double *a, const double *r, const double *go, double *ga, double *gr) {
+    const int D = p->ent_dim, C = D / 2;
+    const int head = p->neg_side == KO_NEG_HEAD;
+    switch (p->model) {
+    case KO_TRANSE_L2: case KO_TRANSE_L1:
+        for (int d = 0; d < D; ++d) { ga[d] += go[d]; gr[d] += head ? -go[d] : go[d]; }
+        break;
+    case KO_DISTMULT:
+        for (int d = 0; d < D; ++d) { ga[d] += go[d] * r[d]; gr[d] += go[d] * a[d]; }
+        break;
+    case KO_COMPLEX:
+        for (int j = 0; j < C; ++j) {
+            double rre = r[j], rim = head ? -r[C + j] : r[C + j];
+            /* o_re = a_re rre - a_im rim ; o_im = a_re rim + a_im rre */
+            ga[j]     += go[j] * rre + go[C + j] * rim;
+            ga[C + j] += -go[j] * rim + go[C + j] * rre;
+            double d_rre = go[j] * a[j] + go[C + j] * a[C + j];
+            double d_rim = -go[j] * a[C + j] + go[C + j] * a[j];
+            gr[j] += d_rre;
+            gr[C + j] += head ? -d_rim : d_rim;
+        }
+        break;
+    case KO_ROTATE:
+        for (int j = 0; j < C; ++j) {
+            double rre = cos(r[j]), rim = sin(r[j]);
+            if (head) rim = -rim;
+            double o_re = a[j] * rre - a[C + j] * rim, o_im = a[j] * rim + a[C + j] * rre;
+            ga[j]     += go[j] * rre + go[C + j] * rim;
+            ga[C + j] += -go[j] * rim + go[C + j] * rre;
+            /* tail side do/dtheta = i o ; head side do/dtheta = -i o */
+            double d_th = -go[j] * o_im + go[C + j] * o_re;
+            gr[j] += head ? -d_th : d_th;
+        }
+        break;
+    }
+}
+
+/* ------------------------------------------------------------------------------------------------ */
+/* loss and gradients of one mini-batch                                                               */
+
+/*
+ * h, r, t : [b] ids of the positive triples.   neg : [(b / chunk) * k] corrupting entity ids; positives
+ * chunk*c .. chunk*(c+1)-1 share neg[c*k .. c*k+k-1]  (Sec. 3.3).
+ * w_fixed : NULL, or [b*k] weights to use instead of computing them (finite-difference tests freeze them).
+ * pos_score [b], neg_score [b*k], w_out [b*k] : outputs, each may be NULL.
+ * dE / dR : NULL (no gradients wanted) or zero-initialised [n_slots * dim] accumulators; row s of dE
+ * belongs to entity ent_ids[s] (ascending list), or to entity s when ent_ids == NULL.
+ * Returns 0, or -1 on bad arguments, -2 if an id has no slot.
+ */
+int ko_loss_grad(const ko_params *p, const void *E, const void *R,
+                 const int64_t *h, const int64_t *r, const int64_t *t, int64_t b,
+                 const int64_t *neg, int64_t k, int64_t chunk, const double *w_fixed,
+                 double *loss_out, double *pos_score, double *neg_score, double *w_out,
+                 const int64_t *ent_ids, int64_t n_ent_slots, double *dE,
+                 const int64_t *rel_ids, int64_t n_rel_slots, double *dR) {
+    if (b <= 0 || chunk <= 0 || b % chunk != 0 || k < 0) return -1;
+    if ((p->model == KO_COMPLEX || p->model == KO_ROTATE) && (p->ent_dim % 2)) return -1;
+    const int De = p->ent_dim, Dr = p->rel_dim, f64 = p->tables_f64;
+    const int head_side = p->neg_side == KO_NEG_HEAD;
+    const int use_split = p->bf16_inputs || p->split_form;
+    double *hv = malloc(sizeof(double) * De), *tv = malloc(sizeof(double) * De), *nv = malloc(sizeof(double) * De);
+    double *rv = malloc(sizeof(double) * (Dr > De ? Dr : De));
+    double *ov = malloc(sizeof(double) * De), *go = malloc(sizeof(double) * De);
+    double *fneg = malloc(sizeof(double) * (k > 0 ? k : 1)), *w = malloc(sizeof(double) * (k > 0 ? k : 1));
+    double total = 0.0;
+    int rc = 0;
+
+    for (int64_t i = 0; i < b && rc == 0; ++i) {
+        const int64_t c = i / chunk;
+        fetch_row(E, f64, h[i], De, hv);
+        fetch_row(R, f64, r[i], Dr, rv);
+        fetch_row(E, f64, t[i], De, tv);
+        const double fpos = score_triple(p, hv, rv, tv);
+        if (pos_score) pos_score[i] = fpos;
+
+        if (use_split) {
+            split_o(p, head_side ? tv : hv, rv, ov);
+            if (p->bf16_inputs) for (int d = 0; d < De; ++d) ov[d] = round_bf16(ov[d]);
+        }
+        /* scores of this positive's k negatives */
+        for (int64_t j = 0; j < k; ++j) {
+            fetch_row(E, f64, neg[c * k + j], De, nv);
+            if (use_split) {
+                if (p->bf16_inputs) for (int d = 0; d < De; ++d) nv[d] = round_bf16(nv[d]);
+                fneg[j] = pair_score(p, ov, nv);
+            } else {
+                fneg[j] = head_side ? score_triple(p, nv, rv, tv) : score_triple(p, hv, rv, nv);
+            }
+            if (neg_score) neg_score[i * k + j] = fneg[j];
+        }
+        /* weights of the negatives: uniform, or softmax of temperature * score (held constant) */
+        if (w_fixed) {
+            for (int64_t j = 0; j < k; ++j) w[j] = w_fixed[i * k + j];
+        } else if (p->adv_temperature > 0 && k > 0) {
+            double mx = -INFINITY, z = 0.0;
+            for (int64_t j = 0; j < k; ++j) if (p->adv_temperature * fneg[j] > mx) mx = p->adv_temperature * fneg[j];
+            for (int64_t j = 0; j < k; ++j) { w[j] = exp(p->adv_temperature * fneg[j] - mx); z += w[j]; }
+            for (int64_t j = 0; j < k; ++j) w[j] /= z;
+        } else {
+            for (int64_t j = 0; j < k; ++j) w[j] = 1.0 / (double)k;
+        }
+        if (w_out) for (int64_t j = 0; j < k; ++j) w_out[i * k + j] = w[j];
+
+        /* logistic loss: y = +1 for the positive, y = -1 for each negative */
+        double li = softplus(-fpos);
+        for (int64_t j = 0; j < k; ++j) li += w[j] * softplus(fneg[j]);
+        total += li / (double)b;
+
+        if (!dE) continue;
+        const int64_t sh = slot_of(ent_ids, n_ent_slots, h[i]);
+        const int64_t st = slot_of(ent_ids, n_ent_slots, t[i]);
+        const int64_t sr = slot_of(rel_ids, n_rel_slots, r[i]);
+        if (sh < 0 || st < 0 || sr < 0) { rc = -2; break; }
+        double *gh = dE + sh * De, *gt = dE + st * De, *gr = dR + sr * Dr;
+        const double cpos = -sigmoid(-fpos) / (double)b; /* d/df softplus(-f) / b */
+        grad_triple(p, hv, rv, tv, cpos, gh, gr, gt);
+        if (use_split) memset(go, 0, sizeof(double) * De);
+        for (int64_t j = 0; j < k; ++j) {
+            const int64_t n = neg[c * k + j];
+            const int64_t sn = slot_of(ent_ids, n_ent_slots, n);
+            if (sn < 0) { rc = -2; break; }
+            double cneg = w[j] * sigmoid(fneg[j]) / (double)b; /* d/df softplus(f) * w / b */
+            fetch_row(E, f64, n, De, nv);
+            if (use_split) {
+                if (p->bf16_inputs) {
+                    /* the coefficient that multiplies the rounded operands in the backward products */
+                    if (p->model == KO_TRANSE_L2) {
+                        double dist = p->gamma - fneg[j];
+                        double wq = dist > 0 ? round_bf16(cneg / dist) : 0.0;
+                        cneg = wq * dist;
+                    } else {
+                        cneg = round_bf16(cneg);
+                    }
+                    for (int d = 0; d < De; ++d) nv[d] = round_bf16(nv[d]);
+                }
+                pair_grad(p, ov, nv, cneg, go, dE + sn * De);
+            } else if (head_side) {
+                grad_triple(p, nv, rv, tv, cneg, dE + sn * De, gr, gt);
+            } else {
+                grad_triple(p, hv, rv, nv, cneg, gh, gr, dE + sn * De);
+            }
+        }
+        if (use_split && rc == 0)
+            split_o_backward(p, head_side ? tv : hv, rv, go, head_side ? gt : gh, gr);
+    }
+    if (loss_out) *loss_out = total;
+    free(hv); free(tv); free(nv); free(rv); free(ov); free(go); free(fneg); free(w);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------------------------------ */
+/* duplicates                                                                                         */
+
+static int cmp_i64(const void *a, const void *b) {
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* distinct values of keys[0..n) ascending in uniq, their multiplicities in cnt; returns how many */
+int64_t ko_dedup(const int64_t *keys, int64_t n, int64_t *uniq, int64_t *cnt) {
+    if (n <= 0) return 0;
+    int64_t *tmp = malloc(sizeof(int64_t) * n);
+    memcpy(tmp, keys, sizeof(int64_t) * n);
+    qsort(tmp, n, sizeof(int64_t), cmp_i64);
+    int64_t u = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (u > 0 && uniq[u - 1] == tmp[i]) cnt[u - 1] += 1;
+        else { uniq[u] = tmp[i]; cnt[u] = 1; ++u; }
+    }
+    free(tmp);
+    return u;
+}
+
+/* ------------------------------------------------------------------------------------------------ */
+/* Adagrad                                                                                            */
+
+/* rows ids[0..n) (or rows 0..n-1 when ids == NULL) of table/state, with gradient rows grad[s*dim ..] */
+void ko_adagrad_rows(float *table, float *state, const int64_t *ids, int64_t n, int dim, const double *grad,
+                     double lr, double eps) {
+    for (int64_t s = 0; s < n; ++s) {
+        const int64_t row = ids ? ids[s] : s;
+        float *th = table + row * (int64_t)dim, *st = state + row * (int64_t)dim;
+        const double *g = grad + s * (int64_t)dim;
+        for (int d = 0; d < dim; ++d) {
+            double S = (double)st[d] + g[d] * g[d];
+            double x = (double)th[d] - lr * g[d] / (sqrt(S) + eps);
+            st[d] = (float)S;
+            th[d] = (float)x;
+        }
+    }
+}
+
+/*
+ * One whole step on fp32 tables: loss, gradients, Adagrad.  dense != 0: gradients are accumulated in
+ * arrays as large as the tables and every row is updated (rows with zero gradient come out bit-identical);
+ * dense == 0: only the distinct rows that occur in the batch get a gradient row and an update.
+ * Both give the same tables bit for bit (checked in the tests).
+ */
+int ko_train_step(const ko_params *p, float *E, float *SE, int64_t n_ent, float *R, float *SR, int64_t n_rel,
+                  const int64_t *h, const int64_t *r, const int64_t *t, int64_t b,
+                  const int64_t *neg, int64_t k, int64_t chunk, double lr, double eps, int dense,
+                  double *loss_out, double *pos_score, double *neg_score) {
+    if (p->tables_f64) return -1;
+    if (b <= 0 || chunk <= 0 || b % chunk != 0) return -1;
+    const int64_t n_neg = (b / chunk) * k, n_keys = 2 * b + n_neg;
+    for (int64_t i = 0; i < b; ++i)
+        if (h[i] < 0 || h[i] >= n_ent || t[i] < 0 || t[i] >= n_ent || r[i] < 0 || r[i] >= n_rel) return -1;
+    for (int64_t j = 0; j < n_neg; ++j) if (neg[j] < 0 || neg[j] >= n_ent) return -1;
+
+    int64_t *ent_ids = NULL, *rel_ids = NULL, ue = n_ent, ur = n_rel;
+    if (!dense) {
+        int64_t *keys = malloc(sizeof(int64_t) * n_keys), *cnt = malloc(sizeof(int64_t) * n_keys);
+        memcpy(keys, h, sizeof(int64_t) * b);
+        memcpy(keys + b, t, sizeof(int64_t) * b);
+        memcpy(keys + 2 * b, neg, sizeof(int64_t) * n_neg);
+        ent_ids = malloc(sizeof(int64_t) * n_keys);
+        ue = ko_dedup(keys, n_keys, ent_ids, cnt);
+        rel_ids = malloc(sizeof(int64_t) * b);
+        ur = ko_dedup(r, b, rel_ids, cnt);
+        free(keys); free(cnt);
+    }
+    double *dE = calloc((size_t)ue * p->ent_dim, sizeof(double));
+    double *dR = calloc((size_t)ur * p->rel_dim, sizeof(double));
+    int rc = (dE && dR) ? 0 : -3;
+    if (rc == 0)
+        rc = ko_loss_grad(p, E, R, h, r, t, b, neg, k, chunk, NULL, loss_out, pos_score, neg_score, NULL,
+                          ent_ids, ue, dE, rel_ids, ur, dR);
+    if (rc == 0) {
+        ko_adagrad_rows(E, SE, ent_ids, ue, p->ent_dim, dE, lr, eps);
+        ko_adagrad_rows(R, SR, rel_ids, ur, p->rel_dim, dR, lr, eps);
+    }
+    free(dE); free(dR); free(ent_ids); free(rel_ids);
+    return rc;
+}
