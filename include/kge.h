@@ -1,0 +1,142 @@
+/*
+ * kge.h -- C ABI of libkge: one mini-batch step of knowledge-graph-embedding training on one AMD MI355X.
+ *
+ * The step is steps 2-4 of the mini-batch loop of the DGL-KE paper (arXiv 2004.08532, Sec. 3.1): fetch the
+ * embedding rows a mini-batch touches, run the forward and backward computation on them, and apply the
+ * optimizer to exactly those rows of the global tables.  Step 1 (sampling) is the caller's: positives and the
+ * jointly sampled corrupting entities (Sec. 3.3) arrive as id arrays.
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer on the context's device unless it is marked (host).  Tables,
+ *     optimizer state, id arrays and outputs are owned by the caller and must stay alive and unmodified
+ *     until the stream has finished the work the call enqueued.  The library owns only its workspace, which
+ *     is allocated in kge_create and never grows.
+ *   - Calls that take a stream ENQUEUE work and return; they do not synchronise.
+ *   - Return value: KGE_OK (0) or a negative kge_status.  When an error is detected on the host nothing has
+ *     been enqueued and no caller memory has been touched.  No C++ exception crosses this boundary.
+ *   - Tables are row-major, contiguous fp32, rows of ent_dim (rel_dim) floats, 16-byte aligned.
+ *   - A context is bound to one device and is not re-entrant: use it from one thread and one stream at a
+ *     time.
+ */
+#ifndef KGE_H
+#define KGE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kge_ctx kge_ctx; /* opaque */
+
+/* Score functions of Table 1 of the paper.  Distance models are used as f = gamma - distance; DistMult and
+ * ComplEx ignore gamma.  TransE-L2 uses the un-squared norm (Table 1, Sec. 3.3).  RotatE is
+ * gamma - sum_j |h_j r_j - t_j| over complex coordinates.  Rows of ComplEx / RotatE entities (and ComplEx
+ * relations) are [real parts | imaginary parts]; a RotatE relation row holds ent_dim/2 phases in radians. */
+typedef enum {
+    KGE_TRANSE_L2 = 0,
+    KGE_TRANSE_L1 = 1,
+    KGE_DISTMULT = 2,
+    KGE_COMPLEX = 3,
+    KGE_ROTATE = 4
+} kge_model;
+
+/* Which entity of each positive is replaced to form its negatives (Sec. 2: only entities are corrupted). */
+typedef enum { KGE_NEG_TAIL = 0, KGE_NEG_HEAD = 1 } kge_neg_side;
+
+typedef enum {
+    KGE_OK = 0,
+    KGE_ERR_INVALID_ARG = -1, /* null pointer, size out of range, b not a multiple of chunk, bad enum   */
+    KGE_ERR_UNSUPPORTED = -2, /* a combination this build does not implement                             */
+    KGE_ERR_WORKSPACE = -3,   /* b, k or b/chunk exceed what the context was created for                 */
+    KGE_ERR_DEVICE = -4,      /* a HIP call failed; kge_last_error has the text                          */
+    KGE_ERR_INDEX_RANGE = -5  /* validate_indices found an id outside its table                          */
+} kge_status;
+
+typedef struct {
+    int32_t model;             /* kge_model                                                               */
+    int32_t device;            /* HIP device ordinal                                                      */
+    int64_t num_entities;      /* rows of the entity table   (< 2^32)                                     */
+    int64_t num_relations;     /* rows of the relation table (< 2^32)                                     */
+    int32_t ent_dim;           /* floats per entity row: multiple of 4 (8 for ComplEx / RotatE), <= 1024  */
+    int32_t rel_dim;           /* floats per relation row: ent_dim, or ent_dim/2 for RotatE               */
+    int32_t max_batch;         /* largest b a call may pass                                               */
+    int32_t max_neg_per_chunk; /* largest k                                                               */
+    int32_t max_chunks;        /* largest b / chunk                                                       */
+    int32_t gemm_input;        /* 0: fp32 operands; 1: bf16 operands, fp32 accumulation (GEMM models)     */
+    int32_t adagrad_mode;      /* 0: element-wise state, same shape as the table                          */
+    float adagrad_eps;         /* added to sqrt(state); 0 selects the default 1e-10                       */
+    float adv_temperature;     /* 0: negatives weigh 1/k each; > 0: softmax(temperature * score) weights  */
+    int32_t validate_indices;  /* != 0: kge_train_step / kge_score range-check ids on the device and the  */
+                               /* next kge_check_indices call reports the result                          */
+} kge_config;
+
+/* Create a context and its workspace on cfg->device.  (host) cfg, (host) out.  The workspace is sized from
+ * max_batch, max_neg_per_chunk, max_chunks and ent_dim and stays allocated until kge_destroy. */
+int kge_create(const kge_config* cfg, kge_ctx** out);
+
+/* Free the workspace and the context.  kge_destroy(NULL) does nothing.  The caller must have synchronised
+ * every stream that still runs work of this context. */
+void kge_destroy(kge_ctx* ctx);
+
+/*
+ * One training step (Sec. 3.1 steps 2-4 with the negative sampling layout of Sec. 3.3).
+ *
+ *   ent [num_entities x ent_dim], ent_state (same shape): entity table and its Adagrad accumulator, updated
+ *   in place; rel, rel_state likewise [num_relations x rel_dim].
+ *   h, r, t [b]: int64 ids of the positive triples.
+ *   neg [(b / chunk) * k]: int64 corrupting entity ids; positives chunk*c .. chunk*c + chunk - 1 share
+ *   neg[c*k .. c*k + k - 1].  neg_side says whether they replace the tail or the head.
+ *   Loss (Sec. 2, logistic loss with y = +1 on positives and -1 on negatives):
+ *       L = (1/b) sum_i [ log(1 + exp(-f+_i)) + sum_j w_ij log(1 + exp(f-_ij)) ],
+ *   w_ij = 1/k, or softmax_j(adv_temperature * f-_ij) held constant in the backward pass.
+ *   Update: for every distinct row that occurs among h, t, neg (entities) or r (relations), with g the sum of
+ *   all gradient contributions to that row:  state += g*g ; row -= lr * g / (sqrt(state) + eps).
+ *   All reads of the tables use the values from before this step.  Rows that do not occur are not written.
+ *   loss_out: device float, receives L; may be NULL.
+ *
+ * Requirements: b > 0, chunk > 0, b % chunk == 0, k > 0, and the workspace limits of kge_create.
+ * Ids must lie inside their tables (a caller contract unless validate_indices is set).
+ */
+int kge_train_step(kge_ctx* ctx, float* ent, float* ent_state, float* rel, float* rel_state,
+                   const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,
+                   const int64_t* neg, int64_t k, int64_t chunk, int32_t neg_side,
+                   float gamma, float lr, void* hip_stream, float* loss_out);
+
+/*
+ * Forward only: scores of the positives and of their chunked negatives (Table 1; Sec. 3.3 for the layout).
+ * pos_out [b] receives f(h_i, r_i, t_i); neg_out [b*k], row-major with one row per positive, receives
+ * f(h_i, r_i, n) (tail side) or f(n, r_i, t_i) (head side) for the k corrupting entities of i's chunk; either
+ * may be NULL.  k may be 0 when neg_out is NULL.  Tables are not modified.
+ */
+int kge_score(kge_ctx* ctx, const float* ent, const float* rel,
+              const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,
+              const int64_t* neg, int64_t k, int64_t chunk, int32_t neg_side, float gamma,
+              void* hip_stream, float* pos_out, float* neg_out);
+
+/*
+ * Test hook for the duplicate reduction of the last kge_train_step on this context (Sec. 2: mini-batches
+ * touch few rows, and one row may be touched many times).  which = 0: entity rows (the multiset
+ * {h_i} + {t_i} + {neg}); which = 1: relation rows ({r_i}).  uniq_out receives the distinct ids in ascending
+ * order, count_out their multiplicities, *n_unique_out how many there are; each output array must hold as
+ * many elements as the multiset has (2b + (b/chunk)*k, or b).  Enqueues on hip_stream.
+ */
+int kge_get_dedup(kge_ctx* ctx, int32_t which, int64_t* uniq_out, int32_t* count_out, int64_t* n_unique_out,
+                  void* hip_stream);
+
+/* Synchronises hip_stream and returns KGE_ERR_INDEX_RANGE if any call since the last check saw an id outside
+ * its table (contexts created with validate_indices), else KGE_OK.  Rows with a bad id are skipped by the
+ * kernels, never dereferenced. */
+int kge_check_indices(kge_ctx* ctx, void* hip_stream);
+
+/* (host) Text of the last error on this context ("" if none); valid until the next call on the context.
+ * kge_last_error(NULL) returns the text of the last failed kge_create on this thread. */
+const char* kge_last_error(const kge_ctx* ctx);
+
+/* Bytes of device workspace the context holds. */
+int64_t kge_workspace_bytes(const kge_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KGE_H */

@@ -48,14 +48,15 @@ def _load():
         vp, i64, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double
         lib.ko_loss_grad.restype = ctypes.c_int
         lib.ko_loss_grad.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, vp, vp, i64, vp, i64, i64, vp,
-                                     vp, vp, vp, vp, vp, i64, vp, vp, i64, vp]
+                                     vp, vp, vp, vp, vp, i64, vp, vp, vp, i64, vp, vp]
         lib.ko_dedup.restype = i64
         lib.ko_dedup.argtypes = [vp, i64, vp, vp]
         lib.ko_adagrad_rows.restype = None
         lib.ko_adagrad_rows.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, dbl, dbl]
         lib.ko_train_step.restype = ctypes.c_int
         lib.ko_train_step.argtypes = [ctypes.POINTER(_Params), vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
-                                      vp, i64, i64, dbl, dbl, ctypes.c_int, vp, vp, vp]
+                                      vp, i64, i64, dbl, dbl, ctypes.c_int, vp, vp, vp,
+                                      vp, vp, vp, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -98,15 +99,17 @@ def loss_and_grad(model, E, R, h, r, t, neg, k, chunk, neg_side, gamma, adv_temp
     w = np.zeros((b, k), np.float64)
     dE = np.zeros(E.shape, np.float64) if want_grad else None
     dR = np.zeros(R.shape, np.float64) if want_grad else None
+    aE = np.zeros(E.shape, np.float64) if want_grad else None
+    aR = np.zeros(R.shape, np.float64) if want_grad else None
     wf = None if w_fixed is None else np.ascontiguousarray(w_fixed, dtype=np.float64)
     rc = lib.ko_loss_grad(ctypes.byref(p), _ptr(E), _ptr(R), _ptr(h), _ptr(r), _ptr(t), b, _ptr(neg), k, chunk,
                           _ptr(wf), ctypes.addressof(loss), _ptr(pos), _ptr(negs), _ptr(w),
-                          None, E.shape[0], _ptr(dE), None, R.shape[0], _ptr(dR))
+                          None, E.shape[0], _ptr(dE), _ptr(aE), None, R.shape[0], _ptr(dR), _ptr(aR))
     if rc != 0:
         raise ValueError(f"ko_loss_grad failed with {rc}")
     out = {"loss": loss.value, "pos": pos, "neg": negs, "w": w}
     if want_grad:
-        out["dE"], out["dR"] = dE, dR
+        out["dE"], out["dR"], out["absE"], out["absR"] = dE, dR, aE, aR
     return out
 
 
@@ -143,8 +146,12 @@ def adagrad_rows(table, state, ids, grad, lr, eps):
 
 
 def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr, eps=1e-10, adv_temperature=0.0,
-               dense=False, bf16_inputs=False, rotate_squared=False, want_scores=False):
-    """One step, in place on float32 E, SE, R, SR.  Returns loss (and scores when asked)."""
+               dense=False, bf16_inputs=False, rotate_squared=False, want_scores=False, report=False):
+    """One step, in place on float32 E, SE, R, SR.  Returns loss (and scores when asked).
+
+    report=True (touched-rows mode) returns ``(loss, rep)`` where rep holds, for the distinct rows of the step,
+    ``ent_ids``, ``dE`` (their summed gradient rows) and ``absE`` (magnitudes of the terms, per element), and the
+    same for relations: what the tests need to bound rounding effects, not part of the method."""
     lib = _load()
     for a in (E, SE, R, SR):
         assert a.dtype == np.float32 and a.flags.c_contiguous
@@ -155,11 +162,26 @@ def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr,
     loss = ctypes.c_double(0.0)
     pos = np.zeros(b, np.float64) if want_scores else None
     negs = np.zeros((b, k), np.float64) if want_scores else None
+    rep = None
+    extra = [None] * 8
+    if report:
+        assert not dense
+        nk = 2 * b + neg.shape[0]
+        rep = {"ent_ids": np.zeros(nk, np.int64), "dE": np.zeros((nk, E.shape[1])), "absE": np.zeros((nk, E.shape[1])),
+               "rel_ids": np.zeros(b, np.int64), "dR": np.zeros((b, R.shape[1])), "absR": np.zeros((b, R.shape[1]))}
+        ne, nr = ctypes.c_int64(0), ctypes.c_int64(0)
+        extra = [_ptr(rep["ent_ids"]), ctypes.addressof(ne), _ptr(rep["dE"]), _ptr(rep["absE"]),
+                 _ptr(rep["rel_ids"]), ctypes.addressof(nr), _ptr(rep["dR"]), _ptr(rep["absR"])]
     rc = lib.ko_train_step(ctypes.byref(p), _ptr(E), _ptr(SE), E.shape[0], _ptr(R), _ptr(SR), R.shape[0],
                            _ptr(h), _ptr(r), _ptr(t), b, _ptr(neg), k, chunk, float(lr), float(eps), int(dense),
-                           ctypes.addressof(loss), _ptr(pos), _ptr(negs))
+                           ctypes.addressof(loss), _ptr(pos), _ptr(negs), *extra)
     if rc != 0:
         raise ValueError(f"ko_train_step failed with {rc}")
+    if report:
+        for key, n in (("ent_ids", ne.value), ("dE", ne.value), ("absE", ne.value), ("rel_ids", nr.value),
+                       ("dR", nr.value), ("absR", nr.value)):
+            rep[key] = rep[key][:n]
+        return loss.value, rep
     if want_scores:
         return loss.value, pos, negs
     return loss.value

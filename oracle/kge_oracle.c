@@ -216,6 +216,77 @@ static void grad_triple(const ko_params *p, const double *h, const double *r, co
     }
 }
 
+/*
+ * Condition measure for the parity tests (not part of the method): an upper estimate, per element, of the
+ * magnitudes of the terms that the gradient contribution of one triple is built from.  Where grad_triple forms
+ * coef * (x - y) this adds |coef| * (|x| + |y|), so that (unit roundoff) * (sum of these over all triples) bounds
+ * the error of evaluating the same gradient in a shorter floating-point format, including cancellation inside
+ * a single contribution.  For TransE-L1 a coordinate whose difference is within roundoff of zero may get the
+ * other sign in a shorter format; its whole contribution is then charged (scaled so that 2^-20 of it covers it).
+ */
+static void grad_triple_mag(const ko_params *p, const double *h, const double *r, const double *t, double coef,
+                            double *mh, double *mr, double *mt) {
+    const int D = p->ent_dim;
+    const double ac = fabs(coef);
+    switch (p->model) {
+    case KO_TRANSE_L2: {
+        double s = 0.0;
+        for (int d = 0; d < D; ++d) { double u = h[d] + r[d] - t[d]; s += u * u; }
+        double dist = sqrt(s);
+        if (dist == 0.0) return;
+        for (int d = 0; d < D; ++d) {
+            double m = ac * (fabs(h[d]) + fabs(r[d]) + fabs(t[d])) / dist;
+            mh[d] += m; mr[d] += m; mt[d] += m;
+        }
+        return;
+    }
+    case KO_TRANSE_L1:
+        for (int d = 0; d < D; ++d) {
+            double u = h[d] + r[d] - t[d], scale = fabs(h[d]) + fabs(r[d]) + fabs(t[d]);
+            double m = fabs(u) <= 9.5367431640625e-07 * scale ? 2.0 * ac * 1048576.0 : ac;
+            mh[d] += m; mr[d] += m; mt[d] += m;
+        }
+        return;
+    case KO_DISTMULT:
+        for (int d = 0; d < D; ++d) {
+            mh[d] += ac * fabs(r[d] * t[d]);
+            mr[d] += ac * fabs(h[d] * t[d]);
+            mt[d] += ac * fabs(h[d] * r[d]);
+        }
+        return;
+    case KO_COMPLEX: {
+        const int C = D / 2;
+        for (int j = 0; j < C; ++j) {
+            double hre = fabs(h[j]), him = fabs(h[C + j]), rre = fabs(r[j]), rim = fabs(r[C + j]);
+            double tre = fabs(t[j]), tim = fabs(t[C + j]);
+            mh[j] += ac * (rre * tre + rim * tim); mh[C + j] += ac * (rim * tre + rre * tim);
+            mr[j] += ac * (hre * tre + him * tim); mr[C + j] += ac * (him * tre + hre * tim);
+            mt[j] += ac * (hre * rre + him * rim); mt[C + j] += ac * (hre * rim + him * rre);
+        }
+        return;
+    }
+    case KO_ROTATE: {
+        const int C = D / 2;
+        for (int j = 0; j < C; ++j) {
+            double c = cos(r[j]), s = sin(r[j]);
+            double p_re = h[j] * c - h[C + j] * s, p_im = h[j] * s + h[C + j] * c;
+            double q_re = p_re - t[j], q_im = p_im - t[C + j];
+            double m = p->rotate_squared ? 0.5 : sqrt(q_re * q_re + q_im * q_im);
+            if (m == 0.0) continue;
+            /* magnitudes of the terms of q_re, q_im, divided by |q| (the direction e = q / |q|) */
+            double T_re = (fabs(h[j] * c) + fabs(h[C + j] * s) + fabs(t[j])) / m;
+            double T_im = (fabs(h[j] * s) + fabs(h[C + j] * c) + fabs(t[C + j])) / m;
+            mt[j] += ac * T_re; mt[C + j] += ac * T_im;
+            mh[j] += ac * (T_re * fabs(c) + T_im * fabs(s));
+            mh[C + j] += ac * (T_re * fabs(s) + T_im * fabs(c));
+            mr[j] += ac * (T_re * fabs(p_im) + T_im * fabs(p_re));
+        }
+        return;
+    }
+    default: return;
+    }
+}
+
 /* ------------------------------------------------------------------------------------------------ */
 /* bf16_inputs mode: the Sec. 3.3 split.  o depends on the uncorrupted entity a and the relation only. */
 
@@ -342,6 +413,12 @@ static void split_o_backward(const ko_params *p, const double *a, const double *
 /* ------------------------------------------------------------------------------------------------ */
 /* loss and gradients of one mini-batch                                                               */
 
+/* acc[slot] += v */
+static void add_rows(double *acc, int64_t slot, int dim, const double *v) {
+    double *dst = acc + slot * (int64_t)dim;
+    for (int d = 0; d < dim; ++d) dst[d] += v[d];
+}
+
 /*
  * h, r, t : [b] ids of the positive triples.   neg : [(b / chunk) * k] corrupting entity ids; positives
  * chunk*c .. chunk*(c+1)-1 share neg[c*k .. c*k+k-1]  (Sec. 3.3).
@@ -349,14 +426,15 @@ static void split_o_backward(const ko_params *p, const double *a, const double *
  * pos_score [b], neg_score [b*k], w_out [b*k] : outputs, each may be NULL.
  * dE / dR : NULL (no gradients wanted) or zero-initialised [n_slots * dim] accumulators; row s of dE
  * belongs to entity ent_ids[s] (ascending list), or to entity s when ent_ids == NULL.
+ * aE / aR : NULL or accumulators of the same shape for the condition measure of grad_triple_mag.
  * Returns 0, or -1 on bad arguments, -2 if an id has no slot.
  */
 int ko_loss_grad(const ko_params *p, const void *E, const void *R,
                  const int64_t *h, const int64_t *r, const int64_t *t, int64_t b,
                  const int64_t *neg, int64_t k, int64_t chunk, const double *w_fixed,
                  double *loss_out, double *pos_score, double *neg_score, double *w_out,
-                 const int64_t *ent_ids, int64_t n_ent_slots, double *dE,
-                 const int64_t *rel_ids, int64_t n_rel_slots, double *dR) {
+                 const int64_t *ent_ids, int64_t n_ent_slots, double *dE, double *aE,
+                 const int64_t *rel_ids, int64_t n_rel_slots, double *dR, double *aR) {
     if (b <= 0 || chunk <= 0 || b % chunk != 0 || k < 0) return -1;
     if ((p->model == KO_COMPLEX || p->model == KO_ROTATE) && (p->ent_dim % 2)) return -1;
     const int De = p->ent_dim, Dr = p->rel_dim, f64 = p->tables_f64;
@@ -365,6 +443,8 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
     double *hv = malloc(sizeof(double) * De), *tv = malloc(sizeof(double) * De), *nv = malloc(sizeof(double) * De);
     double *rv = malloc(sizeof(double) * (Dr > De ? Dr : De));
     double *ov = malloc(sizeof(double) * De), *go = malloc(sizeof(double) * De);
+    double *th = malloc(sizeof(double) * De), *tt = malloc(sizeof(double) * De);
+    double *tr = malloc(sizeof(double) * (Dr > De ? Dr : De));
     double *fneg = malloc(sizeof(double) * (k > 0 ? k : 1)), *w = malloc(sizeof(double) * (k > 0 ? k : 1));
     double total = 0.0;
     int rc = 0;
@@ -415,9 +495,14 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
         const int64_t st = slot_of(ent_ids, n_ent_slots, t[i]);
         const int64_t sr = slot_of(rel_ids, n_rel_slots, r[i]);
         if (sh < 0 || st < 0 || sr < 0) { rc = -2; break; }
-        double *gh = dE + sh * De, *gt = dE + st * De, *gr = dR + sr * Dr;
+        /* every triple's contribution is formed in scratch rows (th, tr, tt) and then added to the rows'
+         * accumulators; the optional aE / aR receive the magnitudes of the terms involved (a condition
+         * measure used by the parity tests, not part of the method) */
         const double cpos = -sigmoid(-fpos) / (double)b; /* d/df softplus(-f) / b */
-        grad_triple(p, hv, rv, tv, cpos, gh, gr, gt);
+        memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
+        grad_triple(p, hv, rv, tv, cpos, th, tr, tt);
+        add_rows(dE, sh, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, st, De, tt);
+        if (aE) grad_triple_mag(p, hv, rv, tv, cpos, aE + sh * De, aR + sr * Dr, aE + st * De);
         if (use_split) memset(go, 0, sizeof(double) * De);
         for (int64_t j = 0; j < k; ++j) {
             const int64_t n = neg[c * k + j];
@@ -425,6 +510,11 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
             if (sn < 0) { rc = -2; break; }
             double cneg = w[j] * sigmoid(fneg[j]) / (double)b; /* d/df softplus(f) * w / b */
             fetch_row(E, f64, n, De, nv);
+            memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
+            if (aE) {
+                if (head_side) grad_triple_mag(p, nv, rv, tv, cneg, aE + sn * De, aR + sr * Dr, aE + st * De);
+                else grad_triple_mag(p, hv, rv, nv, cneg, aE + sh * De, aR + sr * Dr, aE + sn * De);
+            }
             if (use_split) {
                 if (p->bf16_inputs) {
                     /* the coefficient that multiplies the rounded operands in the backward products */
@@ -437,18 +527,25 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
                     }
                     for (int d = 0; d < De; ++d) nv[d] = round_bf16(nv[d]);
                 }
-                pair_grad(p, ov, nv, cneg, go, dE + sn * De);
+                pair_grad(p, ov, nv, cneg, go, tt);
+                add_rows(dE, sn, De, tt);
             } else if (head_side) {
-                grad_triple(p, nv, rv, tv, cneg, dE + sn * De, gr, gt);
+                grad_triple(p, nv, rv, tv, cneg, th, tr, tt); /* (n, r, t) */
+                add_rows(dE, sn, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, st, De, tt);
             } else {
-                grad_triple(p, hv, rv, nv, cneg, gh, gr, dE + sn * De);
+                grad_triple(p, hv, rv, nv, cneg, th, tr, tt); /* (h, r, n) */
+                add_rows(dE, sh, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, sn, De, tt);
             }
         }
-        if (use_split && rc == 0)
-            split_o_backward(p, head_side ? tv : hv, rv, go, head_side ? gt : gh, gr);
+        if (use_split && rc == 0) {
+            memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr);
+            split_o_backward(p, head_side ? tv : hv, rv, go, th, tr);
+            add_rows(dE, head_side ? st : sh, De, th); add_rows(dR, sr, Dr, tr);
+        }
     }
     if (loss_out) *loss_out = total;
     free(hv); free(tv); free(nv); free(rv); free(ov); free(go); free(fneg); free(w);
+    free(th); free(tt); free(tr);
     return rc;
 }
 
@@ -503,7 +600,9 @@ void ko_adagrad_rows(float *table, float *state, const int64_t *ids, int64_t n, 
 int ko_train_step(const ko_params *p, float *E, float *SE, int64_t n_ent, float *R, float *SR, int64_t n_rel,
                   const int64_t *h, const int64_t *r, const int64_t *t, int64_t b,
                   const int64_t *neg, int64_t k, int64_t chunk, double lr, double eps, int dense,
-                  double *loss_out, double *pos_score, double *neg_score) {
+                  double *loss_out, double *pos_score, double *neg_score,
+                  int64_t *ent_ids_out, int64_t *n_ent_out, double *dE_out, double *aE_out,
+                  int64_t *rel_ids_out, int64_t *n_rel_out, double *dR_out, double *aR_out) {
     if (p->tables_f64) return -1;
     if (b <= 0 || chunk <= 0 || b % chunk != 0) return -1;
     const int64_t n_neg = (b / chunk) * k, n_keys = 2 * b + n_neg;
@@ -525,10 +624,22 @@ int ko_train_step(const ko_params *p, float *E, float *SE, int64_t n_ent, float 
     }
     double *dE = calloc((size_t)ue * p->ent_dim, sizeof(double));
     double *dR = calloc((size_t)ur * p->rel_dim, sizeof(double));
+    /* optional report for the tests (touched-rows mode only): ids, gradient rows, sums of |contribution| */
+    const int report = !dense && ent_ids_out && dE_out && aE_out && rel_ids_out && dR_out && aR_out;
+    if (report) {
+        memset(aE_out, 0, sizeof(double) * (size_t)ue * p->ent_dim);
+        memset(aR_out, 0, sizeof(double) * (size_t)ur * p->rel_dim);
+    }
     int rc = (dE && dR) ? 0 : -3;
     if (rc == 0)
         rc = ko_loss_grad(p, E, R, h, r, t, b, neg, k, chunk, NULL, loss_out, pos_score, neg_score, NULL,
-                          ent_ids, ue, dE, rel_ids, ur, dR);
+                          ent_ids, ue, dE, report ? aE_out : NULL, rel_ids, ur, dR, report ? aR_out : NULL);
+    if (rc == 0 && report) {
+        memcpy(ent_ids_out, ent_ids, sizeof(int64_t) * ue); *n_ent_out = ue;
+        memcpy(rel_ids_out, rel_ids, sizeof(int64_t) * ur); *n_rel_out = ur;
+        memcpy(dE_out, dE, sizeof(double) * (size_t)ue * p->ent_dim);
+        memcpy(dR_out, dR, sizeof(double) * (size_t)ur * p->rel_dim);
+    }
     if (rc == 0) {
         ko_adagrad_rows(E, SE, ent_ids, ue, p->ent_dim, dE, lr, eps);
         ko_adagrad_rows(R, SR, rel_ids, ur, p->rel_dim, dR, lr, eps);

@@ -1,0 +1,208 @@
+// Row gather with fused positive forward (paper Sec. 3.1 step 2 and the first half of step 3).
+//
+// One wavefront per row.  A wave reads the rows it needs with 16-byte loads (a 1600-byte row is 100 such
+// loads, lanes 0..63 then 0..35, so every request is a run of whole cache lines), forms
+//     o_i = phi(a_i, r_i)   (Sec. 3.3: o = h + r for TransE; a*r, a*conj(r), rotations for the other models)
+// scores the positive pair psi(o_i, c_i) (Table 1) with a shuffle reduction, and writes o_i once into the
+// dense staging array that the chunked negative scoring reads.  Waves past the positives copy the k
+// corrupting rows of every chunk into staging (the O(bkd/g) rows of Sec. 3.3) and compute |n|^2 for TransE-L2.
+#include "kge_common.h"
+
+namespace {
+
+struct GatherArgs {
+    const float* E;
+    const float* R;
+    const int64_t* h;
+    const int64_t* r;
+    const int64_t* t;
+    const int64_t* neg;
+    int b, n_neg, D, Dr, side, bf16;
+    float gamma;
+    int64_t n_ent, n_rel;
+    float* O;
+    float* Nst;
+    float* fpos;
+    float* pos_out;
+    float* o_n2;
+    float* n_n2;
+    uint16_t* Obf;
+    uint16_t* Nbf;
+};
+
+__device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
+
+__device__ __forceinline__ void store_bf16x4(uint16_t* dst, const float* v, float* rounded) {
+    uint16_t q[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { q[e] = f32_to_bf16(v[e]); rounded[e] = bf16_to_f32(q[e]); }
+    uint2 pk = make_uint2((uint32_t)q[0] | ((uint32_t)q[1] << 16), (uint32_t)q[2] | ((uint32_t)q[3] << 16));
+    *reinterpret_cast<uint2*>(dst) = pk;
+}
+
+// NV = 16-byte vectors per lane: ceil(D/4/64) for the real models, ceil(D/8/64) (re, im) pairs for the complex ones.
+template <int MODEL, int NV>
+__global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int D = a.D;
+    constexpr bool CPLX = (MODEL == KGE_COMPLEX || MODEL == KGE_ROTATE);
+    const int nvec = CPLX ? D / 8 : D / 4;   // vectors (or re/im vector pairs) per row
+    const int im_off = D / 2;                // float offset of the imaginary half
+
+    if (row >= a.b + a.n_neg) return;
+
+    if (row >= a.b) {  // ---- a corrupting row: copy it to staging
+        const int j = row - a.b;
+        const int64_t id = clamp_id(a.neg[j], a.n_ent);
+        const float* src = a.E + id * (int64_t)D;
+        float* dst = a.Nst + (int64_t)j * D;
+        float nn = 0.f;
+        const int nv4 = D / 4;
+#pragma unroll
+        for (int it = 0; it < (CPLX ? 2 * NV : NV); ++it) {
+            const int v = lane + it * 64;
+            if (v < nv4) {
+                float4 x = ld4(src + 4 * v);
+                float xv[4] = {x.x, x.y, x.z, x.w};
+                if (a.bf16) {
+                    float rq[4];
+                    store_bf16x4(a.Nbf + (int64_t)j * D + 4 * v, xv, rq);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) xv[e] = rq[e];
+                }
+                st4(dst + 4 * v, x);
+                nn += xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3];
+            }
+        }
+        if (MODEL == KGE_TRANSE_L2) {
+            nn = wave_sum(nn);
+            if (lane == 0) a.n_n2[j] = nn;
+        }
+        return;
+    }
+
+    // ---- a positive: rows a (kept entity), r, c (the entity that the negatives replace)
+    const int i = row;
+    const int64_t hid = clamp_id(a.h[i], a.n_ent), tid = clamp_id(a.t[i], a.n_ent);
+    const int64_t rid = clamp_id(a.r[i], a.n_rel);
+    const bool head = a.side == KGE_NEG_HEAD;
+    const float* pa = a.E + (head ? tid : hid) * (int64_t)D;
+    const float* pc = a.E + (head ? hid : tid) * (int64_t)D;
+    const float* pr = a.R + rid * (int64_t)a.Dr;
+    float* po = a.O + (int64_t)i * D;
+    float acc = 0.f, on = 0.f;
+
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+        const int v = lane + it * 64;
+        if (v >= nvec) continue;
+        if constexpr (!CPLX) {
+            const float4 A = ld4(pa + 4 * v), Rr = ld4(pr + 4 * v), Cc = ld4(pc + 4 * v);
+            const float av[4] = {A.x, A.y, A.z, A.w}, rv[4] = {Rr.x, Rr.y, Rr.z, Rr.w}, cv[4] = {Cc.x, Cc.y, Cc.z, Cc.w};
+            float ov[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (MODEL == KGE_DISTMULT) ov[e] = av[e] * rv[e];
+                else ov[e] = head ? av[e] - rv[e] : av[e] + rv[e];
+            }
+            st4(po + 4 * v, make_float4(ov[0], ov[1], ov[2], ov[3]));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (MODEL == KGE_DISTMULT) acc += ov[e] * cv[e];
+                else if (MODEL == KGE_TRANSE_L1) acc += fabsf(ov[e] - cv[e]);
+                else { const float u = ov[e] - cv[e]; acc += u * u; }
+            }
+            if (MODEL == KGE_TRANSE_L2 || a.bf16) {
+                float nv[4] = {ov[0], ov[1], ov[2], ov[3]};
+                if (a.bf16) store_bf16x4(a.Obf + (int64_t)i * D + 4 * v, ov, nv);
+                on += nv[0] * nv[0] + nv[1] * nv[1] + nv[2] * nv[2] + nv[3] * nv[3];
+            }
+        } else {
+            const float4 Are = ld4(pa + 4 * v), Aim = ld4(pa + im_off + 4 * v);
+            const float4 Cre = ld4(pc + 4 * v), Cim = ld4(pc + im_off + 4 * v);
+            const float are[4] = {Are.x, Are.y, Are.z, Are.w}, aim[4] = {Aim.x, Aim.y, Aim.z, Aim.w};
+            const float cre[4] = {Cre.x, Cre.y, Cre.z, Cre.w}, cim[4] = {Cim.x, Cim.y, Cim.z, Cim.w};
+            float rre[4], rim[4];
+            if (MODEL == KGE_ROTATE) {
+                const float4 Th = ld4(pr + 4 * v);
+                const float th[4] = {Th.x, Th.y, Th.z, Th.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sincosf(th[e], &rim[e], &rre[e]);
+            } else {
+                const float4 Rre = ld4(pr + 4 * v), Rim = ld4(pr + im_off + 4 * v);
+                rre[0] = Rre.x; rre[1] = Rre.y; rre[2] = Rre.z; rre[3] = Rre.w;
+                rim[0] = Rim.x; rim[1] = Rim.y; rim[2] = Rim.z; rim[3] = Rim.w;
+            }
+            float ore[4], oim[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float ri = head ? -rim[e] : rim[e];  // head corruption: o = t * conj(r)
+                ore[e] = are[e] * rre[e] - aim[e] * ri;
+                oim[e] = are[e] * ri + aim[e] * rre[e];
+            }
+            st4(po + 4 * v, make_float4(ore[0], ore[1], ore[2], ore[3]));
+            st4(po + im_off + 4 * v, make_float4(oim[0], oim[1], oim[2], oim[3]));
+            if (a.bf16) {
+                float tmp[4];
+                store_bf16x4(a.Obf + (int64_t)i * D + 4 * v, ore, tmp);
+                store_bf16x4(a.Obf + (int64_t)i * D + im_off + 4 * v, oim, tmp);
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (MODEL == KGE_COMPLEX) acc += ore[e] * cre[e] + oim[e] * cim[e];
+                else {
+                    const float qre = ore[e] - cre[e], qim = oim[e] - cim[e];
+                    acc += sqrtf(qre * qre + qim * qim);
+                }
+            }
+        }
+    }
+    acc = wave_sum(acc);
+    if (MODEL == KGE_TRANSE_L2) on = wave_sum(on);
+    if (lane == 0) {
+        float f;
+        if (MODEL == KGE_TRANSE_L2) f = a.gamma - sqrtf(acc);
+        else if (MODEL == KGE_TRANSE_L1 || MODEL == KGE_ROTATE) f = a.gamma - acc;
+        else f = acc;
+        a.fpos[i] = f;
+        if (a.pos_out) a.pos_out[i] = f;
+        if (MODEL == KGE_TRANSE_L2) a.o_n2[i] = on;
+    }
+}
+
+template <int MODEL>
+void launch_nv(const GatherArgs& a, int nv, dim3 grid, hipStream_t st) {
+    switch (nv) {
+    case 1: hipLaunchKernelGGL((k_gather<MODEL, 1>), grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_gather<MODEL, 2>), grid, dim3(256), 0, st, a); break;
+    case 3: hipLaunchKernelGGL((k_gather<MODEL, 3>), grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((k_gather<MODEL, 4>), grid, dim3(256), 0, st, a); break;
+    }
+}
+
+}  // namespace
+
+void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const int64_t* h, const int64_t* r,
+                       const int64_t* t, int b, const int64_t* neg, int n_neg, int side, float gamma,
+                       float* pos_out, hipStream_t st) {
+    GatherArgs a;
+    a.E = E; a.R = R; a.h = h; a.r = r; a.t = t; a.neg = neg;
+    a.b = b; a.n_neg = n_neg; a.D = c->cfg.ent_dim; a.Dr = c->cfg.rel_dim; a.side = side;
+    a.bf16 = c->cfg.gemm_input;
+    a.gamma = gamma; a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
+    a.O = c->O; a.Nst = c->Nst; a.fpos = c->fpos; a.pos_out = pos_out; a.o_n2 = c->o_n2; a.n_n2 = c->n_n2;
+    a.Obf = c->Obf; a.Nbf = c->Nbf;
+    const int model = c->cfg.model;
+    const bool cplx = model == KGE_COMPLEX || model == KGE_ROTATE;
+    const int nvec = cplx ? a.D / 8 : a.D / 4;
+    const int nv = (nvec + 63) / 64;
+    const dim3 grid((b + n_neg + 3) / 4);
+    switch (model) {
+    case KGE_TRANSE_L2: launch_nv<KGE_TRANSE_L2>(a, nv, grid, st); break;
+    case KGE_TRANSE_L1: launch_nv<KGE_TRANSE_L1>(a, nv, grid, st); break;
+    case KGE_DISTMULT: launch_nv<KGE_DISTMULT>(a, nv, grid, st); break;
+    case KGE_COMPLEX: launch_nv<KGE_COMPLEX>(a, nv, grid, st); break;
+    default: launch_nv<KGE_ROTATE>(a, nv, grid, st); break;
+    }
+}

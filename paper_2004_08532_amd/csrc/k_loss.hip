@@ -1,0 +1,284 @@
+// Logistic loss (paper Sec. 2) on the positive and negative scores, its derivatives, and the chain rule from
+// dL/do back to the head / tail / relation rows (the back-propagation half of Sec. 3.1 step 3).
+//
+// k_loss: one wavefront per positive.  The k negative scores of the row are read by the 64 lanes, the optional
+// softmax weights use shuffle reductions for the maximum and the sum, and the row leaves behind the
+// coefficient matrix W that the backward products consume:
+//     W_ij = w_ij * sigmoid(f-_ij) / b               (DistMult, ComplEx, RotatE, TransE-L1)
+//     W_ij = w_ij * sigmoid(f-_ij) / (b * dist_ij)    (TransE-L2, so that dO = W N - rowsum(W) o)
+// k_chain: one wavefront per positive.  Adds the positive pair's own term to dL/do, pushes it through
+// o = phi(a, r) and writes the three gradient rows of the positive (kept entity, replaced entity, relation).
+#include "kge_common.h"
+
+namespace {
+
+__device__ __forceinline__ float sigmoidf_(float x) {
+    if (x >= 0.f) return 1.f / (1.f + expf(-x));
+    const float e = expf(x);
+    return e / (1.f + e);
+}
+__device__ __forceinline__ float softplusf_(float x) { return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x))); }
+
+struct LossArgs {
+    float* S;  // in: negative scores (distances when is_dist); out: W
+    int ld_s, b, k;
+    const float* fpos;
+    float gamma, alpha;
+    int is_dist;  // TransE-L2 training path: S holds distances, score = gamma - S
+    int bf16;
+    float* cpos;
+    float* row_loss;
+    float* w_rowsum;
+    uint16_t* Wbf;
+};
+
+__global__ __launch_bounds__(256) void k_loss(LossArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= a.b) return;
+    float* s = a.S + (int64_t)i * a.ld_s;
+    const float invb = 1.f / (float)a.b;
+    const float fp = a.fpos[i];
+    const int k = a.k;
+
+    float mx = -INFINITY, z = 1.f;
+    if (a.alpha > 0.f) {
+        for (int j = lane; j < k; j += 64) {
+            const float f = a.is_dist ? a.gamma - s[j] : s[j];
+            mx = fmaxf(mx, a.alpha * f);
+        }
+        mx = wave_max(mx);
+        float zz = 0.f;
+        for (int j = lane; j < k; j += 64) {
+            const float f = a.is_dist ? a.gamma - s[j] : s[j];
+            zz += expf(a.alpha * f - mx);
+        }
+        z = wave_sum(zz);
+    }
+    float li = 0.f, rs = 0.f;
+    for (int j = lane; j < k; j += 64) {
+        const float raw = s[j];
+        const float f = a.is_dist ? a.gamma - raw : raw;
+        const float w = a.alpha > 0.f ? expf(a.alpha * f - mx) / z : 1.f / (float)k;
+        li += w * softplusf_(f);
+        float coef = w * sigmoidf_(f) * invb;
+        if (a.is_dist) coef = raw > 0.f ? coef / raw : 0.f;
+        if (a.bf16) {
+            const uint16_t q = f32_to_bf16(coef);
+            a.Wbf[(int64_t)i * a.ld_s + j] = q;
+            coef = bf16_to_f32(q);
+        }
+        s[j] = coef;
+        rs += coef;
+    }
+    li = wave_sum(li);
+    rs = wave_sum(rs);
+    if (lane == 0) {
+        a.row_loss[i] = (softplusf_(-fp) + li) * invb;
+        a.cpos[i] = -sigmoidf_(-fp) * invb;
+        a.w_rowsum[i] = rs;
+    }
+}
+
+struct ChainArgs {
+    const float* E;
+    const float* R;
+    const int64_t* h;
+    const int64_t* r;
+    const int64_t* t;
+    int b, D, Dr, side;
+    int64_t n_ent, n_rel;
+    const float* O;
+    const float* GO;
+    const float* cpos;
+    float* Gent;
+    float* Grel;
+};
+
+__device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
+
+template <int MODEL, int NV>
+__global__ __launch_bounds__(256) void k_chain(ChainArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= a.b) return;
+    constexpr bool CPLX = (MODEL == KGE_COMPLEX || MODEL == KGE_ROTATE);
+    const int D = a.D;
+    const int nvec = CPLX ? D / 8 : D / 4;
+    const int im_off = D / 2;
+    const bool head = a.side == KGE_NEG_HEAD;
+    const int64_t hid = clamp_id(a.h[i], a.n_ent), tid = clamp_id(a.t[i], a.n_ent);
+    const int64_t rid = clamp_id(a.r[i], a.n_rel);
+    const float* pa = a.E + (head ? tid : hid) * (int64_t)D;
+    const float* pc = a.E + (head ? hid : tid) * (int64_t)D;
+    const float* pr = a.R + rid * (int64_t)a.Dr;
+    const float* po = a.O + (int64_t)i * D;
+    const float* pg = a.GO + (int64_t)i * D;
+    // key positions: heads 0..b-1, tails b..2b-1
+    float* ga = a.Gent + (int64_t)(head ? a.b + i : i) * D;
+    float* gc = a.Gent + (int64_t)(head ? i : a.b + i) * D;
+    float* gr = a.Grel + (int64_t)i * a.Dr;
+    const float cp = a.cpos[i];
+
+    if constexpr (!CPLX) {
+        float4 Ov[NV], Cv[NV];
+        float ss = 0.f;
+#pragma unroll
+        for (int it = 0; it < NV; ++it) {
+            const int v = lane + it * 64;
+            if (v < nvec) {
+                Ov[it] = ld4(po + 4 * v);
+                Cv[it] = ld4(pc + 4 * v);
+                if (MODEL == KGE_TRANSE_L2) {
+                    const float u0 = Ov[it].x - Cv[it].x, u1 = Ov[it].y - Cv[it].y, u2 = Ov[it].z - Cv[it].z,
+                                u3 = Ov[it].w - Cv[it].w;
+                    ss += u0 * u0 + u1 * u1 + u2 * u2 + u3 * u3;
+                }
+            }
+        }
+        float inv = 0.f;
+        if (MODEL == KGE_TRANSE_L2) {
+            ss = wave_sum(ss);
+            inv = ss > 0.f ? 1.f / sqrtf(ss) : 0.f;
+        }
+#pragma unroll
+        for (int it = 0; it < NV; ++it) {
+            const int v = lane + it * 64;
+            if (v >= nvec) continue;
+            const float4 G = ld4(pg + 4 * v);
+            const float ov[4] = {Ov[it].x, Ov[it].y, Ov[it].z, Ov[it].w};
+            const float cv[4] = {Cv[it].x, Cv[it].y, Cv[it].z, Cv[it].w};
+            const float gv[4] = {G.x, G.y, G.z, G.w};
+            float oa[4], oc[4], orl[4];
+            if (MODEL == KGE_DISTMULT) {
+                const float4 A = ld4(pa + 4 * v), Rr = ld4(pr + 4 * v);
+                const float av[4] = {A.x, A.y, A.z, A.w}, rv[4] = {Rr.x, Rr.y, Rr.z, Rr.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float go = gv[e] + cp * cv[e];
+                    oc[e] = cp * ov[e];
+                    oa[e] = go * rv[e];
+                    orl[e] = go * av[e];
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float u = ov[e] - cv[e];
+                    const float dir = MODEL == KGE_TRANSE_L2 ? u * inv : (float)((u > 0.f) - (u < 0.f));
+                    const float go = gv[e] - cp * dir;  // d psi / d o = -dir
+                    oc[e] = cp * dir;
+                    oa[e] = go;
+                    orl[e] = head ? -go : go;
+                }
+            }
+            st4(ga + 4 * v, make_float4(oa[0], oa[1], oa[2], oa[3]));
+            st4(gc + 4 * v, make_float4(oc[0], oc[1], oc[2], oc[3]));
+            st4(gr + 4 * v, make_float4(orl[0], orl[1], orl[2], orl[3]));
+        }
+    } else {
+#pragma unroll
+        for (int it = 0; it < NV; ++it) {
+            const int v = lane + it * 64;
+            if (v >= nvec) continue;
+            const float4 Ore = ld4(po + 4 * v), Oim = ld4(po + im_off + 4 * v);
+            const float4 Cre = ld4(pc + 4 * v), Cim = ld4(pc + im_off + 4 * v);
+            const float4 Gre = ld4(pg + 4 * v), Gim = ld4(pg + im_off + 4 * v);
+            const float4 Are = ld4(pa + 4 * v), Aim = ld4(pa + im_off + 4 * v);
+            const float ore[4] = {Ore.x, Ore.y, Ore.z, Ore.w}, oim[4] = {Oim.x, Oim.y, Oim.z, Oim.w};
+            const float cre[4] = {Cre.x, Cre.y, Cre.z, Cre.w}, cim[4] = {Cim.x, Cim.y, Cim.z, Cim.w};
+            const float gre[4] = {Gre.x, Gre.y, Gre.z, Gre.w}, gim[4] = {Gim.x, Gim.y, Gim.z, Gim.w};
+            const float are[4] = {Are.x, Are.y, Are.z, Are.w}, aim[4] = {Aim.x, Aim.y, Aim.z, Aim.w};
+            float rre[4], rim[4];
+            if (MODEL == KGE_ROTATE) {
+                const float4 Th = ld4(pr + 4 * v);
+                const float th[4] = {Th.x, Th.y, Th.z, Th.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sincosf(th[e], &rim[e], &rre[e]);
+            } else {
+                const float4 Rre = ld4(pr + 4 * v), Rim = ld4(pr + im_off + 4 * v);
+                rre[0] = Rre.x; rre[1] = Rre.y; rre[2] = Rre.z; rre[3] = Rre.w;
+                rim[0] = Rim.x; rim[1] = Rim.y; rim[2] = Rim.z; rim[3] = Rim.w;
+            }
+            float oa_re[4], oa_im[4], oc_re[4], oc_im[4], or_a[4], or_b[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float g_re, g_im;
+                if (MODEL == KGE_COMPLEX) {  // psi = o . c (real dot product of the [re|im] rows)
+                    g_re = gre[e] + cp * cre[e];
+                    g_im = gim[e] + cp * cim[e];
+                    oc_re[e] = cp * ore[e];
+                    oc_im[e] = cp * oim[e];
+                } else {  // psi = gamma - sum |o - c|
+                    const float q_re = ore[e] - cre[e], q_im = oim[e] - cim[e];
+                    const float m2 = q_re * q_re + q_im * q_im;
+                    const float invm = m2 > 0.f ? 1.f / sqrtf(m2) : 0.f;
+                    const float e_re = q_re * invm, e_im = q_im * invm;
+                    g_re = gre[e] - cp * e_re;
+                    g_im = gim[e] - cp * e_im;
+                    oc_re[e] = cp * e_re;
+                    oc_im[e] = cp * e_im;
+                }
+                const float ri = head ? -rim[e] : rim[e];  // o = a * (rre + i ri)
+                oa_re[e] = g_re * rre[e] + g_im * ri;      // g * conj(rre + i ri)
+                oa_im[e] = g_im * rre[e] - g_re * ri;
+                if (MODEL == KGE_COMPLEX) {
+                    const float d_rre = g_re * are[e] + g_im * aim[e];
+                    const float d_ri = -g_re * aim[e] + g_im * are[e];
+                    or_a[e] = d_rre;
+                    or_b[e] = head ? -d_ri : d_ri;
+                } else {
+                    const float d_th = -g_re * oim[e] + g_im * ore[e];  // do/dtheta = +i o (tail), -i o (head)
+                    or_a[e] = head ? -d_th : d_th;
+                }
+            }
+            st4(ga + 4 * v, make_float4(oa_re[0], oa_re[1], oa_re[2], oa_re[3]));
+            st4(ga + im_off + 4 * v, make_float4(oa_im[0], oa_im[1], oa_im[2], oa_im[3]));
+            st4(gc + 4 * v, make_float4(oc_re[0], oc_re[1], oc_re[2], oc_re[3]));
+            st4(gc + im_off + 4 * v, make_float4(oc_im[0], oc_im[1], oc_im[2], oc_im[3]));
+            st4(gr + 4 * v, make_float4(or_a[0], or_a[1], or_a[2], or_a[3]));
+            if (MODEL == KGE_COMPLEX) st4(gr + im_off + 4 * v, make_float4(or_b[0], or_b[1], or_b[2], or_b[3]));
+        }
+    }
+}
+
+template <int MODEL>
+void launch_chain_nv(const ChainArgs& a, int nv, dim3 grid, hipStream_t st) {
+    switch (nv) {
+    case 1: hipLaunchKernelGGL((k_chain<MODEL, 1>), grid, dim3(256), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((k_chain<MODEL, 2>), grid, dim3(256), 0, st, a); break;
+    case 3: hipLaunchKernelGGL((k_chain<MODEL, 3>), grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL((k_chain<MODEL, 4>), grid, dim3(256), 0, st, a); break;
+    }
+}
+
+}  // namespace
+
+void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st) {
+    LossArgs a;
+    a.S = c->S; a.ld_s = c->ld_s; a.b = b; a.k = k; a.fpos = c->fpos; a.gamma = gamma;
+    a.alpha = c->cfg.adv_temperature; a.is_dist = c->cfg.model == KGE_TRANSE_L2;
+    a.bf16 = c->cfg.gemm_input;
+    a.cpos = c->cpos; a.row_loss = c->row_loss; a.w_rowsum = c->w_rowsum; a.Wbf = c->Wbf;
+    hipLaunchKernelGGL(k_loss, dim3((b + 3) / 4), dim3(256), 0, st, a);
+}
+
+void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const int64_t* h, const int64_t* r,
+                      const int64_t* t, int b, int side, float gamma, hipStream_t st) {
+    (void)gamma;
+    ChainArgs a;
+    a.E = E; a.R = R; a.h = h; a.r = r; a.t = t; a.b = b; a.D = c->cfg.ent_dim; a.Dr = c->cfg.rel_dim;
+    a.side = side; a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
+    a.O = c->O; a.GO = c->GO; a.cpos = c->cpos; a.Gent = c->Gent; a.Grel = c->Grel;
+    const int model = c->cfg.model;
+    const bool cplx = model == KGE_COMPLEX || model == KGE_ROTATE;
+    const int nvec = cplx ? a.D / 8 : a.D / 4;
+    const int nv = (nvec + 63) / 64;
+    const dim3 grid((b + 3) / 4);
+    switch (model) {
+    case KGE_TRANSE_L2: launch_chain_nv<KGE_TRANSE_L2>(a, nv, grid, st); break;
+    case KGE_TRANSE_L1: launch_chain_nv<KGE_TRANSE_L1>(a, nv, grid, st); break;
+    case KGE_DISTMULT: launch_chain_nv<KGE_DISTMULT>(a, nv, grid, st); break;
+    case KGE_COMPLEX: launch_chain_nv<KGE_COMPLEX>(a, nv, grid, st); break;
+    default: launch_chain_nv<KGE_ROTATE>(a, nv, grid, st); break;
+    }
+}

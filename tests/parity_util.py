@@ -1,0 +1,145 @@
+"""Shared helpers of the GPU parity tests: run the HIP library and the CPU oracle on the same seeded inputs and
+compare element by element.
+
+Tolerances.  Scores and loss: 1e-5; embeddings: 1e-4; each relative to max(|oracle value|, floor) with floor = 1
+for scores and loss and the initialisation bound (gamma + 2) / dim for embedding elements (pure relative error
+is meaningless for values that start near zero).
+
+Adagrad divides by sqrt(S) + eps, so an element whose accumulated gradient is far smaller than the terms it was
+summed from turns the fp32 rounding of those terms into a visible change of the update: with g the summed
+gradient, A the sum of the magnitudes of the terms it is built from (the oracle's condition measure; it
+includes cancellation inside one contribution, e.g. h + r - t) and rho * A the fp32 rounding of that sum, the update
+lr * g / (sqrt(S + g^2) + eps) can differ by |U(g +- rho A) - U(g)|.  The per-step check therefore allows
+        1e-4 * max(|x|, floor)  +  max |U(g +- rho A) - U(g)|,      rho = 2^-20 (16 fp32 roundoffs)
+per element, with g, A and S taken from the oracle.  For ordinarily conditioned elements the second term is
+far below the first; the tests report how many elements needed it.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+from harness import configs, graphs
+
+SCORE_TOL = 1e-5
+EMB_TOL = 1e-4
+RHO = 2.0 ** -20
+
+
+def rel_err(got: np.ndarray, want: np.ndarray, floor: float) -> float:
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    if got.size == 0:
+        return 0.0
+    return float(np.max(np.abs(got - want) / np.maximum(np.abs(want), floor)))
+
+
+def dev(x: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def rounding_allowance(g, A, S_prev, lr, eps):
+    """Largest change of the Adagrad update and of the new state when g moves by +-RHO * A."""
+    d = RHO * A
+
+    def upd(x):
+        return lr * x / (np.sqrt(S_prev + x * x) + eps)
+
+    u0 = upd(g)
+    du = np.maximum(np.abs(upd(g + d) - u0), np.abs(upd(g - d) - u0))
+    ds = 2.0 * np.abs(g) * d + d * d
+    return du, ds
+
+
+class Pair:
+    """Tables on the host (oracle) and on the device (library), advanced together."""
+
+    def __init__(self, w: configs.Workload, kge, validate=False, E=None, R=None):
+        self.w = w
+        if E is None:
+            E, R = configs.init_tables(w)
+        self.E, self.R = E.copy(), R.copy()
+        self.SE, self.SR = np.zeros_like(self.E), np.zeros_like(self.R)
+        self.dE, self.dR = dev(self.E), dev(self.R)
+        self.dSE, self.dSR = torch.zeros_like(self.dE), torch.zeros_like(self.dR)
+        self.ctx = kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
+                                  max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks,
+                                  gemm_input=int(w.bf16_inputs), adv_temperature=w.adv_temperature,
+                                  validate_indices=validate)
+        self.loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+        self.floor = graphs.init_bound(w.gamma, w.ent_dim)
+        self.eps = 1e-10
+        self.stats = {"elements": 0, "needed_allowance": 0, "worst_ratio": 0.0}
+
+    # -- forward only -------------------------------------------------------------------------------------
+    def score_both(self, h, r, t, neg, side):
+        w = self.w
+        b, k = h.shape[0], neg.shape[-1]
+        pos = torch.empty(b, dtype=torch.float32, device="cuda")
+        ng = torch.empty((b, k), dtype=torch.float32, device="cuda")
+        self.ctx.score(self.dE, self.dR, dev(h), dev(r), dev(t), dev(neg.reshape(-1)), k, w.chunk, side, w.gamma,
+                       pos_out=pos, neg_out=ng)
+        torch.cuda.synchronize()
+        opos, oneg = oracle.scores(w.model, self.E, self.R, h, r, t, neg, k, w.chunk, side, w.gamma,
+                                   bf16_inputs=w.bf16_inputs)
+        return pos.cpu().numpy(), ng.cpu().numpy(), opos, oneg
+
+    # -- one step on both sides, no comparison of tables ----------------------------------------------------
+    def step_both(self, h, r, t, neg, side, report=False):
+        w = self.w
+        k = neg.shape[-1]
+        self.ctx.train_step(self.dE, self.dSE, self.dR, self.dSR, dev(h), dev(r), dev(t), dev(neg.reshape(-1)), k,
+                            w.chunk, side, w.gamma, w.lr, loss_out=self.loss)
+        torch.cuda.synchronize()
+        want = oracle.train_step(w.model, self.E, self.SE, self.R, self.SR, h, r, t, neg, k, w.chunk, side, w.gamma,
+                                 w.lr, eps=self.eps, adv_temperature=w.adv_temperature, bf16_inputs=w.bf16_inputs,
+                                 report=report)
+        return float(self.loss.item()), want
+
+    # -- one step from identical tables, every touched element checked, then tables re-synchronised ----------
+    def step_checked(self, h, r, t, neg, side):
+        w = self.w
+        ent_ids = np.unique(np.concatenate([h, t, neg.reshape(-1)]))
+        rel_ids = np.unique(r)
+        S_prev = {"E": self.SE[ent_ids].astype(np.float64), "R": self.SR[rel_ids].astype(np.float64)}
+        got_loss, (want_loss, rep) = self.step_both(h, r, t, neg, side, report=True)
+        assert abs(got_loss - want_loss) <= SCORE_TOL * max(1.0, abs(want_loss)), (got_loss, want_loss)
+        assert np.array_equal(rep["ent_ids"], ent_ids) and np.array_equal(rep["rel_ids"], rel_ids)
+        for name, ids, host, host_s, devt, devs, g, A in (
+                ("E", ent_ids, self.E, self.SE, self.dE, self.dSE, rep["dE"], rep["absE"]),
+                ("R", rel_ids, self.R, self.SR, self.dR, self.dSR, rep["dR"], rep["absR"])):
+            idx = torch.from_numpy(ids).cuda()
+            got = devt[idx].cpu().numpy().astype(np.float64)
+            got_s = devs[idx].cpu().numpy().astype(np.float64)
+            want, want_s = host[ids].astype(np.float64), host_s[ids].astype(np.float64)
+            du, ds = rounding_allowance(g, A, S_prev[name], w.lr, self.eps)
+            base = EMB_TOL * np.maximum(np.abs(want), self.floor)
+            ratio = np.abs(got - want) / (base + du)
+            worst = float(ratio.max())
+            self.stats["elements"] += ratio.size
+            self.stats["needed_allowance"] += int((np.abs(got - want) > base).sum())
+            self.stats["worst_ratio"] = max(self.stats["worst_ratio"], worst)
+            wi = np.unravel_index(np.argmax(ratio), ratio.shape)
+            assert worst <= 1.0, (name, worst, wi, "got", got[wi], "want", want[wi], "g", g[wi], "A", A[wi],
+                                  "S_prev", S_prev[name][wi])
+            s_ratio = np.abs(got_s - want_s) / (1e-5 * want_s + ds + 1e-30)
+            si = np.unravel_index(np.argmax(s_ratio), s_ratio.shape)
+            assert s_ratio.max() <= 1.0, (name + " state", float(s_ratio.max()), si, "got", got_s[si], "want",
+                                          want_s[si], "g", g[si], "A", A[si], "S_prev", S_prev[name][si])
+            # re-synchronise the touched rows so that the next step starts from identical tables
+            devt[idx] = torch.from_numpy(host[ids]).cuda()
+            devs[idx] = torch.from_numpy(host_s[ids]).cuda()
+
+    def table_error_profile(self):
+        """Distribution of the embedding error after free-running steps (no re-synchronisation)."""
+        out = {}
+        for name, d, hst in (("E", self.dE, self.E), ("R", self.dR, self.R)):
+            err = np.abs(d.cpu().numpy().astype(np.float64) - hst) / np.maximum(np.abs(hst), self.floor)
+            out[name] = {"max": float(err.max()), "frac_over_tol": float((err > EMB_TOL).mean()),
+                         "p9999": float(np.quantile(err, 0.9999)), "median_nonzero": float(np.median(err[err > 0]))
+                         if (err > 0).any() else 0.0}
+        return out
+
+    def close(self):
+        self.ctx.close()
