@@ -1,0 +1,207 @@
+"""Benchmark of the KGE training step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--entities N]
+
+One "step" is one whole mini-batch step through the C ABI (gather, positive and chunked negative scoring, loss,
+backward, duplicate reduction, sparse Adagrad) on synthetic inputs that are resident in HBM before the timed
+region starts.  The default workload is the Freebase-scale configuration (86,054,151 entities, 14,824 relations,
+TransE-L2, dim 400, b = 1000, one chunk of 1000, k = 200) with the full entity table and its Adagrad state in HBM.
+Prints ONE JSON line.  The roofline object is for the kernel with the largest share of the step; the per-kernel
+times behind it are measured in this process with HIP events around every kernel (kge_profile) over a second
+pass of the same kind of steps, and all of them are listed under "kernels".
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E
+FP32_MATRIX_PEAK_TFLOPS = 157.3
+BF16_MATRIX_PEAK_TFLOPS = 2500.0
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="freebase-transe_l2")
+    ap.add_argument("--entities", type=int, default=0, help="override the entity count (debugging)")
+    ap.add_argument("--profile-steps", type=int, default=500)
+    ap.add_argument("--cpu-steps", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def algorithmic_work(w, h, r, t, neg):
+    """Per-step algorithmic bytes / flops of every kernel, averaged over the given steps (ids on the host).
+
+    gather : every gathered row read once and every staged row (o_i, corrupting rows) written once
+    update : per distinct row, table and state read and written (4 rows) plus every gradient row read once
+    GEMMs  : 2 b k D flops forward, 4 b k D backward; pair kernels: b k D_c pair-coordinates
+    """
+    n = h.shape[0]
+    D, Dr, b, k, C = w.ent_dim, w.rel_dim, w.batch, w.neg_per_chunk, w.n_chunks
+    ue = np.mean([np.unique(np.concatenate([h[s], t[s], neg[s].reshape(-1)])).size for s in range(n)])
+    ur = np.mean([np.unique(r[s]).size for s in range(n)])
+    n_keys = 2 * b + C * k
+    return {
+        "gather": {"bytes": 4.0 * ((2 * b + C * k) * D + b * Dr) + 4.0 * (b + C * k) * D},
+        "update": {"bytes": ue * 16.0 * D + n_keys * 4.0 * D + ur * 16.0 * Dr + b * 4.0 * Dr},
+        "neg_score": {"flops": 2.0 * b * k * D},
+        "neg_backward": {"flops": 4.0 * b * k * D},
+        "chain": {"bytes": 4.0 * (6 * b * D + 2 * b * Dr)},
+        "loss": {"bytes": 8.0 * b * k},
+        "sort": {"bytes": 8.0 * (n_keys + b)},
+        "unique_entity_rows": float(ue), "unique_relation_rows": float(ur),
+    }
+
+
+def cpu_baseline(w, steps):
+    """The oracle, as it is, on the host: same batch shape, entity table cut down so that it fits and initialises
+    quickly.  Single thread."""
+    import oracle
+    from harness import configs
+
+    n_ent = min(w.n_entities, 1_000_000)
+    wc = w.scaled(n_entities=n_ent)
+    bs = configs.BatchStream(wc, materialise=False)
+    E, R = configs.init_tables(wc)
+    SE, SR = np.zeros_like(E), np.zeros_like(R)
+    batches = [bs.step(s) for s in range(steps)]
+    t0 = time.perf_counter()
+    for h, r, t, neg, side in batches:
+        oracle.train_step(wc.model, E, SE, R, SR, h, r, t, neg, wc.neg_per_chunk, wc.chunk, side, wc.gamma, wc.lr,
+                          adv_temperature=wc.adv_temperature, bf16_inputs=wc.bf16_inputs)
+    dt = time.perf_counter() - t0
+    return {"value": steps * wc.batch / dt, "unit": "triples/s", "cores": 1, "kind": "oracle",
+            "sample": f"{steps} steps of the same batch shape (b={wc.batch}, g={wc.chunk}, k={wc.neg_per_chunk}, "
+                      f"dim={wc.ent_dim}) over a {n_ent:,}-entity table on the host, {dt:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    import paper_2004_08532_amd as kge
+    from harness import configs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda", 0)
+    w = configs.ALL[args.workload]
+    if args.entities:
+        w = w.scaled(n_entities=args.entities, name=w.name + f"-{args.entities}ent")
+    need = 2 * (w.n_entities * w.ent_dim + w.n_relations * w.rel_dim) * 4
+    free, _total = torch.cuda.mem_get_info(dev)
+    if need + (4 << 30) > free:
+        print(f"bench.py: workload {w.name} needs {need / 2**30:.1f} GiB of HBM, {free / 2**30:.1f} GiB free",
+              file=sys.stderr)
+        sys.exit(3)
+
+    K, W, P = args.steps, args.warmup, args.profile_steps
+    t_setup = time.perf_counter()
+    bs = configs.BatchStream(w, materialise=w.n_triples > 0 and w.n_triples <= 50_000_000)
+    h, r, t, neg, sides = bs.steps(0, W + K + P)
+    neg = neg.reshape(neg.shape[0], -1)
+    dh, dr, dt_, dn = (torch.from_numpy(x).to(dev) for x in (h, r, t, neg))
+    E, R = configs.init_tables(w, device=dev)
+    SE, SR = torch.zeros_like(E), torch.zeros_like(R)
+    ctx = kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
+                         max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks, gemm_input=int(w.bf16_inputs),
+                         adv_temperature=w.adv_temperature)
+    losses = torch.zeros(W + K + P, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize(dev)
+    setup_s = time.perf_counter() - t_setup
+
+    def run(lo, hi):
+        ctx.train_steps(E, SE, R, SR, dh[lo:hi], dr[lo:hi], dt_[lo:hi], dn[lo:hi], w.neg_per_chunk, w.chunk,
+                        sides[lo:hi].tolist(), w.gamma, w.lr, loss_out=losses[lo:hi])
+
+    run(0, W)
+    torch.cuda.synchronize(dev)
+    t0 = time.perf_counter()
+    run(W, W + K)
+    torch.cuda.synchronize(dev)
+    elapsed = time.perf_counter() - t0
+
+    # second pass: the same kind of steps with HIP events around every kernel
+    kernels = {}
+    roofline = None
+    if P > 0:
+        ctx.profile(True)
+        run(W + K, W + K + P)
+        ms, nsteps = ctx.profile_read()
+        ctx.profile(False)
+        work = algorithmic_work(w, h[W + K:], r[W + K:], t[W + K:], neg[W + K:])
+        gemm = w.model in ("transe_l2", "distmult", "complex")
+        for name, total_ms in ms.items():
+            avg_us = 1e3 * total_ms / max(nsteps, 1)
+            ent = {"avg_us": avg_us}
+            wk = work.get(name, {})
+            if "bytes" in wk and avg_us > 0:
+                ent.update(bound="hbm", achieved=wk["bytes"] / (avg_us * 1e-6) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s")
+            elif "flops" in wk and avg_us > 0:
+                peak = (BF16_MATRIX_PEAK_TFLOPS if w.bf16_inputs else FP32_MATRIX_PEAK_TFLOPS) if gemm \
+                    else FP32_VECTOR_PEAK_TFLOPS
+                ent.update(bound="mfma" if gemm else "alu", achieved=wk["flops"] / (avg_us * 1e-6) / 1e12, peak=peak,
+                           unit="TFLOP/s")
+            if "achieved" in ent:
+                ent["frac"] = ent["achieved"] / ent["peak"]
+            kernels[name] = ent
+        on_stream = {n: e for n, e in kernels.items() if n != "sort"}  # the sort overlaps on its own stream
+        dom = max(on_stream, key=lambda n: on_stream[n]["avg_us"])
+        d = kernels[dom]
+        roofline = {"kernel": dom, "bound": d.get("bound"), "achieved": d.get("achieved"), "peak": d.get("peak"),
+                    "unit": d.get("unit"), "frac": d.get("frac"), "traffic": None, "avg_us": d["avg_us"],
+                    "unique_entity_rows_per_step": work["unique_entity_rows"],
+                    "unique_relation_rows_per_step": work["unique_relation_rows"]}
+
+    loss_first = float(losses[W].item())
+    loss_last = float(losses[W + K - 1].item())
+    ctx.close()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        del E, SE
+        torch.cuda.empty_cache()
+        cpu = cpu_baseline(w, args.cpu_steps)
+
+    out = {
+        "metric": "positive triples/sec per MI355X at fixed negs",
+        "value": K * w.batch / elapsed,
+        "unit": "triples/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": 1e3 * elapsed / K,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16-in/f32-acc" if w.bf16_inputs else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "model": w.model, "entities": w.n_entities, "relations": w.n_relations,
+                   "dim": w.ent_dim, "batch": w.batch, "chunk": w.chunk, "neg_per_chunk": w.neg_per_chunk,
+                   "table_plus_state_GiB": round(need / 2 ** 30, 2), "setup_s": round(setup_s, 1),
+                   "loss_first": loss_first, "loss_last": loss_last},
+        "roofline": roofline,
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

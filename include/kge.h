@@ -104,6 +104,18 @@ int kge_train_step(kge_ctx* ctx, float* ent, float* ent_state, float* rel, float
                    float gamma, float lr, void* hip_stream, float* loss_out);
 
 /*
+ * n_steps training steps in a row with ids staged on the device beforehand: step s uses h[s*b .. s*b + b - 1]
+ * (r, t likewise) and neg[s*(b/chunk)*k ..].  neg_sides: (host) array of n_steps kge_neg_side values, or NULL for
+ * tail corruption throughout.  loss_out: device float[n_steps] or NULL.  Same result as n_steps calls of
+ * kge_train_step; exists so that a whole pass over pre-sampled mini-batches (Sec. 3.1 step 1 done ahead of time)
+ * costs one call.
+ */
+int kge_train_steps(kge_ctx* ctx, float* ent, float* ent_state, float* rel, float* rel_state,
+                    const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,
+                    const int64_t* neg, int64_t k, int64_t chunk, const int32_t* neg_sides, int64_t n_steps,
+                    float gamma, float lr, void* hip_stream, float* loss_out);
+
+/*
  * Forward only: scores of the positives and of their chunked negatives (Table 1; Sec. 3.3 for the layout).
  * pos_out [b] receives f(h_i, r_i, t_i); neg_out [b*k], row-major with one row per positive, receives
  * f(h_i, r_i, n) (tail side) or f(n, r_i, t_i) (head side) for the k corrupting entities of i's chunk; either
@@ -128,6 +140,28 @@ int kge_get_dedup(kge_ctx* ctx, int32_t which, int64_t* uniq_out, int32_t* count
  * its table (contexts created with validate_indices), else KGE_OK.  Rows with a bad id are skipped by the
  * kernels, never dereferenced. */
 int kge_check_indices(kge_ctx* ctx, void* hip_stream);
+
+/*
+ * Per-kernel timing for measurement (the paper reports where time goes per phase, Sec. 6.1.3; this is the
+ * library's counterpart).  kge_profile(ctx, 1) makes every following kge_train_step / kge_train_steps bracket
+ * each of its kernels with HIP events on the stream the kernel runs on and synchronise that stream after every
+ * step; kge_profile(ctx, 0) restores normal asynchronous operation.  Either call clears the accumulated times.
+ * kge_profile_read: (host) ms_out[KGE_PROF_SLOTS] receives the summed kernel times in milliseconds per slot,
+ * (host) *steps_out the number of steps they cover.  kge_profile_slot_name: (host) static name of a slot.
+ */
+enum {
+    KGE_PROF_GATHER = 0,   /* row gather + positive scores             */
+    KGE_PROF_SCORE = 1,    /* chunked negative scoring                  */
+    KGE_PROF_LOSS = 2,     /* loss and backward coefficients            */
+    KGE_PROF_BACKWARD = 3, /* dL/do and gradient rows of the negatives  */
+    KGE_PROF_CHAIN = 4,    /* chain rule to head / tail / relation rows */
+    KGE_PROF_SORT = 5,     /* (id, position) sort, on its own stream    */
+    KGE_PROF_UPDATE = 6,   /* segment sum + sparse Adagrad              */
+    KGE_PROF_SLOTS = 7
+};
+int kge_profile(kge_ctx* ctx, int32_t enable);
+int kge_profile_read(kge_ctx* ctx, double* ms_out, int64_t* steps_out);
+const char* kge_profile_slot_name(int32_t slot);
 
 /* (host) Text of the last error on this context ("" if none); valid until the next call on the context.
  * kge_last_error(NULL) returns the text of the last failed kge_create on this thread. */

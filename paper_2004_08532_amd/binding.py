@@ -23,8 +23,10 @@ KGE_OK, KGE_ERR_INVALID_ARG, KGE_ERR_UNSUPPORTED, KGE_ERR_WORKSPACE, KGE_ERR_DEV
 MODEL_IDS = {"transe_l2": KGE_TRANSE_L2, "transe_l1": KGE_TRANSE_L1, "distmult": KGE_DISTMULT,
              "complex": KGE_COMPLEX, "rotate": KGE_ROTATE}
 
-EXPORTS = ("kge_create", "kge_destroy", "kge_train_step", "kge_score", "kge_get_dedup", "kge_check_indices",
-           "kge_last_error", "kge_workspace_bytes")
+EXPORTS = ("kge_create", "kge_destroy", "kge_train_step", "kge_train_steps", "kge_score", "kge_get_dedup",
+           "kge_check_indices", "kge_last_error", "kge_workspace_bytes", "kge_profile", "kge_profile_read",
+           "kge_profile_slot_name")
+KGE_PROF_SLOTS = 7
 
 
 class kge_config(ctypes.Structure):
@@ -45,8 +47,11 @@ class KgeError(RuntimeError):
 
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
-        from . import build as _build
-        _build.build(verbose=False)
+        import importlib.util
+        spec = importlib.util.spec_from_file_location("_kge_build", os.path.join(_HERE, "csrc", "build.py"))
+        mod = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(mod)
+        mod.build(verbose=False)
     lib = ctypes.CDLL(LIB_PATH)
     vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_float
     lib.kge_create.restype = ctypes.c_int
@@ -55,6 +60,14 @@ def _load() -> ctypes.CDLL:
     lib.kge_destroy.argtypes = [vp]
     lib.kge_train_step.restype = ctypes.c_int
     lib.kge_train_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, i32, f32, f32, vp, vp]
+    lib.kge_train_steps.restype = ctypes.c_int
+    lib.kge_train_steps.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, vp, i64, f32, f32, vp, vp]
+    lib.kge_profile.restype = ctypes.c_int
+    lib.kge_profile.argtypes = [vp, i32]
+    lib.kge_profile_read.restype = ctypes.c_int
+    lib.kge_profile_read.argtypes = [vp, vp, vp]
+    lib.kge_profile_slot_name.restype = ctypes.c_char_p
+    lib.kge_profile_slot_name.argtypes = [i32]
     lib.kge_score.restype = ctypes.c_int
     lib.kge_score.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, i32, f32, vp, vp, vp]
     lib.kge_get_dedup.restype = ctypes.c_int
@@ -116,6 +129,37 @@ def kge_train_step(ctx, ent, ent_state, rel, rel_state, h, r, t, b, neg, k, chun
     _check(ctx, rc)
 
 
+def kge_train_steps(ctx, ent, ent_state, rel, rel_state, h, r, t, b, neg, k, chunk, neg_sides, n_steps, gamma, lr,
+                    hip_stream=None, loss_out=None) -> None:
+    """h, r, t: device int64 [n_steps, b]; neg: device int64 [n_steps, (b/chunk)*k]; neg_sides: host sequence or None."""
+    f, i = torch.float32, torch.int64
+    sides = None
+    if neg_sides is not None:
+        sides = (ctypes.c_int32 * int(n_steps))(*[int(x) for x in neg_sides])
+    rc = _lib.kge_train_steps(ctx, _dev_ptr(ent, f, "ent"), _dev_ptr(ent_state, f, "ent_state"),
+                              _dev_ptr(rel, f, "rel"), _dev_ptr(rel_state, f, "rel_state"),
+                              _dev_ptr(h, i, "h"), _dev_ptr(r, i, "r"), _dev_ptr(t, i, "t"), int(b),
+                              _dev_ptr(neg, i, "neg"), int(k), int(chunk), sides, int(n_steps), float(gamma),
+                              float(lr), _stream(hip_stream), _dev_ptr(loss_out, f, "loss_out"))
+    _check(ctx, rc)
+
+
+def kge_profile(ctx, enable) -> None:
+    _check(ctx, _lib.kge_profile(ctx, int(bool(enable))))
+
+
+def kge_profile_read(ctx):
+    """Returns ({slot name: summed kernel milliseconds}, steps covered)."""
+    ms = (ctypes.c_double * KGE_PROF_SLOTS)()
+    steps = ctypes.c_int64(0)
+    _check(ctx, _lib.kge_profile_read(ctx, ms, ctypes.byref(steps)))
+    return {kge_profile_slot_name(s): ms[s] for s in range(KGE_PROF_SLOTS)}, int(steps.value)
+
+
+def kge_profile_slot_name(slot) -> str:
+    return _lib.kge_profile_slot_name(int(slot)).decode()
+
+
 def kge_score(ctx, ent, rel, h, r, t, b, neg, k, chunk, neg_side, gamma, hip_stream=None, pos_out=None,
               neg_out=None) -> None:
     f, i = torch.float32, torch.int64
@@ -166,6 +210,17 @@ class KgeContext:
                    stream=None):
         kge_train_step(self.ctx, ent, ent_state, rel, rel_state, h, r, t, h.numel(), neg, k, chunk, neg_side, gamma,
                        lr, stream, loss_out)
+
+    def train_steps(self, ent, ent_state, rel, rel_state, h, r, t, neg, k, chunk, neg_sides, gamma, lr, loss_out=None,
+                    stream=None):
+        kge_train_steps(self.ctx, ent, ent_state, rel, rel_state, h, r, t, h.shape[1], neg, k, chunk, neg_sides,
+                        h.shape[0], gamma, lr, stream, loss_out)
+
+    def profile(self, enable):
+        kge_profile(self.ctx, enable)
+
+    def profile_read(self):
+        return kge_profile_read(self.ctx)
 
     def score(self, ent, rel, h, r, t, neg, k, chunk, neg_side, gamma, pos_out=None, neg_out=None, stream=None):
         kge_score(self.ctx, ent, rel, h, r, t, h.numel(), neg, k, chunk, neg_side, gamma, stream, pos_out, neg_out)

@@ -1,4 +1,7 @@
-"""Builds libkge.so (HIP, gfx950 only) next to this file.  Usage: python -m paper_2004_08532_amd.build"""
+"""Builds libkge.so (HIP, gfx950 only) into the package directory.
+
+Run as a file (python paper_2004_08532_amd/csrc/build.py) or load with importlib: it must not be imported through
+the package, whose __init__ loads the library this script produces."""
 from __future__ import annotations
 
 import concurrent.futures
@@ -7,10 +10,10 @@ import os
 import subprocess
 import sys
 
-HERE = os.path.dirname(os.path.abspath(__file__))
-ROOT = os.path.dirname(HERE)
-CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "libkge.so")
+CSRC = os.path.dirname(os.path.abspath(__file__))
+PKG = os.path.dirname(CSRC)
+ROOT = os.path.dirname(PKG)
+LIB = os.path.join(PKG, "libkge.so")
 BUILD_DIR = os.path.join(ROOT, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

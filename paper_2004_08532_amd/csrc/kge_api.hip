@@ -64,6 +64,76 @@ void forward(kge_ctx* c, const float* ent, const float* rel, const int64_t* h, c
     }
 }
 
+// ---- optional per-kernel timing (kge_profile): every kernel of a step is bracketed by events on the stream it
+// runs on, the stream is synchronised after the step, and the elapsed times are accumulated per slot.
+struct ProfScope {
+    kge_ctx* c;
+    int slot;
+    hipStream_t st;
+    ProfScope(kge_ctx* c_, int slot_, hipStream_t st_) : c(c_), slot(slot_), st(st_) {
+        if (c->prof_on) (void)hipEventRecord(c->prof_ev[slot][0], st);
+    }
+    ~ProfScope() {
+        if (c->prof_on) (void)hipEventRecord(c->prof_ev[slot][1], st);
+    }
+};
+
+int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state, const int64_t* h,
+                 const int64_t* r, const int64_t* t, int B, const int64_t* neg, int K, int G, int side, float gamma,
+                 float lr, hipStream_t st, float* loss_out) {
+    const int n_neg = (B / G) * K;
+    // the key sort needs only the ids: it runs beside the forward/backward kernels and joins before the update
+    KGE_HIP(c, hipEventRecord(c->ev_fork, st));
+    KGE_HIP(c, hipStreamWaitEvent(c->side_stream, c->ev_fork, 0));
+    {
+        ProfScope p(c, KGE_PROF_SORT, c->side_stream);
+        kge_launch_sort(c, h, r, t, B, neg, n_neg, c->side_stream);
+    }
+    KGE_HIP(c, hipEventRecord(c->ev_join, c->side_stream));
+    if (c->cfg.validate_indices) {
+        const int n = B > n_neg ? B : n_neg;
+        hipLaunchKernelGGL(k_validate, dim3((n + 255) / 256), dim3(256), 0, st, h, r, t, B, neg, n_neg,
+                           c->cfg.num_entities, c->cfg.num_relations, c->flags);
+    }
+    {
+        ProfScope p(c, KGE_PROF_GATHER, st);
+        kge_launch_gather(c, ent, rel, h, r, t, B, neg, n_neg, side, gamma, nullptr, st);
+    }
+    {
+        ProfScope p(c, KGE_PROF_SCORE, st);
+        if (is_gemm_model(c->cfg.model)) kge_gemm_neg_score(c, B, K, G, gamma, c->S, c->ld_s, 1, st);
+        else kge_pair_neg_score(c, B, K, G, gamma, c->S, c->ld_s, st);
+    }
+    {
+        ProfScope p(c, KGE_PROF_LOSS, st);
+        kge_launch_loss(c, B, K, gamma, st);
+    }
+    {
+        ProfScope p(c, KGE_PROF_BACKWARD, st);
+        if (is_gemm_model(c->cfg.model)) kge_gemm_neg_backward(c, B, K, G, st);
+        else kge_pair_neg_backward(c, B, K, G, st);
+    }
+    {
+        ProfScope p(c, KGE_PROF_CHAIN, st);
+        kge_launch_chain(c, ent, rel, h, r, t, B, side, gamma, st);
+    }
+    KGE_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
+    {
+        ProfScope p(c, KGE_PROF_UPDATE, st);
+        kge_launch_update(c, ent, ent_state, rel, rel_state, 2 * B + n_neg, B, lr, B, loss_out, st);
+    }
+    KGE_HIP(c, hipGetLastError());
+    if (c->prof_on) {
+        KGE_HIP(c, hipStreamSynchronize(st));
+        for (int s = 0; s < KGE_PROF_SLOTS; ++s) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, c->prof_ev[s][0], c->prof_ev[s][1]) == hipSuccess) c->prof_ms[s] += ms;
+        }
+        c->prof_steps += 1;
+    }
+    return KGE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -154,6 +224,9 @@ void kge_destroy(kge_ctx* c) {
     if (c->side_stream) { (void)hipStreamSynchronize(c->side_stream); (void)hipStreamDestroy(c->side_stream); }
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    for (int s = 0; s < KGE_PROF_SLOTS; ++s)
+        for (int e = 0; e < 2; ++e)
+            if (c->prof_ev[s][e]) (void)hipEventDestroy(c->prof_ev[s][e]);
     if (c->ws_base) (void)hipFree(c->ws_base);
     delete c;
 }
@@ -168,23 +241,31 @@ int kge_train_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* 
     const int rc = check_batch(c, ent, rel, h, r, t, b, neg, k, chunk, neg_side, true);
     if (rc != KGE_OK) return rc;
     KGE_HIP(c, hipSetDevice(c->cfg.device));
-    hipStream_t st = (hipStream_t)hip_stream;
-    const int B = (int)b, K = (int)k, G = (int)chunk, n_neg = (B / G) * K;
+    return enqueue_step(c, ent, ent_state, rel, rel_state, h, r, t, (int)b, neg, (int)k, (int)chunk, neg_side, gamma,
+                        lr, (hipStream_t)hip_stream, loss_out);
+}
 
-    // the key sort needs only the ids: it runs beside the forward/backward kernels and joins before the update
-    KGE_HIP(c, hipEventRecord(c->ev_fork, st));
-    KGE_HIP(c, hipStreamWaitEvent(c->side_stream, c->ev_fork, 0));
-    kge_launch_sort(c, h, r, t, B, neg, n_neg, c->side_stream);
-    KGE_HIP(c, hipEventRecord(c->ev_join, c->side_stream));
-
-    forward(c, ent, rel, h, r, t, B, neg, K, G, neg_side, gamma, nullptr, c->S, c->ld_s, 1, st);
-    kge_launch_loss(c, B, K, gamma, st);
-    if (is_gemm_model(c->cfg.model)) kge_gemm_neg_backward(c, B, K, G, st);
-    else kge_pair_neg_backward(c, B, K, G, st);
-    kge_launch_chain(c, ent, rel, h, r, t, B, neg_side, gamma, st);
-    KGE_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
-    kge_launch_update(c, ent, ent_state, rel, rel_state, 2 * B + n_neg, B, lr, B, loss_out, st);
-    KGE_HIP(c, hipGetLastError());
+int kge_train_steps(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state,
+                    const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,
+                    const int64_t* neg, int64_t k, int64_t chunk, const int32_t* neg_sides, int64_t n_steps,
+                    float gamma, float lr, void* hip_stream, float* loss_out) {
+    if (!c) return KGE_ERR_INVALID_ARG;
+    c->err[0] = 0;
+    if (!ent_state || !rel_state) return fail(c, KGE_ERR_INVALID_ARG, "null optimizer state%s");
+    if (n_steps < 0) return fail(c, KGE_ERR_INVALID_ARG, "negative step count%s");
+    int rc = check_batch(c, ent, rel, h, r, t, b, neg, k, chunk, KGE_NEG_TAIL, true);
+    if (rc != KGE_OK) return rc;
+    for (int64_t s = 0; neg_sides && s < n_steps; ++s)
+        if (neg_sides[s] != KGE_NEG_TAIL && neg_sides[s] != KGE_NEG_HEAD)
+            return fail(c, KGE_ERR_INVALID_ARG, "neg_sides entries must be 0 or 1%s");
+    KGE_HIP(c, hipSetDevice(c->cfg.device));
+    const int64_t n_neg = (b / chunk) * k;
+    for (int64_t s = 0; s < n_steps; ++s) {
+        rc = enqueue_step(c, ent, ent_state, rel, rel_state, h + s * b, r + s * b, t + s * b, (int)b, neg + s * n_neg,
+                          (int)k, (int)chunk, neg_sides ? neg_sides[s] : KGE_NEG_TAIL, gamma, lr,
+                          (hipStream_t)hip_stream, loss_out ? loss_out + s : nullptr);
+        if (rc != KGE_OK) return rc;
+    }
     return KGE_OK;
 }
 
@@ -231,6 +312,32 @@ int kge_check_indices(kge_ctx* c, void* hip_stream) {
         return fail(c, KGE_ERR_INDEX_RANGE, "an id was outside its table%s");
     }
     return KGE_OK;
+}
+
+int kge_profile(kge_ctx* c, int32_t enable) {
+    if (!c) return KGE_ERR_INVALID_ARG;
+    c->err[0] = 0;
+    KGE_HIP(c, hipSetDevice(c->cfg.device));
+    if (enable && !c->prof_ev[0][0]) {
+        for (int s = 0; s < KGE_PROF_SLOTS; ++s)
+            for (int e = 0; e < 2; ++e) KGE_HIP(c, hipEventCreate(&c->prof_ev[s][e]));
+    }
+    c->prof_on = enable != 0;
+    for (int s = 0; s < KGE_PROF_SLOTS; ++s) c->prof_ms[s] = 0.0;
+    c->prof_steps = 0;
+    return KGE_OK;
+}
+
+int kge_profile_read(kge_ctx* c, double* ms_out, int64_t* steps_out) {
+    if (!c || !ms_out || !steps_out) return KGE_ERR_INVALID_ARG;
+    for (int s = 0; s < KGE_PROF_SLOTS; ++s) ms_out[s] = c->prof_ms[s];
+    *steps_out = c->prof_steps;
+    return KGE_OK;
+}
+
+const char* kge_profile_slot_name(int32_t slot) {
+    static const char* names[KGE_PROF_SLOTS] = {"gather", "neg_score", "loss", "neg_backward", "chain", "sort", "update"};
+    return slot >= 0 && slot < KGE_PROF_SLOTS ? names[slot] : "";
 }
 
 const char* kge_last_error(const kge_ctx* c) { return c ? c->err : g_create_err; }

@@ -50,6 +50,10 @@ struct kge_ctx {
     int64_t last_ent_keys, last_rel_keys;  // sizes of the last train step's key lists (0: none yet)
     hipStream_t side_stream;        // runs the key sort beside the forward/backward kernels
     hipEvent_t ev_fork, ev_join;
+    bool prof_on;                   // kge_profile: bracket every kernel with events
+    hipEvent_t prof_ev[KGE_PROF_SLOTS][2];
+    double prof_ms[KGE_PROF_SLOTS];
+    int64_t prof_steps;
     char err[512];
 };
 
