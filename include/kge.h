@@ -108,7 +108,10 @@ int kge_train_step(kge_ctx* ctx, float* ent, float* ent_state, float* rel, float
  * (r, t likewise) and neg[s*(b/chunk)*k ..].  neg_sides: (host) array of n_steps kge_neg_side values, or NULL for
  * tail corruption throughout.  loss_out: device float[n_steps] or NULL.  Same result as n_steps calls of
  * kge_train_step; exists so that a whole pass over pre-sampled mini-batches (Sec. 3.1 step 1 done ahead of time)
- * costs one call.
+ * costs one call.  On a stream that can be captured (any stream but the legacy default stream) the steps are
+ * replayed from HIP graphs that the context builds on the first call and keeps for later calls with the same
+ * arguments; such a call may allocate (graph objects, the per-step side array) and must not itself be made
+ * while the stream is being captured by the caller (then, and on the default stream, it launches kernel by kernel).
  */
 int kge_train_steps(kge_ctx* ctx, float* ent, float* ent_state, float* rel, float* rel_state,
                     const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,

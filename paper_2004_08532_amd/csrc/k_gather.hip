@@ -6,6 +6,8 @@
 // scores the positive pair psi(o_i, c_i) (Table 1) with a shuffle reduction, and writes o_i once into the
 // dense staging array that the chunked negative scoring reads.  Waves past the positives copy the k
 // corrupting rows of every chunk into staging (the O(bkd/g) rows of Sec. 3.3) and compute |n|^2 for TransE-L2.
+// In a training step the same launch carries extra blocks that bring the step's key lists into (id, position)
+// order for the duplicate reduction (rank_block below): that work needs only the ids, so it rides along here.
 #include "kge_common.h"
 
 namespace {
@@ -13,11 +15,8 @@ namespace {
 struct GatherArgs {
     const float* E;
     const float* R;
-    const int64_t* h;
-    const int64_t* r;
-    const int64_t* t;
-    const int64_t* neg;
-    int b, n_neg, D, Dr, side, bf16;
+    StepIds ids;
+    int b, n_neg, D, Dr, bf16;
     float gamma;
     int64_t n_ent, n_rel;
     float* O;
@@ -28,7 +27,56 @@ struct GatherArgs {
     float* n_n2;
     uint16_t* Obf;
     uint16_t* Nbf;
+    int gather_blocks;       // blocks [0, gather_blocks) gather rows
+    int ent_rank_blocks;     // the next ent_rank_blocks blocks order the entity key list, the rest the relation keys
+    KeyList ent, rel;
 };
+
+constexpr int RANK_ITEMS = 8;  // keys ranked per block: 8 keys x 32 threads
+
+// Orders a key list by brute-force ranking: rank(i) = #{j : key_j < key_i} + #{j < i : key_j == key_i}.  The lists
+// are a few thousand keys, so the n^2 comparisons, spread over n/8 blocks that run beside the gather blocks of the
+// same launch, cost less than one pass of a single-workgroup sort, need no other kernel and no other stream, and
+// give exactly the order a stable sort by id would (equal ids in position order).  Every block holds the whole
+// list in LDS; 32 threads share one key and each scans every 32nd entry.
+__device__ __forceinline__ void rank_block(const KeyList& l, int blk, uint32_t* keys) {
+    const int tid = threadIdx.x, n = l.n;
+    const int n4 = (n + 3) & ~3;  // the tail is padded with 0xffffffff, which is larger than any id
+    // 16 independent loads per thread are issued before the first is used: one round of memory latency per 4096 keys
+    const int64_t step = l.step_ptr ? *l.step_ptr : 0;
+    for (int base = 0; base < n4; base += 16 * 256) {
+        int64_t raw[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int i = base + u * 256 + tid;
+            raw[u] = *key_address(l, step, i < n ? i : 0);  // unconditional: all 16 loads go out together
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int i = base + u * 256 + tid;
+            if (i < n4) keys[i] = i < n ? clamp_key(l, raw[u]) : 0xffffffffu;
+        }
+    }
+    __syncthreads();
+    const int item = blk * RANK_ITEMS + (tid >> 5), t = tid & 31;
+    if (item >= n) return;
+    const uint32_t ki = keys[item];
+    int cnt = 0;
+#pragma unroll 4
+    for (int j = 4 * t; j < n4; j += 128) {
+        const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
+        cnt += (kj.x < ki || (kj.x == ki && j < item)) ? 1 : 0;
+        cnt += (kj.y < ki || (kj.y == ki && j + 1 < item)) ? 1 : 0;
+        cnt += (kj.z < ki || (kj.z == ki && j + 2 < item)) ? 1 : 0;
+        cnt += (kj.w < ki || (kj.w == ki && j + 3 < item)) ? 1 : 0;
+    }
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 32);
+    if (t == 0) {
+        l.key[0][cnt] = ki;
+        l.pos[0][cnt] = (uint32_t)item;
+    }
+}
 
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
 
@@ -43,6 +91,13 @@ __device__ __forceinline__ void store_bf16x4(uint16_t* dst, const float* v, floa
 // NV = 16-byte vectors per lane: ceil(D/4/64) for the real models, ceil(D/8/64) (re, im) pairs for the complex ones.
 template <int MODEL, int NV>
 __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
+    extern __shared__ uint32_t rank_keys[];
+    if ((int)blockIdx.x >= a.gather_blocks) {
+        const int rb = blockIdx.x - a.gather_blocks;
+        if (rb < a.ent_rank_blocks) rank_block(a.ent, rb, rank_keys);
+        else rank_block(a.rel, rb - a.ent_rank_blocks, rank_keys);
+        return;
+    }
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int D = a.D;
@@ -51,10 +106,11 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
     const int im_off = D / 2;                // float offset of the imaginary half
 
     if (row >= a.b + a.n_neg) return;
+    const StepView sv = step_view(a.ids);
 
     if (row >= a.b) {  // ---- a corrupting row: copy it to staging
         const int j = row - a.b;
-        const int64_t id = clamp_id(a.neg[j], a.n_ent);
+        const int64_t id = clamp_id(sv.neg[j], a.n_ent);
         const float* src = a.E + id * (int64_t)D;
         float* dst = a.Nst + (int64_t)j * D;
         float nn = 0.f;
@@ -84,9 +140,9 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
 
     // ---- a positive: rows a (kept entity), r, c (the entity that the negatives replace)
     const int i = row;
-    const int64_t hid = clamp_id(a.h[i], a.n_ent), tid = clamp_id(a.t[i], a.n_ent);
-    const int64_t rid = clamp_id(a.r[i], a.n_rel);
-    const bool head = a.side == KGE_NEG_HEAD;
+    const int64_t hid = clamp_id(sv.h[i], a.n_ent), tid = clamp_id(sv.t[i], a.n_ent);
+    const int64_t rid = clamp_id(sv.r[i], a.n_rel);
+    const bool head = sv.side == KGE_NEG_HEAD;
     const float* pa = a.E + (head ? tid : hid) * (int64_t)D;
     const float* pc = a.E + (head ? hid : tid) * (int64_t)D;
     const float* pr = a.R + rid * (int64_t)a.Dr;
@@ -172,23 +228,23 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
 }
 
 template <int MODEL>
-void launch_nv(const GatherArgs& a, int nv, dim3 grid, hipStream_t st) {
+void launch_nv(const GatherArgs& a, int nv, dim3 grid, size_t lds, hipStream_t st) {
     switch (nv) {
-    case 1: hipLaunchKernelGGL((k_gather<MODEL, 1>), grid, dim3(256), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((k_gather<MODEL, 2>), grid, dim3(256), 0, st, a); break;
-    case 3: hipLaunchKernelGGL((k_gather<MODEL, 3>), grid, dim3(256), 0, st, a); break;
-    default: hipLaunchKernelGGL((k_gather<MODEL, 4>), grid, dim3(256), 0, st, a); break;
+    case 1: hipLaunchKernelGGL((k_gather<MODEL, 1>), grid, dim3(256), lds, st, a); break;
+    case 2: hipLaunchKernelGGL((k_gather<MODEL, 2>), grid, dim3(256), lds, st, a); break;
+    case 3: hipLaunchKernelGGL((k_gather<MODEL, 3>), grid, dim3(256), lds, st, a); break;
+    default: hipLaunchKernelGGL((k_gather<MODEL, 4>), grid, dim3(256), lds, st, a); break;
     }
 }
 
 }  // namespace
 
-void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const int64_t* h, const int64_t* r,
-                       const int64_t* t, int b, const int64_t* neg, int n_neg, int side, float gamma,
-                       float* pos_out, hipStream_t st) {
+void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds& ids, float gamma, float* pos_out,
+                       bool with_keys, hipStream_t st) {
     GatherArgs a;
-    a.E = E; a.R = R; a.h = h; a.r = r; a.t = t; a.neg = neg;
-    a.b = b; a.n_neg = n_neg; a.D = c->cfg.ent_dim; a.Dr = c->cfg.rel_dim; a.side = side;
+    const int b = ids.b, n_neg = ids.n_neg;
+    a.E = E; a.R = R; a.ids = ids;
+    a.b = b; a.n_neg = n_neg; a.D = c->cfg.ent_dim; a.Dr = c->cfg.rel_dim;
     a.bf16 = c->cfg.gemm_input;
     a.gamma = gamma; a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
     a.O = c->O; a.Nst = c->Nst; a.fpos = c->fpos; a.pos_out = pos_out; a.o_n2 = c->o_n2; a.n_n2 = c->n_n2;
@@ -197,12 +253,24 @@ void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const int64_t
     const bool cplx = model == KGE_COMPLEX || model == KGE_ROTATE;
     const int nvec = cplx ? a.D / 8 : a.D / 4;
     const int nv = (nvec + 63) / 64;
-    const dim3 grid((b + n_neg + 3) / 4);
+    a.gather_blocks = (b + n_neg + 3) / 4;
+    a.ent_rank_blocks = 0;
+    int rank_blocks = 0;
+    size_t lds = 0;
+    if (with_keys) {
+        kge_make_key_lists(c, ids, &a.ent, &a.rel);
+        a.ent_rank_blocks = (a.ent.n + RANK_ITEMS - 1) / RANK_ITEMS;
+        rank_blocks = a.ent_rank_blocks + (a.rel.n + RANK_ITEMS - 1) / RANK_ITEMS;
+        lds = sizeof(uint32_t) * (size_t)((a.ent.n + 3) & ~3);  // the entity list is the longer one
+        c->ebuf = 0;
+        c->rbuf = 0;
+    }
+    const dim3 grid(a.gather_blocks + rank_blocks);
     switch (model) {
-    case KGE_TRANSE_L2: launch_nv<KGE_TRANSE_L2>(a, nv, grid, st); break;
-    case KGE_TRANSE_L1: launch_nv<KGE_TRANSE_L1>(a, nv, grid, st); break;
-    case KGE_DISTMULT: launch_nv<KGE_DISTMULT>(a, nv, grid, st); break;
-    case KGE_COMPLEX: launch_nv<KGE_COMPLEX>(a, nv, grid, st); break;
-    default: launch_nv<KGE_ROTATE>(a, nv, grid, st); break;
+    case KGE_TRANSE_L2: launch_nv<KGE_TRANSE_L2>(a, nv, grid, lds, st); break;
+    case KGE_TRANSE_L1: launch_nv<KGE_TRANSE_L1>(a, nv, grid, lds, st); break;
+    case KGE_DISTMULT: launch_nv<KGE_DISTMULT>(a, nv, grid, lds, st); break;
+    case KGE_COMPLEX: launch_nv<KGE_COMPLEX>(a, nv, grid, lds, st); break;
+    default: launch_nv<KGE_ROTATE>(a, nv, grid, lds, st); break;
     }
 }

@@ -39,42 +39,84 @@ struct GemmArgs {
     int64_t sX;
     float gamma;
     int store_dist;      // EPI_L2_FWD: store the distance instead of gamma - distance
+    int gx, gy, tiles;   // tiles along N, along M, and in total (over all chunks); set by launch()
 };
 
 constexpr int TILE = 32;
 constexpr int KC_PITCH = 36;                 // floats; 16-byte aligned rows, conflict-free 128-bit reads
 constexpr int REGION = TILE * KC_PITCH;      // floats per staged operand block
 
-// Load one 32x32 block of an operand into registers (zero-filled outside the matrix).
+// Loads 32x32 blocks of one operand into registers (zero-filled outside the matrix).  The per-lane row pointers
+// and edge masks are set up once; a block load is then four 16-byte loads and a few selects.
 // KC: element (row, kk) at base[(r0 + row) * ld + k0 + kk]; lane covers row = lane/8 + 8*it, kk = 4*(lane%8)..+3
 // MC: element (row, kk) at base[(k0 + kk) * ld + r0 + row]; lane covers kk = lane/8 + 8*it, row = 4*(lane%8)..+3
 template <bool KC>
-__device__ __forceinline__ void gload(const float* base, int ld, int r0, int rows, int k0, int K, int lane, float4 (&reg)[4]) {
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int major = (lane >> 3) + 8 * it;
-        const int minor = 4 * (lane & 7);
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+struct BlockLoader {
+    const float* p[4];  // KC: start of the lane's row; MC: row (lane/8 + 8*it) of K-block 0 at the lane's column
+    bool ok[4];         // KC: the lane's row exists; MC: unused
+    const float* p0_safe;  // an address that is always valid to read 16 bytes from
+    int minor, major0, ld, K;
+    bool m1, m2, m3, any;  // MC: which of the lane's 4 consecutive rows exist
+    __device__ __forceinline__ void init(const float* base, int ld_, int r0, int rows, int K_, int lane) {
+        minor = 4 * (lane & 7);
+        major0 = lane >> 3;
+        ld = ld_;
+        K = K_;
+        p0_safe = base;
         if (KC) {
-            const int gr = r0 + major, gk = k0 + minor;
-            if (gr < rows && gk < K) {
-                v = ld4(base + (int64_t)gr * ld + gk);
-                if (gk + 1 >= K) v.y = 0.f;
-                if (gk + 2 >= K) v.z = 0.f;
-                if (gk + 3 >= K) v.w = 0.f;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const int gr = r0 + major0 + 8 * it;
+                ok[it] = gr < rows;
+                p[it] = base + (int64_t)(ok[it] ? gr : 0) * ld;  // start of the row: always readable
             }
+            any = true; m1 = m2 = m3 = true;
         } else {
-            const int gk = k0 + major, gr = r0 + minor;
-            if (gk < K && gr < rows) {
-                v = ld4(base + (int64_t)gk * ld + gr);
-                if (gr + 1 >= rows) v.y = 0.f;
-                if (gr + 2 >= rows) v.z = 0.f;
-                if (gr + 3 >= rows) v.w = 0.f;
+            const int gr = r0 + minor;
+            any = gr < rows; m1 = gr + 1 < rows; m2 = gr + 2 < rows; m3 = gr + 3 < rows;
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                ok[it] = true;
+                p[it] = base + (int64_t)(major0 + 8 * it) * ld + (any ? gr : 0);
             }
         }
-        reg[it] = v;
     }
-}
+    // Branch-free: the four loads are issued unconditionally (from a clamped, always valid address) and masked
+    // afterwards, so that all of them, and those of the other operand, are in flight together.
+    __device__ __forceinline__ void load(int kb, float4 (&reg)[4]) const {
+        const int k0 = kb * 32;
+        if (KC) {
+            const int gk = k0 + minor;
+            const bool kin = gk < K;
+            const int koff = kin ? gk : 0;  // the first 16 bytes of a row are always there
+#pragma unroll
+            for (int it = 0; it < 4; ++it) reg[it] = ld4(p[it] + koff);
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const bool v0 = ok[it] && kin;
+                reg[it].x = v0 ? reg[it].x : 0.f;
+                reg[it].y = (v0 && gk + 1 < K) ? reg[it].y : 0.f;
+                reg[it].z = (v0 && gk + 2 < K) ? reg[it].z : 0.f;
+                reg[it].w = (v0 && gk + 3 < K) ? reg[it].w : 0.f;
+            }
+        } else {
+            bool kin[4];
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                kin[it] = k0 + major0 + 8 * it < K;
+                reg[it] = ld4(kin[it] ? p[it] + (int64_t)k0 * ld : p0_safe);
+            }
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {
+                const bool v0 = any && kin[it];
+                reg[it].x = v0 ? reg[it].x : 0.f;
+                reg[it].y = (v0 && m1) ? reg[it].y : 0.f;
+                reg[it].z = (v0 && m2) ? reg[it].z : 0.f;
+                reg[it].w = (v0 && m3) ? reg[it].w : 0.f;
+            }
+        }
+    }
+};
 
 template <bool KC>
 __device__ __forceinline__ void lds_store(float* region, int lane, const float4 (&reg)[4]) {
@@ -103,7 +145,13 @@ template <int NW, bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(NW * 64) void k_gemm_f32(GemmArgs g) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int n0 = blockIdx.x * TILE, m0 = blockIdx.y * TILE, c = blockIdx.z;
+    // Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Give each XCD
+    // a contiguous range of tiles (row-major, column tiles fastest) so that the tiles that share an A row-block
+    // run on one XCD and re-read it from that L2 instead of from memory.
+    const int per_xcd = gridDim.x >> 3;
+    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= g.tiles) return;
+    const int n0 = (tile % g.gx) * TILE, m0 = ((tile / g.gx) % g.gy) * TILE, c = tile / (g.gx * g.gy);
     const float* A = g.A + c * g.sA;
     const float* B = g.B + c * g.sB;
     float* As = lds[w][0];
@@ -116,18 +164,22 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_f32(GemmArgs g) {
 
     const int nblk = (g.K + TILE - 1) / TILE;
     float4 ra[4], rb[4];
+    BlockLoader<A_KC> la;
+    BlockLoader<B_KC> lb;
+    la.init(A, g.lda, m0, g.M, g.K, lane);
+    lb.init(B, g.ldb, n0, g.N, g.K, lane);
     int kb = w;
     if (kb < nblk) {
-        gload<A_KC>(A, g.lda, m0, g.M, kb * TILE, g.K, lane, ra);
-        gload<B_KC>(B, g.ldb, n0, g.N, kb * TILE, g.K, lane, rb);
+        la.load(kb, ra);
+        lb.load(kb, rb);
     }
     while (kb < nblk) {
         lds_store<A_KC>(As, lane, ra);
         lds_store<B_KC>(Bs, lane, rb);
         const int nxt = kb + NW;
         if (nxt < nblk) {  // next block's global loads fly while this block is multiplied
-            gload<A_KC>(A, g.lda, m0, g.M, nxt * TILE, g.K, lane, ra);
-            gload<B_KC>(B, g.ldb, n0, g.N, nxt * TILE, g.K, lane, rb);
+            la.load(nxt, ra);
+            lb.load(nxt, rb);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -184,19 +236,23 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_f32(GemmArgs g) {
     }
 }
 
-// Number of K-splitting waves: enough waves in flight to cover the chip when there are few tiles, never more
-// than there are K-blocks.
+// Number of K-splitting waves per tile.  With few tiles every K-block gets its own wave (one round of memory
+// latency, all SIMDs of the CU busy); with thousands of tiles four waves per tile keep the cross-wave sum cheap.
 int pick_nw(int tiles, int nblk) {
+    if (tiles >= 1024) return 4;
     int nw = 4;
-    while (nw < 16 && tiles * nw < 2048 && nw * 2 <= nblk) nw *= 2;
+    while (nw < 16 && nw < nblk) nw *= 2;
     return nw;
 }
 
 template <bool A_KC, bool B_KC, int EPI>
-void launch(const GemmArgs& g, int chunks, hipStream_t st) {
-    const dim3 grid((g.N + TILE - 1) / TILE, (g.M + TILE - 1) / TILE, chunks);
+void launch(GemmArgs g, int chunks, hipStream_t st) {
+    g.gx = (g.N + TILE - 1) / TILE;
+    g.gy = (g.M + TILE - 1) / TILE;
+    g.tiles = g.gx * g.gy * chunks;
+    const dim3 grid(8 * ((g.tiles + 7) / 8));
     const int nblk = (g.K + TILE - 1) / TILE;
-    const int nw = pick_nw(grid.x * grid.y * grid.z, nblk);
+    const int nw = pick_nw(g.tiles, nblk);
     if (nw == 4) hipLaunchKernelGGL((k_gemm_f32<4, A_KC, B_KC, EPI>), grid, dim3(256), 0, st, g);
     else if (nw == 8) hipLaunchKernelGGL((k_gemm_f32<8, A_KC, B_KC, EPI>), grid, dim3(512), 0, st, g);
     else hipLaunchKernelGGL((k_gemm_f32<16, A_KC, B_KC, EPI>), grid, dim3(1024), 0, st, g);

@@ -83,10 +83,8 @@ __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
 struct ChainArgs {
     const float* E;
     const float* R;
-    const int64_t* h;
-    const int64_t* r;
-    const int64_t* t;
-    int b, D, Dr, side;
+    StepIds ids;
+    int b, D, Dr;
     int64_t n_ent, n_rel;
     const float* O;
     const float* GO;
@@ -106,9 +104,10 @@ __global__ __launch_bounds__(256) void k_chain(ChainArgs a) {
     const int D = a.D;
     const int nvec = CPLX ? D / 8 : D / 4;
     const int im_off = D / 2;
-    const bool head = a.side == KGE_NEG_HEAD;
-    const int64_t hid = clamp_id(a.h[i], a.n_ent), tid = clamp_id(a.t[i], a.n_ent);
-    const int64_t rid = clamp_id(a.r[i], a.n_rel);
+    const StepView sv = step_view(a.ids);
+    const bool head = sv.side == KGE_NEG_HEAD;
+    const int64_t hid = clamp_id(sv.h[i], a.n_ent), tid = clamp_id(sv.t[i], a.n_ent);
+    const int64_t rid = clamp_id(sv.r[i], a.n_rel);
     const float* pa = a.E + (head ? tid : hid) * (int64_t)D;
     const float* pc = a.E + (head ? hid : tid) * (int64_t)D;
     const float* pr = a.R + rid * (int64_t)a.Dr;
@@ -262,12 +261,11 @@ void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st) {
     hipLaunchKernelGGL(k_loss, dim3((b + 3) / 4), dim3(256), 0, st, a);
 }
 
-void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const int64_t* h, const int64_t* r,
-                      const int64_t* t, int b, int side, float gamma, hipStream_t st) {
-    (void)gamma;
+void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st) {
     ChainArgs a;
-    a.E = E; a.R = R; a.h = h; a.r = r; a.t = t; a.b = b; a.D = c->cfg.ent_dim; a.Dr = c->cfg.rel_dim;
-    a.side = side; a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
+    const int b = ids.b;
+    a.E = E; a.R = R; a.ids = ids; a.b = b; a.D = c->cfg.ent_dim; a.Dr = c->cfg.rel_dim;
+    a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
     a.O = c->O; a.GO = c->GO; a.cpos = c->cpos; a.Gent = c->Gent; a.Grel = c->Grel;
     const int model = c->cfg.model;
     const bool cplx = model == KGE_COMPLEX || model == KGE_ROTATE;

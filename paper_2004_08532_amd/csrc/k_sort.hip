@@ -1,41 +1,23 @@
-// Duplicate reduction, part 1: sort the (row id, position) pairs of a mini-batch.
+// Duplicate reduction, part 1, for LONG key lists: sort the (row id, position) pairs of a mini-batch.
 //
 // A mini-batch touches few rows and may touch one row many times (paper Sec. 2); before the optimizer runs,
-// all gradient rows of one embedding row have to be added up.  The key lists are short (2b + (b/g)k entity
-// keys, b relation keys: a few thousand), so each list is sorted by ONE workgroup of 1024 threads with a
-// least-significant-digit radix sort, 8 bits per pass, over only as many bits as the table's row count needs.
-// Within a pass every wavefront owns a contiguous slice of the list; equal digits inside a 64-key round are
-// ranked with ballots, so the sort is stable and equal ids end up ordered by position.  That makes the order
-// in which the update kernel adds gradient rows a function of the ids alone.  Block 0 sorts the entity keys,
-// block 1 the relation keys; the kernel runs on its own stream beside the forward/backward kernels.
+// all gradient rows of one embedding row have to be added up, so the key lists (2b + (b/g)k entity keys, b
+// relation keys) are brought into (id, position) order.  Lists of up to KGE_RANK_MAX_KEYS keys are ordered by the
+// rank blocks of the gather launch (k_gather.hip).  Longer lists are sorted here: ONE workgroup of 1024 threads per
+// list, least-significant-digit radix sort, 8 bits per pass, over only as many bits as the table's row count
+// needs, ping-ponging through global memory.  Within a pass every wavefront owns a contiguous slice of the list;
+// equal digits inside a 64-key round are ranked with ballots, so the sort is stable and equal ids end up ordered
+// by position.  Block 0 sorts the entity keys, block 1 the relation keys; the kernel runs on its own stream beside
+// the forward/backward kernels.  This file also holds the export of distinct ids and counts (test hook).
 #include "kge_common.h"
 
 namespace {
 
-struct SortList {
-    const int64_t* src[3];  // the key list is the concatenation of up to three id arrays
-    int n_src[3];
-    int n;
-    int passes;
-    int64_t n_ids;          // ids are clamped into [0, n_ids)
-    uint32_t* key[2];
-    uint32_t* pos[2];
-};
-
-__device__ __forceinline__ uint32_t fetch_key(const SortList& l, int idx) {
-    int64_t id;
-    if (idx < l.n_src[0]) id = l.src[0][idx];
-    else if (idx < l.n_src[0] + l.n_src[1]) id = l.src[1][idx - l.n_src[0]];
-    else id = l.src[2][idx - l.n_src[0] - l.n_src[1]];
-    id = id < 0 ? 0 : (id >= l.n_ids ? l.n_ids - 1 : id);
-    return (uint32_t)id;
-}
-
 constexpr int SORT_THREADS = 1024;
 constexpr int SORT_WAVES = SORT_THREADS / 64;
 
-__global__ __launch_bounds__(SORT_THREADS) void k_sort(SortList ent, SortList rel) {
-    const SortList& l = blockIdx.x == 0 ? ent : rel;
+__global__ __launch_bounds__(SORT_THREADS) void k_sort(KeyList ent, KeyList rel) {
+    const KeyList& l = blockIdx.x == 0 ? ent : rel;
     __shared__ volatile uint32_t hist[SORT_WAVES][256];
     __shared__ uint32_t wave_tot[4];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -169,25 +151,35 @@ int passes_for(int64_t n_ids) {
 
 }  // namespace
 
-void kge_launch_sort(kge_ctx* c, const int64_t* h, const int64_t* r, const int64_t* t, int b,
-                     const int64_t* neg, int n_neg, hipStream_t st) {
-    SortList e = {}, rl = {};
-    e.src[0] = h; e.src[1] = t; e.src[2] = neg;
+void kge_make_key_lists(kge_ctx* c, const StepIds& ids, KeyList* ent, KeyList* rel) {
+    KeyList e = {}, rl = {};
+    const int b = ids.b, n_neg = ids.n_neg;
+    e.src[0] = ids.h; e.src[1] = ids.t; e.src[2] = ids.neg;
     e.n_src[0] = b; e.n_src[1] = b; e.n_src[2] = n_neg;
+    e.step_stride[0] = b; e.step_stride[1] = b; e.step_stride[2] = n_neg; e.step_ptr = ids.step_ptr;
     e.n = 2 * b + n_neg;
     e.passes = passes_for(c->cfg.num_entities);
     e.n_ids = c->cfg.num_entities;
     e.key[0] = c->ekey[0]; e.key[1] = c->ekey[1]; e.pos[0] = c->epos[0]; e.pos[1] = c->epos[1];
-    rl.src[0] = r; rl.src[1] = r; rl.src[2] = r;
+    rl.src[0] = ids.r; rl.src[1] = ids.r; rl.src[2] = ids.r;
     rl.n_src[0] = b; rl.n_src[1] = 0; rl.n_src[2] = 0;
+    rl.step_stride[0] = b; rl.step_stride[1] = b; rl.step_stride[2] = b; rl.step_ptr = ids.step_ptr;
     rl.n = b;
     rl.passes = passes_for(c->cfg.num_relations);
     rl.n_ids = c->cfg.num_relations;
     rl.key[0] = c->rkey[0]; rl.key[1] = c->rkey[1]; rl.pos[0] = c->rpos[0]; rl.pos[1] = c->rpos[1];
-    c->ebuf = (e.passes - 1) & 1;
-    c->rbuf = (rl.passes - 1) & 1;
     c->last_ent_keys = e.n;
     c->last_rel_keys = rl.n;
+    *ent = e;
+    *rel = rl;
+}
+
+// Radix sort of both key lists (lists too long for the rank path of the gather launch).
+void kge_launch_sort(kge_ctx* c, const StepIds& ids, hipStream_t st) {
+    KeyList e, rl;
+    kge_make_key_lists(c, ids, &e, &rl);
+    c->ebuf = (e.passes - 1) & 1;
+    c->rbuf = (rl.passes - 1) & 1;
     hipLaunchKernelGGL(k_sort, dim3(2), dim3(SORT_THREADS), 0, st, e, rl);
 }
 

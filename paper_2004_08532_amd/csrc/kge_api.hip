@@ -1,6 +1,7 @@
 // C ABI of libkge: argument checks, workspace, and the order in which the kernels of one step are enqueued.
 // See include/kge.h for the contract of each entry point.
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -25,13 +26,28 @@ int fail(kge_ctx* c, int code, const char* fmt, const char* detail = "") {
 
 bool is_gemm_model(int m) { return m == KGE_TRANSE_L2 || m == KGE_DISTMULT || m == KGE_COMPLEX; }
 
-__global__ void k_validate(const int64_t* h, const int64_t* r, const int64_t* t, int b, const int64_t* neg, int n_neg,
-                           int64_t n_ent, int64_t n_rel, int* flag) {
+__global__ void k_validate(StepIds ids, int64_t n_ent, int64_t n_rel, int* flag) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    const StepView v = step_view(ids);
     bool bad = false;
-    if (i < b) bad = h[i] < 0 || h[i] >= n_ent || t[i] < 0 || t[i] >= n_ent || r[i] < 0 || r[i] >= n_rel;
-    if (i < n_neg) bad = bad || neg[i] < 0 || neg[i] >= n_ent;
+    if (i < ids.b)
+        bad = v.h[i] < 0 || v.h[i] >= n_ent || v.t[i] < 0 || v.t[i] >= n_ent || v.r[i] < 0 || v.r[i] >= n_rel;
+    if (i < ids.n_neg) bad = bad || v.neg[i] < 0 || v.neg[i] >= n_ent;
     if (bad) atomicOr(flag, 1);
+}
+
+void launch_validate(kge_ctx* c, const StepIds& ids, hipStream_t st) {
+    const int n = ids.b > ids.n_neg ? ids.b : ids.n_neg;
+    hipLaunchKernelGGL(k_validate, dim3((n + 255) / 256), dim3(256), 0, st, ids, c->cfg.num_entities,
+                       c->cfg.num_relations, c->flags);
+}
+
+StepIds direct_ids(const int64_t* h, const int64_t* r, const int64_t* t, int b, const int64_t* neg, int n_neg, int side,
+                   float* loss_out) {
+    StepIds ids;
+    ids.h = h; ids.r = r; ids.t = t; ids.neg = neg; ids.b = b; ids.n_neg = n_neg; ids.side = side;
+    ids.step_ptr = nullptr; ids.sides = nullptr; ids.loss_out = loss_out;
+    return ids;
 }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -48,19 +64,13 @@ int check_batch(kge_ctx* c, const void* ent, const void* rel, const int64_t* h, 
     return KGE_OK;
 }
 
-void forward(kge_ctx* c, const float* ent, const float* rel, const int64_t* h, const int64_t* r, const int64_t* t,
-             int b, const int64_t* neg, int k, int chunk, int side, float gamma, float* pos_out, float* neg_out,
-             int ld_out, int dist_mode, hipStream_t st) {
-    const int n_neg = (b / chunk) * k;
-    if (c->cfg.validate_indices) {
-        const int n = b > n_neg ? b : n_neg;
-        hipLaunchKernelGGL(k_validate, dim3((n + 255) / 256), dim3(256), 0, st, h, r, t, b, neg, n_neg,
-                           c->cfg.num_entities, c->cfg.num_relations, c->flags);
-    }
-    kge_launch_gather(c, ent, rel, h, r, t, b, neg, n_neg, side, gamma, pos_out, st);
+void forward(kge_ctx* c, const float* ent, const float* rel, const StepIds& ids, int k, int chunk, float gamma,
+             float* pos_out, float* neg_out, int ld_out, int dist_mode, hipStream_t st) {
+    if (c->cfg.validate_indices) launch_validate(c, ids, st);
+    kge_launch_gather(c, ent, rel, ids, gamma, pos_out, false, st);
     if (neg_out && k > 0) {
-        if (is_gemm_model(c->cfg.model)) kge_gemm_neg_score(c, b, k, chunk, gamma, neg_out, ld_out, dist_mode, st);
-        else kge_pair_neg_score(c, b, k, chunk, gamma, neg_out, ld_out, st);
+        if (is_gemm_model(c->cfg.model)) kge_gemm_neg_score(c, ids.b, k, chunk, gamma, neg_out, ld_out, dist_mode, st);
+        else kge_pair_neg_score(c, ids.b, k, chunk, gamma, neg_out, ld_out, st);
     }
 }
 
@@ -78,26 +88,25 @@ struct ProfScope {
     }
 };
 
-int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state, const int64_t* h,
-                 const int64_t* r, const int64_t* t, int B, const int64_t* neg, int K, int G, int side, float gamma,
-                 float lr, hipStream_t st, float* loss_out) {
-    const int n_neg = (B / G) * K;
-    // the key sort needs only the ids: it runs beside the forward/backward kernels and joins before the update
-    KGE_HIP(c, hipEventRecord(c->ev_fork, st));
-    KGE_HIP(c, hipStreamWaitEvent(c->side_stream, c->ev_fork, 0));
-    {
-        ProfScope p(c, KGE_PROF_SORT, c->side_stream);
-        kge_launch_sort(c, h, r, t, B, neg, n_neg, c->side_stream);
+int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state, const StepIds& ids, int K,
+                 int G, float gamma, float lr, hipStream_t st) {
+    const int B = ids.b;
+    // Ordering the key lists needs only the ids.  Short lists are ordered by extra blocks of the gather launch;
+    // long ones by a radix sort on a second stream that joins before the update.
+    const bool long_lists = 2 * B + ids.n_neg > KGE_RANK_MAX_KEYS;
+    if (long_lists) {
+        KGE_HIP(c, hipEventRecord(c->ev_fork, st));
+        KGE_HIP(c, hipStreamWaitEvent(c->side_stream, c->ev_fork, 0));
+        {
+            ProfScope p(c, KGE_PROF_SORT, c->side_stream);
+            kge_launch_sort(c, ids, c->side_stream);
+        }
+        KGE_HIP(c, hipEventRecord(c->ev_join, c->side_stream));
     }
-    KGE_HIP(c, hipEventRecord(c->ev_join, c->side_stream));
-    if (c->cfg.validate_indices) {
-        const int n = B > n_neg ? B : n_neg;
-        hipLaunchKernelGGL(k_validate, dim3((n + 255) / 256), dim3(256), 0, st, h, r, t, B, neg, n_neg,
-                           c->cfg.num_entities, c->cfg.num_relations, c->flags);
-    }
+    if (c->cfg.validate_indices) launch_validate(c, ids, st);
     {
         ProfScope p(c, KGE_PROF_GATHER, st);
-        kge_launch_gather(c, ent, rel, h, r, t, B, neg, n_neg, side, gamma, nullptr, st);
+        kge_launch_gather(c, ent, rel, ids, gamma, nullptr, !long_lists, st);
     }
     {
         ProfScope p(c, KGE_PROF_SCORE, st);
@@ -115,22 +124,70 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
     }
     {
         ProfScope p(c, KGE_PROF_CHAIN, st);
-        kge_launch_chain(c, ent, rel, h, r, t, B, side, gamma, st);
+        kge_launch_chain(c, ent, rel, ids, st);
     }
-    KGE_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
+    if (long_lists) KGE_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
     {
         ProfScope p(c, KGE_PROF_UPDATE, st);
-        kge_launch_update(c, ent, ent_state, rel, rel_state, 2 * B + n_neg, B, lr, B, loss_out, st);
+        kge_launch_update(c, ent, ent_state, rel, rel_state, ids, lr, st);
     }
     KGE_HIP(c, hipGetLastError());
     if (c->prof_on) {
         KGE_HIP(c, hipStreamSynchronize(st));
         for (int s = 0; s < KGE_PROF_SLOTS; ++s) {
             float ms = 0.f;
+            if (s == KGE_PROF_SORT && !long_lists) continue;  // no separate sort kernel ran
             if (hipEventElapsedTime(&ms, c->prof_ev[s][0], c->prof_ev[s][1]) == hipSuccess) c->prof_ms[s] += ms;
         }
         c->prof_steps += 1;
     }
+    return KGE_OK;
+}
+
+// ---- replay: kge_train_steps captures UNROLL consecutive steps (and one single step for the remainder) into HIP
+// graphs whose kernels take the step number from device memory, so the same two graphs serve every step of every
+// call with the same arguments.  A graph launch costs the host about as much as one kernel launch.
+constexpr int REPLAY_UNROLL = 8;
+
+struct ReplayKey {
+    void *ent, *ent_state, *rel, *rel_state;
+    const void *h, *r, *t, *neg;
+    int64_t b, k, chunk;
+    float gamma, lr;
+    float* loss_out;
+    bool has_sides;
+    bool operator==(const ReplayKey& o) const { return memcmp(this, &o, sizeof(ReplayKey)) == 0; }
+};
+
+struct ReplayCache {
+    bool valid = false;
+    ReplayKey key;
+    hipGraphExec_t many = nullptr;  // REPLAY_UNROLL steps
+    hipGraphExec_t one = nullptr;   // one step
+};
+
+void replay_drop(ReplayCache* rc) {
+    if (rc->many) (void)hipGraphExecDestroy(rc->many);
+    if (rc->one) (void)hipGraphExecDestroy(rc->one);
+    rc->many = rc->one = nullptr;
+    rc->valid = false;
+}
+
+int capture_steps(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state, const StepIds& ids, int K,
+                  int G, float gamma, float lr, hipStream_t st, int n, hipGraphExec_t* out) {
+    hipGraph_t graph = nullptr;
+    KGE_HIP(c, hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+    int rc = KGE_OK;
+    for (int s = 0; s < n && rc == KGE_OK; ++s) rc = enqueue_step(c, ent, ent_state, rel, rel_state, ids, K, G, gamma, lr, st);
+    hipError_t e = hipStreamEndCapture(st, &graph);
+    if (rc != KGE_OK) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+    }
+    if (e != hipSuccess) return fail(c, KGE_ERR_DEVICE, "hipStreamEndCapture: %s", hipGetErrorString(e));
+    e = hipGraphInstantiate(out, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) return fail(c, KGE_ERR_DEVICE, "hipGraphInstantiate: %s", hipGetErrorString(e));
     return KGE_OK;
 }
 
@@ -185,7 +242,9 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t o_rl = take(B * 4), o_wrs = take(B * 4);
     const size_t o_ek0 = take(EK * 4), o_ek1 = take(EK * 4), o_ep0 = take(EK * 4), o_ep1 = take(EK * 4);
     const size_t o_rk0 = take(B * 4), o_rk1 = take(B * 4), o_rp0 = take(B * 4), o_rp1 = take(B * 4);
-    const size_t o_flags = take(256);
+    const size_t te = EK / 8 + 1, tr = B / 8 + 1;
+    const size_t o_pfe = take(te * D * 4), o_ple = take(te * D * 4), o_pfr = take(tr * Dr * 4), o_plr = take(tr * Dr * 4);
+    const size_t o_flags = take(256), o_step = take(256);
     c->ws_bytes = (int64_t)off;
 
     hipError_t e = hipMalloc(&c->ws_base, off);
@@ -203,7 +262,10 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->epos[0] = (uint32_t*)(base + o_ep0); c->epos[1] = (uint32_t*)(base + o_ep1);
     c->rkey[0] = (uint32_t*)(base + o_rk0); c->rkey[1] = (uint32_t*)(base + o_rk1);
     c->rpos[0] = (uint32_t*)(base + o_rp0); c->rpos[1] = (uint32_t*)(base + o_rp1);
+    c->Pfirst_e = (float*)(base + o_pfe); c->Plast_e = (float*)(base + o_ple);
+    c->Pfirst_r = (float*)(base + o_pfr); c->Plast_r = (float*)(base + o_plr);
     c->flags = (int*)(base + o_flags);
+    c->step_counter = (int64_t*)(base + o_step);
 
     bool ok = hipMemset(c->ws_base, 0, off) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking) == hipSuccess;
@@ -227,6 +289,11 @@ void kge_destroy(kge_ctx* c) {
     for (int s = 0; s < KGE_PROF_SLOTS; ++s)
         for (int e = 0; e < 2; ++e)
             if (c->prof_ev[s][e]) (void)hipEventDestroy(c->prof_ev[s][e]);
+    if (c->replay) {
+        replay_drop((ReplayCache*)c->replay);
+        delete (ReplayCache*)c->replay;
+    }
+    if (c->sides_dev) (void)hipFree(c->sides_dev);
     if (c->ws_base) (void)hipFree(c->ws_base);
     delete c;
 }
@@ -241,8 +308,8 @@ int kge_train_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* 
     const int rc = check_batch(c, ent, rel, h, r, t, b, neg, k, chunk, neg_side, true);
     if (rc != KGE_OK) return rc;
     KGE_HIP(c, hipSetDevice(c->cfg.device));
-    return enqueue_step(c, ent, ent_state, rel, rel_state, h, r, t, (int)b, neg, (int)k, (int)chunk, neg_side, gamma,
-                        lr, (hipStream_t)hip_stream, loss_out);
+    const StepIds ids = direct_ids(h, r, t, (int)b, neg, (int)((b / chunk) * k), neg_side, loss_out);
+    return enqueue_step(c, ent, ent_state, rel, rel_state, ids, (int)k, (int)chunk, gamma, lr, (hipStream_t)hip_stream);
 }
 
 int kge_train_steps(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state,
@@ -258,14 +325,72 @@ int kge_train_steps(kge_ctx* c, float* ent, float* ent_state, float* rel, float*
     for (int64_t s = 0; neg_sides && s < n_steps; ++s)
         if (neg_sides[s] != KGE_NEG_TAIL && neg_sides[s] != KGE_NEG_HEAD)
             return fail(c, KGE_ERR_INVALID_ARG, "neg_sides entries must be 0 or 1%s");
+    if (n_steps == 0) return KGE_OK;
     KGE_HIP(c, hipSetDevice(c->cfg.device));
+    hipStream_t st = (hipStream_t)hip_stream;
     const int64_t n_neg = (b / chunk) * k;
-    for (int64_t s = 0; s < n_steps; ++s) {
-        rc = enqueue_step(c, ent, ent_state, rel, rel_state, h + s * b, r + s * b, t + s * b, (int)b, neg + s * n_neg,
-                          (int)k, (int)chunk, neg_sides ? neg_sides[s] : KGE_NEG_TAIL, gamma, lr,
-                          (hipStream_t)hip_stream, loss_out ? loss_out + s : nullptr);
-        if (rc != KGE_OK) return rc;
+
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    (void)hipStreamIsCapturing(st, &cap);
+    static const bool replay_enabled = []() {
+        const char* e = getenv("KGE_TRAIN_STEPS_REPLAY");  // "0" turns graph replay off (measurement aid)
+        return !(e && e[0] == '0');
+    }();
+    if (!replay_enabled || c->prof_on || n_steps < 4 || cap != hipStreamCaptureStatusNone || st == nullptr ||
+        st == hipStreamLegacy) {
+        // plain launches: timing mode, very short runs, the caller is capturing this stream itself, or the stream
+        // is the legacy default stream, which cannot be captured
+        for (int64_t s = 0; s < n_steps; ++s) {
+            const StepIds ids = direct_ids(h + s * b, r + s * b, t + s * b, (int)b, neg + s * n_neg, (int)n_neg,
+                                           neg_sides ? neg_sides[s] : KGE_NEG_TAIL, loss_out ? loss_out + s : nullptr);
+            rc = enqueue_step(c, ent, ent_state, rel, rel_state, ids, (int)k, (int)chunk, gamma, lr, st);
+            if (rc != KGE_OK) return rc;
+        }
+        return KGE_OK;
     }
+
+    // replay path
+    if (neg_sides) {
+        if (c->sides_cap < n_steps) {
+            KGE_HIP(c, hipStreamSynchronize(st));
+            if (c->sides_dev) KGE_HIP(c, hipFree(c->sides_dev));
+            c->sides_dev = nullptr;
+            c->sides_cap = 0;
+            KGE_HIP(c, hipMalloc((void**)&c->sides_dev, sizeof(int32_t) * (size_t)n_steps));
+            c->sides_cap = n_steps;
+            if (c->replay) replay_drop((ReplayCache*)c->replay);  // the graphs hold the old pointer
+        }
+        KGE_HIP(c, hipMemcpyAsync(c->sides_dev, neg_sides, sizeof(int32_t) * (size_t)n_steps, hipMemcpyHostToDevice, st));
+    }
+    KGE_HIP(c, hipMemsetAsync(c->step_counter, 0, sizeof(int64_t), st));
+
+    ReplayKey key;
+    memset(&key, 0, sizeof(key));
+    key.ent = ent; key.ent_state = ent_state; key.rel = rel; key.rel_state = rel_state;
+    key.h = h; key.r = r; key.t = t; key.neg = neg; key.b = b; key.k = k; key.chunk = chunk;
+    key.gamma = gamma; key.lr = lr; key.loss_out = loss_out; key.has_sides = neg_sides != nullptr;
+    if (!c->replay) c->replay = new (std::nothrow) ReplayCache();
+    ReplayCache* cache = (ReplayCache*)c->replay;
+    if (!cache) return fail(c, KGE_ERR_DEVICE, "out of host memory%s");
+    if (!cache->valid || !(cache->key == key)) {
+        replay_drop(cache);
+        StepIds ids = direct_ids(h, r, t, (int)b, neg, (int)n_neg, KGE_NEG_TAIL, loss_out);
+        ids.step_ptr = c->step_counter;
+        ids.sides = neg_sides ? c->sides_dev : nullptr;
+        rc = capture_steps(c, ent, ent_state, rel, rel_state, ids, (int)k, (int)chunk, gamma, lr, st, REPLAY_UNROLL,
+                           &cache->many);
+        if (rc == KGE_OK)
+            rc = capture_steps(c, ent, ent_state, rel, rel_state, ids, (int)k, (int)chunk, gamma, lr, st, 1, &cache->one);
+        if (rc != KGE_OK) {
+            replay_drop(cache);
+            return rc;
+        }
+        cache->key = key;
+        cache->valid = true;
+    }
+    int64_t done = 0;
+    for (; done + REPLAY_UNROLL <= n_steps; done += REPLAY_UNROLL) KGE_HIP(c, hipGraphLaunch(cache->many, st));
+    for (; done < n_steps; ++done) KGE_HIP(c, hipGraphLaunch(cache->one, st));
     return KGE_OK;
 }
 
@@ -279,8 +404,8 @@ int kge_score(kge_ctx* c, const float* ent, const float* rel,
     if (rc != KGE_OK) return rc;
     KGE_HIP(c, hipSetDevice(c->cfg.device));
     const int kk = neg_out ? (int)k : 0;
-    forward(c, ent, rel, h, r, t, (int)b, neg, kk, (int)chunk, neg_side, gamma, pos_out, neg_out, (int)k, 0,
-            (hipStream_t)hip_stream);
+    const StepIds ids = direct_ids(h, r, t, (int)b, neg, (int)((b / chunk) * kk), neg_side, nullptr);
+    forward(c, ent, rel, ids, kk, (int)chunk, gamma, pos_out, neg_out, (int)k, 0, (hipStream_t)hip_stream);
     KGE_HIP(c, hipGetLastError());
     return KGE_OK;
 }

@@ -40,6 +40,10 @@ struct kge_ctx {
     uint16_t* Obf;   // bf16 copies of O, Nst, W (gemm_input = 1)
     uint16_t* Nbf;
     uint16_t* Wbf;
+    float* Pfirst_e;    // partial sums of runs that cross 8-position tiles of the sorted key list (see k_update.hip)
+    float* Plast_e;
+    float* Pfirst_r;
+    float* Plast_r;
     uint32_t* ekey[2];  // entity sort ping-pong: keys
     uint32_t* epos[2];  //                        positions in the key list
     uint32_t* rkey[2];  // relation sort ping-pong
@@ -50,6 +54,10 @@ struct kge_ctx {
     int64_t last_ent_keys, last_rel_keys;  // sizes of the last train step's key lists (0: none yet)
     hipStream_t side_stream;        // runs the key sort beside the forward/backward kernels
     hipEvent_t ev_fork, ev_join;
+    int64_t* step_counter;          // device: the step a replayed graph is at
+    int32_t* sides_dev;             // device: per-step sides of the current kge_train_steps call
+    int64_t sides_cap;
+    void* replay;                   // cached graphs of kge_train_steps (ReplayCache in kge_api.hip)
     bool prof_on;                   // kge_profile: bracket every kernel with events
     hipEvent_t prof_ev[KGE_PROF_SLOTS][2];
     double prof_ms[KGE_PROF_SLOTS];
@@ -58,12 +66,48 @@ struct kge_ctx {
 };
 
 // ---------------------------------------------------------------------------------------------------------
+// The ids of one step, as the kernels receive them.
+// Direct mode: step_ptr == nullptr and h, r, t, neg point at this step's ids.
+// Replay mode (one captured HIP graph serves every step of kge_train_steps): h, r, t, neg point at the ids of
+// step 0, consecutive steps lie b (n_neg) entries apart, *step_ptr (device memory, advanced by the last kernel of
+// every step) says which step is running, sides (device, may be null) holds one kge_neg_side per step and
+// loss_out one float per step.
+// ---------------------------------------------------------------------------------------------------------
+struct StepIds {
+    const int64_t* h;
+    const int64_t* r;
+    const int64_t* t;
+    const int64_t* neg;
+    int b, n_neg, side;
+    const int64_t* step_ptr;
+    const int32_t* sides;
+    float* loss_out;
+};
+
+// A key list of the duplicate reduction: the concatenation of up to three id arrays (entities: heads | tails |
+// corrupting ids; relations: r), to be brought into (id, position) order.
+struct KeyList {
+    const int64_t* src[3];
+    int n_src[3];
+    int64_t step_stride[3];  // replay mode: src[i] advances by this many entries per step
+    const int64_t* step_ptr;
+    int n;                   // total number of keys
+    int passes;              // radix passes needed for ids < n_ids (8 bits each)
+    int64_t n_ids;           // ids are clamped into [0, n_ids)
+    uint32_t* key[2];        // sorted ids (ping-pong halves; the rank path writes half 0)
+    uint32_t* pos[2];        // position in the key list of each sorted entry
+};
+void kge_make_key_lists(kge_ctx* c, const StepIds& ids, KeyList* ent, KeyList* rel);
+
+// ---------------------------------------------------------------------------------------------------------
 // Host-side launchers (each in the source file named after its kernel group)
 // ---------------------------------------------------------------------------------------------------------
 // a1/a2: gather rows, o_i, positive scores, norms
-void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const int64_t* h, const int64_t* r,
-                       const int64_t* t, int b, const int64_t* neg, int n_neg, int side, float gamma,
-                       float* pos_out, hipStream_t st);
+// with_keys: the same launch also brings the key lists into (id, position) order (lists of up to
+// KGE_RANK_MAX_KEYS keys; longer lists go through kge_launch_sort)
+void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds& ids, float gamma, float* pos_out,
+                       bool with_keys, hipStream_t st);
+constexpr int KGE_RANK_MAX_KEYS = 16384;
 // a3: negative scores of every chunk into out[b x ld_out]: matrix-product models / elementwise-reduce models
 void kge_gemm_neg_score(kge_ctx* c, int b, int k, int g, float gamma, float* out, int ld_out, int dist_mode,
                         hipStream_t st);
@@ -74,14 +118,12 @@ void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st);
 void kge_gemm_neg_backward(kge_ctx* c, int b, int k, int g, hipStream_t st);
 void kge_pair_neg_backward(kge_ctx* c, int b, int k, int g, hipStream_t st);
 // a5: positive-pair term and chain rule through phi -> gradient rows of heads, tails and relations
-void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const int64_t* h, const int64_t* r,
-                      const int64_t* t, int b, int side, float gamma, hipStream_t st);
+void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
 // a6: sort (id, position) of the entity and relation key lists
-void kge_launch_sort(kge_ctx* c, const int64_t* h, const int64_t* r, const int64_t* t, int b,
-                     const int64_t* neg, int n_neg, hipStream_t st);
+void kge_launch_sort(kge_ctx* c, const StepIds& ids, hipStream_t st);
 // a7: per distinct row, sum its gradient rows and apply Adagrad; also reduces the loss terms
-void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, int n_ent_keys, int n_rel_keys,
-                       float lr, int b, float* loss_out, hipStream_t st);
+void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, const StepIds& ids, float lr,
+                       hipStream_t st);
 // test hook: distinct ids and multiplicities from the sorted keys
 void kge_launch_dedup_export(kge_ctx* c, int which, int64_t* uniq, int32_t* count, int64_t* n_unique,
                              hipStream_t st);
@@ -90,6 +132,40 @@ void kge_launch_dedup_export(kge_ctx* c, int which, int64_t* uniq, int32_t* coun
 // Device helpers
 // ---------------------------------------------------------------------------------------------------------
 #ifdef __HIPCC__
+struct StepView {
+    const int64_t* h;
+    const int64_t* r;
+    const int64_t* t;
+    const int64_t* neg;
+    int side;
+    int64_t step;
+};
+__device__ __forceinline__ StepView step_view(const StepIds& s) {
+    StepView v;
+    v.step = s.step_ptr ? *s.step_ptr : 0;
+    v.h = s.h + v.step * s.b;
+    v.r = s.r + v.step * s.b;
+    v.t = s.t + v.step * s.b;
+    v.neg = s.neg + v.step * s.n_neg;
+    v.side = s.sides ? s.sides[v.step] : s.side;
+    return v;
+}
+// Address of entry idx of a key list (branch-free, so that a thread can have many of these loads in flight).
+__device__ __forceinline__ const int64_t* key_address(const KeyList& l, int64_t step, int idx) {
+    const int a = l.n_src[0], ab = a + l.n_src[1];
+    const int64_t* p0 = l.src[0] + step * l.step_stride[0] + idx;
+    const int64_t* p1 = l.src[1] + step * l.step_stride[1] + (idx - a);
+    const int64_t* p2 = l.src[2] + step * l.step_stride[2] + (idx - ab);
+    return idx < a ? p0 : (idx < ab ? p1 : p2);
+}
+__device__ __forceinline__ uint32_t clamp_key(const KeyList& l, int64_t id) {
+    id = id < 0 ? 0 : (id >= l.n_ids ? l.n_ids - 1 : id);
+    return (uint32_t)id;
+}
+__device__ __forceinline__ uint32_t fetch_key(const KeyList& l, int idx) {
+    const int64_t step = l.step_ptr ? *l.step_ptr : 0;
+    return clamp_key(l, *key_address(l, step, idx));
+}
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

@@ -216,6 +216,18 @@ def test_zero_distance_pairs_have_zero_gradient(kge):
         p.close()
 
 
+def test_long_key_lists_take_the_radix_sort_path(kge):
+    """More than 16384 entity keys per step: the key lists are sorted by the radix kernel on the second stream
+    instead of the rank blocks of the gather launch."""
+    w = ragged("distmult", n_entities=3001, ent_dim=16, rel_dim=16, batch=512, chunk=64, neg_per_chunk=2000, steps=2)
+    assert 2 * w.batch + w.n_chunks * w.neg_per_chunk > 16384
+    p = Pair(w, kge)
+    try:
+        run_steps(p, configs.BatchStream(w), 2, check_dedup_at=(0, 1))
+    finally:
+        p.close()
+
+
 # ------------------------------------------------------------------------------------------------------------
 # properties that do not need the oracle's arithmetic
 
@@ -290,3 +302,57 @@ def test_index_validation_reports_out_of_range_ids_without_touching_memory_outsi
         p.ctx.check_indices()  # flag is cleared by the failed check
     finally:
         p.close()
+
+
+def test_train_steps_graph_replay_equals_step_by_step(kge):
+    """kge_train_steps replays captured graphs; the result must equal kge_train_step called once per step, bit for
+    bit, on every replay: first use (capture), reuse with new ids in the same buffers, a step count that is not a
+    multiple of the unroll factor, with eager work and synchronisation in between."""
+    w = configs.TINY.scaled(name="tiny-replay", side_mode="alternate")
+    bs = configs.BatchStream(w)
+    E0, R0 = configs.init_tables(w)
+    stream = torch.cuda.Stream()
+    n_per_call, rounds = 21, 3
+
+    def fresh():
+        dE, dR = dev(E0), dev(R0)
+        return dE, torch.zeros_like(dE), dR, torch.zeros_like(dR)
+
+    def make_ctx():
+        return kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
+                              max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks)
+
+    # step by step
+    ctx = make_ctx()
+    aE, aSE, aR, aSR = fresh()
+    loss_a = torch.zeros(n_per_call * rounds, device="cuda")
+    with torch.cuda.stream(stream):
+        for s in range(n_per_call * rounds):
+            h, r, t, neg, side = bs.step(s)
+            ctx.train_step(aE, aSE, aR, aSR, dev(h), dev(r), dev(t), dev(neg.reshape(-1)), w.neg_per_chunk, w.chunk,
+                           side, w.gamma, w.lr, loss_out=loss_a[s:s + 1])
+            stream.synchronize()
+    ctx.close()
+
+    # replayed: the same device buffers are refilled for every call, so the second and third call reuse the graphs
+    ctx = make_ctx()
+    bE, bSE, bR, bSR = fresh()
+    loss_b = torch.zeros(n_per_call, device="cuda")
+    H = torch.zeros((n_per_call, w.batch), dtype=torch.int64, device="cuda")
+    Rr, T = torch.zeros_like(H), torch.zeros_like(H)
+    N = torch.zeros((n_per_call, w.n_chunks * w.neg_per_chunk), dtype=torch.int64, device="cuda")
+    scratch = torch.zeros(1000, device="cuda")
+    for rd in range(rounds):
+        h, r, t, neg, sides = bs.steps(rd * n_per_call, n_per_call)
+        H.copy_(torch.from_numpy(h)); Rr.copy_(torch.from_numpy(r)); T.copy_(torch.from_numpy(t))
+        N.copy_(torch.from_numpy(neg.reshape(n_per_call, -1)))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            ctx.train_steps(bE, bSE, bR, bSR, H, Rr, T, N, w.neg_per_chunk, w.chunk, sides.tolist(), w.gamma, w.lr,
+                            loss_out=loss_b)
+        stream.synchronize()
+        scratch.add_(1.0)  # unrelated eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(loss_b, loss_a[rd * n_per_call:(rd + 1) * n_per_call]), rd
+    assert torch.equal(aE, bE) and torch.equal(aSE, bSE) and torch.equal(aR, bR) and torch.equal(aSR, bSR)
+    ctx.close()
