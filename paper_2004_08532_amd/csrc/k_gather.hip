@@ -25,6 +25,9 @@ struct GatherArgs {
     float* pos_out;
     float* o_n2;
     float* n_n2;
+    float* cpos;      // dL/df+_i = -sigmoid(-f+_i) / b
+    float* inv_dpos;  // TransE-L2: 1 / |o_i - c_i| (0 if the distance is 0)
+    float* row_loss;  // softplus(-f+_i) / b
     uint16_t* Obf;
     uint16_t* Nbf;
     int gather_blocks;       // blocks [0, gather_blocks) gather rows
@@ -223,7 +226,15 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
         else f = acc;
         a.fpos[i] = f;
         if (a.pos_out) a.pos_out[i] = f;
-        if (MODEL == KGE_TRANSE_L2) a.o_n2[i] = on;
+        if (MODEL == KGE_TRANSE_L2) {
+            a.o_n2[i] = on;
+            a.inv_dpos[i] = acc > 0.f ? 1.f / sqrtf(acc) : 0.f;
+        }
+        // positive part of the logistic loss (Sec. 2, y = +1) and its derivative
+        const float invb = 1.f / (float)a.b;
+        const float e = expf(-fabsf(f));
+        a.row_loss[i] = (fmaxf(-f, 0.f) + log1pf(e)) * invb;
+        a.cpos[i] = -((f >= 0.f ? e : 1.f) / (1.f + e)) * invb;
     }
 }
 
@@ -248,6 +259,7 @@ void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds
     a.bf16 = c->cfg.gemm_input;
     a.gamma = gamma; a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
     a.O = c->O; a.Nst = c->Nst; a.fpos = c->fpos; a.pos_out = pos_out; a.o_n2 = c->o_n2; a.n_n2 = c->n_n2;
+    a.cpos = c->cpos; a.inv_dpos = c->inv_dpos; a.row_loss = c->row_loss;
     a.Obf = c->Obf; a.Nbf = c->Nbf;
     const int model = c->cfg.model;
     const bool cplx = model == KGE_COMPLEX || model == KGE_ROTATE;

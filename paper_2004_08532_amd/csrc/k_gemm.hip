@@ -12,17 +12,27 @@
 // Kernel shape.  These products are small (0.16 GFLOP forward at b = 1000, k = 200, D = 400) and the chip has
 // 1024 SIMDs, so a workgroup owns one 32x32 output tile and its NW wavefronts split the K dimension: wave w
 // takes K-blocks w, w + NW, ... of 32.  Each wave stages its own 32x32 A and B blocks in a private LDS
-// region (coalesced 16-byte global loads, no workgroup barrier in the main loop), feeds
-// v_mfma_f32_32x32x2_f32, and the NW partial tiles are summed through LDS in a fixed order at the end, so
-// results do not depend on scheduling.  Operands may be stored K-contiguous ("KC": [rows][K]) or
-// row-contiguous ("MC": [K][rows]); both are read from memory as they lie, no transposed copies are made.
+// region (coalesced, branch-free 16-byte global loads that are all in flight together; no workgroup barrier in
+// the main loop), feeds v_mfma_f32_32x32x2_f32, and the NW partial tiles are summed through LDS in a fixed
+// order at the end, so results do not depend on scheduling.  Operands may be stored K-contiguous ("KC":
+// [rows][K]) or row-contiguous ("MC": [K][rows]); both are read from memory as they lie.
+//
+// What is fused into the backward launch (one launch computes dO and dN; their tiles run side by side):
+//   * with uniform negative weights W is an elementwise function of the stored score, so it is formed while the
+//     A operand is loaded (no separate loss kernel, no W matrix in memory); the tiles of dO that own column
+//     block 0 also add up softplus(f-) for the loss value, and TransE-L2's rowsum(W) / colsum(W) fall out of the
+//     same loads;
+//   * for TransE-L2 and DistMult the chain rule from dL/do to the head, tail and relation gradient rows is
+//     elementwise, so the dO epilogue writes those rows directly (no dL/do array, no separate chain kernel);
+//     the rows it needs for that are fetched before the K loop starts.
 #include "kge_common.h"
 
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-enum { EPI_PLAIN = 0, EPI_L2_FWD = 1, EPI_MINUS_ROWV_X = 2, EPI_MINUS_AROWSUM_X = 3 };
+enum { EPI_PLAIN = 0, EPI_L2_FWD = 1, EPI_L2_DO = 2, EPI_L2_DN = 3, EPI_CHAIN_L2 = 4, EPI_CHAIN_DM = 5 };
+enum { TF_NONE = 0, TF_DOT = 1, TF_L2 = 2 };  // how the A operand is derived from what is stored
 
 struct GemmArgs {
     const float* A;
@@ -31,29 +41,61 @@ struct GemmArgs {
     int M, N, K;
     int lda, ldb, ldc;
     int64_t sA, sB, sC;  // chunk strides (floats)
-    const float* rowv;   // indexed by m (per chunk stride s_rowv)
-    const float* colv;   // indexed by n (per chunk stride s_colv)
+    const float* rowv;   // EPI_L2_FWD: |o|^2 per row (chunk stride s_rowv)
+    const float* colv;   // EPI_L2_FWD: |n|^2 per column (chunk stride s_colv)
     int64_t s_rowv, s_colv;
-    const float* X;      // [M x ldx] correction operand
+    const float* X;      // [M x ldx] operand of the TransE-L2 correction term (o rows for dO, n rows for dN)
     int ldx;
     int64_t sX;
     float gamma;
     int store_dist;      // EPI_L2_FWD: store the distance instead of gamma - distance
-    int gx, gy, tiles;   // tiles along N, along M, and in total (over all chunks); set by launch()
+    int gx, gy, tiles;   // tiles along N, along M, and in total (over all chunks); set by the launchers
+    // A-operand transform (uniform negative weights): W = wk * sigmoid(f) [/ distance]
+    float wk;            // 1 / (k b)
+    float* neg_loss_part;  // [tiles along M, all chunks] sum of wk * softplus(f-) over the tile's rows
+    // chain-rule epilogues
+    StepIds ids;
+    const float* E;
+    const float* R;
+    const float* cpos;
+    const float* inv_dpos;
+    float* Gent;
+    float* Grel;
+    int b, D;
+    int64_t n_ent, n_rel;
 };
 
 constexpr int TILE = 32;
 constexpr int KC_PITCH = 36;                 // floats; 16-byte aligned rows, conflict-free 128-bit reads
 constexpr int REGION = TILE * KC_PITCH;      // floats per staged operand block
 
+__device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
+
+// W from a stored score (TF_DOT) or distance (TF_L2); optionally accumulates softplus(f).
+// Every W element is formed once per tile that reads it (a dozen times per step in all), so this uses the
+// hardware exp2 / log2 / reciprocal (1 ulp each; the argument scaling costs another few ulp at |f| ~ 10), which
+// keeps W within about 1e-6 relative: the same size as the rounding of the fp32 products it is multiplied into.
+template <int TF, bool LOSS>
+__device__ __forceinline__ float w_from_stored(float raw, float gamma, float wk, float& loss) {
+    const float f = TF == TF_L2 ? gamma - raw : raw;
+    const float e = __builtin_amdgcn_exp2f(-fabsf(f) * 1.4426950408889634f);  // exp(-|f|) in (0, 1]
+    const float sig = (f >= 0.f ? 1.f : e) * __builtin_amdgcn_rcpf(1.f + e);
+    if (LOSS) loss += fmaxf(f, 0.f) + __builtin_amdgcn_logf(1.f + e) * 0.6931471805599453f;
+    const float coef = wk * sig;
+    if (TF == TF_L2) return raw > 0.f ? coef * __builtin_amdgcn_rcpf(raw) : 0.f;
+    return coef;
+}
+
 // Loads 32x32 blocks of one operand into registers (zero-filled outside the matrix).  The per-lane row pointers
-// and edge masks are set up once; a block load is then four 16-byte loads and a few selects.
+// and edge masks are set up once.  Loads are branch-free: the four loads of a block are issued unconditionally
+// (from a clamped, always valid address) and masked afterwards, so that all of them, and those of the other
+// operand, are in flight together.
 // KC: element (row, kk) at base[(r0 + row) * ld + k0 + kk]; lane covers row = lane/8 + 8*it, kk = 4*(lane%8)..+3
 // MC: element (row, kk) at base[(k0 + kk) * ld + r0 + row]; lane covers kk = lane/8 + 8*it, row = 4*(lane%8)..+3
 template <bool KC>
 struct BlockLoader {
-    const float* p[4];  // KC: start of the lane's row; MC: row (lane/8 + 8*it) of K-block 0 at the lane's column
-    bool ok[4];         // KC: the lane's row exists; MC: unused
+    const float* p[4];     // KC: start of the lane's row; MC: row (lane/8 + 8*it) of K-block 0 at the lane's column
+    bool ok[4];            // KC: the lane's row exists
     const float* p0_safe;  // an address that is always valid to read 16 bytes from
     int minor, major0, ld, K;
     bool m1, m2, m3, any;  // MC: which of the lane's 4 consecutive rows exist
@@ -81,39 +123,50 @@ struct BlockLoader {
             }
         }
     }
-    // Branch-free: the four loads are issued unconditionally (from a clamped, always valid address) and masked
-    // afterwards, so that all of them, and those of the other operand, are in flight together.
-    __device__ __forceinline__ void load(int kb, float4 (&reg)[4]) const {
+    __device__ __forceinline__ void issue(int kb, float4 (&reg)[4]) const {
         const int k0 = kb * 32;
         if (KC) {
             const int gk = k0 + minor;
-            const bool kin = gk < K;
-            const int koff = kin ? gk : 0;  // the first 16 bytes of a row are always there
+            const int koff = gk < K ? gk : 0;  // the first 16 bytes of a row are always there
 #pragma unroll
             for (int it = 0; it < 4; ++it) reg[it] = ld4(p[it] + koff);
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const bool v0 = ok[it] && kin;
-                reg[it].x = v0 ? reg[it].x : 0.f;
-                reg[it].y = (v0 && gk + 1 < K) ? reg[it].y : 0.f;
-                reg[it].z = (v0 && gk + 2 < K) ? reg[it].z : 0.f;
-                reg[it].w = (v0 && gk + 3 < K) ? reg[it].w : 0.f;
-            }
         } else {
-            bool kin[4];
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                kin[it] = k0 + major0 + 8 * it < K;
-                reg[it] = ld4(kin[it] ? p[it] + (int64_t)k0 * ld : p0_safe);
-            }
+            for (int it = 0; it < 4; ++it)
+                reg[it] = ld4(k0 + major0 + 8 * it < K ? p[it] + (int64_t)k0 * ld : p0_safe);
+        }
+    }
+    // validity of element e (0..3) of register it for K-block kb
+    __device__ __forceinline__ bool valid(int kb, int it, int e) const {
+        const int k0 = kb * 32;
+        if (KC) return ok[it] && k0 + minor + e < K;
+        const bool kin = k0 + major0 + 8 * it < K;
+        return kin && (e == 0 ? any : (e == 1 ? m1 : (e == 2 ? m2 : m3)));
+    }
+    __device__ __forceinline__ void mask(int kb, float4 (&reg)[4]) const {
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const bool v0 = any && kin[it];
-                reg[it].x = v0 ? reg[it].x : 0.f;
-                reg[it].y = (v0 && m1) ? reg[it].y : 0.f;
-                reg[it].z = (v0 && m2) ? reg[it].z : 0.f;
-                reg[it].w = (v0 && m3) ? reg[it].w : 0.f;
+        for (int it = 0; it < 4; ++it) {
+            reg[it].x = valid(kb, it, 0) ? reg[it].x : 0.f;
+            reg[it].y = valid(kb, it, 1) ? reg[it].y : 0.f;
+            reg[it].z = valid(kb, it, 2) ? reg[it].z : 0.f;
+            reg[it].w = valid(kb, it, 3) ? reg[it].w : 0.f;
+        }
+    }
+    // mask + W transform of the valid elements
+    template <int TF, bool LOSS>
+    __device__ __forceinline__ void mask_tf(int kb, float4 (&reg)[4], float gamma, float wk, float& loss) const {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            float v[4] = {reg[it].x, reg[it].y, reg[it].z, reg[it].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float l = 0.f;
+                const float wv = w_from_stored<TF, LOSS>(v[e], gamma, wk, l);
+                const bool ok_ = valid(kb, it, e);
+                v[e] = ok_ ? wv : 0.f;
+                if (LOSS) loss += ok_ ? l : 0.f;
             }
+            reg[it] = make_float4(v[0], v[1], v[2], v[3]);
         }
     }
 };
@@ -141,26 +194,63 @@ __device__ __forceinline__ void lds_frag(const float* region, int lane, int q, f
     }
 }
 
-template <int NW, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(NW * 64) void k_gemm_f32(GemmArgs g) {
-    __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Each XCD gets a
+// contiguous range of tiles (row-major, column tiles fastest), so the tiles that share an A row-block run on one
+// XCD and re-read it from that L2 instead of from memory.  q = index of the workgroup within its XCD.
+__device__ __forceinline__ int xcd_tile(int q, int per_xcd) { return (blockIdx.x & 7) * per_xcd + q; }
+
+// One 32x32 output tile: K loop, cross-wave sum, epilogue.
+template <int NW, bool A_KC, bool B_KC, int TF, int EPI, bool IS_DO>
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*lds)[2][REGION]) {
+    constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM;
+    constexpr bool WANT_ASUM = EPI == EPI_L2_DO || EPI == EPI_L2_DN || EPI == EPI_CHAIN_L2;
+    constexpr bool WANT_LOSS = TF != TF_NONE && IS_DO;  // the dO tiles of column block 0 add up the loss
+    constexpr int NE = TILE * TILE / (NW * 64);           // output elements per thread
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    // Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Give each XCD
-    // a contiguous range of tiles (row-major, column tiles fastest) so that the tiles that share an A row-block
-    // run on one XCD and re-read it from that L2 instead of from memory.
-    const int per_xcd = gridDim.x >> 3;
-    const int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (tile >= g.tiles) return;
-    const int n0 = (tile % g.gx) * TILE, m0 = ((tile / g.gx) % g.gy) * TILE, c = tile / (g.gx * g.gy);
+    const int n0 = (tile % g.gx) * TILE, mt = (tile / g.gx) % g.gy, m0 = mt * TILE, c = tile / (g.gx * g.gy);
     const float* A = g.A + c * g.sA;
     const float* B = g.B + c * g.sB;
     float* As = lds[w][0];
     float* Bs = lds[w][1];
 
+    // ---- chain-rule epilogues: fetch what they need now, so that it arrives while the K loop runs
+    float e_o[NE], e_c[NE], e_a[NE], e_r[NE], e_cp[NE], e_inv[NE];
+    int64_t e_pa[NE], e_pc[NE];  // gradient-row positions of the kept / replaced entity
+    bool e_head = false;
+    if (CHAIN) {
+        const StepView sv = step_view(g.ids);
+        e_head = sv.side == KGE_NEG_HEAD;
+#pragma unroll
+        for (int it = 0; it < NE; ++it) {
+            const int e = threadIdx.x + it * NW * 64;
+            const int gm = m0 + (e >> 5), gn = n0 + (e & 31);
+            const bool in = gm < g.M && gn < g.N;
+            const int i = c * g.M + (in ? gm : 0);  // index of the positive in the mini-batch
+            const int d = in ? gn : 0;
+            const int64_t hid = clamp_id(sv.h[i], g.n_ent), tid = clamp_id(sv.t[i], g.n_ent);
+            const int64_t aid = e_head ? tid : hid, cid = e_head ? hid : tid;
+            e_o[it] = g.X[(int64_t)i * g.ldx + d];
+            e_c[it] = g.E[cid * g.D + d];
+            e_cp[it] = g.cpos[i];
+            e_pa[it] = e_head ? (int64_t)g.b + i : i;
+            e_pc[it] = e_head ? i : (int64_t)g.b + i;
+            e_a[it] = 0.f; e_r[it] = 0.f; e_inv[it] = 0.f;
+            if (EPI == EPI_CHAIN_DM) {
+                const int64_t rid = clamp_id(sv.r[i], g.n_rel);
+                e_a[it] = g.E[aid * g.D + d];
+                e_r[it] = g.R[rid * g.D + d];
+            } else {
+                e_inv[it] = g.inv_dpos[i];
+            }
+        }
+    }
+
     floatx16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    float a_sum = 0.f;  // EPI_MINUS_AROWSUM_X: sum over this lane's K-values of A[m = lane%32][.]
+    float a_sum = 0.f;  // sum over this lane's K-values of A[m = lane%32][.]  (rowsum / colsum of W)
+    float loss = 0.f;
+    const bool loss_tile = WANT_LOSS && n0 == 0;
 
     const int nblk = (g.K + TILE - 1) / TILE;
     float4 ra[4], rb[4];
@@ -170,16 +260,25 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_f32(GemmArgs g) {
     lb.init(B, g.ldb, n0, g.N, g.K, lane);
     int kb = w;
     if (kb < nblk) {
-        la.load(kb, ra);
-        lb.load(kb, rb);
+        la.issue(kb, ra);
+        lb.issue(kb, rb);
     }
     while (kb < nblk) {
+        if (TF == TF_NONE) {
+            la.mask(kb, ra);
+        } else if (loss_tile) {
+            la.template mask_tf<TF, WANT_LOSS>(kb, ra, g.gamma, g.wk, loss);
+        } else {
+            float unused = 0.f;
+            la.template mask_tf<TF, false>(kb, ra, g.gamma, g.wk, unused);
+        }
+        lb.mask(kb, rb);
         lds_store<A_KC>(As, lane, ra);
         lds_store<B_KC>(Bs, lane, rb);
         const int nxt = kb + NW;
         if (nxt < nblk) {  // next block's global loads fly while this block is multiplied
-            la.load(nxt, ra);
-            lb.load(nxt, rb);
+            la.issue(nxt, ra);
+            lb.issue(nxt, rb);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -192,7 +291,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_f32(GemmArgs g) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[t], fb[t], acc, 0, 0, 0);
-                if (EPI == EPI_MINUS_AROWSUM_X) a_sum += fa[t];
+                if (WANT_ASUM) a_sum += fa[t];
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -206,56 +305,118 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_f32(GemmArgs g) {
         const int i = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
         As[i * TILE + (lane & 31)] = acc[v];
     }
-    if (EPI == EPI_MINUS_AROWSUM_X) {
+    if (WANT_ASUM) {
         a_sum += __shfl_xor(a_sum, 32, 64);
         if (lane < 32) Bs[lane] = a_sum;
     }
+    if (WANT_LOSS) {
+        loss = wave_sum(loss);
+        if (lane == 0) Bs[32] = loss;
+    }
     __syncthreads();
+    if (WANT_LOSS && loss_tile && threadIdx.x == 0) {
+        float s = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) s += lds[ww][1][32];
+        g.neg_loss_part[c * g.gy + mt] = s * g.wk;
+    }
     float* C = g.C + c * g.sC;
-    for (int e = threadIdx.x; e < TILE * TILE; e += NW * 64) {
+#pragma unroll
+    for (int it = 0; it < NE; ++it) {
+        const int e = threadIdx.x + it * NW * 64;
         const int i = e >> 5, j = e & 31;
         const int gm = m0 + i, gn = n0 + j;
         if (gm >= g.M || gn >= g.N) continue;
         float s = 0.f;
 #pragma unroll
         for (int ww = 0; ww < NW; ++ww) s += lds[ww][0][e];
-        float out = s;
-        if (EPI == EPI_L2_FWD) {
-            const float d2 = g.rowv[c * g.s_rowv + gm] + g.colv[c * g.s_colv + gn] - 2.f * s;
-            const float d = sqrtf(fmaxf(d2, 0.f));
-            out = g.store_dist ? d : g.gamma - d;
-        } else if (EPI == EPI_MINUS_ROWV_X) {
-            out = s - g.rowv[c * g.s_rowv + gm] * g.X[c * g.sX + (int64_t)gm * g.ldx + gn];
-        } else if (EPI == EPI_MINUS_AROWSUM_X) {
-            float rs = 0.f;
+        float rs = 0.f;
+        if (WANT_ASUM) {
 #pragma unroll
             for (int ww = 0; ww < NW; ++ww) rs += lds[ww][1][i];
-            out = s - rs * g.X[c * g.sX + (int64_t)gm * g.ldx + gn];
         }
-        C[(int64_t)gm * g.ldc + gn] = out;
+        if (EPI == EPI_PLAIN) {
+            C[(int64_t)gm * g.ldc + gn] = s;
+        } else if (EPI == EPI_L2_FWD) {
+            const float d2 = g.rowv[c * g.s_rowv + gm] + g.colv[c * g.s_colv + gn] - 2.f * s;
+            const float d = sqrtf(fmaxf(d2, 0.f));
+            C[(int64_t)gm * g.ldc + gn] = g.store_dist ? d : g.gamma - d;
+        } else if (EPI == EPI_L2_DO || EPI == EPI_L2_DN) {
+            C[(int64_t)gm * g.ldc + gn] = s - rs * g.X[c * g.sX + (int64_t)gm * g.ldx + gn];
+        } else if (EPI == EPI_CHAIN_L2) {
+            // dL/do = W n - rowsum(W) o  +  dL/df+ * d(gamma - |o - c|)/do
+            const float dir = (e_o[it] - e_c[it]) * e_inv[it];
+            const float go = s - rs * e_o[it] - e_cp[it] * dir;
+            g.Gent[e_pa[it] * g.D + gn] = go;
+            g.Gent[e_pc[it] * g.D + gn] = e_cp[it] * dir;
+            g.Grel[(int64_t)(c * g.M + gm) * g.D + gn] = e_head ? -go : go;
+        } else {  // EPI_CHAIN_DM: o = a * r, psi = o . x
+            const float go = s + e_cp[it] * e_c[it];
+            g.Gent[e_pa[it] * g.D + gn] = go * e_r[it];
+            g.Gent[e_pc[it] * g.D + gn] = e_cp[it] * e_o[it];
+            g.Grel[(int64_t)(c * g.M + gm) * g.D + gn] = go * e_a[it];
+        }
+    }
+}
+
+template <int NW, int EPI>
+__global__ __launch_bounds__(NW * 64) void k_gemm_fwd(GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
+    const int tile = xcd_tile(blockIdx.x >> 3, gridDim.x >> 3);
+    if (tile >= g.tiles) return;
+    gemm_tile<NW, true, true, TF_NONE, EPI, false>(g, tile, lds);
+}
+
+// dN tiles first (their K is the chunk size, they run longest), then dO tiles; each XCD gets its share of both.
+template <int NW, int TF, int EPI_O, int EPI_N>
+__global__ __launch_bounds__(NW * 64) void k_gemm_bwd(GemmArgs gO, GemmArgs gN, int per_xcd_n, int per_xcd_o) {
+    __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
+    const int q = blockIdx.x >> 3;
+    if (q < per_xcd_n) {
+        const int tile = xcd_tile(q, per_xcd_n);
+        if (tile < gN.tiles) gemm_tile<NW, false, false, TF, EPI_N, false>(gN, tile, lds);
+    } else {
+        const int tile = xcd_tile(q - per_xcd_n, per_xcd_o);
+        if (tile < gO.tiles) gemm_tile<NW, true, false, TF, EPI_O, true>(gO, tile, lds);
     }
 }
 
 // Number of K-splitting waves per tile.  With few tiles every K-block gets its own wave (one round of memory
 // latency, all SIMDs of the CU busy); with thousands of tiles four waves per tile keep the cross-wave sum cheap.
-int pick_nw(int tiles, int nblk) {
+int pick_nw(int tiles, int nblk, int cap) {
     if (tiles >= 1024) return 4;
     int nw = 4;
-    while (nw < 16 && nw < nblk) nw *= 2;
+    while (nw < cap && nw < nblk) nw *= 2;
     return nw;
 }
 
-template <bool A_KC, bool B_KC, int EPI>
-void launch(GemmArgs g, int chunks, hipStream_t st) {
+void set_tiling(GemmArgs& g, int chunks) {
     g.gx = (g.N + TILE - 1) / TILE;
     g.gy = (g.M + TILE - 1) / TILE;
     g.tiles = g.gx * g.gy * chunks;
+}
+
+template <int EPI>
+void launch_fwd(GemmArgs g, int chunks, hipStream_t st) {
+    set_tiling(g, chunks);
     const dim3 grid(8 * ((g.tiles + 7) / 8));
-    const int nblk = (g.K + TILE - 1) / TILE;
-    const int nw = pick_nw(g.tiles, nblk);
-    if (nw == 4) hipLaunchKernelGGL((k_gemm_f32<4, A_KC, B_KC, EPI>), grid, dim3(256), 0, st, g);
-    else if (nw == 8) hipLaunchKernelGGL((k_gemm_f32<8, A_KC, B_KC, EPI>), grid, dim3(512), 0, st, g);
-    else hipLaunchKernelGGL((k_gemm_f32<16, A_KC, B_KC, EPI>), grid, dim3(1024), 0, st, g);
+    const int nw = pick_nw(g.tiles, (g.K + TILE - 1) / TILE, 16);
+    if (nw == 4) hipLaunchKernelGGL((k_gemm_fwd<4, EPI>), grid, dim3(256), 0, st, g);
+    else if (nw == 8) hipLaunchKernelGGL((k_gemm_fwd<8, EPI>), grid, dim3(512), 0, st, g);
+    else hipLaunchKernelGGL((k_gemm_fwd<16, EPI>), grid, dim3(1024), 0, st, g);
+}
+
+template <int TF, int EPI_O, int EPI_N>
+void launch_bwd(GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st) {
+    set_tiling(gO, chunks);
+    set_tiling(gN, chunks);
+    const int per_n = (gN.tiles + 7) / 8, per_o = (gO.tiles + 7) / 8;
+    const dim3 grid(8 * (per_n + per_o));
+    const int nblk = ((gO.K > gN.K ? gO.K : gN.K) + TILE - 1) / TILE;
+    // at most 8 waves: 74 KB of LDS per workgroup, so two workgroups share a CU
+    const int nw = pick_nw(gO.tiles + gN.tiles, nblk, 8);
+    if (nw == 4) hipLaunchKernelGGL((k_gemm_bwd<4, TF, EPI_O, EPI_N>), grid, dim3(256), 0, st, gO, gN, per_n, per_o);
+    else hipLaunchKernelGGL((k_gemm_bwd<8, TF, EPI_O, EPI_N>), grid, dim3(512), 0, st, gO, gN, per_n, per_o);
 }
 
 }  // namespace
@@ -273,32 +434,52 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     g.rowv = c->o_n2; g.colv = c->n_n2; g.s_rowv = gsz; g.s_colv = k;
     g.gamma = gamma; g.store_dist = dist_mode;
     const int chunks = b / gsz;
-    if (c->cfg.model == KGE_TRANSE_L2) launch<true, true, EPI_L2_FWD>(g, chunks, st);
-    else launch<true, true, EPI_PLAIN>(g, chunks, st);
+    if (c->cfg.model == KGE_TRANSE_L2) launch_fwd<EPI_L2_FWD>(g, chunks, st);
+    else launch_fwd<EPI_PLAIN>(g, chunks, st);
 }
 
-// dO_c = W_c N_c (- rowsum(W) o)  and  dN_c = W_c^T O_c (- colsum(W) n), the latter straight into the gradient
-// rows of the corrupting entities (key positions 2b ..).
-void kge_gemm_neg_backward(kge_ctx* c, int b, int k, int gsz, hipStream_t st) {
-    const int D = c->cfg.ent_dim;
+bool kge_gemm_backward_forms_w(const kge_ctx* c) { return c->cfg.adv_temperature == 0.f; }
+bool kge_gemm_backward_does_chain(const kge_ctx* c) {
+    return c->cfg.model == KGE_TRANSE_L2 || c->cfg.model == KGE_DISTMULT;
+}
+int kge_gemm_loss_parts(const kge_ctx* c, int b, int gsz) {
+    return kge_gemm_backward_forms_w(c) ? (b / gsz) * ((gsz + TILE - 1) / TILE) : 0;
+}
+
+// dO_c = W_c N_c (- rowsum(W) o)  and  dN_c = W_c^T O_c (- colsum(W) n) in one launch.  dN goes straight into the
+// gradient rows of the corrupting entities (key positions 2b ..); dO goes through the chain rule into the
+// gradient rows of the positives (TransE-L2, DistMult) or into GO for k_chain (ComplEx).
+void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const StepIds& ids, int k, int gsz, float gamma,
+                           hipStream_t st) {
+    const int D = c->cfg.ent_dim, b = ids.b;
     const int chunks = b / gsz;
-    const bool l2 = c->cfg.model == KGE_TRANSE_L2;
+    const int model = c->cfg.model;
     GemmArgs g = {};
     g.A = c->S; g.B = c->Nst; g.C = c->GO;
     g.M = gsz; g.N = D; g.K = k;
     g.lda = c->ld_s; g.ldb = D; g.ldc = D;
     g.sA = (int64_t)gsz * c->ld_s; g.sB = (int64_t)k * D; g.sC = (int64_t)gsz * D;
-    g.rowv = c->w_rowsum; g.s_rowv = gsz;
     g.X = c->O; g.ldx = D; g.sX = (int64_t)gsz * D;
-    if (l2) launch<true, false, EPI_MINUS_ROWV_X>(g, chunks, st);
-    else launch<true, false, EPI_PLAIN>(g, chunks, st);
+    g.gamma = gamma; g.wk = 1.f / ((float)k * (float)b); g.neg_loss_part = c->neg_loss_part;
+    g.ids = ids; g.E = E; g.R = R; g.cpos = c->cpos; g.inv_dpos = c->inv_dpos; g.Gent = c->Gent; g.Grel = c->Grel;
+    g.b = b; g.D = D; g.n_ent = c->cfg.num_entities; g.n_rel = c->cfg.num_relations;
 
-    GemmArgs q = {};
+    GemmArgs q = g;
     q.A = c->S; q.B = c->O; q.C = c->Gent + (int64_t)2 * b * D;
     q.M = k; q.N = D; q.K = gsz;
     q.lda = c->ld_s; q.ldb = D; q.ldc = D;
     q.sA = (int64_t)gsz * c->ld_s; q.sB = (int64_t)gsz * D; q.sC = (int64_t)k * D;
     q.X = c->Nst; q.ldx = D; q.sX = (int64_t)k * D;
-    if (l2) launch<false, false, EPI_MINUS_AROWSUM_X>(q, chunks, st);
-    else launch<false, false, EPI_PLAIN>(q, chunks, st);
+
+    const bool tf = kge_gemm_backward_forms_w(c);
+    if (model == KGE_TRANSE_L2) {
+        if (tf) launch_bwd<TF_L2, EPI_CHAIN_L2, EPI_L2_DN>(g, q, chunks, st);
+        else launch_bwd<TF_NONE, EPI_CHAIN_L2, EPI_L2_DN>(g, q, chunks, st);
+    } else if (model == KGE_DISTMULT) {
+        if (tf) launch_bwd<TF_DOT, EPI_CHAIN_DM, EPI_PLAIN>(g, q, chunks, st);
+        else launch_bwd<TF_NONE, EPI_CHAIN_DM, EPI_PLAIN>(g, q, chunks, st);
+    } else {
+        if (tf) launch_bwd<TF_DOT, EPI_PLAIN, EPI_PLAIN>(g, q, chunks, st);
+        else launch_bwd<TF_NONE, EPI_PLAIN, EPI_PLAIN>(g, q, chunks, st);
+    }
 }

@@ -32,7 +32,9 @@ struct UpdateArgs {
     int tiles[2];
     int D[2];
     float lr, eps;
-    const float* row_loss;
+    const float* row_loss;       // [b] per-positive loss terms
+    const float* neg_loss_part;  // [n_loss_parts] negative-side loss sums of the backward launch (may be none)
+    int n_loss_parts;
     int b;
     float* loss_out;        // direct mode: this step's scalar; replay mode: one float per step
     int64_t* step_ptr;      // replay mode: which step is running; advanced by k_update_fixup
@@ -60,6 +62,7 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update_tiles(UpdateArgs a) {
         __shared__ float part[UPD_THREADS];
         float s = 0.f;
         for (int i = tid; i < a.b; i += UPD_THREADS) s += a.row_loss[i];
+        for (int i = tid; i < a.n_loss_parts; i += UPD_THREADS) s += a.neg_loss_part[i];
         part[tid] = s;
         __syncthreads();
         for (int o = UPD_THREADS / 2; o > 0; o >>= 1) {
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update_fixup(UpdateArgs a) {
 }  // namespace
 
 void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, const StepIds& ids, float lr,
-                       hipStream_t st) {
+                       int n_loss_parts, hipStream_t st) {
     UpdateArgs a;
     const int b = ids.b, n_ent_keys = 2 * ids.b + ids.n_neg, n_rel_keys = ids.b;
     float* loss_out = ids.loss_out;
@@ -228,6 +231,7 @@ void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, con
     a.tiles[0] = (n_ent_keys + TILE_R - 1) / TILE_R; a.tiles[1] = (n_rel_keys + TILE_R - 1) / TILE_R;
     a.D[0] = c->cfg.ent_dim; a.D[1] = c->cfg.rel_dim;
     a.lr = lr; a.eps = c->eps; a.row_loss = c->row_loss; a.b = b; a.loss_out = loss_out;
+    a.neg_loss_part = c->neg_loss_part; a.n_loss_parts = n_loss_parts;
     const int tiles = a.tiles[0] + a.tiles[1];
     hipLaunchKernelGGL(k_update_tiles, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
     hipLaunchKernelGGL(k_update_fixup, dim3(tiles), dim3(UPD_THREADS), 0, st, a);

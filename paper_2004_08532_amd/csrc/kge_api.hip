@@ -113,30 +113,38 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
         if (is_gemm_model(c->cfg.model)) kge_gemm_neg_score(c, B, K, G, gamma, c->S, c->ld_s, 1, st);
         else kge_pair_neg_score(c, B, K, G, gamma, c->S, c->ld_s, st);
     }
-    {
+    // The matrix-product models fold the loss (uniform weights) and the chain rule (TransE-L2, DistMult) into
+    // the backward launch; whatever is not folded runs as its own kernel.
+    const bool gemm = is_gemm_model(c->cfg.model);
+    const bool run_loss = !(gemm && kge_gemm_backward_forms_w(c));
+    const bool run_chain = !(gemm && kge_gemm_backward_does_chain(c));
+    const int n_loss_parts = gemm ? kge_gemm_loss_parts(c, B, G) : 0;
+    if (run_loss) {
         ProfScope p(c, KGE_PROF_LOSS, st);
         kge_launch_loss(c, B, K, gamma, st);
     }
     {
         ProfScope p(c, KGE_PROF_BACKWARD, st);
-        if (is_gemm_model(c->cfg.model)) kge_gemm_neg_backward(c, B, K, G, st);
+        if (gemm) kge_gemm_neg_backward(c, ent, rel, ids, K, G, gamma, st);
         else kge_pair_neg_backward(c, B, K, G, st);
     }
-    {
+    if (run_chain) {
         ProfScope p(c, KGE_PROF_CHAIN, st);
         kge_launch_chain(c, ent, rel, ids, st);
     }
     if (long_lists) KGE_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
     {
         ProfScope p(c, KGE_PROF_UPDATE, st);
-        kge_launch_update(c, ent, ent_state, rel, rel_state, ids, lr, st);
+        kge_launch_update(c, ent, ent_state, rel, rel_state, ids, lr, n_loss_parts, st);
     }
     KGE_HIP(c, hipGetLastError());
     if (c->prof_on) {
         KGE_HIP(c, hipStreamSynchronize(st));
         for (int s = 0; s < KGE_PROF_SLOTS; ++s) {
             float ms = 0.f;
-            if (s == KGE_PROF_SORT && !long_lists) continue;  // no separate sort kernel ran
+            if ((s == KGE_PROF_SORT && !long_lists) || (s == KGE_PROF_LOSS && !run_loss) ||
+                (s == KGE_PROF_CHAIN && !run_chain))
+                continue;  // that kernel did not run in this configuration
             if (hipEventElapsedTime(&ms, c->prof_ev[s][0], c->prof_ev[s][1]) == hipSuccess) c->prof_ms[s] += ms;
         }
         c->prof_steps += 1;
@@ -239,7 +247,8 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t o_O = take(B * D * 4), o_N = take(NR * D * 4), o_S = take(B * c->ld_s * 4), o_GO = take(B * D * 4);
     const size_t o_Ge = take(EK * D * 4), o_Gr = take(B * Dr * 4);
     const size_t o_fpos = take(B * 4), o_on2 = take(B * 4), o_nn2 = take(NR * 4), o_cpos = take(B * 4);
-    const size_t o_rl = take(B * 4), o_wrs = take(B * 4);
+    const size_t o_rl = take(B * 4), o_wrs = take(B * 4), o_idp = take(B * 4);
+    const size_t o_nlp = take((B / 32 + cfg->max_chunks + 1) * 4);
     const size_t o_ek0 = take(EK * 4), o_ek1 = take(EK * 4), o_ep0 = take(EK * 4), o_ep1 = take(EK * 4);
     const size_t o_rk0 = take(B * 4), o_rk1 = take(B * 4), o_rp0 = take(B * 4), o_rp1 = take(B * 4);
     const size_t te = EK / 8 + 1, tr = B / 8 + 1;
@@ -258,6 +267,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->GO = (float*)(base + o_GO); c->Gent = (float*)(base + o_Ge); c->Grel = (float*)(base + o_Gr);
     c->fpos = (float*)(base + o_fpos); c->o_n2 = (float*)(base + o_on2); c->n_n2 = (float*)(base + o_nn2);
     c->cpos = (float*)(base + o_cpos); c->row_loss = (float*)(base + o_rl); c->w_rowsum = (float*)(base + o_wrs);
+    c->inv_dpos = (float*)(base + o_idp); c->neg_loss_part = (float*)(base + o_nlp);
     c->ekey[0] = (uint32_t*)(base + o_ek0); c->ekey[1] = (uint32_t*)(base + o_ek1);
     c->epos[0] = (uint32_t*)(base + o_ep0); c->epos[1] = (uint32_t*)(base + o_ep1);
     c->rkey[0] = (uint32_t*)(base + o_rk0); c->rkey[1] = (uint32_t*)(base + o_rk1);

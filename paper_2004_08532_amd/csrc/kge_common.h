@@ -36,7 +36,9 @@ struct kge_ctx {
     float* n_n2;     // [max_neg_rows]       |n_j|^2          (TransE-L2)
     float* cpos;     // [max_batch]          dL/df+_i
     float* row_loss; // [max_batch]          loss terms of positive i, already divided by b
-    float* w_rowsum; // [max_batch]          sum_j W_ij       (TransE-L2)
+    float* w_rowsum; // [max_batch]          sum_j W_ij       (TransE-L2, self-adversarial path)
+    float* inv_dpos; // [max_batch]          1 / |o_i - c_i|  (TransE-L2)
+    float* neg_loss_part;  // [max_batch/32 + max_chunks]  negative-side loss sums written by the backward launch
     uint16_t* Obf;   // bf16 copies of O, Nst, W (gemm_input = 1)
     uint16_t* Nbf;
     uint16_t* Wbf;
@@ -115,7 +117,11 @@ void kge_pair_neg_score(kge_ctx* c, int b, int k, int g, float gamma, float* out
 // a4: loss terms and backward coefficients (in place over S)
 void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st);
 // a5: dL/do and the gradient rows of the corrupting entities
-void kge_gemm_neg_backward(kge_ctx* c, int b, int k, int g, hipStream_t st);
+void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const StepIds& ids, int k, int g, float gamma,
+                           hipStream_t st);
+bool kge_gemm_backward_forms_w(const kge_ctx* c);     // W is formed inside the backward launch (no k_loss)
+bool kge_gemm_backward_does_chain(const kge_ctx* c);  // the backward launch writes the positives' gradient rows
+int kge_gemm_loss_parts(const kge_ctx* c, int b, int g);
 void kge_pair_neg_backward(kge_ctx* c, int b, int k, int g, hipStream_t st);
 // a5: positive-pair term and chain rule through phi -> gradient rows of heads, tails and relations
 void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
@@ -123,7 +129,7 @@ void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds&
 void kge_launch_sort(kge_ctx* c, const StepIds& ids, hipStream_t st);
 // a7: per distinct row, sum its gradient rows and apply Adagrad; also reduces the loss terms
 void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, const StepIds& ids, float lr,
-                       hipStream_t st);
+                       int n_loss_parts, hipStream_t st);
 // test hook: distinct ids and multiplicities from the sorted keys
 void kge_launch_dedup_export(kge_ctx* c, int which, int64_t* uniq, int32_t* count, int64_t* n_unique,
                              hipStream_t st);
