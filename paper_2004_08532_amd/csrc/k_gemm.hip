@@ -143,30 +143,15 @@ struct BlockLoader {
         const bool kin = k0 + major0 + 8 * it < K;
         return kin && (e == 0 ? any : (e == 1 ? m1 : (e == 2 ? m2 : m3)));
     }
-    __device__ __forceinline__ void mask(int kb, float4 (&reg)[4]) const {
+    // Elements outside the matrix become `fill` (0 for a plain operand; for an operand that still goes through
+    // w_from_stored, the value that function maps to W = 0 and loss 0).
+    __device__ __forceinline__ void mask(int kb, float4 (&reg)[4], float fill) const {
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
-            reg[it].x = valid(kb, it, 0) ? reg[it].x : 0.f;
-            reg[it].y = valid(kb, it, 1) ? reg[it].y : 0.f;
-            reg[it].z = valid(kb, it, 2) ? reg[it].z : 0.f;
-            reg[it].w = valid(kb, it, 3) ? reg[it].w : 0.f;
-        }
-    }
-    // mask + W transform of the valid elements
-    template <int TF, bool LOSS>
-    __device__ __forceinline__ void mask_tf(int kb, float4 (&reg)[4], float gamma, float wk, float& loss) const {
-#pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            float v[4] = {reg[it].x, reg[it].y, reg[it].z, reg[it].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float l = 0.f;
-                const float wv = w_from_stored<TF, LOSS>(v[e], gamma, wk, l);
-                const bool ok_ = valid(kb, it, e);
-                v[e] = ok_ ? wv : 0.f;
-                if (LOSS) loss += ok_ ? l : 0.f;
-            }
-            reg[it] = make_float4(v[0], v[1], v[2], v[3]);
+            reg[it].x = valid(kb, it, 0) ? reg[it].x : fill;
+            reg[it].y = valid(kb, it, 1) ? reg[it].y : fill;
+            reg[it].z = valid(kb, it, 2) ? reg[it].z : fill;
+            reg[it].w = valid(kb, it, 3) ? reg[it].w : fill;
         }
     }
 };
@@ -215,7 +200,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
 
     // ---- chain-rule epilogues: fetch what they need now, so that it arrives while the K loop runs
     float e_o[NE], e_c[NE], e_a[NE], e_r[NE], e_cp[NE], e_inv[NE];
-    int64_t e_pa[NE], e_pc[NE];  // gradient-row positions of the kept / replaced entity
     bool e_head = false;
     if (CHAIN) {
         const StepView sv = step_view(g.ids);
@@ -232,8 +216,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             e_o[it] = g.X[(int64_t)i * g.ldx + d];
             e_c[it] = g.E[cid * g.D + d];
             e_cp[it] = g.cpos[i];
-            e_pa[it] = e_head ? (int64_t)g.b + i : i;
-            e_pc[it] = e_head ? i : (int64_t)g.b + i;
             e_a[it] = 0.f; e_r[it] = 0.f; e_inv[it] = 0.f;
             if (EPI == EPI_CHAIN_DM) {
                 const int64_t rid = clamp_id(sv.r[i], g.n_rel);
@@ -264,15 +246,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         lb.issue(kb, rb);
     }
     while (kb < nblk) {
-        if (TF == TF_NONE) {
-            la.mask(kb, ra);
-        } else if (loss_tile) {
-            la.template mask_tf<TF, WANT_LOSS>(kb, ra, g.gamma, g.wk, loss);
-        } else {
-            float unused = 0.f;
-            la.template mask_tf<TF, false>(kb, ra, g.gamma, g.wk, unused);
-        }
-        lb.mask(kb, rb);
+        // a stored score of -inf / distance of +inf gives W = 0 and no loss: the fill for elements outside W
+        la.mask(kb, ra, TF == TF_NONE ? 0.f : (TF == TF_DOT ? -INFINITY : INFINITY));
+        lb.mask(kb, rb, 0.f);
         lds_store<A_KC>(As, lane, ra);
         lds_store<B_KC>(Bs, lane, rb);
         const int nxt = kb + NW;
@@ -288,6 +264,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             float fa[4], fb[4];
             lds_frag<A_KC>(As, lane, q, fa);
             lds_frag<B_KC>(Bs, lane, q, fb);
+            if (TF != TF_NONE) {  // every element of the block is read by exactly one lane here
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    if (loss_tile) fa[t] = w_from_stored<TF, true>(fa[t], g.gamma, g.wk, loss);
+                    else { float unused = 0.f; fa[t] = w_from_stored<TF, false>(fa[t], g.gamma, g.wk, unused); }
+                }
+            }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[t], fb[t], acc, 0, 0, 0);
@@ -327,6 +310,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         const int i = e >> 5, j = e & 31;
         const int gm = m0 + i, gn = n0 + j;
         if (gm >= g.M || gn >= g.N) continue;
+        const int bi = c * g.M + gm;  // index of the positive in the mini-batch (chain epilogues)
         float s = 0.f;
 #pragma unroll
         for (int ww = 0; ww < NW; ++ww) s += lds[ww][0][e];
@@ -347,14 +331,14 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             // dL/do = W n - rowsum(W) o  +  dL/df+ * d(gamma - |o - c|)/do
             const float dir = (e_o[it] - e_c[it]) * e_inv[it];
             const float go = s - rs * e_o[it] - e_cp[it] * dir;
-            g.Gent[e_pa[it] * g.D + gn] = go;
-            g.Gent[e_pc[it] * g.D + gn] = e_cp[it] * dir;
-            g.Grel[(int64_t)(c * g.M + gm) * g.D + gn] = e_head ? -go : go;
+            g.Gent[(int64_t)(e_head ? g.b + bi : bi) * g.D + gn] = go;
+            g.Gent[(int64_t)(e_head ? bi : g.b + bi) * g.D + gn] = e_cp[it] * dir;
+            g.Grel[(int64_t)bi * g.D + gn] = e_head ? -go : go;
         } else {  // EPI_CHAIN_DM: o = a * r, psi = o . x
             const float go = s + e_cp[it] * e_c[it];
-            g.Gent[e_pa[it] * g.D + gn] = go * e_r[it];
-            g.Gent[e_pc[it] * g.D + gn] = e_cp[it] * e_o[it];
-            g.Grel[(int64_t)(c * g.M + gm) * g.D + gn] = go * e_a[it];
+            g.Gent[(int64_t)(e_head ? g.b + bi : bi) * g.D + gn] = go * e_r[it];
+            g.Gent[(int64_t)(e_head ? bi : g.b + bi) * g.D + gn] = e_cp[it] * e_o[it];
+            g.Grel[(int64_t)bi * g.D + gn] = go * e_a[it];
         }
     }
 }
@@ -368,8 +352,10 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_fwd(GemmArgs g) {
 }
 
 // dN tiles first (their K is the chunk size, they run longest), then dO tiles; each XCD gets its share of both.
+// Held to 128 registers so that four waves fit on every SIMD (two 8-wave workgroups per CU): all tiles of the
+// Freebase-scale step are then resident at once instead of running in two rounds.
 template <int NW, int TF, int EPI_O, int EPI_N>
-__global__ __launch_bounds__(NW * 64) void k_gemm_bwd(GemmArgs gO, GemmArgs gN, int per_xcd_n, int per_xcd_o) {
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_gemm_bwd(GemmArgs gO, GemmArgs gN, int per_xcd_n, int per_xcd_o) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
     const int q = blockIdx.x >> 3;
     if (q < per_xcd_n) {

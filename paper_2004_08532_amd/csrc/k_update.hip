@@ -3,22 +3,23 @@
 //     S += g^2 ;  theta -= lr * g / (sqrt(S) + eps)
 // Table rows that are not in the batch are never touched.
 //
-// Work is cut by POSITION in the sorted key list, not by row id, so a hub entity that occurs a hundred times in a
-// batch (degree-skewed graphs) does not serialise one workgroup: k_update_tiles gives every workgroup a tile of 8
-// consecutive sorted positions.  Its threads each own one 16-byte column slice; all 8 gradient-row loads and the
-// table / state loads of the runs that lie wholly inside the tile are issued together, then the runs are summed in
-// sorted order.  A run that lies inside the tile is finished on the spot.  A run that crosses a tile boundary
-// leaves a partial sum per tile (the tile's first run in P_first, its last run in P_last), and k_update_fixup, in
-// which the workgroup of the tile where such a run starts adds those partial sums in tile order, finishes it.
-// No atomics, every sum has a fixed order, so the result is a function of the ids and the gradient rows alone.
-// Entity and relation rows go through the same launches; the last workgroup of k_update_tiles adds the
-// per-positive loss terms in a fixed order.
+// Work is cut by POSITION in the sorted key list, not by row id: every workgroup gets a tile of 8 consecutive
+// sorted positions, and a run of equal keys (one distinct row) belongs to the tile in which it ENDS.  The first
+// 16-byte-per-thread row group of the workgroup issues all gradient-row loads of the tile and the table / state
+// loads of the runs that end in it together, then walks the tile in sorted order.  If the tile's first run began
+// in an earlier tile (a row that occurs often: hub entities of degree-skewed graphs, frequent relations), the
+// whole workgroup first finds where it began (one parallel look-back over the keys) and adds up those earlier
+// gradient rows, split over its row groups, through LDS.  Positions of a run that goes on into the next tile are
+// skipped: that tile's workgroup reads them.  One launch, no atomics on data, every sum has a fixed order, so the
+// result is a function of the ids and the gradient rows alone.  Entity and relation rows go through the same
+// launch; its last workgroup adds the loss terms in a fixed order and advances the device step counter.
 #include "kge_common.h"
 
 namespace {
 
 constexpr int TILE_R = 8;
-constexpr int UPD_THREADS = 128;
+constexpr int UPD_THREADS = 512;
+constexpr int LOOKBACK_U = 8;  // gradient rows in flight per thread while summing the earlier part of a run
 
 struct UpdateArgs {
     float* T[2];             // tables: entity, relation
@@ -26,8 +27,6 @@ struct UpdateArgs {
     const float* G[2];       // gradient rows, indexed by key position
     const uint32_t* key[2];  // sorted ids
     const uint32_t* pos[2];  // key position of each sorted entry
-    float* Pfirst[2];        // [tiles x D] partial sum of a tile's first run when it began in an earlier tile
-    float* Plast[2];         // [tiles x D] partial sum of a tile's last run when it goes on in the next tile
     int n[2];                // key list lengths
     int tiles[2];
     int D[2];
@@ -37,7 +36,7 @@ struct UpdateArgs {
     int n_loss_parts;
     int b;
     float* loss_out;        // direct mode: this step's scalar; replay mode: one float per step
-    int64_t* step_ptr;      // replay mode: which step is running; advanced by k_update_fixup
+    int64_t* step_ptr;      // replay mode: which step is running; advanced here, by the one thread that reads it
 };
 
 __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
@@ -55,11 +54,12 @@ __device__ __forceinline__ void adagrad4(float4 g, float4& x, float4& s, float l
     x.w -= adagrad1(g.w, s.w, lr, eps);
 }
 
-__global__ __launch_bounds__(UPD_THREADS) void k_update_tiles(UpdateArgs a) {
+__global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
     int tile = blockIdx.x;
     const int tid = threadIdx.x;
+    __shared__ __attribute__((aligned(16))) float4 red[UPD_THREADS];
     if (tile == a.tiles[0] + a.tiles[1]) {  // ---- loss: fixed-order tree over the b row terms
-        __shared__ float part[UPD_THREADS];
+        float* part = reinterpret_cast<float*>(red);
         float s = 0.f;
         for (int i = tid; i < a.b; i += UPD_THREADS) s += a.row_loss[i];
         for (int i = tid; i < a.n_loss_parts; i += UPD_THREADS) s += a.neg_loss_part[i];
@@ -69,24 +69,32 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update_tiles(UpdateArgs a) {
             if (tid < o) part[tid] += part[tid + o];
             __syncthreads();
         }
-        if (tid == 0 && a.loss_out) a.loss_out[a.step_ptr ? *a.step_ptr : 0] = part[0];
+        if (tid == 0) {
+            const int64_t step = a.step_ptr ? *a.step_ptr : 0;
+            if (a.loss_out) a.loss_out[step] = part[0];
+            if (a.step_ptr) *a.step_ptr = step + 1;  // no other thread of this launch reads the counter
+        }
         return;
     }
     const int which = tile >= a.tiles[0];
     if (which) tile -= a.tiles[0];
-    const int n = a.n[which], D = a.D[which];
+    const int n = a.n[which], D = a.D[which], D4 = D / 4;
     const uint32_t* keys = a.key[which];
+    const uint32_t* poss = a.pos[which];
     const int p0 = tile * TILE_R, p1 = min(p0 + TILE_R, n), cnt = p1 - p0;
 
     // keys p0-1 .. p1 and positions p0 .. p1-1 of this tile, read once and shared
     __shared__ uint32_t sk[TILE_R + 2];
     __shared__ uint32_t sp[TILE_R];
+    __shared__ int lookback;
     if (tid < TILE_R + 2) {
         const int q = p0 - 1 + tid;
         sk[tid] = (q >= 0 && q <= p1 && q < n) ? keys[q] : 0u;
     } else if (tid >= 64 && tid < 64 + TILE_R) {
         const int q = p0 + tid - 64;
-        sp[tid - 64] = q < p1 ? a.pos[which][q] : 0u;
+        sp[tid - 64] = q < p1 ? poss[q] : 0u;
+    } else if (tid == 128) {
+        lookback = 1 << 30;
     }
     __syncthreads();
     // everything below is uniform over the workgroup: keep it in scalar registers
@@ -95,122 +103,96 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update_tiles(UpdateArgs a) {
     for (int j = 0; j < TILE_R + 2; ++j) key[j] = __builtin_amdgcn_readfirstlane(sk[j]);
 #pragma unroll
     for (int j = 0; j < TILE_R; ++j) gpos[j] = __builtin_amdgcn_readfirstlane(sp[j]);
+    const uint32_t last_key = __builtin_amdgcn_readfirstlane(sk[cnt]);
     const bool starts_before = p0 > 0 && key[0] == key[1];
-    const bool goes_on = p1 < n && __builtin_amdgcn_readfirstlane(sk[cnt]) == __builtin_amdgcn_readfirstlane(sk[cnt + 1]);
+    const bool goes_on = p1 < n && last_key == __builtin_amdgcn_readfirstlane(sk[cnt + 1]);
 
-    // per position: does a run end here, and is that run wholly inside the tile
-    bool ends[TILE_R], whole[TILE_R];
-    {
-        bool first_run = true;
+    // per position: is its run finished by this tile (need), and does a run end here (ends)
+    bool ends[TILE_R], need[TILE_R];
 #pragma unroll
-        for (int j = 0; j < TILE_R; ++j) {
-            ends[j] = j < cnt && (j == cnt - 1 || key[j + 2] != key[j + 1]);
-            const bool cut_front = first_run && starts_before;
-            const bool cut_back = j == cnt - 1 && goes_on;
-            whole[j] = ends[j] && !cut_front && !cut_back;
-            if (ends[j]) first_run = false;
+    for (int j = 0; j < TILE_R; ++j) {
+        need[j] = j < cnt && !(goes_on && key[j + 1] == last_key);
+        ends[j] = need[j] && (j == cnt - 1 || key[j + 2] != key[j + 1]);
+    }
+
+    // how many positions before the tile belong to its first run (0 if that run is not finished here)
+    int n_before = 0;
+    if (starts_before && need[0]) {
+        for (int base = 0;; base += UPD_THREADS) {
+            const int q = p0 - 1 - (base + tid);
+            const bool differs = q < 0 || keys[q < 0 ? 0 : q] != key[1];
+            if (differs) atomicMin(&lookback, base + tid);
+            __syncthreads();
+            n_before = lookback;
+            if (n_before < (1 << 30)) break;
+            __syncthreads();
         }
     }
+
     const float* G = a.G[which];
     float* Tb = a.T[which];
     float* Sb = a.St[which];
+    // thread -> (row group, 16-byte column slice); wide rows are walked in slices of `lanes` columns
+    const int lanes = D4 < UPD_THREADS ? D4 : UPD_THREADS;
+    const int groups = UPD_THREADS / lanes;
+    const int grp = tid / lanes, lane = tid - grp * lanes;
 
-    for (int v = tid; v < D / 4; v += UPD_THREADS) {
+    for (int v0 = 0; v0 < D4; v0 += lanes) {
+        const int v = v0 + lane;
+        const bool active = grp < groups && v < D4;
+        float4 before = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (n_before > 0) {  // uniform
+            float4 part = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (active) {
+                for (int i = grp; i < n_before; i += groups * LOOKBACK_U) {
+                    uint32_t gp[LOOKBACK_U];
+                    float4 g[LOOKBACK_U];
+#pragma unroll
+                    for (int u = 0; u < LOOKBACK_U; ++u) {
+                        const int ii = i + u * groups;
+                        gp[u] = poss[p0 - 1 - (ii < n_before ? ii : 0)];
+                    }
+#pragma unroll
+                    for (int u = 0; u < LOOKBACK_U; ++u) g[u] = ld4(G + (int64_t)gp[u] * D + 4 * v);
+#pragma unroll
+                    for (int u = 0; u < LOOKBACK_U; ++u) {
+                        if (i + u * groups < n_before) part = add4(part, g[u]);
+                    }
+                }
+            }
+            red[tid] = part;
+            __syncthreads();
+            if (grp == 0 && active) {
+                for (int g2 = 0; g2 < groups; ++g2) before = add4(before, red[g2 * lanes + lane]);
+            }
+            __syncthreads();
+        }
+        if (grp != 0 || !active) continue;
+
         float4 g[TILE_R], x[TILE_R], s[TILE_R];
 #pragma unroll
         for (int j = 0; j < TILE_R; ++j) {
             g[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (j < cnt) g[j] = ld4(G + (int64_t)gpos[j] * D + 4 * v);
+            if (need[j]) g[j] = ld4(G + (int64_t)gpos[j] * D + 4 * v);
         }
 #pragma unroll
         for (int j = 0; j < TILE_R; ++j) {
-            if (whole[j]) {
+            if (ends[j]) {
                 x[j] = ld4(Tb + (int64_t)key[j + 1] * D + 4 * v);
                 s[j] = ld4(Sb + (int64_t)key[j + 1] * D + 4 * v);
             }
         }
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        bool first_run = true;
+        float4 acc = before;
 #pragma unroll
         for (int j = 0; j < TILE_R; ++j) {
-            if (j < cnt) acc = add4(acc, g[j]);
+            if (need[j]) acc = add4(acc, g[j]);
             if (ends[j]) {
-                if (whole[j]) {
-                    adagrad4(acc, x[j], s[j], a.lr, a.eps);
-                    st4(Sb + (int64_t)key[j + 1] * D + 4 * v, s[j]);
-                    st4(Tb + (int64_t)key[j + 1] * D + 4 * v, x[j]);
-                } else if (first_run && starts_before) {
-                    st4(a.Pfirst[which] + (int64_t)tile * D + 4 * v, acc);
-                } else {
-                    st4(a.Plast[which] + (int64_t)tile * D + 4 * v, acc);
-                }
+                adagrad4(acc, x[j], s[j], a.lr, a.eps);
+                st4(Sb + (int64_t)key[j + 1] * D + 4 * v, s[j]);
+                st4(Tb + (int64_t)key[j + 1] * D + 4 * v, x[j]);
                 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-                first_run = false;
             }
         }
-    }
-}
-
-// Finishes the runs that cross tile boundaries.  The workgroup of the tile in which such a run STARTS owns it.
-__global__ __launch_bounds__(UPD_THREADS) void k_update_fixup(UpdateArgs a) {
-    int tile = blockIdx.x;
-    const int tid = threadIdx.x;
-    // last kernel of a step and the only one that does not read the step counter: advance it for the next step
-    if (a.step_ptr && tile == 0 && tid == 0) *a.step_ptr = *a.step_ptr + 1;
-    const int which = tile >= a.tiles[0];
-    if (which) tile -= a.tiles[0];
-    const int n = a.n[which], D = a.D[which];
-    const uint32_t* keys = a.key[which];
-    const int p0 = tile * TILE_R, p1 = min(p0 + TILE_R, n);
-    if (p1 >= n) return;
-    const uint32_t key = keys[p1 - 1];
-    if (keys[p1] != key) return;  // the tile's last run ends with the tile
-    // does the run begin in this tile?  (at most 8 keys back)
-    int s = p1 - 1;
-    while (s > p0 && keys[s - 1] == key) --s;
-    if (s == p0 && p0 > 0 && keys[p0 - 1] == key) return;  // the run began in an earlier tile
-    // tiles tile+1 .. tile+m start with this run.  Thread i looks at tile tile+1+i (and further ones in rounds of
-    // 128): the run covers it completely and goes on iff its last key and the key after it are both `key`.
-    __shared__ int first_stop;
-    if (tid == 0) first_stop = 1 << 30;
-    __syncthreads();
-    int m = 0;
-    for (int base = 0;; base += UPD_THREADS) {
-        const int q = p1 + (base + tid) * TILE_R;  // first position of tile tile+1+base+tid
-        bool stops = true;                         // does the run end inside (or before) that tile
-        if (q < n && keys[q] == key) {
-            const int e = min(q + TILE_R, n);
-            stops = !(e < n && keys[e - 1] == key && keys[e] == key);
-        }
-        if (stops) atomicMin(&first_stop, base + tid);
-        __syncthreads();
-        const int fs = first_stop;
-        if (fs < (1 << 30)) {
-            // tile+1+fs is the last tile that holds part of the run, unless the run does not reach it at all
-            const int q2 = p1 + fs * TILE_R;
-            m = fs + ((q2 < n && keys[q2] == key) ? 1 : 0);
-            break;
-        }
-        __syncthreads();
-    }
-    float* th = a.T[which] + (int64_t)key * D;
-    float* st = a.St[which] + (int64_t)key * D;
-    const float* Pf = a.Pfirst[which];
-    for (int v = tid; v < D / 4; v += UPD_THREADS) {
-        float4 x = ld4(th + 4 * v), sv = ld4(st + 4 * v);
-        float4 g = ld4(a.Plast[which] + (int64_t)tile * D + 4 * v);
-        int i = 1;
-        for (; i + 3 <= m; i += 4) {
-            const float4 g0 = ld4(Pf + (int64_t)(tile + i) * D + 4 * v);
-            const float4 g1 = ld4(Pf + (int64_t)(tile + i + 1) * D + 4 * v);
-            const float4 g2 = ld4(Pf + (int64_t)(tile + i + 2) * D + 4 * v);
-            const float4 g3 = ld4(Pf + (int64_t)(tile + i + 3) * D + 4 * v);
-            g = add4(g, add4(add4(g0, g1), add4(g2, g3)));
-        }
-        for (; i <= m; ++i) g = add4(g, ld4(Pf + (int64_t)(tile + i) * D + 4 * v));
-        adagrad4(g, x, sv, a.lr, a.eps);
-        st4(st + 4 * v, sv);
-        st4(th + 4 * v, x);
     }
 }
 
@@ -226,13 +208,11 @@ void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, con
     a.G[0] = c->Gent; a.G[1] = c->Grel;
     a.key[0] = c->ekey[c->ebuf]; a.key[1] = c->rkey[c->rbuf];
     a.pos[0] = c->epos[c->ebuf]; a.pos[1] = c->rpos[c->rbuf];
-    a.Pfirst[0] = c->Pfirst_e; a.Pfirst[1] = c->Pfirst_r; a.Plast[0] = c->Plast_e; a.Plast[1] = c->Plast_r;
     a.n[0] = n_ent_keys; a.n[1] = n_rel_keys;
     a.tiles[0] = (n_ent_keys + TILE_R - 1) / TILE_R; a.tiles[1] = (n_rel_keys + TILE_R - 1) / TILE_R;
     a.D[0] = c->cfg.ent_dim; a.D[1] = c->cfg.rel_dim;
     a.lr = lr; a.eps = c->eps; a.row_loss = c->row_loss; a.b = b; a.loss_out = loss_out;
     a.neg_loss_part = c->neg_loss_part; a.n_loss_parts = n_loss_parts;
     const int tiles = a.tiles[0] + a.tiles[1];
-    hipLaunchKernelGGL(k_update_tiles, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
-    hipLaunchKernelGGL(k_update_fixup, dim3(tiles), dim3(UPD_THREADS), 0, st, a);
+    hipLaunchKernelGGL(k_update, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
 }

@@ -251,8 +251,6 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t o_nlp = take((B / 32 + cfg->max_chunks + 1) * 4);
     const size_t o_ek0 = take(EK * 4), o_ek1 = take(EK * 4), o_ep0 = take(EK * 4), o_ep1 = take(EK * 4);
     const size_t o_rk0 = take(B * 4), o_rk1 = take(B * 4), o_rp0 = take(B * 4), o_rp1 = take(B * 4);
-    const size_t te = EK / 8 + 1, tr = B / 8 + 1;
-    const size_t o_pfe = take(te * D * 4), o_ple = take(te * D * 4), o_pfr = take(tr * Dr * 4), o_plr = take(tr * Dr * 4);
     const size_t o_flags = take(256), o_step = take(256);
     c->ws_bytes = (int64_t)off;
 
@@ -272,8 +270,6 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->epos[0] = (uint32_t*)(base + o_ep0); c->epos[1] = (uint32_t*)(base + o_ep1);
     c->rkey[0] = (uint32_t*)(base + o_rk0); c->rkey[1] = (uint32_t*)(base + o_rk1);
     c->rpos[0] = (uint32_t*)(base + o_rp0); c->rpos[1] = (uint32_t*)(base + o_rp1);
-    c->Pfirst_e = (float*)(base + o_pfe); c->Plast_e = (float*)(base + o_ple);
-    c->Pfirst_r = (float*)(base + o_pfr); c->Plast_r = (float*)(base + o_plr);
     c->flags = (int*)(base + o_flags);
     c->step_counter = (int64_t*)(base + o_step);
 

@@ -42,10 +42,6 @@ struct kge_ctx {
     uint16_t* Obf;   // bf16 copies of O, Nst, W (gemm_input = 1)
     uint16_t* Nbf;
     uint16_t* Wbf;
-    float* Pfirst_e;    // partial sums of runs that cross 8-position tiles of the sorted key list (see k_update.hip)
-    float* Plast_e;
-    float* Pfirst_r;
-    float* Plast_r;
     uint32_t* ekey[2];  // entity sort ping-pong: keys
     uint32_t* epos[2];  //                        positions in the key list
     uint32_t* rkey[2];  // relation sort ping-pong
