@@ -105,7 +105,7 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
     for (int j = 0; j < TILE_R; ++j) gpos[j] = __builtin_amdgcn_readfirstlane(sp[j]);
     const uint32_t last_key = __builtin_amdgcn_readfirstlane(sk[cnt]);
     const bool starts_before = p0 > 0 && key[0] == key[1];
-    const bool goes_on = p1 < n && last_key == __builtin_amdgcn_readfirstlane(sk[cnt + 1]);
+    const bool goes_on = p1 < n && last_key == (uint32_t)__builtin_amdgcn_readfirstlane(sk[cnt + 1]);
 
     // per position: is its run finished by this tile (need), and does a run end here (ends)
     bool ends[TILE_R], need[TILE_R];
