@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--profile-steps", type=int, default=500)
     ap.add_argument("--cpu-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device copy of this size, as the known-size kernel that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     return ap.parse_args()
 
 
@@ -123,6 +126,11 @@ def main():
                          max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks, gemm_input=int(w.bf16_inputs),
                          adv_temperature=w.adv_temperature)
     losses = torch.zeros(W + K + P, dtype=torch.float32, device=dev)
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib << 18, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        del src, dst
     torch.cuda.synchronize(dev)
     setup_s = time.perf_counter() - t_setup
 
