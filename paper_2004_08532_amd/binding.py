@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libkge.so")
+LIB_PATH = os.environ.get("KGE_LIBRARY", os.path.join(_HERE, "libkge.so"))  # KGE_LIBRARY: another build of the same library
 
 KGE_TRANSE_L2, KGE_TRANSE_L1, KGE_DISTMULT, KGE_COMPLEX, KGE_ROTATE = 0, 1, 2, 3, 4
 KGE_NEG_TAIL, KGE_NEG_HEAD = 0, 1

@@ -19,7 +19,7 @@ namespace {
 
 constexpr int TILE_R = 8;
 constexpr int UPD_THREADS = 512;
-constexpr int LOOKBACK_U = 8;  // gradient rows in flight per thread while summing the earlier part of a run
+constexpr int LOOKBACK_U = 16;  // gradient rows in flight per thread while summing the earlier part of a run
 
 struct UpdateArgs {
     float* T[2];             // tables: entity, relation
@@ -87,6 +87,7 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
     __shared__ uint32_t sk[TILE_R + 2];
     __shared__ uint32_t sp[TILE_R];
     __shared__ int lookback;
+    __shared__ uint32_t back_pos[UPD_THREADS];
     if (tid < TILE_R + 2) {
         const int q = p0 - 1 + tid;
         sk[tid] = (q >= 0 && q <= p1 && q < n) ? keys[q] : 0u;
@@ -115,83 +116,79 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
         ends[j] = need[j] && (j == cnt - 1 || key[j + 2] != key[j + 1]);
     }
 
-    // how many positions before the tile belong to its first run (0 if that run is not finished here)
-    int n_before = 0;
-    if (starts_before && need[0]) {
-        for (int base = 0;; base += UPD_THREADS) {
-            const int q = p0 - 1 - (base + tid);
-            const bool differs = q < 0 || keys[q < 0 ? 0 : q] != key[1];
-            if (differs) atomicMin(&lookback, base + tid);
-            __syncthreads();
-            n_before = lookback;
-            if (n_before < (1 << 30)) break;
-            __syncthreads();
-        }
-    }
-
     const float* G = a.G[which];
     float* Tb = a.T[which];
     float* Sb = a.St[which];
-    // thread -> (row group, 16-byte column slice); wide rows are walked in slices of `lanes` columns
-    const int lanes = D4 < UPD_THREADS ? D4 : UPD_THREADS;
+    // thread -> (row group, 16-byte column slice); rows are at most 4 * UPD_THREADS floats long (checked on the host)
+    const int lanes = D4;
     const int groups = UPD_THREADS / lanes;
-    const int grp = tid / lanes, lane = tid - grp * lanes;
+    const int grp = tid / lanes, v = tid - grp * lanes;
+    const bool active = grp < groups;
 
-    for (int v0 = 0; v0 < D4; v0 += lanes) {
-        const int v = v0 + lane;
-        const bool active = grp < groups && v < D4;
-        float4 before = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (n_before > 0) {  // uniform
-            float4 part = make_float4(0.f, 0.f, 0.f, 0.f);
+    // ---- the part of the tile's first run that lies before the tile (only if that run is finished here)
+    // Look-back in chunks of UPD_THREADS positions: thread i reads key and gradient-row position of sorted entry
+    // p0 - 1 - (base + i); the first entry with another key ends the run.  The positions go to LDS, and the row
+    // groups add up the gradient rows of the chunk, LOOKBACK_U rows per thread in flight.
+    float4 before = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (starts_before && need[0]) {  // uniform
+        float4 part = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int base = 0;; base += UPD_THREADS) {
+            const int q = p0 - 1 - (base + tid);
+            const uint32_t kq = keys[q < 0 ? 0 : q], pq = poss[q < 0 ? 0 : q];
+            const bool differs = q < 0 || kq != key[1];
+            const unsigned long long bal = __ballot(differs);
+            if ((tid & 63) == 0 && bal) atomicMin(&lookback, base + tid + __builtin_ctzll(bal));  // one per wave
+            back_pos[tid] = pq;
+            __syncthreads();
+            const int stop = lookback;                                    // first entry that is not in the run
+            const int m = (stop < base + UPD_THREADS ? stop : base + UPD_THREADS) - base;  // run entries in this chunk
             if (active) {
-                for (int i = grp; i < n_before; i += groups * LOOKBACK_U) {
-                    uint32_t gp[LOOKBACK_U];
+                for (int i = grp; i < m; i += groups * LOOKBACK_U) {
                     float4 g[LOOKBACK_U];
 #pragma unroll
                     for (int u = 0; u < LOOKBACK_U; ++u) {
                         const int ii = i + u * groups;
-                        gp[u] = poss[p0 - 1 - (ii < n_before ? ii : 0)];
+                        g[u] = ld4(G + (int64_t)back_pos[ii < m ? ii : i] * D + 4 * v);
                     }
 #pragma unroll
-                    for (int u = 0; u < LOOKBACK_U; ++u) g[u] = ld4(G + (int64_t)gp[u] * D + 4 * v);
-#pragma unroll
                     for (int u = 0; u < LOOKBACK_U; ++u) {
-                        if (i + u * groups < n_before) part = add4(part, g[u]);
+                        if (i + u * groups < m) part = add4(part, g[u]);
                     }
                 }
             }
-            red[tid] = part;
-            __syncthreads();
-            if (grp == 0 && active) {
-                for (int g2 = 0; g2 < groups; ++g2) before = add4(before, red[g2 * lanes + lane]);
-            }
-            __syncthreads();
+            if (stop < (1 << 30)) break;
+            __syncthreads();  // back_pos is overwritten by the next chunk
         }
-        if (grp != 0 || !active) continue;
+        red[tid] = part;
+        __syncthreads();
+        if (grp == 0) {
+            for (int g2 = 0; g2 < groups; ++g2) before = add4(before, red[g2 * lanes + v]);
+        }
+    }
+    if (grp != 0) return;
 
-        float4 g[TILE_R], x[TILE_R], s[TILE_R];
+    float4 g[TILE_R], x[TILE_R], s[TILE_R];
 #pragma unroll
-        for (int j = 0; j < TILE_R; ++j) {
-            g[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (need[j]) g[j] = ld4(G + (int64_t)gpos[j] * D + 4 * v);
+    for (int j = 0; j < TILE_R; ++j) {
+        g[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (need[j]) g[j] = ld4(G + (int64_t)gpos[j] * D + 4 * v);
+    }
+#pragma unroll
+    for (int j = 0; j < TILE_R; ++j) {
+        if (ends[j]) {
+            x[j] = ld4(Tb + (int64_t)key[j + 1] * D + 4 * v);
+            s[j] = ld4(Sb + (int64_t)key[j + 1] * D + 4 * v);
         }
+    }
+    float4 acc = before;
 #pragma unroll
-        for (int j = 0; j < TILE_R; ++j) {
-            if (ends[j]) {
-                x[j] = ld4(Tb + (int64_t)key[j + 1] * D + 4 * v);
-                s[j] = ld4(Sb + (int64_t)key[j + 1] * D + 4 * v);
-            }
-        }
-        float4 acc = before;
-#pragma unroll
-        for (int j = 0; j < TILE_R; ++j) {
-            if (need[j]) acc = add4(acc, g[j]);
-            if (ends[j]) {
-                adagrad4(acc, x[j], s[j], a.lr, a.eps);
-                st4(Sb + (int64_t)key[j + 1] * D + 4 * v, s[j]);
-                st4(Tb + (int64_t)key[j + 1] * D + 4 * v, x[j]);
-                acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            }
+    for (int j = 0; j < TILE_R; ++j) {
+        if (need[j]) acc = add4(acc, g[j]);
+        if (ends[j]) {
+            adagrad4(acc, x[j], s[j], a.lr, a.eps);
+            st4(Sb + (int64_t)key[j + 1] * D + 4 * v, s[j]);
+            st4(Tb + (int64_t)key[j + 1] * D + 4 * v, x[j]);
+            acc = make_float4(0.f, 0.f, 0.f, 0.f);
         }
     }
 }
