@@ -4,15 +4,16 @@
 // Table rows that are not in the batch are never touched.
 //
 // Work is cut by POSITION in the sorted key list, not by row id: every workgroup gets a tile of 8 consecutive
-// sorted positions, and a run of equal keys (one distinct row) belongs to the tile in which it ENDS.  The first
-// 16-byte-per-thread row group of the workgroup issues all gradient-row loads of the tile and the table / state
-// loads of the runs that end in it together, then walks the tile in sorted order.  If the tile's first run began
-// in an earlier tile (a row that occurs often: hub entities of degree-skewed graphs, frequent relations), the
-// whole workgroup first finds where it began (one parallel look-back over the keys) and adds up those earlier
-// gradient rows, split over its row groups, through LDS.  Positions of a run that goes on into the next tile are
-// skipped: that tile's workgroup reads them.  One launch, no atomics on data, every sum has a fixed order, so the
-// result is a function of the ids and the gradient rows alone.  Entity and relation rows go through the same
-// launch; its last workgroup adds the loss terms in a fixed order and advances the device step counter.
+// sorted positions, and a run of equal keys (one distinct row) belongs to the tile in which it ENDS.  One row
+// group of the workgroup (one thread per 16 bytes of a row: the "walkers") asks for the table / state rows of the
+// runs that end in the tile and for the tile's gradient rows, then walks the tile in sorted order.  If the tile's
+// first run began in an earlier tile (a row that occurs often: hub entities of degree-skewed graphs, frequent
+// relations), the other waves of the workgroup (the "helpers") find where it began with one parallel look-back
+// over the keys and add up those earlier gradient rows, split over their row groups, while the walkers' table
+// rows are still on their way; the sums reach the walkers through LDS.  Positions of a run that goes on into the
+// next tile are skipped: that tile's workgroup reads them.  One launch, no atomics on data, every sum has a fixed
+// order, so the result is a function of the ids and the gradient rows alone.  Entity and relation rows go through
+// the same launch; its last workgroup adds the loss terms in a fixed order and advances the device step counter.
 #include "kge_common.h"
 
 namespace {
@@ -54,6 +55,13 @@ __device__ __forceinline__ void adagrad4(float4 g, float4& x, float4& s, float l
     x.w -= adagrad1(g.w, s.w, lr, eps);
 }
 
+// Workgroup barrier that orders LDS traffic only: global loads that are still in flight stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
     int tile = blockIdx.x;
     const int tid = threadIdx.x;
@@ -83,30 +91,25 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
     const uint32_t* poss = a.pos[which];
     const int p0 = tile * TILE_R, p1 = min(p0 + TILE_R, n), cnt = p1 - p0;
 
-    // keys p0-1 .. p1 and positions p0 .. p1-1 of this tile, read once and shared
-    __shared__ uint32_t sk[TILE_R + 2];
-    __shared__ uint32_t sp[TILE_R];
+    // keys p0-1 .. p1 and positions p0 .. p1-1 of this tile: the addresses are the same for every thread, and so is
+    // everything computed from them below, so it all lives in scalar registers
     __shared__ int lookback;
     __shared__ uint32_t back_pos[UPD_THREADS];
-    if (tid < TILE_R + 2) {
-        const int q = p0 - 1 + tid;
-        sk[tid] = (q >= 0 && q <= p1 && q < n) ? keys[q] : 0u;
-    } else if (tid >= 64 && tid < 64 + TILE_R) {
-        const int q = p0 + tid - 64;
-        sp[tid - 64] = q < p1 ? poss[q] : 0u;
-    } else if (tid == 128) {
-        lookback = 1 << 30;
-    }
-    __syncthreads();
-    // everything below is uniform over the workgroup: keep it in scalar registers
     uint32_t key[TILE_R + 2], gpos[TILE_R];
 #pragma unroll
-    for (int j = 0; j < TILE_R + 2; ++j) key[j] = __builtin_amdgcn_readfirstlane(sk[j]);
+    for (int j = 0; j < TILE_R + 2; ++j) {
+        const int q = p0 - 1 + j;
+        key[j] = __builtin_amdgcn_readfirstlane(keys[q < 0 ? 0 : (q < n ? q : n - 1)]);
+    }
 #pragma unroll
-    for (int j = 0; j < TILE_R; ++j) gpos[j] = __builtin_amdgcn_readfirstlane(sp[j]);
-    const uint32_t last_key = __builtin_amdgcn_readfirstlane(sk[cnt]);
+    for (int j = 0; j < TILE_R; ++j) gpos[j] = __builtin_amdgcn_readfirstlane(poss[p0 + j < n ? p0 + j : n - 1]);
+    uint32_t last_key = key[1], next_key = key[2];  // key[cnt], key[cnt + 1]
+#pragma unroll
+    for (int j = 1; j < TILE_R; ++j) {
+        if (j < cnt) { last_key = key[j + 1]; next_key = key[j + 2]; }
+    }
     const bool starts_before = p0 > 0 && key[0] == key[1];
-    const bool goes_on = p1 < n && last_key == (uint32_t)__builtin_amdgcn_readfirstlane(sk[cnt + 1]);
+    const bool goes_on = p1 < n && last_key == next_key;
 
     // per position: is its run finished by this tile (need), and does a run end here (ends)
     bool ends[TILE_R], need[TILE_R];
@@ -119,36 +122,43 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
     const float* G = a.G[which];
     float* Tb = a.T[which];
     float* Sb = a.St[which];
-    // thread -> (row group, 16-byte column slice); rows are at most 4 * UPD_THREADS floats long (checked on the host)
-    const int lanes = D4;
-    const int groups = UPD_THREADS / lanes;
-    const int grp = tid / lanes, v = tid - grp * lanes;
-    const bool active = grp < groups;
+    const int lanes = D4;  // threads per row: one 16-byte column slice each (rows are at most 4 * 256 floats long)
+    const int v = tid % lanes;
+    // The first `walkers` threads (whole waves) hold the row group that walks the tile; the other waves only help
+    // with a run that began before the tile (only if that run is finished here).
+    const int walkers = (lanes + 63) & ~63;
+    const bool look = starts_before && need[0];  // uniform
 
-    // ---- the part of the tile's first run that lies before the tile (only if that run is finished here)
-    // Look-back in chunks of UPD_THREADS positions: thread i reads key and gradient-row position of sorted entry
-    // p0 - 1 - (base + i); the first entry with another key ends the run.  The positions go to LDS, and the row
-    // groups add up the gradient rows of the chunk, LOOKBACK_U rows per thread in flight.
-    float4 before = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (starts_before && need[0]) {  // uniform
+    if (tid >= walkers) {
+        // ---- helper waves: the part of the tile's first run that lies before the tile
+        // Look-back in chunks: helper thread i reads key and gradient-row position of sorted entry p0 - 1 - (base + i);
+        // the first entry with another key ends the run.  The positions go to LDS, and the helpers, in row groups of
+        // `lanes` threads, add up the gradient rows of the chunk, LOOKBACK_U rows per thread in flight.  The sums of
+        // the row groups go to the walkers through LDS.
+        if (!look) return;
+        const int o = tid - walkers, n_look = UPD_THREADS - walkers;
+        const int groups = n_look / lanes, grp = o / lanes;
+        const bool active = grp < groups;
+        if (o == 0) lookback = 1 << 30;
         float4 part = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int base = 0;; base += UPD_THREADS) {
-            const int q = p0 - 1 - (base + tid);
+        lds_barrier();  // (1)
+        for (int base = 0;; base += n_look) {
+            const int q = p0 - 1 - (base + o);
             const uint32_t kq = keys[q < 0 ? 0 : q], pq = poss[q < 0 ? 0 : q];
             const bool differs = q < 0 || kq != key[1];
             const unsigned long long bal = __ballot(differs);
-            if ((tid & 63) == 0 && bal) atomicMin(&lookback, base + tid + __builtin_ctzll(bal));  // one per wave
-            back_pos[tid] = pq;
-            __syncthreads();
-            const int stop = lookback;                                    // first entry that is not in the run
-            const int m = (stop < base + UPD_THREADS ? stop : base + UPD_THREADS) - base;  // run entries in this chunk
+            if ((tid & 63) == 0 && bal) atomicMin(&lookback, base + o + __builtin_ctzll(bal));  // one per wave
+            back_pos[o] = pq;
+            lds_barrier();  // (2)
+            const int stop = lookback;                                          // first entry that is not in the run
+            const int m = (stop < base + n_look ? stop : base + n_look) - base;  // run entries in this chunk
             if (active) {
                 for (int i = grp; i < m; i += groups * LOOKBACK_U) {
                     float4 g[LOOKBACK_U];
 #pragma unroll
                     for (int u = 0; u < LOOKBACK_U; ++u) {
                         const int ii = i + u * groups;
-                        g[u] = ld4(G + (int64_t)back_pos[ii < m ? ii : i] * D + 4 * v);
+                        g[u] = ld4(G + (int64_t)back_pos[ii < m ? ii : i] * D + 4 * (o % lanes));
                     }
 #pragma unroll
                     for (int u = 0; u < LOOKBACK_U; ++u) {
@@ -157,30 +167,50 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
                 }
             }
             if (stop < (1 << 30)) break;
-            __syncthreads();  // back_pos is overwritten by the next chunk
+            lds_barrier();  // (3) back_pos is overwritten by the next chunk
         }
-        red[tid] = part;
-        __syncthreads();
-        if (grp == 0) {
-            for (int g2 = 0; g2 < groups; ++g2) before = add4(before, red[g2 * lanes + v]);
+        red[o] = part;
+        lds_barrier();  // (4)
+        return;
+    }
+
+    // ---- walker waves.  A wave gets its loads back in the order it issued them, and the table and state rows of the
+    // runs that end here come from far away (random rows of a table that fills the memory): they are asked for
+    // first, and while they travel the walkers only pass the helpers' barriers, which order LDS traffic and do not
+    // wait for loads.
+    const bool walker = tid < lanes;
+    float4 x[TILE_R], s[TILE_R];
+    if (walker) {
+#pragma unroll
+        for (int j = 0; j < TILE_R; ++j) {
+            if (ends[j]) {
+                x[j] = ld4(Tb + (int64_t)key[j + 1] * D + 4 * v);
+                s[j] = ld4(Sb + (int64_t)key[j + 1] * D + 4 * v);
+            }
         }
     }
-    if (grp != 0) return;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (look) {
+        lds_barrier();  // (1)
+        for (;;) {
+            lds_barrier();  // (2)
+            if (lookback < (1 << 30)) break;
+            lds_barrier();  // (3)
+        }
+        lds_barrier();  // (4)
+        if (walker) {
+            const int groups = (UPD_THREADS - walkers) / lanes;
+            for (int g2 = 0; g2 < groups; ++g2) acc = add4(acc, red[g2 * lanes + v]);
+        }
+    }
+    if (!walker) return;
 
-    float4 g[TILE_R], x[TILE_R], s[TILE_R];
+    float4 g[TILE_R];
 #pragma unroll
     for (int j = 0; j < TILE_R; ++j) {
         g[j] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (need[j]) g[j] = ld4(G + (int64_t)gpos[j] * D + 4 * v);
     }
-#pragma unroll
-    for (int j = 0; j < TILE_R; ++j) {
-        if (ends[j]) {
-            x[j] = ld4(Tb + (int64_t)key[j + 1] * D + 4 * v);
-            s[j] = ld4(Sb + (int64_t)key[j + 1] * D + 4 * v);
-        }
-    }
-    float4 acc = before;
 #pragma unroll
     for (int j = 0; j < TILE_R; ++j) {
         if (need[j]) acc = add4(acc, g[j]);
