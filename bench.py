@@ -7,8 +7,10 @@ backward, duplicate reduction, sparse Adagrad) on synthetic inputs that are resi
 region starts.  The default workload is the Freebase-scale configuration (86,054,151 entities, 14,824 relations,
 TransE-L2, dim 400, b = 1000, one chunk of 1000, k = 200) with the full entity table and its Adagrad state in HBM.
 Prints ONE JSON line.  The roofline object is for the kernel with the largest share of the step; the per-kernel
-times behind it are measured in this process with HIP events around every kernel (kge_profile) over a second
-pass of the same kind of steps, and all of them are listed under "kernels".
+times behind it are measured in this process (kge_profile: every kernel is launched with a start and a stop
+event that take the dispatch's own timestamps) over a second pass of the same kind of steps, and all of them are
+listed under "kernels".  "traffic" is bytes per launch from hardware counters, read from the summary under
+profiles/ (null for a workload that has none).
 """
 from __future__ import annotations
 
@@ -68,6 +70,20 @@ def algorithmic_work(w, h, r, t, neg):
         "sort": {"bytes": 8.0 * (n_keys + b)},
         "unique_entity_rows": float(ue), "unique_relation_rows": float(ur),
     }
+
+
+def measured_traffic(workload):
+    """HBM-side bytes per launch of every kernel, from the rocprofv3 counter summary under profiles/ (two --pmc
+    runs, scaled by a plain copy of known size; the file states the commands).  {} if there is none for this
+    workload."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            f = line.split()
+            if len(f) == 6 and not line.startswith("#"):
+                out[f[0]] = 1024.0 * (float(f[2]) * float(f[4]) + float(f[3]) * float(f[5]))
+    return out
 
 
 def cpu_baseline(w, steps):
@@ -174,11 +190,14 @@ def main():
             if "achieved" in ent:
                 ent["frac"] = ent["achieved"] / ent["peak"]
             kernels[name] = ent
+        traffic = measured_traffic(w.name)
+        for name, ent in kernels.items():
+            ent["traffic"] = traffic.get(name)
         on_stream = {n: e for n, e in kernels.items() if n != "sort"}  # the sort overlaps on its own stream
         dom = max(on_stream, key=lambda n: on_stream[n]["avg_us"])
         d = kernels[dom]
         roofline = {"kernel": dom, "bound": d.get("bound"), "achieved": d.get("achieved"), "peak": d.get("peak"),
-                    "unit": d.get("unit"), "frac": d.get("frac"), "traffic": None, "avg_us": d["avg_us"],
+                    "unit": d.get("unit"), "frac": d.get("frac"), "traffic": d.get("traffic"), "avg_us": d["avg_us"],
                     "unique_entity_rows_per_step": work["unique_entity_rows"],
                     "unique_relation_rows_per_step": work["unique_relation_rows"]}
 

@@ -146,9 +146,10 @@ int kge_check_indices(kge_ctx* ctx, void* hip_stream);
 
 /*
  * Per-kernel timing for measurement (the paper reports where time goes per phase, Sec. 6.1.3; this is the
- * library's counterpart).  kge_profile(ctx, 1) makes every following kge_train_step / kge_train_steps bracket
- * each of its kernels with HIP events on the stream the kernel runs on and synchronise that stream after every
- * step; kge_profile(ctx, 0) restores normal asynchronous operation.  Either call clears the accumulated times.
+ * library's counterpart).  kge_profile(ctx, 1) makes every following kge_train_step / kge_train_steps launch
+ * each of its kernels with a start and a stop event that receive the dispatch's own begin / end timestamps (the
+ * duration a kernel trace reports), and synchronise the stream after every step; kge_profile(ctx, 0) restores
+ * normal asynchronous operation.  Either call clears the accumulated times.
  * kge_profile_read: (host) ms_out[KGE_PROF_SLOTS] receives the summed kernel times in milliseconds per slot,
  * (host) *steps_out the number of steps they cover.  kge_profile_slot_name: (host) static name of a slot.
  */

@@ -239,12 +239,12 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
 }
 
 template <int MODEL>
-void launch_nv(const GatherArgs& a, int nv, dim3 grid, size_t lds, hipStream_t st) {
+void launch_nv(kge_ctx* c, const GatherArgs& a, int nv, dim3 grid, size_t lds, hipStream_t st) {
     switch (nv) {
-    case 1: hipLaunchKernelGGL((k_gather<MODEL, 1>), grid, dim3(256), lds, st, a); break;
-    case 2: hipLaunchKernelGGL((k_gather<MODEL, 2>), grid, dim3(256), lds, st, a); break;
-    case 3: hipLaunchKernelGGL((k_gather<MODEL, 3>), grid, dim3(256), lds, st, a); break;
-    default: hipLaunchKernelGGL((k_gather<MODEL, 4>), grid, dim3(256), lds, st, a); break;
+    case 1: KGE_LAUNCH(c, (k_gather<MODEL, 1>), grid, dim3(256), lds, st, a); break;
+    case 2: KGE_LAUNCH(c, (k_gather<MODEL, 2>), grid, dim3(256), lds, st, a); break;
+    case 3: KGE_LAUNCH(c, (k_gather<MODEL, 3>), grid, dim3(256), lds, st, a); break;
+    default: KGE_LAUNCH(c, (k_gather<MODEL, 4>), grid, dim3(256), lds, st, a); break;
     }
 }
 
@@ -279,10 +279,10 @@ void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds
     }
     const dim3 grid(a.gather_blocks + rank_blocks);
     switch (model) {
-    case KGE_TRANSE_L2: launch_nv<KGE_TRANSE_L2>(a, nv, grid, lds, st); break;
-    case KGE_TRANSE_L1: launch_nv<KGE_TRANSE_L1>(a, nv, grid, lds, st); break;
-    case KGE_DISTMULT: launch_nv<KGE_DISTMULT>(a, nv, grid, lds, st); break;
-    case KGE_COMPLEX: launch_nv<KGE_COMPLEX>(a, nv, grid, lds, st); break;
-    default: launch_nv<KGE_ROTATE>(a, nv, grid, lds, st); break;
+    case KGE_TRANSE_L2: launch_nv<KGE_TRANSE_L2>(c, a, nv, grid, lds, st); break;
+    case KGE_TRANSE_L1: launch_nv<KGE_TRANSE_L1>(c, a, nv, grid, lds, st); break;
+    case KGE_DISTMULT: launch_nv<KGE_DISTMULT>(c, a, nv, grid, lds, st); break;
+    case KGE_COMPLEX: launch_nv<KGE_COMPLEX>(c, a, nv, grid, lds, st); break;
+    default: launch_nv<KGE_ROTATE>(c, a, nv, grid, lds, st); break;
     }
 }

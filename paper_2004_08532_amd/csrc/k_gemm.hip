@@ -383,17 +383,17 @@ void set_tiling(GemmArgs& g, int chunks) {
 }
 
 template <int EPI>
-void launch_fwd(GemmArgs g, int chunks, hipStream_t st) {
+void launch_fwd(kge_ctx* c, GemmArgs g, int chunks, hipStream_t st) {
     set_tiling(g, chunks);
     const dim3 grid(8 * ((g.tiles + 7) / 8));
     const int nw = pick_nw(g.tiles, (g.K + TILE - 1) / TILE, 16);
-    if (nw == 4) hipLaunchKernelGGL((k_gemm_fwd<4, EPI>), grid, dim3(256), 0, st, g);
-    else if (nw == 8) hipLaunchKernelGGL((k_gemm_fwd<8, EPI>), grid, dim3(512), 0, st, g);
-    else hipLaunchKernelGGL((k_gemm_fwd<16, EPI>), grid, dim3(1024), 0, st, g);
+    if (nw == 4) KGE_LAUNCH(c, (k_gemm_fwd<4, EPI>), grid, dim3(256), 0, st, g);
+    else if (nw == 8) KGE_LAUNCH(c, (k_gemm_fwd<8, EPI>), grid, dim3(512), 0, st, g);
+    else KGE_LAUNCH(c, (k_gemm_fwd<16, EPI>), grid, dim3(1024), 0, st, g);
 }
 
 template <int TF, int EPI_O, int EPI_N>
-void launch_bwd(GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st) {
+void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st) {
     set_tiling(gO, chunks);
     set_tiling(gN, chunks);
     const int per_n = (gN.tiles + 7) / 8, per_o = (gO.tiles + 7) / 8;
@@ -401,8 +401,8 @@ void launch_bwd(GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st) {
     const int nblk = ((gO.K > gN.K ? gO.K : gN.K) + TILE - 1) / TILE;
     // at most 8 waves: 74 KB of LDS per workgroup, so two workgroups share a CU
     const int nw = pick_nw(gO.tiles + gN.tiles, nblk, 8);
-    if (nw == 4) hipLaunchKernelGGL((k_gemm_bwd<4, TF, EPI_O, EPI_N>), grid, dim3(256), 0, st, gO, gN, per_n, per_o);
-    else hipLaunchKernelGGL((k_gemm_bwd<8, TF, EPI_O, EPI_N>), grid, dim3(512), 0, st, gO, gN, per_n, per_o);
+    if (nw == 4) KGE_LAUNCH(c, (k_gemm_bwd<4, TF, EPI_O, EPI_N>), grid, dim3(256), 0, st, gO, gN, per_n, per_o);
+    else KGE_LAUNCH(c, (k_gemm_bwd<8, TF, EPI_O, EPI_N>), grid, dim3(512), 0, st, gO, gN, per_n, per_o);
 }
 
 }  // namespace
@@ -420,8 +420,8 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     g.rowv = c->o_n2; g.colv = c->n_n2; g.s_rowv = gsz; g.s_colv = k;
     g.gamma = gamma; g.store_dist = dist_mode;
     const int chunks = b / gsz;
-    if (c->cfg.model == KGE_TRANSE_L2) launch_fwd<EPI_L2_FWD>(g, chunks, st);
-    else launch_fwd<EPI_PLAIN>(g, chunks, st);
+    if (c->cfg.model == KGE_TRANSE_L2) launch_fwd<EPI_L2_FWD>(c, g, chunks, st);
+    else launch_fwd<EPI_PLAIN>(c, g, chunks, st);
 }
 
 bool kge_gemm_backward_forms_w(const kge_ctx* c) { return c->cfg.adv_temperature == 0.f; }
@@ -459,13 +459,13 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
 
     const bool tf = kge_gemm_backward_forms_w(c);
     if (model == KGE_TRANSE_L2) {
-        if (tf) launch_bwd<TF_L2, EPI_CHAIN_L2, EPI_L2_DN>(g, q, chunks, st);
-        else launch_bwd<TF_NONE, EPI_CHAIN_L2, EPI_L2_DN>(g, q, chunks, st);
+        if (tf) launch_bwd<TF_L2, EPI_CHAIN_L2, EPI_L2_DN>(c, g, q, chunks, st);
+        else launch_bwd<TF_NONE, EPI_CHAIN_L2, EPI_L2_DN>(c, g, q, chunks, st);
     } else if (model == KGE_DISTMULT) {
-        if (tf) launch_bwd<TF_DOT, EPI_CHAIN_DM, EPI_PLAIN>(g, q, chunks, st);
-        else launch_bwd<TF_NONE, EPI_CHAIN_DM, EPI_PLAIN>(g, q, chunks, st);
+        if (tf) launch_bwd<TF_DOT, EPI_CHAIN_DM, EPI_PLAIN>(c, g, q, chunks, st);
+        else launch_bwd<TF_NONE, EPI_CHAIN_DM, EPI_PLAIN>(c, g, q, chunks, st);
     } else {
-        if (tf) launch_bwd<TF_DOT, EPI_PLAIN, EPI_PLAIN>(g, q, chunks, st);
-        else launch_bwd<TF_NONE, EPI_PLAIN, EPI_PLAIN>(g, q, chunks, st);
+        if (tf) launch_bwd<TF_DOT, EPI_PLAIN, EPI_PLAIN>(c, g, q, chunks, st);
+        else launch_bwd<TF_NONE, EPI_PLAIN, EPI_PLAIN>(c, g, q, chunks, st);
     }
 }

@@ -241,12 +241,12 @@ __global__ __launch_bounds__(256) void k_chain(ChainArgs a) {
 }
 
 template <int MODEL>
-void launch_chain_nv(const ChainArgs& a, int nv, dim3 grid, hipStream_t st) {
+void launch_chain_nv(kge_ctx* c, const ChainArgs& a, int nv, dim3 grid, hipStream_t st) {
     switch (nv) {
-    case 1: hipLaunchKernelGGL((k_chain<MODEL, 1>), grid, dim3(256), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((k_chain<MODEL, 2>), grid, dim3(256), 0, st, a); break;
-    case 3: hipLaunchKernelGGL((k_chain<MODEL, 3>), grid, dim3(256), 0, st, a); break;
-    default: hipLaunchKernelGGL((k_chain<MODEL, 4>), grid, dim3(256), 0, st, a); break;
+    case 1: KGE_LAUNCH(c, (k_chain<MODEL, 1>), grid, dim3(256), 0, st, a); break;
+    case 2: KGE_LAUNCH(c, (k_chain<MODEL, 2>), grid, dim3(256), 0, st, a); break;
+    case 3: KGE_LAUNCH(c, (k_chain<MODEL, 3>), grid, dim3(256), 0, st, a); break;
+    default: KGE_LAUNCH(c, (k_chain<MODEL, 4>), grid, dim3(256), 0, st, a); break;
     }
 }
 
@@ -258,7 +258,7 @@ void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st) {
     a.alpha = c->cfg.adv_temperature; a.is_dist = c->cfg.model == KGE_TRANSE_L2;
     a.bf16 = c->cfg.gemm_input;
     a.cpos = c->cpos; a.row_loss = c->row_loss; a.w_rowsum = c->w_rowsum; a.Wbf = c->Wbf;
-    hipLaunchKernelGGL(k_loss, dim3((b + 3) / 4), dim3(256), 0, st, a);
+    KGE_LAUNCH(c, k_loss, dim3((b + 3) / 4), dim3(256), 0, st, a);
 }
 
 void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st) {
@@ -273,10 +273,10 @@ void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds&
     const int nv = (nvec + 63) / 64;
     const dim3 grid((b + 3) / 4);
     switch (model) {
-    case KGE_TRANSE_L2: launch_chain_nv<KGE_TRANSE_L2>(a, nv, grid, st); break;
-    case KGE_TRANSE_L1: launch_chain_nv<KGE_TRANSE_L1>(a, nv, grid, st); break;
-    case KGE_DISTMULT: launch_chain_nv<KGE_DISTMULT>(a, nv, grid, st); break;
-    case KGE_COMPLEX: launch_chain_nv<KGE_COMPLEX>(a, nv, grid, st); break;
-    default: launch_chain_nv<KGE_ROTATE>(a, nv, grid, st); break;
+    case KGE_TRANSE_L2: launch_chain_nv<KGE_TRANSE_L2>(c, a, nv, grid, st); break;
+    case KGE_TRANSE_L1: launch_chain_nv<KGE_TRANSE_L1>(c, a, nv, grid, st); break;
+    case KGE_DISTMULT: launch_chain_nv<KGE_DISTMULT>(c, a, nv, grid, st); break;
+    case KGE_COMPLEX: launch_chain_nv<KGE_COMPLEX>(c, a, nv, grid, st); break;
+    default: launch_chain_nv<KGE_ROTATE>(c, a, nv, grid, st); break;
     }
 }

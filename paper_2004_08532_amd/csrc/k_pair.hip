@@ -176,8 +176,8 @@ void kge_pair_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     PairArgs a = {};
     a.O = c->O; a.Nst = c->Nst; a.S = out; a.ld_s = ld_out; a.g = gsz; a.k = k; a.D = c->cfg.ent_dim; a.gamma = gamma;
     const dim3 grid((k + PT - 1) / PT, (gsz + PT - 1) / PT, b / gsz);
-    if (c->cfg.model == KGE_ROTATE) hipLaunchKernelGGL(k_pair_fwd<true>, grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(k_pair_fwd<false>, grid, dim3(256), 0, st, a);
+    if (c->cfg.model == KGE_ROTATE) KGE_LAUNCH(c, k_pair_fwd<true>, grid, dim3(256), 0, st, a);
+    else KGE_LAUNCH(c, k_pair_fwd<false>, grid, dim3(256), 0, st, a);
 }
 
 void kge_pair_neg_backward(kge_ctx* c, int b, int k, int gsz, hipStream_t st) {
@@ -186,6 +186,6 @@ void kge_pair_neg_backward(kge_ctx* c, int b, int k, int gsz, hipStream_t st) {
     a.GO = c->GO; a.Gneg = c->Gent + (int64_t)2 * b * a.D;
     const int n_i_tiles = (gsz + BT - 1) / BT, n_j_tiles = (k + BT - 1) / BT;
     const dim3 grid(n_i_tiles + n_j_tiles, b / gsz);
-    if (c->cfg.model == KGE_ROTATE) hipLaunchKernelGGL(k_pair_bwd<true>, grid, dim3(256), 0, st, a, n_i_tiles);
-    else hipLaunchKernelGGL(k_pair_bwd<false>, grid, dim3(256), 0, st, a, n_i_tiles);
+    if (c->cfg.model == KGE_ROTATE) KGE_LAUNCH(c, k_pair_bwd<true>, grid, dim3(256), 0, st, a, n_i_tiles);
+    else KGE_LAUNCH(c, k_pair_bwd<false>, grid, dim3(256), 0, st, a, n_i_tiles);
 }

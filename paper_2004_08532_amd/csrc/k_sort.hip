@@ -180,7 +180,7 @@ void kge_launch_sort(kge_ctx* c, const StepIds& ids, hipStream_t st) {
     kge_make_key_lists(c, ids, &e, &rl);
     c->ebuf = (e.passes - 1) & 1;
     c->rbuf = (rl.passes - 1) & 1;
-    hipLaunchKernelGGL(k_sort, dim3(2), dim3(SORT_THREADS), 0, st, e, rl);
+    KGE_LAUNCH(c, k_sort, dim3(2), dim3(SORT_THREADS), 0, st, e, rl);
 }
 
 void kge_launch_dedup_export(kge_ctx* c, int which, int64_t* uniq, int32_t* count, int64_t* n_unique,

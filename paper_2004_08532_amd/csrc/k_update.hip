@@ -241,5 +241,5 @@ void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, con
     a.lr = lr; a.eps = c->eps; a.row_loss = c->row_loss; a.b = b; a.loss_out = loss_out;
     a.neg_loss_part = c->neg_loss_part; a.n_loss_parts = n_loss_parts;
     const int tiles = a.tiles[0] + a.tiles[1];
-    hipLaunchKernelGGL(k_update, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
+    KGE_LAUNCH(c, k_update, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
 }

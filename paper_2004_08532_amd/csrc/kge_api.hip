@@ -74,18 +74,15 @@ void forward(kge_ctx* c, const float* ent, const float* rel, const StepIds& ids,
     }
 }
 
-// ---- optional per-kernel timing (kge_profile): every kernel of a step is bracketed by events on the stream it
-// runs on, the stream is synchronised after the step, and the elapsed times are accumulated per slot.
+// ---- optional per-kernel timing (kge_profile): the one kernel launched inside a scope carries the scope's two
+// events as its start / stop events (KGE_LAUNCH), the stream is synchronised after the step, and the elapsed times
+// are accumulated per slot.
 struct ProfScope {
     kge_ctx* c;
-    int slot;
-    hipStream_t st;
-    ProfScope(kge_ctx* c_, int slot_, hipStream_t st_) : c(c_), slot(slot_), st(st_) {
-        if (c->prof_on) (void)hipEventRecord(c->prof_ev[slot][0], st);
+    ProfScope(kge_ctx* c_, int slot) : c(c_) {
+        if (c->prof_on) { c->launch_ev0 = c->prof_ev[slot][0]; c->launch_ev1 = c->prof_ev[slot][1]; }
     }
-    ~ProfScope() {
-        if (c->prof_on) (void)hipEventRecord(c->prof_ev[slot][1], st);
-    }
+    ~ProfScope() { c->launch_ev0 = nullptr; c->launch_ev1 = nullptr; }
 };
 
 int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state, const StepIds& ids, int K,
@@ -98,18 +95,18 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
         KGE_HIP(c, hipEventRecord(c->ev_fork, st));
         KGE_HIP(c, hipStreamWaitEvent(c->side_stream, c->ev_fork, 0));
         {
-            ProfScope p(c, KGE_PROF_SORT, c->side_stream);
+            ProfScope p(c, KGE_PROF_SORT);
             kge_launch_sort(c, ids, c->side_stream);
         }
         KGE_HIP(c, hipEventRecord(c->ev_join, c->side_stream));
     }
     if (c->cfg.validate_indices) launch_validate(c, ids, st);
     {
-        ProfScope p(c, KGE_PROF_GATHER, st);
+        ProfScope p(c, KGE_PROF_GATHER);
         kge_launch_gather(c, ent, rel, ids, gamma, nullptr, !long_lists, st);
     }
     {
-        ProfScope p(c, KGE_PROF_SCORE, st);
+        ProfScope p(c, KGE_PROF_SCORE);
         if (is_gemm_model(c->cfg.model)) kge_gemm_neg_score(c, B, K, G, gamma, c->S, c->ld_s, 1, st);
         else kge_pair_neg_score(c, B, K, G, gamma, c->S, c->ld_s, st);
     }
@@ -120,21 +117,21 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
     const bool run_chain = !(gemm && kge_gemm_backward_does_chain(c));
     const int n_loss_parts = gemm ? kge_gemm_loss_parts(c, B, G) : 0;
     if (run_loss) {
-        ProfScope p(c, KGE_PROF_LOSS, st);
+        ProfScope p(c, KGE_PROF_LOSS);
         kge_launch_loss(c, B, K, gamma, st);
     }
     {
-        ProfScope p(c, KGE_PROF_BACKWARD, st);
+        ProfScope p(c, KGE_PROF_BACKWARD);
         if (gemm) kge_gemm_neg_backward(c, ent, rel, ids, K, G, gamma, st);
         else kge_pair_neg_backward(c, B, K, G, st);
     }
     if (run_chain) {
-        ProfScope p(c, KGE_PROF_CHAIN, st);
+        ProfScope p(c, KGE_PROF_CHAIN);
         kge_launch_chain(c, ent, rel, ids, st);
     }
     if (long_lists) KGE_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
     {
-        ProfScope p(c, KGE_PROF_UPDATE, st);
+        ProfScope p(c, KGE_PROF_UPDATE);
         kge_launch_update(c, ent, ent_state, rel, rel_state, ids, lr, n_loss_parts, st);
     }
     KGE_HIP(c, hipGetLastError());

@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "kge.h"
+#include <hip/hip_ext.h>
 
 // ---------------------------------------------------------------------------------------------------------
 // Context.  All device buffers are carved out of one allocation made in kge_create.
@@ -60,8 +61,24 @@ struct kge_ctx {
     hipEvent_t prof_ev[KGE_PROF_SLOTS][2];
     double prof_ms[KGE_PROF_SLOTS];
     int64_t prof_steps;
+    hipEvent_t launch_ev0, launch_ev1;  // set by a profiling scope: the next KGE_LAUNCH takes its own start/stop
+                                        // timestamps into them
     char err[512];
 };
+
+// Kernel launch.  While profiling, the launch carries a start and a stop event that receive the dispatch's own
+// begin / end timestamps (the ones a kernel trace shows), not the time at which a marker between kernels was
+// processed.  One timed launch per profiling scope.
+#define KGE_LAUNCH(c, kernel, grid, block, lds, st, ...)                                                            \
+    do {                                                                                                            \
+        if ((c)->launch_ev0) {                                                                                      \
+            hipExtLaunchKernelGGL(kernel, grid, block, lds, st, (c)->launch_ev0, (c)->launch_ev1, 0, __VA_ARGS__);  \
+            (c)->launch_ev0 = nullptr;                                                                              \
+            (c)->launch_ev1 = nullptr;                                                                              \
+        } else {                                                                                                    \
+            hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);                                          \
+        }                                                                                                           \
+    } while (0)
 
 // ---------------------------------------------------------------------------------------------------------
 // The ids of one step, as the kernels receive them.
