@@ -48,7 +48,7 @@ def _load():
         vp, i64, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double
         lib.ko_loss_grad.restype = ctypes.c_int
         lib.ko_loss_grad.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, vp, vp, i64, vp, i64, i64, vp,
-                                     vp, vp, vp, vp, vp, i64, vp, vp, vp, i64, vp, vp]
+                                     vp, vp, vp, vp, vp, i64, vp, vp, vp, i64, vp, vp, vp, vp]
         lib.ko_dedup.restype = i64
         lib.ko_dedup.argtypes = [vp, i64, vp, vp]
         lib.ko_adagrad_rows.restype = None
@@ -56,7 +56,7 @@ def _load():
         lib.ko_train_step.restype = ctypes.c_int
         lib.ko_train_step.argtypes = [ctypes.POINTER(_Params), vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
                                       vp, i64, i64, dbl, dbl, ctypes.c_int, vp, vp, vp,
-                                      vp, vp, vp, vp, vp, vp, vp, vp]
+                                      vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -104,7 +104,7 @@ def loss_and_grad(model, E, R, h, r, t, neg, k, chunk, neg_side, gamma, adv_temp
     wf = None if w_fixed is None else np.ascontiguousarray(w_fixed, dtype=np.float64)
     rc = lib.ko_loss_grad(ctypes.byref(p), _ptr(E), _ptr(R), _ptr(h), _ptr(r), _ptr(t), b, _ptr(neg), k, chunk,
                           _ptr(wf), ctypes.addressof(loss), _ptr(pos), _ptr(negs), _ptr(w),
-                          None, E.shape[0], _ptr(dE), _ptr(aE), None, R.shape[0], _ptr(dR), _ptr(aR))
+                          None, E.shape[0], _ptr(dE), _ptr(aE), None, R.shape[0], _ptr(dR), _ptr(aR), None, None)
     if rc != 0:
         raise ValueError(f"ko_loss_grad failed with {rc}")
     out = {"loss": loss.value, "pos": pos, "neg": negs, "w": w}
@@ -150,8 +150,8 @@ def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr,
     """One step, in place on float32 E, SE, R, SR.  Returns loss (and scores when asked).
 
     report=True (touched-rows mode) returns ``(loss, rep)`` where rep holds, for the distinct rows of the step,
-    ``ent_ids``, ``dE`` (their summed gradient rows) and ``absE`` (magnitudes of the terms, per element), and the
-    same for relations: what the tests need to bound rounding effects, not part of the method."""
+    ``ent_ids``, ``dE`` (their summed gradient rows), ``absE`` (magnitudes of the terms, per element) and ``maxE``
+    (largest share of a single negative pair in that element), and the same for relations: what the tests need to bound rounding effects, not part of the method."""
     lib = _load()
     for a in (E, SE, R, SR):
         assert a.dtype == np.float32 and a.flags.c_contiguous
@@ -163,23 +163,25 @@ def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr,
     pos = np.zeros(b, np.float64) if want_scores else None
     negs = np.zeros((b, k), np.float64) if want_scores else None
     rep = None
-    extra = [None] * 8
+    extra = [None] * 10
     if report:
         assert not dense
         nk = 2 * b + neg.shape[0]
         rep = {"ent_ids": np.zeros(nk, np.int64), "dE": np.zeros((nk, E.shape[1])), "absE": np.zeros((nk, E.shape[1])),
-               "rel_ids": np.zeros(b, np.int64), "dR": np.zeros((b, R.shape[1])), "absR": np.zeros((b, R.shape[1]))}
+               "rel_ids": np.zeros(b, np.int64), "dR": np.zeros((b, R.shape[1])), "absR": np.zeros((b, R.shape[1])),
+               "maxE": np.zeros((nk, E.shape[1])), "maxR": np.zeros((b, R.shape[1]))}
         ne, nr = ctypes.c_int64(0), ctypes.c_int64(0)
         extra = [_ptr(rep["ent_ids"]), ctypes.addressof(ne), _ptr(rep["dE"]), _ptr(rep["absE"]),
-                 _ptr(rep["rel_ids"]), ctypes.addressof(nr), _ptr(rep["dR"]), _ptr(rep["absR"])]
+                 _ptr(rep["rel_ids"]), ctypes.addressof(nr), _ptr(rep["dR"]), _ptr(rep["absR"]),
+                 _ptr(rep["maxE"]), _ptr(rep["maxR"])]
     rc = lib.ko_train_step(ctypes.byref(p), _ptr(E), _ptr(SE), E.shape[0], _ptr(R), _ptr(SR), R.shape[0],
                            _ptr(h), _ptr(r), _ptr(t), b, _ptr(neg), k, chunk, float(lr), float(eps), int(dense),
                            ctypes.addressof(loss), _ptr(pos), _ptr(negs), *extra)
     if rc != 0:
         raise ValueError(f"ko_train_step failed with {rc}")
     if report:
-        for key, n in (("ent_ids", ne.value), ("dE", ne.value), ("absE", ne.value), ("rel_ids", nr.value),
-                       ("dR", nr.value), ("absR", nr.value)):
+        for key, n in (("ent_ids", ne.value), ("dE", ne.value), ("absE", ne.value), ("maxE", ne.value),
+                       ("rel_ids", nr.value), ("dR", nr.value), ("absR", nr.value), ("maxR", nr.value)):
             rep[key] = rep[key][:n]
         return loss.value, rep
     if want_scores:

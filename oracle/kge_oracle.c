@@ -427,6 +427,9 @@ static void add_rows(double *acc, int64_t slot, int dim, const double *v) {
  * dE / dR : NULL (no gradients wanted) or zero-initialised [n_slots * dim] accumulators; row s of dE
  * belongs to entity ent_ids[s] (ascending list), or to entity s when ent_ids == NULL.
  * aE / aR : NULL or accumulators of the same shape for the condition measure of grad_triple_mag.
+ * mE / mR : NULL or arrays of the same shape that receive, per element, the largest grad_triple_mag measure of a
+ *           single (positive, negative) pair: how much one backward coefficient weighs in that element (the tests
+ *           bound with it what a coefficient that rounds to the neighbouring bfloat16 value can change).
  * Returns 0, or -1 on bad arguments, -2 if an id has no slot.
  */
 int ko_loss_grad(const ko_params *p, const void *E, const void *R,
@@ -434,7 +437,7 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
                  const int64_t *neg, int64_t k, int64_t chunk, const double *w_fixed,
                  double *loss_out, double *pos_score, double *neg_score, double *w_out,
                  const int64_t *ent_ids, int64_t n_ent_slots, double *dE, double *aE,
-                 const int64_t *rel_ids, int64_t n_rel_slots, double *dR, double *aR) {
+                 const int64_t *rel_ids, int64_t n_rel_slots, double *dR, double *aR, double *mE, double *mR) {
     if (b <= 0 || chunk <= 0 || b % chunk != 0 || k < 0) return -1;
     if ((p->model == KO_COMPLEX || p->model == KO_ROTATE) && (p->ent_dim % 2)) return -1;
     const int De = p->ent_dim, Dr = p->rel_dim, f64 = p->tables_f64;
@@ -514,6 +517,18 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
             if (aE) {
                 if (head_side) grad_triple_mag(p, nv, rv, tv, cneg, aE + sn * De, aR + sr * Dr, aE + st * De);
                 else grad_triple_mag(p, hv, rv, nv, cneg, aE + sh * De, aR + sr * Dr, aE + sn * De);
+            }
+            if (mE && mR) { /* this pair's measure alone, then the element-wise maximum */
+                memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
+                if (head_side) grad_triple_mag(p, nv, rv, tv, cneg, tt, tr, th); /* tt: the negative, th: the kept one */
+                else grad_triple_mag(p, hv, rv, nv, cneg, th, tr, tt);
+                const int64_t sk = head_side ? st : sh;
+                for (int d = 0; d < De; ++d) {
+                    if (th[d] > mE[sk * De + d]) mE[sk * De + d] = th[d];
+                    if (tt[d] > mE[sn * De + d]) mE[sn * De + d] = tt[d];
+                }
+                for (int d = 0; d < Dr; ++d) if (tr[d] > mR[sr * Dr + d]) mR[sr * Dr + d] = tr[d];
+                memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
             }
             if (use_split) {
                 if (p->bf16_inputs) {
@@ -602,7 +617,8 @@ int ko_train_step(const ko_params *p, float *E, float *SE, int64_t n_ent, float 
                   const int64_t *neg, int64_t k, int64_t chunk, double lr, double eps, int dense,
                   double *loss_out, double *pos_score, double *neg_score,
                   int64_t *ent_ids_out, int64_t *n_ent_out, double *dE_out, double *aE_out,
-                  int64_t *rel_ids_out, int64_t *n_rel_out, double *dR_out, double *aR_out) {
+                  int64_t *rel_ids_out, int64_t *n_rel_out, double *dR_out, double *aR_out,
+                  double *mE_out, double *mR_out) {
     if (p->tables_f64) return -1;
     if (b <= 0 || chunk <= 0 || b % chunk != 0) return -1;
     const int64_t n_neg = (b / chunk) * k, n_keys = 2 * b + n_neg;
@@ -629,11 +645,16 @@ int ko_train_step(const ko_params *p, float *E, float *SE, int64_t n_ent, float 
     if (report) {
         memset(aE_out, 0, sizeof(double) * (size_t)ue * p->ent_dim);
         memset(aR_out, 0, sizeof(double) * (size_t)ur * p->rel_dim);
+        if (mE_out && mR_out) {
+            memset(mE_out, 0, sizeof(double) * (size_t)ue * p->ent_dim);
+            memset(mR_out, 0, sizeof(double) * (size_t)ur * p->rel_dim);
+        }
     }
     int rc = (dE && dR) ? 0 : -3;
     if (rc == 0)
         rc = ko_loss_grad(p, E, R, h, r, t, b, neg, k, chunk, NULL, loss_out, pos_score, neg_score, NULL,
-                          ent_ids, ue, dE, report ? aE_out : NULL, rel_ids, ur, dR, report ? aR_out : NULL);
+                          ent_ids, ue, dE, report ? aE_out : NULL, rel_ids, ur, dR, report ? aR_out : NULL,
+                          report ? mE_out : NULL, report ? mR_out : NULL);
     if (rc == 0 && report) {
         memcpy(ent_ids_out, ent_ids, sizeof(int64_t) * ue); *n_ent_out = ue;
         memcpy(rel_ids_out, rel_ids, sizeof(int64_t) * ur); *n_rel_out = ur;

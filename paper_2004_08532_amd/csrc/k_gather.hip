@@ -28,8 +28,6 @@ struct GatherArgs {
     float* cpos;      // dL/df+_i = -sigmoid(-f+_i) / b
     float* inv_dpos;  // TransE-L2: 1 / |o_i - c_i| (0 if the distance is 0)
     float* row_loss;  // softplus(-f+_i) / b
-    uint16_t* Obf;
-    uint16_t* Nbf;
     int gather_blocks;       // blocks [0, gather_blocks) gather rows
     int ent_rank_blocks;     // the next ent_rank_blocks blocks order the entity key list, the rest the relation keys
     KeyList ent, rel;
@@ -83,14 +81,6 @@ __device__ __forceinline__ void rank_block(const KeyList& l, int blk, uint32_t* 
 
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
 
-__device__ __forceinline__ void store_bf16x4(uint16_t* dst, const float* v, float* rounded) {
-    uint16_t q[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { q[e] = f32_to_bf16(v[e]); rounded[e] = bf16_to_f32(q[e]); }
-    uint2 pk = make_uint2((uint32_t)q[0] | ((uint32_t)q[1] << 16), (uint32_t)q[2] | ((uint32_t)q[3] << 16));
-    *reinterpret_cast<uint2*>(dst) = pk;
-}
-
 // NV = 16-byte vectors per lane: ceil(D/4/64) for the real models, ceil(D/8/64) (re, im) pairs for the complex ones.
 template <int MODEL, int NV>
 __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
@@ -124,11 +114,9 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
             if (v < nv4) {
                 float4 x = ld4(src + 4 * v);
                 float xv[4] = {x.x, x.y, x.z, x.w};
-                if (a.bf16) {
-                    float rq[4];
-                    store_bf16x4(a.Nbf + (int64_t)j * D + 4 * v, xv, rq);
+                if (a.bf16) {  // the product kernels round their operands to bf16: the norm is that of the rounded row
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) xv[e] = rq[e];
+                    for (int e = 0; e < 4; ++e) xv[e] = round_bf16(xv[e]);
                 }
                 st4(dst + 4 * v, x);
                 nn += xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3];
@@ -174,7 +162,10 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
             }
             if (MODEL == KGE_TRANSE_L2 || a.bf16) {
                 float nv[4] = {ov[0], ov[1], ov[2], ov[3]};
-                if (a.bf16) store_bf16x4(a.Obf + (int64_t)i * D + 4 * v, ov, nv);
+                if (a.bf16) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) nv[e] = round_bf16(nv[e]);
+                }
                 on += nv[0] * nv[0] + nv[1] * nv[1] + nv[2] * nv[2] + nv[3] * nv[3];
             }
         } else {
@@ -202,11 +193,6 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
             }
             st4(po + 4 * v, make_float4(ore[0], ore[1], ore[2], ore[3]));
             st4(po + im_off + 4 * v, make_float4(oim[0], oim[1], oim[2], oim[3]));
-            if (a.bf16) {
-                float tmp[4];
-                store_bf16x4(a.Obf + (int64_t)i * D + 4 * v, ore, tmp);
-                store_bf16x4(a.Obf + (int64_t)i * D + im_off + 4 * v, oim, tmp);
-            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (MODEL == KGE_COMPLEX) acc += ore[e] * cre[e] + oim[e] * cim[e];
@@ -260,7 +246,6 @@ void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds
     a.gamma = gamma; a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
     a.O = c->O; a.Nst = c->Nst; a.fpos = c->fpos; a.pos_out = pos_out; a.o_n2 = c->o_n2; a.n_n2 = c->n_n2;
     a.cpos = c->cpos; a.inv_dpos = c->inv_dpos; a.row_loss = c->row_loss;
-    a.Obf = c->Obf; a.Nbf = c->Nbf;
     const int model = c->cfg.model;
     const bool cplx = model == KGE_COMPLEX || model == KGE_ROTATE;
     const int nvec = cplx ? a.D / 8 : a.D / 4;

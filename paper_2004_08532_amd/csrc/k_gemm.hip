@@ -30,6 +30,7 @@
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 enum { EPI_PLAIN = 0, EPI_L2_FWD = 1, EPI_L2_DO = 2, EPI_L2_DN = 3, EPI_CHAIN_L2 = 4, EPI_CHAIN_DM = 5 };
 enum { TF_NONE = 0, TF_DOT = 1, TF_L2 = 2 };  // how the A operand is derived from what is stored
@@ -179,13 +180,30 @@ __device__ __forceinline__ void lds_frag(const float* region, int lane, int q, f
     }
 }
 
+// bf16 operands: the eight K-values a lane feeds to MFMA m = 0, 1 of a 32-wide K block:
+// kk = 16 m + 8 * (lane / 32) + 0..7, for row lane % 32.
+template <bool KC>
+__device__ __forceinline__ void lds_frag8(const float* region, int lane, int m, float (&f)[8]) {
+    const int rw = lane & 31, kk = 16 * m + 8 * (lane >> 5);
+    if (KC) {
+        const float4 u = ld4(region + rw * KC_PITCH + kk), v = ld4(region + rw * KC_PITCH + kk + 4);
+        f[0] = u.x; f[1] = u.y; f[2] = u.z; f[3] = u.w; f[4] = v.x; f[5] = v.y; f[6] = v.z; f[7] = v.w;
+    } else {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) f[t] = region[(kk + t) * TILE + rw];
+    }
+}
+
 // Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Each XCD gets a
 // contiguous range of tiles (row-major, column tiles fastest), so the tiles that share an A row-block run on one
 // XCD and re-read it from that L2 instead of from memory.  q = index of the workgroup within its XCD.
 __device__ __forceinline__ int xcd_tile(int q, int per_xcd) { return (blockIdx.x & 7) * per_xcd + q; }
 
 // One 32x32 output tile: K loop, cross-wave sum, epilogue.
-template <int NW, bool A_KC, bool B_KC, int TF, int EPI, bool IS_DO>
+// BF: both operands are rounded to bf16 on their way from LDS to the matrix unit (after the W transform, so W is
+// rounded too) and multiplied by v_mfma_f32_32x32x16_bf16 with fp32 accumulation; the TransE-L2 correction terms
+// then use the rounded o / n rows and the sums of the rounded W.
+template <int NW, bool A_KC, bool B_KC, int TF, int EPI, bool IS_DO, bool BF>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*lds)[2][REGION]) {
     constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM;
     constexpr bool WANT_ASUM = EPI == EPI_L2_DO || EPI == EPI_L2_DN || EPI == EPI_CHAIN_L2;
@@ -259,22 +277,46 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        if (BF) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            float fa[4], fb[4];
-            lds_frag<A_KC>(As, lane, q, fa);
-            lds_frag<B_KC>(Bs, lane, q, fb);
-            if (TF != TF_NONE) {  // every element of the block is read by exactly one lane here
+            for (int m = 0; m < 2; ++m) {
+                float fa[8], fb[8];
+                lds_frag8<A_KC>(As, lane, m, fa);
+                lds_frag8<B_KC>(Bs, lane, m, fb);
+                if (TF != TF_NONE) {
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    if (loss_tile) fa[t] = w_from_stored<TF, true>(fa[t], g.gamma, g.wk, loss);
-                    else { float unused = 0.f; fa[t] = w_from_stored<TF, false>(fa[t], g.gamma, g.wk, unused); }
+                    for (int t = 0; t < 8; ++t) {
+                        if (loss_tile) fa[t] = w_from_stored<TF, true>(fa[t], g.gamma, g.wk, loss);
+                        else { float unused = 0.f; fa[t] = w_from_stored<TF, false>(fa[t], g.gamma, g.wk, unused); }
+                    }
                 }
-            }
+                bf16x8 pa, pb;
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[t], fb[t], acc, 0, 0, 0);
-                if (WANT_ASUM) a_sum += fa[t];
+                for (int t = 0; t < 8; ++t) { pa[t] = (__bf16)fa[t]; pb[t] = (__bf16)fb[t]; }
+                if (WANT_ASUM) {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) a_sum += (float)pa[t];
+                }
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, pb, acc, 0, 0, 0);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float fa[4], fb[4];
+                lds_frag<A_KC>(As, lane, q, fa);
+                lds_frag<B_KC>(Bs, lane, q, fb);
+                if (TF != TF_NONE) {  // every element of the block is read by exactly one lane here
+    #pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        if (loss_tile) fa[t] = w_from_stored<TF, true>(fa[t], g.gamma, g.wk, loss);
+                        else { float unused = 0.f; fa[t] = w_from_stored<TF, false>(fa[t], g.gamma, g.wk, unused); }
+                    }
+                }
+    #pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[t], fb[t], acc, 0, 0, 0);
+                    if (WANT_ASUM) a_sum += fa[t];
+                }
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -326,11 +368,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             const float d = sqrtf(fmaxf(d2, 0.f));
             C[(int64_t)gm * g.ldc + gn] = g.store_dist ? d : g.gamma - d;
         } else if (EPI == EPI_L2_DO || EPI == EPI_L2_DN) {
-            C[(int64_t)gm * g.ldc + gn] = s - rs * g.X[c * g.sX + (int64_t)gm * g.ldx + gn];
+            const float xv = g.X[c * g.sX + (int64_t)gm * g.ldx + gn];
+            C[(int64_t)gm * g.ldc + gn] = s - rs * (BF ? round_bf16(xv) : xv);
         } else if (EPI == EPI_CHAIN_L2) {
             // dL/do = W n - rowsum(W) o  +  dL/df+ * d(gamma - |o - c|)/do
             const float dir = (e_o[it] - e_c[it]) * e_inv[it];
-            const float go = s - rs * e_o[it] - e_cp[it] * dir;
+            const float go = s - rs * (BF ? round_bf16(e_o[it]) : e_o[it]) - e_cp[it] * dir;
             g.Gent[(int64_t)(e_head ? g.b + bi : bi) * g.D + gn] = go;
             g.Gent[(int64_t)(e_head ? bi : g.b + bi) * g.D + gn] = e_cp[it] * dir;
             g.Grel[(int64_t)bi * g.D + gn] = e_head ? -go : go;
@@ -343,27 +386,27 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     }
 }
 
-template <int NW, int EPI>
+template <int NW, int EPI, bool BF>
 __global__ __launch_bounds__(NW * 64) void k_gemm_fwd(GemmArgs g) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
     const int tile = xcd_tile(blockIdx.x >> 3, gridDim.x >> 3);
     if (tile >= g.tiles) return;
-    gemm_tile<NW, true, true, TF_NONE, EPI, false>(g, tile, lds);
+    gemm_tile<NW, true, true, TF_NONE, EPI, false, BF>(g, tile, lds);
 }
 
 // dN tiles first (their K is the chunk size, they run longest), then dO tiles; each XCD gets its share of both.
 // Held to 128 registers so that four waves fit on every SIMD (two 8-wave workgroups per CU): all tiles of the
 // Freebase-scale step are then resident at once instead of running in two rounds.
-template <int NW, int TF, int EPI_O, int EPI_N>
+template <int NW, int TF, int EPI_O, int EPI_N, bool BF>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_gemm_bwd(GemmArgs gO, GemmArgs gN, int per_xcd_n, int per_xcd_o) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
     const int q = blockIdx.x >> 3;
     if (q < per_xcd_n) {
         const int tile = xcd_tile(q, per_xcd_n);
-        if (tile < gN.tiles) gemm_tile<NW, false, false, TF, EPI_N, false>(gN, tile, lds);
+        if (tile < gN.tiles) gemm_tile<NW, false, false, TF, EPI_N, false, BF>(gN, tile, lds);
     } else {
         const int tile = xcd_tile(q - per_xcd_n, per_xcd_o);
-        if (tile < gO.tiles) gemm_tile<NW, true, false, TF, EPI_O, true>(gO, tile, lds);
+        if (tile < gO.tiles) gemm_tile<NW, true, false, TF, EPI_O, true, BF>(gO, tile, lds);
     }
 }
 
@@ -382,17 +425,17 @@ void set_tiling(GemmArgs& g, int chunks) {
     g.tiles = g.gx * g.gy * chunks;
 }
 
-template <int EPI>
+template <int EPI, bool BF>
 void launch_fwd(kge_ctx* c, GemmArgs g, int chunks, hipStream_t st) {
     set_tiling(g, chunks);
     const dim3 grid(8 * ((g.tiles + 7) / 8));
     const int nw = pick_nw(g.tiles, (g.K + TILE - 1) / TILE, 16);
-    if (nw == 4) KGE_LAUNCH(c, (k_gemm_fwd<4, EPI>), grid, dim3(256), 0, st, g);
-    else if (nw == 8) KGE_LAUNCH(c, (k_gemm_fwd<8, EPI>), grid, dim3(512), 0, st, g);
-    else KGE_LAUNCH(c, (k_gemm_fwd<16, EPI>), grid, dim3(1024), 0, st, g);
+    if (nw == 4) KGE_LAUNCH(c, (k_gemm_fwd<4, EPI, BF>), grid, dim3(256), 0, st, g);
+    else if (nw == 8) KGE_LAUNCH(c, (k_gemm_fwd<8, EPI, BF>), grid, dim3(512), 0, st, g);
+    else KGE_LAUNCH(c, (k_gemm_fwd<16, EPI, BF>), grid, dim3(1024), 0, st, g);
 }
 
-template <int TF, int EPI_O, int EPI_N>
+template <int TF, int EPI_O, int EPI_N, bool BF>
 void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st) {
     set_tiling(gO, chunks);
     set_tiling(gN, chunks);
@@ -401,8 +444,8 @@ void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st
     const int nblk = ((gO.K > gN.K ? gO.K : gN.K) + TILE - 1) / TILE;
     // at most 8 waves: 74 KB of LDS per workgroup, so two workgroups share a CU
     const int nw = pick_nw(gO.tiles + gN.tiles, nblk, 8);
-    if (nw == 4) KGE_LAUNCH(c, (k_gemm_bwd<4, TF, EPI_O, EPI_N>), grid, dim3(256), 0, st, gO, gN, per_n, per_o);
-    else KGE_LAUNCH(c, (k_gemm_bwd<8, TF, EPI_O, EPI_N>), grid, dim3(512), 0, st, gO, gN, per_n, per_o);
+    if (nw == 4) KGE_LAUNCH(c, (k_gemm_bwd<4, TF, EPI_O, EPI_N, BF>), grid, dim3(256), 0, st, gO, gN, per_n, per_o);
+    else KGE_LAUNCH(c, (k_gemm_bwd<8, TF, EPI_O, EPI_N, BF>), grid, dim3(512), 0, st, gO, gN, per_n, per_o);
 }
 
 }  // namespace
@@ -420,11 +463,20 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     g.rowv = c->o_n2; g.colv = c->n_n2; g.s_rowv = gsz; g.s_colv = k;
     g.gamma = gamma; g.store_dist = dist_mode;
     const int chunks = b / gsz;
-    if (c->cfg.model == KGE_TRANSE_L2) launch_fwd<EPI_L2_FWD>(c, g, chunks, st);
-    else launch_fwd<EPI_PLAIN>(c, g, chunks, st);
+    const bool bf = c->cfg.gemm_input == 1;
+    if (c->cfg.model == KGE_TRANSE_L2) {
+        if (bf) launch_fwd<EPI_L2_FWD, true>(c, g, chunks, st);
+        else launch_fwd<EPI_L2_FWD, false>(c, g, chunks, st);
+    } else {
+        if (bf) launch_fwd<EPI_PLAIN, true>(c, g, chunks, st);
+        else launch_fwd<EPI_PLAIN, false>(c, g, chunks, st);
+    }
 }
 
-bool kge_gemm_backward_forms_w(const kge_ctx* c) { return c->cfg.adv_temperature == 0.f; }
+// With bf16 operands W is rounded to bf16, and which neighbour a value rounds to should not hinge on the few-ulp
+// error of the fast exp2 / reciprocal used when W is formed on the fly: there the loss kernel forms W (accurate
+// functions, once per element) and the products only round it.
+bool kge_gemm_backward_forms_w(const kge_ctx* c) { return c->cfg.adv_temperature == 0.f && c->cfg.gemm_input == 0; }
 bool kge_gemm_backward_does_chain(const kge_ctx* c) {
     return c->cfg.model == KGE_TRANSE_L2 || c->cfg.model == KGE_DISTMULT;
 }
@@ -458,14 +510,21 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
     q.X = c->Nst; q.ldx = D; q.sX = (int64_t)k * D;
 
     const bool tf = kge_gemm_backward_forms_w(c);
+    const bool bf = c->cfg.gemm_input == 1;
+#define KGE_BWD(TF, EO, EN)                                             \
+    do {                                                                \
+        if (bf) launch_bwd<TF, EO, EN, true>(c, g, q, chunks, st);      \
+        else launch_bwd<TF, EO, EN, false>(c, g, q, chunks, st);        \
+    } while (0)
     if (model == KGE_TRANSE_L2) {
-        if (tf) launch_bwd<TF_L2, EPI_CHAIN_L2, EPI_L2_DN>(c, g, q, chunks, st);
-        else launch_bwd<TF_NONE, EPI_CHAIN_L2, EPI_L2_DN>(c, g, q, chunks, st);
+        if (tf) KGE_BWD(TF_L2, EPI_CHAIN_L2, EPI_L2_DN);
+        else KGE_BWD(TF_NONE, EPI_CHAIN_L2, EPI_L2_DN);
     } else if (model == KGE_DISTMULT) {
-        if (tf) launch_bwd<TF_DOT, EPI_CHAIN_DM, EPI_PLAIN>(c, g, q, chunks, st);
-        else launch_bwd<TF_NONE, EPI_CHAIN_DM, EPI_PLAIN>(c, g, q, chunks, st);
+        if (tf) KGE_BWD(TF_DOT, EPI_CHAIN_DM, EPI_PLAIN);
+        else KGE_BWD(TF_NONE, EPI_CHAIN_DM, EPI_PLAIN);
     } else {
-        if (tf) launch_bwd<TF_DOT, EPI_PLAIN, EPI_PLAIN>(c, g, q, chunks, st);
-        else launch_bwd<TF_NONE, EPI_PLAIN, EPI_PLAIN>(c, g, q, chunks, st);
+        if (tf) KGE_BWD(TF_DOT, EPI_PLAIN, EPI_PLAIN);
+        else KGE_BWD(TF_NONE, EPI_PLAIN, EPI_PLAIN);
     }
+#undef KGE_BWD
 }

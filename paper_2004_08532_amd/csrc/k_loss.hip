@@ -29,7 +29,6 @@ struct LossArgs {
     float* cpos;
     float* row_loss;
     float* w_rowsum;
-    uint16_t* Wbf;
 };
 
 __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
@@ -63,11 +62,7 @@ __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
         li += w * softplusf_(f);
         float coef = w * sigmoidf_(f) * invb;
         if (a.is_dist) coef = raw > 0.f ? coef / raw : 0.f;
-        if (a.bf16) {
-            const uint16_t q = f32_to_bf16(coef);
-            a.Wbf[(int64_t)i * a.ld_s + j] = q;
-            coef = bf16_to_f32(q);
-        }
+        if (a.bf16) coef = round_bf16(coef);  // what the product kernels multiply with
         s[j] = coef;
         rs += coef;
     }
@@ -257,7 +252,7 @@ void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st) {
     a.S = c->S; a.ld_s = c->ld_s; a.b = b; a.k = k; a.fpos = c->fpos; a.gamma = gamma;
     a.alpha = c->cfg.adv_temperature; a.is_dist = c->cfg.model == KGE_TRANSE_L2;
     a.bf16 = c->cfg.gemm_input;
-    a.cpos = c->cpos; a.row_loss = c->row_loss; a.w_rowsum = c->w_rowsum; a.Wbf = c->Wbf;
+    a.cpos = c->cpos; a.row_loss = c->row_loss; a.w_rowsum = c->w_rowsum;
     KGE_LAUNCH(c, k_loss, dim3((b + 3) / 4), dim3(256), 0, st, a);
 }
 

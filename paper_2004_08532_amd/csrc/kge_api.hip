@@ -219,7 +219,9 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
         return fail(nullptr, KGE_ERR_INVALID_ARG, "more than 2^24 entity keys per step%s");
     if (cfg->adagrad_mode != 0) return fail(nullptr, KGE_ERR_UNSUPPORTED, "only element-wise Adagrad state is implemented%s");
     if (cfg->gemm_input != 0 && cfg->gemm_input != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "gemm_input must be 0 or 1%s");
-    if (cfg->gemm_input == 1) return fail(nullptr, KGE_ERR_UNSUPPORTED, "bf16 operands are not implemented yet%s");
+    if (cfg->gemm_input != 0 && cfg->gemm_input != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "gemm_input must be 0 or 1%s");
+    if (cfg->gemm_input == 1 && !is_gemm_model(cfg->model))
+        return fail(nullptr, KGE_ERR_UNSUPPORTED, "bf16 operands exist for the matrix-product models only (TransE-L2, DistMult, ComplEx)%s");
     if (cfg->adv_temperature < 0.f || cfg->adagrad_eps < 0.f) return fail(nullptr, KGE_ERR_INVALID_ARG, "negative temperature or eps%s");
 
     int ndev = 0;

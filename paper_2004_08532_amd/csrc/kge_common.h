@@ -40,9 +40,6 @@ struct kge_ctx {
     float* w_rowsum; // [max_batch]          sum_j W_ij       (TransE-L2, self-adversarial path)
     float* inv_dpos; // [max_batch]          1 / |o_i - c_i|  (TransE-L2)
     float* neg_loss_part;  // [max_batch/32 + max_chunks]  negative-side loss sums written by the backward launch
-    uint16_t* Obf;   // bf16 copies of O, Nst, W (gemm_input = 1)
-    uint16_t* Nbf;
-    uint16_t* Wbf;
     uint32_t* ekey[2];  // entity sort ping-pong: keys
     uint32_t* epos[2];  //                        positions in the key list
     uint32_t* rkey[2];  // relation sort ping-pong
@@ -199,12 +196,6 @@ __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast
 __device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 __device__ __forceinline__ float4 f4(float x) { return make_float4(x, x, x, x); }
 
-// round-to-nearest-even fp32 -> bf16 bits
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7f800000u) == 0x7f800000u) return (uint16_t)(u >> 16);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+// fp32 -> bf16 -> fp32, round to nearest even (the hardware conversion of gfx950)
+__device__ __forceinline__ float round_bf16(float x) { return (float)(__bf16)x; }
 #endif

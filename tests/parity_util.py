@@ -39,9 +39,20 @@ def dev(x: np.ndarray) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(x)).cuda()
 
 
-def rounding_allowance(g, A, S_prev, lr, eps):
-    """Largest change of the Adagrad update and of the new state when g moves by +-RHO * A."""
+# bf16 operands: a backward coefficient whose fp32 and fp64 values round to different bf16 neighbours changes by one
+# bf16 spacing, at most 2^-7 of itself, and with it that pair's share (the oracle's per-pair maximum M) of every
+# gradient element it enters.  Such coefficients are rare (their values must straddle a rounding boundary); room
+# for FLIPS of them in one element.
+BF16_SPACING = 2.0 ** -7
+FLIPS = 3
+
+
+def rounding_allowance(g, A, S_prev, lr, eps, M=None):
+    """Largest change of the Adagrad update and of the new state when g moves by +-RHO * A (plus, with bf16
+    operands, FLIPS coefficients moving to the neighbouring bf16 value)."""
     d = RHO * A
+    if M is not None:
+        d = d + FLIPS * BF16_SPACING * M
 
     def upd(x):
         return lr * x / (np.sqrt(S_prev + x * x) + eps)
@@ -106,14 +117,14 @@ class Pair:
         got_loss, (want_loss, rep) = self.step_both(h, r, t, neg, side, report=True)
         assert abs(got_loss - want_loss) <= SCORE_TOL * max(1.0, abs(want_loss)), (got_loss, want_loss)
         assert np.array_equal(rep["ent_ids"], ent_ids) and np.array_equal(rep["rel_ids"], rel_ids)
-        for name, ids, host, host_s, devt, devs, g, A in (
-                ("E", ent_ids, self.E, self.SE, self.dE, self.dSE, rep["dE"], rep["absE"]),
-                ("R", rel_ids, self.R, self.SR, self.dR, self.dSR, rep["dR"], rep["absR"])):
+        for name, ids, host, host_s, devt, devs, g, A, M in (
+                ("E", ent_ids, self.E, self.SE, self.dE, self.dSE, rep["dE"], rep["absE"], rep["maxE"]),
+                ("R", rel_ids, self.R, self.SR, self.dR, self.dSR, rep["dR"], rep["absR"], rep["maxR"])):
             idx = torch.from_numpy(ids).cuda()
             got = devt[idx].cpu().numpy().astype(np.float64)
             got_s = devs[idx].cpu().numpy().astype(np.float64)
             want, want_s = host[ids].astype(np.float64), host_s[ids].astype(np.float64)
-            du, ds = rounding_allowance(g, A, S_prev[name], w.lr, self.eps)
+            du, ds = rounding_allowance(g, A, S_prev[name], w.lr, self.eps, M if w.bf16_inputs else None)
             base = EMB_TOL * np.maximum(np.abs(want), self.floor)
             ratio = np.abs(got - want) / (base + du)
             worst = float(ratio.max())

@@ -130,6 +130,33 @@ def test_medium_shape_reduced_entities(kge):
         p.close()
 
 
+@pytest.mark.parametrize("alpha", [0.0, 1.0])
+@pytest.mark.parametrize("model", ["transe_l2", "distmult", "complex"])
+def test_bf16_operands_ragged_shapes(kge, model, alpha):
+    """bf16 operands, fp32 accumulation (the matrix-product models): o, the corrupting rows and the backward
+    coefficients are rounded to bf16 before the three products; positives, loss and update stay fp32.  The oracle
+    rounds the same three operands and works in fp64.  A coefficient that the two sides round to different bf16
+    neighbours (their fp32 / fp64 values differ in the last bits) changes one of the k terms of a gradient element
+    by 2^-8 of that term; the per-step tolerance has room for that."""
+    w = ragged(model, adv_temperature=alpha, bf16_inputs=True, name="ragged-bf16-" + model)
+    p = Pair(w, kge)
+    try:
+        run_steps(p, configs.BatchStream(w), w.steps, check_dedup_at=(0,))
+    finally:
+        p.close()
+
+
+def test_large_config_reduced_entities(kge):
+    """Configuration 'large' (TransE-L2, bf16 operands, dim 400, b 2048, g 256, k 1024: 12,288 entity keys per
+    step) with the entity count cut to 100,000 so that the oracle's tables stay small."""
+    w = configs.LARGE.scaled(n_entities=100_000, n_triples=800_000)
+    p = Pair(w, kge)
+    try:
+        run_steps(p, configs.BatchStream(w), 2, check_dedup_at=(0,))
+    finally:
+        p.close()
+
+
 def test_freebase_batch_shape_reduced_entities(kge):
     """The Freebase-scale batch shape (b 1000, g 1000, k 200, dim 400) for TransE-L2 and ComplEx over 200,003
     entities; the full-size table is covered by test_gpu_fullsize.py."""
