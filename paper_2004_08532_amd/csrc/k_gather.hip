@@ -28,71 +28,116 @@ struct GatherArgs {
     float* cpos;      // dL/df+_i = -sigmoid(-f+_i) / b
     float* inv_dpos;  // TransE-L2: 1 / |o_i - c_i| (0 if the distance is 0)
     float* row_loss;  // softplus(-f+_i) / b
-    int gather_blocks;       // blocks [0, gather_blocks) gather rows
-    int ent_rank_blocks;     // the next ent_rank_blocks blocks order the entity key list, the rest the relation keys
+    int rank_blocks;         // blocks [0, rank_blocks) order the key lists, the others gather rows
+    int ent_rank_blocks;     // the first ent_rank_blocks of them order the entity key list, the rest the relation keys
     KeyList ent, rel;
 };
 
-constexpr int RANK_ITEMS = 8;  // keys ranked per block: 8 keys x 32 threads
+// One block size for both kinds of block in a launch: THREADS = 256 for short key lists, 1024 for long ones.  The
+// rank blocks keep the whole key list in (dynamic) LDS, and every block of a launch is given the same amount; with
+// a long list the blocks are large, so that the LDS of a gather block is spread over 16 row-gathering waves and
+// does not limit how many of them a CU holds, and so that fewer blocks load the list.
+constexpr int RANK_LONG_LIST = 6144;  // keys from which on the large blocks are used (measured: 4096 keys are still faster with the small ones)
+template <int THREADS> struct RankShape {
+    static constexpr int R = THREADS == 256 ? 1 : 2;     // keys ranked by one 32-thread group
+    static constexpr int ITEMS = (THREADS / 32) * R;     // keys ranked per block
+    static constexpr int LOADS = THREADS == 256 ? 16 : 4;  // key loads in flight per thread
+};
 
 // Orders a key list by brute-force ranking: rank(i) = #{j : key_j < key_i} + #{j < i : key_j == key_i}.  The lists
-// are a few thousand keys, so the n^2 comparisons, spread over n/8 blocks that run beside the gather blocks of the
-// same launch, cost less than one pass of a single-workgroup sort, need no other kernel and no other stream, and
-// give exactly the order a stable sort by id would (equal ids in position order).  Every block holds the whole
-// list in LDS; 32 threads share one key and each scans every 32nd entry.
+// are a few thousand keys, so the n^2 comparisons, spread over n/8 (n/64) blocks that run beside the gather blocks of
+// the same launch, cost less than one pass of a single-workgroup sort, need no other kernel and no other stream,
+// and give exactly the order a stable sort by id would (equal ids in position order).  Every block holds the whole
+// list in LDS.  A group of 32 threads ranks RANK_R consecutive keys: each thread scans every 32nd 16-byte chunk of
+// the list and compares it with all RANK_R keys, so a chunk read from LDS serves 4 * RANK_R comparisons.  The tie
+// rule costs nothing away from the group's own keys: for entries before them "key_j <= key_i" counts, i.e.
+// key_j < key_i + 1, for entries after them key_j < key_i, so the scan is three loops over one comparison each.
+template <int THREADS>
 __device__ __forceinline__ void rank_block(const KeyList& l, int blk, uint32_t* keys) {
+    constexpr int RANK_R = RankShape<THREADS>::R, RANK_ITEMS = RankShape<THREADS>::ITEMS;
+    constexpr int RANK_LOADS = RankShape<THREADS>::LOADS, GATHER_THREADS = THREADS;
     const int tid = threadIdx.x, n = l.n;
     const int n4 = (n + 3) & ~3;  // the tail is padded with 0xffffffff, which is larger than any id
-    // 16 independent loads per thread are issued before the first is used: one round of memory latency per 4096 keys
+    // independent loads are issued before the first is used: one round of memory latency per 4096 keys
     const int64_t step = l.step_ptr ? *l.step_ptr : 0;
-    for (int base = 0; base < n4; base += 16 * 256) {
-        int64_t raw[16];
+    for (int base = 0; base < n4; base += RANK_LOADS * GATHER_THREADS) {
+        int64_t raw[RANK_LOADS];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int i = base + u * 256 + tid;
-            raw[u] = *key_address(l, step, i < n ? i : 0);  // unconditional: all 16 loads go out together
+        for (int u = 0; u < RANK_LOADS; ++u) {
+            const int i = base + u * GATHER_THREADS + tid;
+            raw[u] = *key_address(l, step, i < n ? i : 0);  // unconditional: all loads go out together
         }
 #pragma unroll
-        for (int u = 0; u < 16; ++u) {
-            const int i = base + u * 256 + tid;
+        for (int u = 0; u < RANK_LOADS; ++u) {
+            const int i = base + u * GATHER_THREADS + tid;
             if (i < n4) keys[i] = i < n ? clamp_key(l, raw[u]) : 0xffffffffu;
         }
     }
     __syncthreads();
-    const int item = blk * RANK_ITEMS + (tid >> 5), t = tid & 31;
-    if (item >= n) return;
-    const uint32_t ki = keys[item];
-    int cnt = 0;
-#pragma unroll 4
-    for (int j = 4 * t; j < n4; j += 128) {
+    const int it0 = blk * RANK_ITEMS + (tid >> 5) * RANK_R, t = tid & 31;
+    if (it0 >= n) return;
+    uint32_t ki[RANK_R];
+    int cnt[RANK_R];
+#pragma unroll
+    for (int r = 0; r < RANK_R; ++r) {
+        ki[r] = keys[it0 + r < n4 ? it0 + r : n4 - 1];  // ids are below 2^31, so ki + 1 does not wrap for real keys
+        cnt[r] = 0;
+    }
+    int j = 4 * t;
+    // entries wholly before the group's keys: key_j <= key_i
+#pragma unroll 2
+    for (; j + 3 < it0; j += 128) {
         const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
-        cnt += (kj.x < ki || (kj.x == ki && j < item)) ? 1 : 0;
-        cnt += (kj.y < ki || (kj.y == ki && j + 1 < item)) ? 1 : 0;
-        cnt += (kj.z < ki || (kj.z == ki && j + 2 < item)) ? 1 : 0;
-        cnt += (kj.w < ki || (kj.w == ki && j + 3 < item)) ? 1 : 0;
+#pragma unroll
+        for (int r = 0; r < RANK_R; ++r) {
+            const uint32_t thr = ki[r] + 1u;
+            cnt[r] += (kj.x < thr) + (kj.y < thr) + (kj.z < thr) + (kj.w < thr);
+        }
+    }
+    // the chunk(s) that hold the group's own keys: the full rule
+    for (; j < it0 + RANK_R && j < n4; j += 128) {
+        const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
+        const uint32_t kv[4] = {kj.x, kj.y, kj.z, kj.w};
+#pragma unroll
+        for (int r = 0; r < RANK_R; ++r) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) cnt[r] += (kv[e] < ki[r] || (kv[e] == ki[r] && j + e < it0 + r)) ? 1 : 0;
+        }
+    }
+    // entries after them: key_j < key_i
+#pragma unroll 2
+    for (; j < n4; j += 128) {
+        const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
+#pragma unroll
+        for (int r = 0; r < RANK_R; ++r) cnt[r] += (kj.x < ki[r]) + (kj.y < ki[r]) + (kj.z < ki[r]) + (kj.w < ki[r]);
     }
 #pragma unroll
-    for (int o = 16; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o, 32);
-    if (t == 0) {
-        l.key[0][cnt] = ki;
-        l.pos[0][cnt] = (uint32_t)item;
+    for (int r = 0; r < RANK_R; ++r) {
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) cnt[r] += __shfl_xor(cnt[r], o, 32);
+        if (t == 0 && it0 + r < n) {
+            l.key[0][cnt[r]] = ki[r];
+            l.pos[0][cnt[r]] = (uint32_t)(it0 + r);
+        }
     }
 }
 
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
 
 // NV = 16-byte vectors per lane: ceil(D/4/64) for the real models, ceil(D/8/64) (re, im) pairs for the complex ones.
-template <int MODEL, int NV>
-__global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
+template <int MODEL, int NV, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
+    constexpr int ROWS_PER_BLOCK = THREADS / 64;
     extern __shared__ uint32_t rank_keys[];
-    if ((int)blockIdx.x >= a.gather_blocks) {
-        const int rb = blockIdx.x - a.gather_blocks;
-        if (rb < a.ent_rank_blocks) rank_block(a.ent, rb, rank_keys);
-        else rank_block(a.rel, rb - a.ent_rank_blocks, rank_keys);
+    // the rank blocks come first: they run longest and need nothing but the ids
+    if ((int)blockIdx.x < a.rank_blocks) {
+        const int rb = blockIdx.x;
+        if (rb < a.ent_rank_blocks) rank_block<THREADS>(a.ent, rb, rank_keys);
+        else rank_block<THREADS>(a.rel, rb - a.ent_rank_blocks, rank_keys);
         return;
     }
     const int lane = threadIdx.x & 63;
-    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int row = (blockIdx.x - a.rank_blocks) * ROWS_PER_BLOCK + (threadIdx.x >> 6);
     const int D = a.D;
     constexpr bool CPLX = (MODEL == KGE_COMPLEX || MODEL == KGE_ROTATE);
     const int nvec = CPLX ? D / 8 : D / 4;   // vectors (or re/im vector pairs) per row
@@ -224,13 +269,39 @@ __global__ __launch_bounds__(256) void k_gather(GatherArgs a) {
     }
 }
 
-template <int MODEL>
+template <int MODEL, int THREADS>
 void launch_nv(kge_ctx* c, const GatherArgs& a, int nv, dim3 grid, size_t lds, hipStream_t st) {
     switch (nv) {
-    case 1: KGE_LAUNCH(c, (k_gather<MODEL, 1>), grid, dim3(256), lds, st, a); break;
-    case 2: KGE_LAUNCH(c, (k_gather<MODEL, 2>), grid, dim3(256), lds, st, a); break;
-    case 3: KGE_LAUNCH(c, (k_gather<MODEL, 3>), grid, dim3(256), lds, st, a); break;
-    default: KGE_LAUNCH(c, (k_gather<MODEL, 4>), grid, dim3(256), lds, st, a); break;
+    case 1: KGE_LAUNCH(c, (k_gather<MODEL, 1, THREADS>), grid, dim3(THREADS), lds, st, a); break;
+    case 2: KGE_LAUNCH(c, (k_gather<MODEL, 2, THREADS>), grid, dim3(THREADS), lds, st, a); break;
+    case 3: KGE_LAUNCH(c, (k_gather<MODEL, 3, THREADS>), grid, dim3(THREADS), lds, st, a); break;
+    default: KGE_LAUNCH(c, (k_gather<MODEL, 4, THREADS>), grid, dim3(THREADS), lds, st, a); break;
+    }
+}
+
+template <int THREADS>
+void launch_model(kge_ctx* c, GatherArgs& a, int nv, int rows, bool with_keys, const StepIds& ids, hipStream_t st) {
+    const int gather_blocks = (rows + THREADS / 64 - 1) / (THREADS / 64);
+    a.ent_rank_blocks = 0;
+    int rank_blocks = 0;
+    size_t lds = 0;
+    if (with_keys) {
+        constexpr int ITEMS = RankShape<THREADS>::ITEMS;
+        kge_make_key_lists(c, ids, &a.ent, &a.rel);
+        a.ent_rank_blocks = (a.ent.n + ITEMS - 1) / ITEMS;
+        rank_blocks = a.ent_rank_blocks + (a.rel.n + ITEMS - 1) / ITEMS;
+        lds = sizeof(uint32_t) * (size_t)((a.ent.n + 3) & ~3);  // the entity list is the longer one
+        c->ebuf = 0;
+        c->rbuf = 0;
+    }
+    a.rank_blocks = rank_blocks;
+    const dim3 grid(gather_blocks + rank_blocks);
+    switch (c->cfg.model) {
+    case KGE_TRANSE_L2: launch_nv<KGE_TRANSE_L2, THREADS>(c, a, nv, grid, lds, st); break;
+    case KGE_TRANSE_L1: launch_nv<KGE_TRANSE_L1, THREADS>(c, a, nv, grid, lds, st); break;
+    case KGE_DISTMULT: launch_nv<KGE_DISTMULT, THREADS>(c, a, nv, grid, lds, st); break;
+    case KGE_COMPLEX: launch_nv<KGE_COMPLEX, THREADS>(c, a, nv, grid, lds, st); break;
+    default: launch_nv<KGE_ROTATE, THREADS>(c, a, nv, grid, lds, st); break;
     }
 }
 
@@ -250,24 +321,6 @@ void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds
     const bool cplx = model == KGE_COMPLEX || model == KGE_ROTATE;
     const int nvec = cplx ? a.D / 8 : a.D / 4;
     const int nv = (nvec + 63) / 64;
-    a.gather_blocks = (b + n_neg + 3) / 4;
-    a.ent_rank_blocks = 0;
-    int rank_blocks = 0;
-    size_t lds = 0;
-    if (with_keys) {
-        kge_make_key_lists(c, ids, &a.ent, &a.rel);
-        a.ent_rank_blocks = (a.ent.n + RANK_ITEMS - 1) / RANK_ITEMS;
-        rank_blocks = a.ent_rank_blocks + (a.rel.n + RANK_ITEMS - 1) / RANK_ITEMS;
-        lds = sizeof(uint32_t) * (size_t)((a.ent.n + 3) & ~3);  // the entity list is the longer one
-        c->ebuf = 0;
-        c->rbuf = 0;
-    }
-    const dim3 grid(a.gather_blocks + rank_blocks);
-    switch (model) {
-    case KGE_TRANSE_L2: launch_nv<KGE_TRANSE_L2>(c, a, nv, grid, lds, st); break;
-    case KGE_TRANSE_L1: launch_nv<KGE_TRANSE_L1>(c, a, nv, grid, lds, st); break;
-    case KGE_DISTMULT: launch_nv<KGE_DISTMULT>(c, a, nv, grid, lds, st); break;
-    case KGE_COMPLEX: launch_nv<KGE_COMPLEX>(c, a, nv, grid, lds, st); break;
-    default: launch_nv<KGE_ROTATE>(c, a, nv, grid, lds, st); break;
-    }
+    if (with_keys && 2 * b + n_neg >= RANK_LONG_LIST) launch_model<1024>(c, a, nv, b + n_neg, with_keys, ids, st);
+    else launch_model<256>(c, a, nv, b + n_neg, with_keys, ids, st);
 }

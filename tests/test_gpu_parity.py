@@ -244,10 +244,10 @@ def test_zero_distance_pairs_have_zero_gradient(kge):
 
 
 def test_long_key_lists_take_the_radix_sort_path(kge):
-    """More than 16384 entity keys per step: the key lists are sorted by the radix kernel on the second stream
+    """More entity keys per step than the rank blocks take: the key lists are sorted by the radix kernel on the second stream
     instead of the rank blocks of the gather launch."""
     w = ragged("distmult", n_entities=3001, ent_dim=16, rel_dim=16, batch=512, chunk=64, neg_per_chunk=2000, steps=2)
-    assert 2 * w.batch + w.n_chunks * w.neg_per_chunk > 16384
+    assert 2 * w.batch + w.n_chunks * w.neg_per_chunk > 16384  # far above the switch-over
     p = Pair(w, kge)
     try:
         run_steps(p, configs.BatchStream(w), 2, check_dedup_at=(0, 1))
