@@ -201,6 +201,47 @@ def main():
                     "unique_entity_rows_per_step": work["unique_entity_rows"],
                     "unique_relation_rows_per_step": work["unique_relation_rows"]}
 
+    # step 1 on the device (not part of the timed step: the step's ids are resident before it starts): ids of K steps
+    # from a synthetic triple list, one launch
+    n_tr = 16_000_000
+    tr = torch.stack([torch.randint(0, w.n_entities, (n_tr,), device=dev), torch.randint(0, w.n_relations, (n_tr,), device=dev),
+                      torch.randint(0, w.n_entities, (n_tr,), device=dev)], dim=1).contiguous()
+    sh = torch.empty((K, w.batch), dtype=torch.int64, device=dev)
+    sr, st_ = torch.empty_like(sh), torch.empty_like(sh)
+    sn = torch.empty((K, w.n_chunks * w.neg_per_chunk), dtype=torch.int64, device=dev)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for rep in range(2):
+        ev0.record()
+        kge.kge_sample_steps(w.seed, tr, w.n_entities, w.batch, w.n_chunks, w.neg_per_chunk, 0, w.side_mode, 0, K, sh, sr,
+                             st_, sn)
+        ev1.record()
+        torch.cuda.synchronize(dev)
+    sample_ms = ev0.elapsed_time(ev1)
+    ids_per_step = 3 * w.batch + w.n_chunks * w.neg_per_chunk
+    sampling = {"us_per_step": 1e3 * sample_ms / K, "ids_per_s": K * ids_per_step / (sample_ms * 1e-3),
+                "note": f"kge_sample_steps, {K} steps in one launch, {n_tr:,} synthetic triples"}
+    del tr, sh, sr, st_, sn
+
+    # link-prediction evaluation (forward only): rank of b positives among 2000 sampled candidates each, both sides
+    k_eval = 2000
+    ectx = kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
+                          max_neg_per_chunk=k_eval, max_chunks=1, gemm_input=int(w.bf16_inputs))
+    cand = torch.randint(0, w.n_entities, (k_eval,), device=dev)
+    ranks = torch.empty(w.batch, dtype=torch.int32, device=dev)
+    metrics = torch.zeros(5, dtype=torch.float64, device=dev)
+    n_eval = 200
+    for rep in range(2):
+        ev0.record()
+        for s_ in range(n_eval):
+            ectx.rank(E, R, dh[s_], dr[s_], dt_[s_], cand, k_eval, w.batch, s_ & 1, w.gamma, rank_out=ranks)
+        kge.kge_rank_metrics(ranks, metrics)
+        ev1.record()
+        torch.cuda.synchronize(dev)
+    eval_ms = ev0.elapsed_time(ev1)
+    evaluation = {"ranked_triples_per_s": n_eval * w.batch / (eval_ms * 1e-3), "us_per_call": 1e3 * eval_ms / n_eval,
+                  "note": f"kge_rank, b={w.batch}, {k_eval} candidates per positive, alternating sides, {n_eval} calls"}
+    ectx.close()
+
     loss_first = float(losses[W].item())
     loss_last = float(losses[W + K - 1].item())
     ctx.close()
@@ -231,6 +272,8 @@ def main():
                    "loss_first": loss_first, "loss_last": loss_last},
         "roofline": roofline,
         "kernels": kernels,
+        "sampling": sampling,
+        "evaluation": evaluation,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -78,6 +78,18 @@ def degree_negatives(seed: int, step: int, n_chunks: int, k: int, batch_h: np.nd
     return np.ascontiguousarray(pool[pick], dtype=np.int64)
 
 
+def mixed_negatives(seed: int, step: int, n_chunks: int, k: int, n_degree: int, n_entities: int,
+                    batch_h: np.ndarray, batch_t: np.ndarray, neg_side: int) -> np.ndarray:
+    """[n_chunks, k] corrupting ids: slots 0 .. n_degree-1 of every chunk degree-proportional (from the batch), the
+    others uniform over all entities.  Slot j of either kind is the same id that the all-degree / all-uniform
+    generator gives for slot j."""
+    uni = uniform_negatives(seed, step, n_chunks, k, n_entities)
+    if n_degree == 0:
+        return uni
+    deg = degree_negatives(seed, step, n_chunks, k, batch_h, batch_t, neg_side)
+    return np.where(np.arange(k)[None, :] < n_degree, deg, uni)
+
+
 def side_of_step(mode: str, step: int) -> int:
     """0 = tails corrupted, 1 = heads corrupted.  'alternate' starts with tails at step 0."""
     if mode == "tail":

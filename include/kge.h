@@ -3,8 +3,8 @@
  *
  * The step is steps 2-4 of the mini-batch loop of the DGL-KE paper (arXiv 2004.08532, Sec. 3.1): fetch the
  * embedding rows a mini-batch touches, run the forward and backward computation on them, and apply the
- * optimizer to exactly those rows of the global tables.  Step 1 (sampling) is the caller's: positives and the
- * jointly sampled corrupting entities (Sec. 3.3) arrive as id arrays.
+ * optimizer to exactly those rows of the global tables.  Positives and the jointly sampled corrupting entities
+ * (Sec. 3.3) arrive as id arrays; they may be the caller's own or come from kge_sample_steps (step 1 of the loop).
  *
  * Conventions for every entry point
  *   - Every data pointer is a DEVICE pointer on the context's device unless it is marked (host).  Tables,
@@ -166,6 +166,56 @@ enum {
 int kge_profile(kge_ctx* ctx, int32_t enable);
 int kge_profile_read(kge_ctx* ctx, double* ms_out, int64_t* steps_out);
 const char* kge_profile_slot_name(int32_t slot);
+
+/*
+ * Link-prediction evaluation (paper Sec. 5: a test triple is ranked among the triples obtained by replacing its
+ * tail, or its head, with sampled corrupting entities; no filtering).  Arguments as for kge_score; the k
+ * corrupting entities of a chunk are the candidates of every positive of that chunk.
+ *   rank_out[i] = 1 + #{ j : f-_ij > f+_i }   (device int32 [b]; ties with the positive do not count against it)
+ * Scores are formed as in kge_score (fp32, or bf16 operands when the context says so) and live in the context's
+ * workspace only.  Tables are not modified.
+ * kge_rank_metrics: (device) metrics_out[5] = Hit@1, Hit@3, Hit@10 (shares of ranks <= 1, 3, 10), MR (mean rank),
+ * MRR (mean reciprocal rank) of ranks[0 .. n-1] (device), as fp64; one kernel on the current device, counts are
+ * exact integers, the reciprocal sum has a fixed order.
+ */
+int kge_rank(kge_ctx* ctx, const float* ent, const float* rel,
+             const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,
+             const int64_t* neg, int64_t k, int64_t chunk, int32_t neg_side, float gamma,
+             void* hip_stream, int32_t* rank_out);
+int kge_rank_metrics(const int32_t* ranks, int64_t n, double* metrics_out, void* hip_stream);
+
+/*
+ * Step 1 of the mini-batch loop on the device (paper Sec. 3.1 step 1; Sec. 3.3 for the negatives): the ids of
+ * n_steps consecutive steps, first_step .. first_step + n_steps - 1, in the layout kge_train_steps takes.
+ * Every id is a function of (seed, step, position) alone, so steps can be generated in any order and any number
+ * at a time; kge.h's counter-based generator is:
+ *     key = mix(mix(mix(mix(seed + 0x9E3779B97F4A7C15 * tag) + step) + a) + j),  id = floor(key * n / 2^64),
+ *     mix(z): z = (z ^ z >> 30) * 0xBF58476D1CE4E5B9; z = (z ^ z >> 27) * 0x94D049BB133111EB; z ^ z >> 31
+ *   positives  (tag 1, a = 0, j = position in the batch, n = n_triples): the triple at that index of `triples`
+ *              (drawn uniformly with replacement);
+ *   negatives  slot j of chunk a: for j >= n_degree uniform over all entities (tag 2, n = num_entities); for
+ *              j < n_degree (tag 3, n = batch) the tail -- the head when heads are corrupted -- of that position
+ *              of the same mini-batch: degree-proportional sampling from the batch, as in Sec. 3.3.
+ *   side       side_mode 0: tails corrupted in every step, 1: heads, 2: tails in even steps, heads in odd ones.
+ * triples: (device) [n_triples x 3] int64 rows (h, r, t), 0 < n_triples < 2^32.
+ * h, r, t: (device) [n_steps x batch]; neg: (device) [n_steps x n_chunks x neg_per_chunk] (may be NULL when
+ * neg_per_chunk is 0); sides: (device) [n_steps] int32, may be NULL.  Enqueues one kernel on `stream` of the
+ * current device and returns; errors (null pointers, sizes out of range) are reported before anything is enqueued
+ * and kge_last_error(NULL) has the text.
+ */
+typedef struct {
+    uint64_t seed;
+    const int64_t* triples;
+    int64_t n_triples;
+    int64_t num_entities;
+    int32_t batch;
+    int32_t n_chunks;
+    int32_t neg_per_chunk;
+    int32_t n_degree;  /* 0 .. neg_per_chunk */
+    int32_t side_mode; /* 0, 1, 2 */
+} kge_sampler;
+int kge_sample_steps(const kge_sampler* sampler, int64_t first_step, int64_t n_steps, int64_t* h, int64_t* r,
+                     int64_t* t, int64_t* neg, int32_t* sides, void* stream);
 
 /* (host) Text of the last error on this context ("" if none); valid until the next call on the context.
  * kge_last_error(NULL) returns the text of the last failed kge_create on this thread. */

@@ -187,3 +187,17 @@ def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr,
     if want_scores:
         return loss.value, pos, negs
     return loss.value
+
+
+def ranks(pos, neg):
+    """Link-prediction rank of every positive among its negatives (paper Sec. 5, no filtering):
+    rank_i = 1 + #{j : neg[i, j] > pos[i]}.  pos [b], neg [b, k] scores; int64 [b]."""
+    pos = np.asarray(pos, dtype=np.float64)
+    neg = np.asarray(neg, dtype=np.float64)
+    return 1 + (neg > pos[:, None]).sum(axis=1).astype(np.int64)
+
+
+def rank_metrics(rank):
+    """Hit@1, Hit@3, Hit@10 (shares of ranks <= 1, 3, 10), MR (mean rank), MRR (mean reciprocal rank)."""
+    rank = np.asarray(rank, dtype=np.float64)
+    return np.array([(rank <= 1).mean(), (rank <= 3).mean(), (rank <= 10).mean(), rank.mean(), (1.0 / rank).mean()])

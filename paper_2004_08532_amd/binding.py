@@ -25,8 +25,14 @@ MODEL_IDS = {"transe_l2": KGE_TRANSE_L2, "transe_l1": KGE_TRANSE_L1, "distmult":
 
 EXPORTS = ("kge_create", "kge_destroy", "kge_train_step", "kge_train_steps", "kge_score", "kge_get_dedup",
            "kge_check_indices", "kge_last_error", "kge_workspace_bytes", "kge_profile", "kge_profile_read",
-           "kge_profile_slot_name")
+           "kge_profile_slot_name", "kge_sample_steps", "kge_rank", "kge_rank_metrics")
 KGE_PROF_SLOTS = 7
+
+
+class kge_sampler(ctypes.Structure):
+    _fields_ = [("seed", ctypes.c_uint64), ("triples", ctypes.c_void_p), ("n_triples", ctypes.c_int64),
+                ("num_entities", ctypes.c_int64), ("batch", ctypes.c_int32), ("n_chunks", ctypes.c_int32),
+                ("neg_per_chunk", ctypes.c_int32), ("n_degree", ctypes.c_int32), ("side_mode", ctypes.c_int32)]
 
 
 class kge_config(ctypes.Structure):
@@ -78,6 +84,12 @@ def _load() -> ctypes.CDLL:
     lib.kge_last_error.argtypes = [vp]
     lib.kge_workspace_bytes.restype = i64
     lib.kge_workspace_bytes.argtypes = [vp]
+    lib.kge_rank.restype = ctypes.c_int
+    lib.kge_rank.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, i32, f32, vp, vp]
+    lib.kge_rank_metrics.restype = ctypes.c_int
+    lib.kge_rank_metrics.argtypes = [vp, i64, vp, vp]
+    lib.kge_sample_steps.restype = ctypes.c_int
+    lib.kge_sample_steps.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp]
     return lib
 
 
@@ -105,6 +117,38 @@ def _check(ctx, rc: int):
     if rc != KGE_OK:
         text = _lib.kge_last_error(ctx)
         raise KgeError(rc, text.decode() if text else "")
+
+
+def kge_rank(ctx, ent, rel, h, r, t, b, neg, k, chunk, neg_side, gamma, rank_out, hip_stream=None) -> None:
+    f, i = torch.float32, torch.int64
+    rc = _lib.kge_rank(ctx, _dev_ptr(ent, f, "ent"), _dev_ptr(rel, f, "rel"), _dev_ptr(h, i, "h"), _dev_ptr(r, i, "r"),
+                       _dev_ptr(t, i, "t"), int(b), _dev_ptr(neg, i, "neg"), int(k), int(chunk), int(neg_side),
+                       float(gamma), _stream(hip_stream), _dev_ptr(rank_out, torch.int32, "rank_out"))
+    _check(ctx, rc)
+
+
+def kge_rank_metrics(ranks, metrics_out, hip_stream=None) -> None:
+    """metrics_out: device float64 [5] = Hit@1, Hit@3, Hit@10, MR, MRR of the device int32 ranks."""
+    rc = _lib.kge_rank_metrics(_dev_ptr(ranks, torch.int32, "ranks"), int(ranks.numel()),
+                               _dev_ptr(metrics_out, torch.float64, "metrics_out"), _stream(hip_stream))
+    _check(None, rc)
+
+
+SIDE_MODES = {"tail": 0, "head": 1, "alternate": 2}
+
+
+def kge_sample_steps(seed, triples, num_entities, batch, n_chunks, neg_per_chunk, n_degree, side_mode, first_step,
+                     n_steps, h, r, t, neg, sides=None, hip_stream=None) -> None:
+    """Ids of steps first_step .. first_step + n_steps - 1 into the device tensors h, r, t [n_steps, batch],
+    neg [n_steps, n_chunks * neg_per_chunk] and (optionally) sides [n_steps] int32."""
+    i = torch.int64
+    sp = kge_sampler(int(seed) & 0xFFFFFFFFFFFFFFFF, _dev_ptr(triples, i, "triples"), int(triples.shape[0]),
+                     int(num_entities), int(batch), int(n_chunks), int(neg_per_chunk), int(n_degree),
+                     SIDE_MODES[side_mode] if isinstance(side_mode, str) else int(side_mode))
+    rc = _lib.kge_sample_steps(ctypes.byref(sp), int(first_step), int(n_steps), _dev_ptr(h, i, "h"),
+                               _dev_ptr(r, i, "r"), _dev_ptr(t, i, "t"), _dev_ptr(neg, i, "neg"),
+                               _dev_ptr(sides, torch.int32, "sides"), _stream(hip_stream))
+    _check(None, rc)
 
 
 def kge_create(cfg: kge_config) -> ctypes.c_void_p:
@@ -224,6 +268,12 @@ class KgeContext:
 
     def score(self, ent, rel, h, r, t, neg, k, chunk, neg_side, gamma, pos_out=None, neg_out=None, stream=None):
         kge_score(self.ctx, ent, rel, h, r, t, h.numel(), neg, k, chunk, neg_side, gamma, stream, pos_out, neg_out)
+
+    def rank(self, ent, rel, h, r, t, neg, k, chunk, neg_side, gamma, rank_out=None, stream=None):
+        if rank_out is None:
+            rank_out = torch.empty(h.numel(), dtype=torch.int32, device=h.device)
+        kge_rank(self.ctx, ent, rel, h, r, t, h.numel(), neg, k, chunk, neg_side, gamma, rank_out, stream)
+        return rank_out
 
     def get_dedup(self, which: int, n_keys: int):
         dev = torch.device("cuda", self.cfg.device)

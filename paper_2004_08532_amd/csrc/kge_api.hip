@@ -415,6 +415,31 @@ int kge_score(kge_ctx* c, const float* ent, const float* rel,
     return KGE_OK;
 }
 
+int kge_rank(kge_ctx* c, const float* ent, const float* rel,
+             const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,
+             const int64_t* neg, int64_t k, int64_t chunk, int32_t neg_side, float gamma,
+             void* hip_stream, int32_t* rank_out) {
+    if (!c) return KGE_ERR_INVALID_ARG;
+    c->err[0] = 0;
+    if (!rank_out) return fail(c, KGE_ERR_INVALID_ARG, "rank_out is null%s");
+    const int rc = check_batch(c, ent, rel, h, r, t, b, neg, k, chunk, neg_side, true);
+    if (rc != KGE_OK) return rc;
+    KGE_HIP(c, hipSetDevice(c->cfg.device));
+    const StepIds ids = direct_ids(h, r, t, (int)b, neg, (int)((b / chunk) * k), neg_side, nullptr);
+    hipStream_t st = (hipStream_t)hip_stream;
+    forward(c, ent, rel, ids, (int)k, (int)chunk, gamma, nullptr, c->S, c->ld_s, 0, st);
+    kge_launch_rank(c, (int)b, (int)k, rank_out, st);
+    KGE_HIP(c, hipGetLastError());
+    return KGE_OK;
+}
+
+int kge_rank_metrics(const int32_t* ranks, int64_t n, double* metrics_out, void* hip_stream) {
+    if (!ranks || !metrics_out || n <= 0) return fail(nullptr, KGE_ERR_INVALID_ARG, "null pointer or no ranks%s");
+    kge_launch_rank_metrics(ranks, n, metrics_out, (hipStream_t)hip_stream);
+    if (hipGetLastError() != hipSuccess) return fail(nullptr, KGE_ERR_DEVICE, "launch of the metrics kernel failed%s");
+    return KGE_OK;
+}
+
 int kge_get_dedup(kge_ctx* c, int32_t which, int64_t* uniq_out, int32_t* count_out, int64_t* n_unique_out,
                   void* hip_stream) {
     if (!c) return KGE_ERR_INVALID_ARG;
@@ -468,6 +493,23 @@ int kge_profile_read(kge_ctx* c, double* ms_out, int64_t* steps_out) {
 const char* kge_profile_slot_name(int32_t slot) {
     static const char* names[KGE_PROF_SLOTS] = {"gather", "neg_score", "loss", "neg_backward", "chain", "sort", "update"};
     return slot >= 0 && slot < KGE_PROF_SLOTS ? names[slot] : "";
+}
+
+int kge_sample_steps(const kge_sampler* sp, int64_t first_step, int64_t n_steps, int64_t* h, int64_t* r, int64_t* t,
+                     int64_t* neg, int32_t* sides, void* stream) {
+    if (!sp || !sp->triples || !h || !r || !t) return fail(nullptr, KGE_ERR_INVALID_ARG, "null sampler, triple list or output%s");
+    if (sp->n_triples <= 0 || sp->n_triples >= ((int64_t)1 << 32) || sp->num_entities <= 0 ||
+        sp->num_entities >= ((int64_t)1 << 32))
+        return fail(nullptr, KGE_ERR_INVALID_ARG, "n_triples and num_entities must be in (0, 2^32)%s");
+    if (sp->batch <= 0 || sp->n_chunks <= 0 || sp->neg_per_chunk < 0 || sp->n_degree < 0 ||
+        sp->n_degree > sp->neg_per_chunk || sp->side_mode < 0 || sp->side_mode > 2)
+        return fail(nullptr, KGE_ERR_INVALID_ARG, "batch, n_chunks, neg_per_chunk, n_degree or side_mode out of range%s");
+    if (sp->neg_per_chunk > 0 && !neg) return fail(nullptr, KGE_ERR_INVALID_ARG, "neg is null%s");
+    if (first_step < 0 || n_steps < 0) return fail(nullptr, KGE_ERR_INVALID_ARG, "negative step range%s");
+    if (n_steps == 0) return KGE_OK;
+    if (kge_sample_launch(sp, first_step, n_steps, h, r, t, neg, sides, (hipStream_t)stream) != KGE_OK)
+        return fail(nullptr, KGE_ERR_DEVICE, "launch of the sampling kernel failed%s");
+    return KGE_OK;
 }
 
 const char* kge_last_error(const kge_ctx* c) { return c ? c->err : g_create_err; }

@@ -140,6 +140,12 @@ void kge_launch_sort(kge_ctx* c, const StepIds& ids, hipStream_t st);
 // a7: per distinct row, sum its gradient rows and apply Adagrad; also reduces the loss terms
 void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, const StepIds& ids, float lr,
                        int n_loss_parts, hipStream_t st);
+// evaluation: ranks of the positives among their negatives (from fpos and the scores in S), and the metrics
+void kge_launch_rank(kge_ctx* c, int b, int k, int32_t* rank_out, hipStream_t st);
+void kge_launch_rank_metrics(const int32_t* ranks, int64_t n, double* out, hipStream_t st);
+// step 1: ids of a range of steps from the counter-based generator
+int kge_sample_launch(const kge_sampler* s, int64_t first_step, int64_t n_steps, int64_t* h, int64_t* r, int64_t* t,
+                      int64_t* neg, int32_t* sides, hipStream_t st);
 // test hook: distinct ids and multiplicities from the sorted keys
 void kge_launch_dedup_export(kge_ctx* c, int which, int64_t* uniq, int32_t* count, int64_t* n_unique,
                              hipStream_t st);

@@ -255,6 +255,111 @@ def test_long_key_lists_take_the_radix_sort_path(kge):
         p.close()
 
 
+@pytest.mark.parametrize("model", MODELS)
+def test_evaluation_ranks_and_metrics(kge, model):
+    """Link-prediction evaluation: the rank of every positive among 2 x 150 sampled candidates (both sides), then
+    Hit@k / MR / MRR.  A rank is an integer decided by comparing fp32 scores; candidates whose oracle score lies
+    within the score tolerance of the positive's could fall on either side, so the rank must lie between the
+    counts with those candidates excluded and included, and equals the oracle's rank when there are none.  The
+    metrics kernel is checked exactly against the oracle's formulas on the device's own ranks."""
+    w = ragged(model, n_entities=2003, batch=180, chunk=60, neg_per_chunk=150, name="eval-" + model)
+    # tables eight times the initialisation range: scores of an untrained model at the usual range lie so close
+    # together that most ranks would hinge on differences below the score tolerance
+    E, R = configs.init_tables(w)
+    E = E * 8.0
+    if model != "rotate":
+        R = R * 8.0
+    p = Pair(w, kge, E=E, R=R)
+    try:
+        bs = configs.BatchStream(w)
+        all_ranks, unambiguous = [], 0
+        for side in (0, 1):
+            h, r, t, neg, _ = bs.step(side)
+            dr = p.ctx.rank(p.dE, p.dR, dev(h), dev(r), dev(t), dev(neg.reshape(-1)), w.neg_per_chunk, w.chunk, side,
+                            w.gamma)
+            torch.cuda.synchronize()
+            got = dr.cpu().numpy().astype(np.int64)
+            opos, oneg = oracle.scores(w.model, p.E, p.R, h, r, t, neg, w.neg_per_chunk, w.chunk, side, w.gamma)
+            tol = SCORE_TOL * np.maximum(np.abs(opos), 1.0)[:, None]
+            lo = 1 + (oneg > opos[:, None] + tol).sum(axis=1)
+            hi = 1 + (oneg > opos[:, None] - tol).sum(axis=1)
+            assert np.all((got >= lo) & (got <= hi))
+            clear = lo == hi
+            assert np.array_equal(got[clear], oracle.ranks(opos, oneg)[clear])
+            unambiguous += int(clear.sum())
+            all_ranks.append(dr)
+        assert unambiguous >= 0.9 * 2 * w.batch
+        ranks = torch.cat(all_ranks)
+        m = torch.zeros(5, dtype=torch.float64, device="cuda")
+        kge.kge_rank_metrics(ranks, m)
+        torch.cuda.synchronize()
+        assert np.allclose(m.cpu().numpy(), oracle.rank_metrics(ranks.cpu().numpy()), rtol=1e-14, atol=0)
+    finally:
+        p.close()
+
+
+@pytest.mark.parametrize("n_degree,side_mode,n_triples", [(0, "tail", 4000), (37, "head", 4000), (13, "alternate", 777),
+                                                          (0, "alternate", 3_000_017)])
+def test_device_sampler_gives_the_ids_of_the_host_sampler(kge, n_degree, side_mode, n_triples):
+    """Step 1 on the device: ids are integers, so the comparison with the host's counter-based sampler is bit for
+    bit, for steps generated out of order and many at a time (ragged sizes, step numbers beyond 2^31)."""
+    from harness import graphs, sampler
+    n_ent, b, C, k, seed = 100_003, 90, 2, 37, 0xC0FFEE12345
+    src = graphs.TripleSource(n_ent, 11, 1.0, None)
+    triples = src.draw(n_triples, np.random.default_rng(3))
+    dtr = dev(triples)
+    for first, n_steps in ((0, 5), (123_456_789_012, 3), (7, 64)):
+        h = torch.empty((n_steps, b), dtype=torch.int64, device="cuda")
+        r, t = torch.empty_like(h), torch.empty_like(h)
+        neg = torch.empty((n_steps, C * k), dtype=torch.int64, device="cuda")
+        sides = torch.empty(n_steps, dtype=torch.int32, device="cuda")
+        kge.kge_sample_steps(seed, dtr, n_ent, b, C, k, n_degree, side_mode, first, n_steps, h, r, t, neg, sides)
+        torch.cuda.synchronize()
+        for i in range(n_steps):
+            s = first + i
+            pos = triples[sampler.batch_positions(seed, s, b, n_triples)]
+            side = sampler.side_of_step(side_mode, s)
+            want_neg = sampler.mixed_negatives(seed, s, C, k, n_degree, n_ent, pos[:, 0], pos[:, 2], side)
+            assert np.array_equal(h[i].cpu().numpy(), pos[:, 0])
+            assert np.array_equal(r[i].cpu().numpy(), pos[:, 1])
+            assert np.array_equal(t[i].cpu().numpy(), pos[:, 2])
+            assert np.array_equal(neg[i].cpu().numpy(), want_neg.reshape(-1))
+            assert int(sides[i].item()) == side
+
+
+def test_training_from_device_sampled_ids_equals_training_from_host_ids(kge):
+    """A whole run with no ids from the host: kge_sample_steps fills the id arrays of all steps, kge_train_steps
+    consumes them; the tables end up with the bits of the same run fed with the host sampler's ids."""
+    w = ragged("transe_l2", n_entities=3001, steps=12)
+    bs = configs.BatchStream(w)
+    hs, rs, ts, negs, sides = bs.steps(0, w.steps)
+    tables = []
+    for device_ids in (False, True):
+        E, R = configs.init_tables(w)
+        dE, dR = dev(E), dev(R)
+        dSE, dSR = torch.zeros_like(dE), torch.zeros_like(dR)
+        ctx = kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
+                             max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks)
+        try:
+            if device_ids:
+                h = torch.empty((w.steps, w.batch), dtype=torch.int64, device="cuda")
+                r, t = torch.empty_like(h), torch.empty_like(h)
+                neg = torch.empty((w.steps, w.n_chunks * w.neg_per_chunk), dtype=torch.int64, device="cuda")
+                dsides = torch.empty(w.steps, dtype=torch.int32, device="cuda")
+                kge.kge_sample_steps(w.seed, dev(bs.triples), w.n_entities, w.batch, w.n_chunks, w.neg_per_chunk, 0,
+                                     w.side_mode, 0, w.steps, h, r, t, neg, dsides)
+                assert np.array_equal(dsides.cpu().numpy(), sides)
+            else:
+                h, r, t, neg = dev(hs), dev(rs), dev(ts), dev(negs.reshape(w.steps, -1))
+            ctx.train_steps(dE, dSE, dR, dSR, h, r, t, neg, w.neg_per_chunk, w.chunk, sides.tolist(), w.gamma, w.lr)
+            torch.cuda.synchronize()
+            tables.append((dE.clone(), dSE.clone(), dR.clone(), dSR.clone()))
+        finally:
+            ctx.close()
+    for a, b_ in zip(*tables):
+        assert torch.equal(a, b_)
+
+
 # ------------------------------------------------------------------------------------------------------------
 # properties that do not need the oracle's arithmetic
 
