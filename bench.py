@@ -42,13 +42,15 @@ def parse():
     ap.add_argument("--profile-steps", type=int, default=500)
     ap.add_argument("--cpu-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rowwise-state", action="store_true",
+                    help="Adagrad with one accumulator per row (adagrad_mode 1) instead of the element-wise state")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device copy of this size, as the known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     return ap.parse_args()
 
 
-def algorithmic_work(w, h, r, t, neg):
+def algorithmic_work(w, h, r, t, neg, rowwise=False):
     """Per-step algorithmic bytes / flops of every kernel, averaged over the given steps (ids on the host).
 
     gather : every gathered row read once and every staged row (o_i, corrupting rows) written once
@@ -62,7 +64,8 @@ def algorithmic_work(w, h, r, t, neg):
     n_keys = 2 * b + C * k
     return {
         "gather": {"bytes": 4.0 * ((2 * b + C * k) * D + b * Dr) + 4.0 * (b + C * k) * D},
-        "update": {"bytes": ue * 16.0 * D + n_keys * 4.0 * D + ur * 16.0 * Dr + b * 4.0 * Dr},
+        "update": {"bytes": ue * (8.0 * D + 8.0 if rowwise else 16.0 * D) + n_keys * 4.0 * D +
+                            ur * (8.0 * Dr + 8.0 if rowwise else 16.0 * Dr) + b * 4.0 * Dr},
         "neg_score": {"flops": 2.0 * b * k * D},
         "neg_backward": {"flops": 4.0 * b * k * D},
         "chain": {"bytes": 4.0 * (6 * b * D + 2 * b * Dr)},
@@ -123,7 +126,8 @@ def main():
     w = configs.ALL[args.workload]
     if args.entities:
         w = w.scaled(n_entities=args.entities, name=w.name + f"-{args.entities}ent")
-    need = 2 * (w.n_entities * w.ent_dim + w.n_relations * w.rel_dim) * 4
+    state_cols = (1, 1) if args.rowwise_state else (w.ent_dim, w.rel_dim)
+    need = (w.n_entities * (w.ent_dim + state_cols[0]) + w.n_relations * (w.rel_dim + state_cols[1])) * 4
     free, _total = torch.cuda.mem_get_info(dev)
     if need + (4 << 30) > free:
         print(f"bench.py: workload {w.name} needs {need / 2**30:.1f} GiB of HBM, {free / 2**30:.1f} GiB free",
@@ -137,10 +141,14 @@ def main():
     neg = neg.reshape(neg.shape[0], -1)
     dh, dr, dt_, dn = (torch.from_numpy(x).to(dev) for x in (h, r, t, neg))
     E, R = configs.init_tables(w, device=dev)
-    SE, SR = torch.zeros_like(E), torch.zeros_like(R)
+    if args.rowwise_state:
+        SE = torch.zeros(w.n_entities, dtype=torch.float32, device=dev)
+        SR = torch.zeros(w.n_relations, dtype=torch.float32, device=dev)
+    else:
+        SE, SR = torch.zeros_like(E), torch.zeros_like(R)
     ctx = kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
                          max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks, gemm_input=int(w.bf16_inputs),
-                         adv_temperature=w.adv_temperature)
+                         adv_temperature=w.adv_temperature, adagrad_mode=int(args.rowwise_state))
     losses = torch.zeros(W + K + P, dtype=torch.float32, device=dev)
     if args.calibration_copy_mib > 0:
         src = torch.ones(args.calibration_copy_mib << 18, dtype=torch.float32, device=dev)
@@ -174,7 +182,7 @@ def main():
         run(W + K, W + K + P)
         ms, nsteps = ctx.profile_read()
         ctx.profile(False)
-        work = algorithmic_work(w, h[W + K:], r[W + K:], t[W + K:], neg[W + K:])
+        work = algorithmic_work(w, h[W + K:], r[W + K:], t[W + K:], neg[W + K:], args.rowwise_state)
         gemm = w.model in ("transe_l2", "distmult", "complex")
         for name, total_ms in ms.items():
             avg_us = 1e3 * total_ms / max(nsteps, 1)
@@ -265,7 +273,7 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16-in/f32-acc" if w.bf16_inputs else "f32",
         "data": "synthetic",
-        "config": {"workload": w.name, "model": w.model, "entities": w.n_entities, "relations": w.n_relations,
+        "config": {"workload": w.name + ("+rowwise-adagrad-state" if args.rowwise_state else ""), "model": w.model, "entities": w.n_entities, "relations": w.n_relations,
                    "dim": w.ent_dim, "batch": w.batch, "chunk": w.chunk, "neg_per_chunk": w.neg_per_chunk,
                    "table_plus_state_GiB": round(need / 2 ** 30, 2), "setup_s": round(setup_s, 1),
                    "host_enqueue_ms_per_step": 1e3 * t_enqueued / K,

@@ -64,7 +64,7 @@ typedef struct {
     int32_t max_neg_per_chunk; /* largest k                                                               */
     int32_t max_chunks;        /* largest b / chunk                                                       */
     int32_t gemm_input;        /* 0: fp32 operands; 1: bf16 operands, fp32 accumulation (GEMM models)     */
-    int32_t adagrad_mode;      /* 0: element-wise state, same shape as the table                          */
+    int32_t adagrad_mode;      /* 0: element-wise state, same shape as the table; 1: one float per row    */
     float adagrad_eps;         /* added to sqrt(state); 0 selects the default 1e-10                       */
     float adv_temperature;     /* 0: negatives weigh 1/k each; > 0: softmax(temperature * score) weights  */
     int32_t validate_indices;  /* != 0: kge_train_step / kge_score range-check ids on the device and the  */
@@ -82,8 +82,8 @@ void kge_destroy(kge_ctx* ctx);
 /*
  * One training step (Sec. 3.1 steps 2-4 with the negative sampling layout of Sec. 3.3).
  *
- *   ent [num_entities x ent_dim], ent_state (same shape): entity table and its Adagrad accumulator, updated
- *   in place; rel, rel_state likewise [num_relations x rel_dim].
+ *   ent [num_entities x ent_dim], ent_state (same shape; [num_entities] floats when adagrad_mode is 1): entity
+ *   table and its Adagrad accumulator, updated in place; rel, rel_state likewise [num_relations x rel_dim].
  *   h, r, t [b]: int64 ids of the positive triples.
  *   neg [(b / chunk) * k]: int64 corrupting entity ids; positives chunk*c .. chunk*c + chunk - 1 share
  *   neg[c*k .. c*k + k - 1].  neg_side says whether they replace the tail or the head.
@@ -91,7 +91,10 @@ void kge_destroy(kge_ctx* ctx);
  *       L = (1/b) sum_i [ log(1 + exp(-f+_i)) + sum_j w_ij log(1 + exp(f-_ij)) ],
  *   w_ij = 1/k, or softmax_j(adv_temperature * f-_ij) held constant in the backward pass.
  *   Update: for every distinct row that occurs among h, t, neg (entities) or r (relations), with g the sum of
- *   all gradient contributions to that row:  state += g*g ; row -= lr * g / (sqrt(state) + eps).
+ *   all gradient contributions to that row:  state += g*g ; row -= lr * g / (sqrt(state) + eps), element by
+ *   element (adagrad_mode 0), or with one accumulator for the whole row (adagrad_mode 1: the optimizer is not
+ *   named in the paper; this variant keeps 1/ent_dim of the state):
+ *   state += mean_d g_d^2 ; row -= lr * g / (sqrt(state) + eps).
  *   All reads of the tables use the values from before this step.  Rows that do not occur are not written.
  *   loss_out: device float, receives L; may be NULL.
  *

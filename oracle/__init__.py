@@ -52,10 +52,10 @@ def _load():
         lib.ko_dedup.restype = i64
         lib.ko_dedup.argtypes = [vp, i64, vp, vp]
         lib.ko_adagrad_rows.restype = None
-        lib.ko_adagrad_rows.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, dbl, dbl]
+        lib.ko_adagrad_rows.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, dbl, dbl, ctypes.c_int]
         lib.ko_train_step.restype = ctypes.c_int
         lib.ko_train_step.argtypes = [ctypes.POINTER(_Params), vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
-                                      vp, i64, i64, dbl, dbl, ctypes.c_int, vp, vp, vp,
+                                      vp, i64, i64, dbl, dbl, ctypes.c_int, ctypes.c_int, vp, vp, vp,
                                       vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
@@ -130,8 +130,9 @@ def dedup(keys):
     return uniq[:u].copy(), cnt[:u].copy()
 
 
-def adagrad_rows(table, state, ids, grad, lr, eps):
-    """In-place Adagrad on rows ``ids`` (or all rows when ids is None) of float32 table/state."""
+def adagrad_rows(table, state, ids, grad, lr, eps, rowwise=False):
+    """In-place Adagrad on rows ``ids`` (or all rows when ids is None) of float32 table/state.  rowwise: state is
+    one float per row, fed with the mean of the squared gradient elements of the row."""
     lib = _load()
     assert table.dtype == np.float32 and state.dtype == np.float32 and table.flags.c_contiguous
     grad = np.ascontiguousarray(grad, dtype=np.float64)
@@ -142,11 +143,13 @@ def adagrad_rows(table, state, ids, grad, lr, eps):
         ids = _ids(ids)
         n = ids.shape[0]
         idp = _ptr(ids)
-    lib.ko_adagrad_rows(_ptr(table), _ptr(state), idp, n, table.shape[1], _ptr(grad), float(lr), float(eps))
+    assert state.shape == ((table.shape[0],) if rowwise else table.shape)
+    lib.ko_adagrad_rows(_ptr(table), _ptr(state), idp, n, table.shape[1], _ptr(grad), float(lr), float(eps),
+                        int(rowwise))
 
 
 def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr, eps=1e-10, adv_temperature=0.0,
-               dense=False, bf16_inputs=False, rotate_squared=False, want_scores=False, report=False):
+               dense=False, bf16_inputs=False, rotate_squared=False, want_scores=False, report=False, rowwise=False):
     """One step, in place on float32 E, SE, R, SR.  Returns loss (and scores when asked).
 
     report=True (touched-rows mode) returns ``(loss, rep)`` where rep holds, for the distinct rows of the step,
@@ -176,6 +179,7 @@ def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr,
                  _ptr(rep["maxE"]), _ptr(rep["maxR"])]
     rc = lib.ko_train_step(ctypes.byref(p), _ptr(E), _ptr(SE), E.shape[0], _ptr(R), _ptr(SR), R.shape[0],
                            _ptr(h), _ptr(r), _ptr(t), b, _ptr(neg), k, chunk, float(lr), float(eps), int(dense),
+                           int(rowwise),
                            ctypes.addressof(loss), _ptr(pos), _ptr(negs), *extra)
     if rc != 0:
         raise ValueError(f"ko_train_step failed with {rc}")

@@ -590,13 +590,26 @@ int64_t ko_dedup(const int64_t *keys, int64_t n, int64_t *uniq, int64_t *cnt) {
 /* ------------------------------------------------------------------------------------------------ */
 /* Adagrad                                                                                            */
 
-/* rows ids[0..n) (or rows 0..n-1 when ids == NULL) of table/state, with gradient rows grad[s*dim ..] */
+/* rows ids[0..n) (or rows 0..n-1 when ids == NULL) of table/state, with gradient rows grad[s*dim ..].
+ * rowwise == 0: element-wise state of the table's shape:  S_d += g_d^2 ;  x_d -= lr g_d / (sqrt(S_d) + eps)
+ * rowwise != 0: one state value per row (state has n_rows floats):
+ *               S += mean_d g_d^2 ;  x_d -= lr g_d / (sqrt(S) + eps)   (a row with zero gradient keeps its bits) */
 void ko_adagrad_rows(float *table, float *state, const int64_t *ids, int64_t n, int dim, const double *grad,
-                     double lr, double eps) {
+                     double lr, double eps, int rowwise) {
     for (int64_t s = 0; s < n; ++s) {
         const int64_t row = ids ? ids[s] : s;
         float *th = table + row * (int64_t)dim, *st = state + row * (int64_t)dim;
         const double *g = grad + s * (int64_t)dim;
+        if (rowwise) {
+            double ms = 0.0;
+            for (int d = 0; d < dim; ++d) ms += g[d] * g[d];
+            ms /= (double)dim;
+            const double S = (double)state[row] + ms;
+            const double den = sqrt(S) + eps;
+            for (int d = 0; d < dim; ++d) th[d] = (float)((double)th[d] - lr * g[d] / den);
+            state[row] = (float)S;
+            continue;
+        }
         for (int d = 0; d < dim; ++d) {
             double S = (double)st[d] + g[d] * g[d];
             double x = (double)th[d] - lr * g[d] / (sqrt(S) + eps);
@@ -614,7 +627,7 @@ void ko_adagrad_rows(float *table, float *state, const int64_t *ids, int64_t n, 
  */
 int ko_train_step(const ko_params *p, float *E, float *SE, int64_t n_ent, float *R, float *SR, int64_t n_rel,
                   const int64_t *h, const int64_t *r, const int64_t *t, int64_t b,
-                  const int64_t *neg, int64_t k, int64_t chunk, double lr, double eps, int dense,
+                  const int64_t *neg, int64_t k, int64_t chunk, double lr, double eps, int dense, int rowwise,
                   double *loss_out, double *pos_score, double *neg_score,
                   int64_t *ent_ids_out, int64_t *n_ent_out, double *dE_out, double *aE_out,
                   int64_t *rel_ids_out, int64_t *n_rel_out, double *dR_out, double *aR_out,
@@ -662,8 +675,8 @@ int ko_train_step(const ko_params *p, float *E, float *SE, int64_t n_ent, float 
         memcpy(dR_out, dR, sizeof(double) * (size_t)ur * p->rel_dim);
     }
     if (rc == 0) {
-        ko_adagrad_rows(E, SE, ent_ids, ue, p->ent_dim, dE, lr, eps);
-        ko_adagrad_rows(R, SR, rel_ids, ur, p->rel_dim, dR, lr, eps);
+        ko_adagrad_rows(E, SE, ent_ids, ue, p->ent_dim, dE, lr, eps, rowwise);
+        ko_adagrad_rows(R, SR, rel_ids, ur, p->rel_dim, dR, lr, eps, rowwise);
     }
     free(dE); free(dR); free(ent_ids); free(rel_ids);
     return rc;

@@ -239,14 +239,15 @@ class KgeContext:
 
     def __init__(self, model, num_entities, num_relations, ent_dim, rel_dim=None, max_batch=1024,
                  max_neg_per_chunk=256, max_chunks=None, device=0, gemm_input=0, adv_temperature=0.0,
-                 adagrad_eps=0.0, validate_indices=False):
+                 adagrad_eps=0.0, validate_indices=False, adagrad_mode=0):
         m = MODEL_IDS[model] if isinstance(model, str) else int(model)
         if rel_dim is None:
             rel_dim = ent_dim // 2 if m == KGE_ROTATE else ent_dim
         if max_chunks is None:
             max_chunks = max_batch
         self.cfg = kge_config(m, int(device), int(num_entities), int(num_relations), int(ent_dim), int(rel_dim),
-                              int(max_batch), int(max_neg_per_chunk), int(max_chunks), int(gemm_input), 0,
+                              int(max_batch), int(max_neg_per_chunk), int(max_chunks), int(gemm_input),
+                              int(adagrad_mode),
                               float(adagrad_eps), float(adv_temperature), int(bool(validate_indices)))
         self.ctx = kge_create(self.cfg)
 

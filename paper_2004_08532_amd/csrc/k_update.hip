@@ -62,6 +62,9 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// ROWWISE: the accumulator is one float per row, fed with the mean of the squared elements of the row's summed
+// gradient:  S += mean_d g_d^2 ;  theta_d -= lr * g_d / (sqrt(S) + eps).
+template <bool ROWWISE>
 __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
     int tile = blockIdx.x;
     const int tid = threadIdx.x;
@@ -180,12 +183,14 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
     // wait for loads.
     const bool walker = tid < lanes;
     float4 x[TILE_R], s[TILE_R];
+    float srow[TILE_R];
     if (walker) {
 #pragma unroll
         for (int j = 0; j < TILE_R; ++j) {
             if (ends[j]) {
                 x[j] = ld4(Tb + (int64_t)key[j + 1] * D + 4 * v);
-                s[j] = ld4(Sb + (int64_t)key[j + 1] * D + 4 * v);
+                if (ROWWISE) srow[j] = Sb[key[j + 1]];
+                else s[j] = ld4(Sb + (int64_t)key[j + 1] * D + 4 * v);
             }
         }
     }
@@ -203,22 +208,55 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
             for (int g2 = 0; g2 < groups; ++g2) acc = add4(acc, red[g2 * lanes + v]);
         }
     }
-    if (!walker) return;
+    // (row-wise state: the other lanes of the walker waves stay, with zeros, for the sums over the row below)
+    if (!ROWWISE && !walker) return;
 
     float4 g[TILE_R];
 #pragma unroll
     for (int j = 0; j < TILE_R; ++j) {
         g[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (need[j]) g[j] = ld4(G + (int64_t)gpos[j] * D + 4 * v);
+        if (need[j] && walker) g[j] = ld4(G + (int64_t)gpos[j] * D + 4 * v);
     }
+    if (!ROWWISE) {
+#pragma unroll
+        for (int j = 0; j < TILE_R; ++j) {
+            if (need[j]) acc = add4(acc, g[j]);
+            if (ends[j]) {
+                adagrad4(acc, x[j], s[j], a.lr, a.eps);
+                st4(Sb + (int64_t)key[j + 1] * D + 4 * v, s[j]);
+                st4(Tb + (int64_t)key[j + 1] * D + 4 * v, x[j]);
+                acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+        return;
+    }
+    // Row-wise state.  First the summed gradient of every run that ends here (kept in g[j]) and, per walker wave, its
+    // sum of squares; one barrier (the helper waves are gone by now, so it is among the walker waves only); then the
+    // walker waves' sums are added in wave order to the mean square of the row and the update is applied.
+    __shared__ float row_ss[TILE_R][UPD_THREADS / 64];
 #pragma unroll
     for (int j = 0; j < TILE_R; ++j) {
         if (need[j]) acc = add4(acc, g[j]);
         if (ends[j]) {
-            adagrad4(acc, x[j], s[j], a.lr, a.eps);
-            st4(Sb + (int64_t)key[j + 1] * D + 4 * v, s[j]);
-            st4(Tb + (int64_t)key[j + 1] * D + 4 * v, x[j]);
+            g[j] = acc;
+            float ss = walker ? acc.x * acc.x + acc.y * acc.y + acc.z * acc.z + acc.w * acc.w : 0.f;
+            ss = wave_sum(ss);
+            if ((tid & 63) == 0) row_ss[j][tid >> 6] = ss;
             acc = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    lds_barrier();
+    if (!walker) return;
+#pragma unroll
+    for (int j = 0; j < TILE_R; ++j) {
+        if (ends[j]) {
+            float tot = 0.f;
+            for (int ww = 0; ww < walkers / 64; ++ww) tot += row_ss[j][ww];
+            const float S_new = srow[j] + tot / (float)D;
+            const float scale = a.lr * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(S_new) + a.eps);
+            x[j].x -= scale * g[j].x; x[j].y -= scale * g[j].y; x[j].z -= scale * g[j].z; x[j].w -= scale * g[j].w;
+            st4(Tb + (int64_t)key[j + 1] * D + 4 * v, x[j]);
+            if (tid == 0) Sb[key[j + 1]] = S_new;
         }
     }
 }
@@ -241,5 +279,6 @@ void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, con
     a.lr = lr; a.eps = c->eps; a.row_loss = c->row_loss; a.b = b; a.loss_out = loss_out;
     a.neg_loss_part = c->neg_loss_part; a.n_loss_parts = n_loss_parts;
     const int tiles = a.tiles[0] + a.tiles[1];
-    KGE_LAUNCH(c, k_update, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
+    if (c->cfg.adagrad_mode == 1) KGE_LAUNCH(c, k_update<true>, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
+    else KGE_LAUNCH(c, k_update<false>, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
 }

@@ -217,7 +217,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
         return fail(nullptr, KGE_ERR_INVALID_ARG, "bad workspace limits%s");
     if ((int64_t)cfg->max_chunks * cfg->max_neg_per_chunk + 2ll * cfg->max_batch > (1 << 24))
         return fail(nullptr, KGE_ERR_INVALID_ARG, "more than 2^24 entity keys per step%s");
-    if (cfg->adagrad_mode != 0) return fail(nullptr, KGE_ERR_UNSUPPORTED, "only element-wise Adagrad state is implemented%s");
+    if (cfg->adagrad_mode != 0 && cfg->adagrad_mode != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "adagrad_mode must be 0 or 1%s");
     if (cfg->gemm_input != 0 && cfg->gemm_input != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "gemm_input must be 0 or 1%s");
     if (cfg->gemm_input != 0 && cfg->gemm_input != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "gemm_input must be 0 or 1%s");
     if (cfg->gemm_input == 1 && !is_gemm_model(cfg->model))

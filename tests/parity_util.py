@@ -63,21 +63,39 @@ def rounding_allowance(g, A, S_prev, lr, eps, M=None):
     return du, ds
 
 
+def rounding_allowance_rowwise(g, A, S_prev_row, lr, eps, M=None):
+    """The same for the row-wise accumulator S += mean_d g_d^2 ; x -= lr g / (sqrt(S) + eps): g [rows, D] moves by at
+    most d = RHO * A element-wise; the row's mean square then moves by at most mean(2 |g| d + d^2)."""
+    d = RHO * A
+    if M is not None:
+        d = d + FLIPS * BF16_SPACING * M
+    ms = (g * g).mean(axis=1)
+    dms = (2.0 * np.abs(g) * d + d * d).mean(axis=1)
+    den = np.sqrt(S_prev_row + ms) + eps
+    den_lo = np.sqrt(np.maximum(S_prev_row + ms - dms, 0.0)) + eps
+    du = lr * d / den_lo[:, None] + lr * np.abs(g) * (1.0 / den_lo - 1.0 / den)[:, None]
+    return du, dms
+
+
 class Pair:
     """Tables on the host (oracle) and on the device (library), advanced together."""
 
-    def __init__(self, w: configs.Workload, kge, validate=False, E=None, R=None):
+    def __init__(self, w: configs.Workload, kge, validate=False, E=None, R=None, rowwise=False):
         self.w = w
+        self.rowwise = rowwise
         if E is None:
             E, R = configs.init_tables(w)
         self.E, self.R = E.copy(), R.copy()
-        self.SE, self.SR = np.zeros_like(self.E), np.zeros_like(self.R)
+        if rowwise:
+            self.SE, self.SR = np.zeros(self.E.shape[0], np.float32), np.zeros(self.R.shape[0], np.float32)
+        else:
+            self.SE, self.SR = np.zeros_like(self.E), np.zeros_like(self.R)
         self.dE, self.dR = dev(self.E), dev(self.R)
-        self.dSE, self.dSR = torch.zeros_like(self.dE), torch.zeros_like(self.dR)
+        self.dSE, self.dSR = dev(self.SE), dev(self.SR)
         self.ctx = kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
                                   max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks,
                                   gemm_input=int(w.bf16_inputs), adv_temperature=w.adv_temperature,
-                                  validate_indices=validate)
+                                  validate_indices=validate, adagrad_mode=int(rowwise))
         self.loss = torch.zeros(1, dtype=torch.float32, device="cuda")
         self.floor = graphs.init_bound(w.gamma, w.ent_dim)
         self.eps = 1e-10
@@ -105,7 +123,7 @@ class Pair:
         torch.cuda.synchronize()
         want = oracle.train_step(w.model, self.E, self.SE, self.R, self.SR, h, r, t, neg, k, w.chunk, side, w.gamma,
                                  w.lr, eps=self.eps, adv_temperature=w.adv_temperature, bf16_inputs=w.bf16_inputs,
-                                 report=report)
+                                 report=report, rowwise=self.rowwise)
         return float(self.loss.item()), want
 
     # -- one step from identical tables, every touched element checked, then tables re-synchronised ----------
@@ -124,7 +142,8 @@ class Pair:
             got = devt[idx].cpu().numpy().astype(np.float64)
             got_s = devs[idx].cpu().numpy().astype(np.float64)
             want, want_s = host[ids].astype(np.float64), host_s[ids].astype(np.float64)
-            du, ds = rounding_allowance(g, A, S_prev[name], w.lr, self.eps, M if w.bf16_inputs else None)
+            allow = rounding_allowance_rowwise if self.rowwise else rounding_allowance
+            du, ds = allow(g, A, S_prev[name], w.lr, self.eps, M if w.bf16_inputs else None)
             base = EMB_TOL * np.maximum(np.abs(want), self.floor)
             ratio = np.abs(got - want) / (base + du)
             worst = float(ratio.max())

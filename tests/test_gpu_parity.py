@@ -146,6 +146,28 @@ def test_bf16_operands_ragged_shapes(kge, model, alpha):
         p.close()
 
 
+@pytest.mark.parametrize("model,alpha", [("transe_l2", 0.0), ("distmult", 1.0), ("rotate", 0.0)])
+def test_rowwise_adagrad_state(kge, model, alpha):
+    """One accumulator per row (adagrad_mode 1): S += mean_d g_d^2 ; row -= lr g / (sqrt(S) + eps).  Several steps
+    without re-initialising the state, so that later steps start from non-zero accumulators; hub rows (duplicates
+    across tile boundaries) included through the skewed sampling of the ragged workload."""
+    w = ragged(model, adv_temperature=alpha, steps=5, name="ragged-rowwise-" + model)
+    p = Pair(w, kge, rowwise=True)
+    try:
+        run_steps(p, configs.BatchStream(w), w.steps, check_dedup_at=(0,))
+    finally:
+        p.close()
+
+
+def test_rowwise_adagrad_freebase_batch_shape(kge):
+    w = configs.FREEBASE_TRANSE.scaled(n_entities=200_003, name="freebase-shape-rowwise")
+    p = Pair(w, kge, rowwise=True)
+    try:
+        run_steps(p, configs.BatchStream(w, materialise=False), 2, check_dedup_at=())
+    finally:
+        p.close()
+
+
 def test_large_config_reduced_entities(kge):
     """Configuration 'large' (TransE-L2, bf16 operands, dim 400, b 2048, g 256, k 1024: 12,288 entity keys per
     step) with the entity count cut to 100,000 so that the oracle's tables stay small."""

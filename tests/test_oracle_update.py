@@ -107,3 +107,58 @@ def test_train_step_rejects_bad_ids():
         oracle.train_step("transe_l2", E, SE, R, SR, h2, r, t, neg, 3, 4, 0, 2.0, 0.1)
     with pytest.raises(ValueError):
         oracle.train_step("transe_l2", E, SE, R, SR, h[:7], r[:7], t[:7], neg[:1], 3, 4, 0, 2.0, 0.1)
+
+
+# ---- row-wise state: one accumulator per row, fed with the mean of the squared gradient elements
+
+def test_rowwise_adagrad_hand_example_and_closed_form():
+    """g = (3, -4, 0, 0): mean g^2 = 25/4, so the first step divides by 5/2: x -= lr * g * 2/5.  Constant g for T
+    steps: S_T = T * mean g^2 and x_T = x_0 - lr * g * sum_tau 1 / (sqrt(tau * mean g^2) + eps)."""
+    g = np.array([[3.0, -4.0, 0.0, 0.0]])
+    th0 = np.array([[1.0, 2.0, 3.0, 4.0]], dtype=np.float32)
+    th, st = th0.copy(), np.zeros(1, np.float32)
+    oracle.adagrad_rows(th, st, None, g, 0.5, 1e-10, rowwise=True)
+    np.testing.assert_allclose(th, [[1.0 - 0.6, 2.0 + 0.8, 3.0, 4.0]], rtol=3e-7)
+    assert st[0] == np.float32(6.25)
+    assert th[0, 2] == th0[0, 2] and th[0, 3] == th0[0, 3]   # zero elements of a touched row do not move
+    th, st = th0.copy(), np.zeros(1, np.float32)
+    lr, eps, T = 0.1, 1e-10, 6
+    for _ in range(T):
+        oracle.adagrad_rows(th, st, None, g, lr, eps, rowwise=True)
+    want = th0.astype(np.float64) - lr * g * sum(1.0 / (math.sqrt(tau * 6.25) + eps) for tau in range(1, T + 1))
+    np.testing.assert_allclose(th, want, rtol=3e-7)
+    np.testing.assert_allclose(st, [T * 6.25], rtol=3e-7)
+
+
+def test_rowwise_equals_elementwise_when_all_elements_have_the_same_magnitude():
+    g = np.array([[0.5, -0.5, 0.5, -0.5], [2.0, 2.0, -2.0, 2.0]])
+    th_e = np.arange(8, dtype=np.float32).reshape(2, 4)
+    th_r = th_e.copy()
+    st_e, st_r = np.zeros_like(th_e), np.zeros(2, np.float32)
+    for _ in range(4):
+        oracle.adagrad_rows(th_e, st_e, None, g, 0.3, 1e-10)
+        oracle.adagrad_rows(th_r, st_r, None, g, 0.3, 1e-10, rowwise=True)
+    assert th_e.tobytes() == th_r.tobytes()
+    assert np.array_equal(st_e[:, 0], st_r)
+
+
+def test_rowwise_step_sums_duplicates_first_and_leaves_other_rows_alone():
+    for model in ("transe_l2", "distmult", "complex", "rotate"):
+        E, R, h, r, t, neg = _small_step_inputs(model)
+        h[:] = 3
+        g = oracle.loss_and_grad(model, E, R, h, r, t, neg, 3, 4, 0, 2.0)
+        outs = []
+        for dense in (True, False):
+            E1, R1 = E.copy(), R.copy()
+            SE, SR = np.zeros(E.shape[0], np.float32), np.zeros(R.shape[0], np.float32)
+            oracle.train_step(model, E1, SE, R1, SR, h, r, t, neg, 3, 4, 0, 2.0, 0.1, rowwise=True, dense=dense)
+            outs.append((E1, SE, R1, SR))
+        for a, b in zip(*outs):
+            assert a.tobytes() == b.tobytes()                 # dense == touched rows, bit for bit
+        E1, SE, R1, SR = outs[0]
+        ms = (g["dE"] ** 2).mean(axis=1)
+        np.testing.assert_allclose(SE, ms, rtol=3e-7, atol=0)  # mean of the SUMMED gradient's squares
+        wantE = E - 0.1 * g["dE"] / (np.sqrt(ms)[:, None] + 1e-10)
+        touched = ms > 0
+        np.testing.assert_allclose(E1[touched], wantE[touched], rtol=2e-6, atol=1e-7)
+        assert E1[~touched].tobytes() == E[~touched].tobytes()
