@@ -62,12 +62,18 @@ def algorithmic_work(w, h, r, t, neg, rowwise=False):
     ue = np.mean([np.unique(np.concatenate([h[s], t[s], neg[s].reshape(-1)])).size for s in range(n)])
     ur = np.mean([np.unique(r[s]).size for s in range(n)])
     n_keys = 2 * b + C * k
+    # elementwise-reduce models: flops per (positive, negative, coordinate): RotatE forward 2 sub, mul, fma, sqrt, add
+    # (the transcendental counted once), backward per side the same difference and norm plus scale and two fma; L1
+    # sub, abs, add forward and sub, select, add per side backward
+    pair_fwd = {"rotate": 6.0, "transe_l1": 3.0}.get(w.model)
+    pair_bwd = {"rotate": 2 * 9.0, "transe_l1": 2 * 3.0}.get(w.model)
+    coords = D // 2 if w.model == "rotate" else D
     return {
         "gather": {"bytes": 4.0 * ((2 * b + C * k) * D + b * Dr) + 4.0 * (b + C * k) * D},
         "update": {"bytes": ue * (8.0 * D + 8.0 if rowwise else 16.0 * D) + n_keys * 4.0 * D +
                             ur * (8.0 * Dr + 8.0 if rowwise else 16.0 * Dr) + b * 4.0 * Dr},
-        "neg_score": {"flops": 2.0 * b * k * D},
-        "neg_backward": {"flops": 4.0 * b * k * D},
+        "neg_score": {"flops": pair_fwd * b * k * coords if pair_fwd else 2.0 * b * k * D},
+        "neg_backward": {"flops": pair_bwd * b * k * coords if pair_bwd else 4.0 * b * k * D},
         "chain": {"bytes": 4.0 * (6 * b * D + 2 * b * Dr)},
         "loss": {"bytes": 8.0 * b * k},
         "sort": {"bytes": 8.0 * (n_keys + b)},

@@ -5,18 +5,20 @@
 // times), but the g*k*D pair terms are an elementwise reduction with a square root or an absolute value in
 // it, so they run on the vector ALUs, not on the matrix units.
 //
-// Forward: a workgroup owns a 32x32 tile of (positive, negative) pairs, stages 32 coordinates of both sides
-// in LDS at a time, and each thread accumulates four pairs (one corrupting row against four positives).
+// Forward: a workgroup owns a 32x32 tile of (positive, negative) pairs and stages 32 coordinates of both sides in
+// LDS at a time; a thread accumulates a 2x2 block of pairs and reads four coordinates of a row with one 16-byte
+// LDS load, so one load serves eight pair terms.  The modulus uses the hardware square root (1 ulp).
 // Backward: threads own coordinates instead of pairs, so the sums over j (for dL/do_i) and over i (for the
 // gradient row of corrupting entity j) stay in registers: one kind of workgroup walks all k negatives for 8
-// positives, the other walks all g positives for 8 negatives.  Nothing is accumulated with atomics.
+// positives, the other walks all g positives for 8 negatives; a workgroup is two groups of threads with 4 rows
+// each, so that rows of 200 coordinates fill its wavefronts.  Nothing is accumulated with atomics.
 #include "kge_common.h"
 
 namespace {
 
 constexpr int PT = 32;       // pair tile edge
 constexpr int PCK = 32;      // coordinates staged per step
-constexpr int PPITCH = 33;
+constexpr int PPITCH = 36;   // floats per staged row: 16-byte aligned rows
 
 struct PairArgs {
     const float* O;    // [b x D]
@@ -29,15 +31,23 @@ struct PairArgs {
 };
 
 template <bool CPLX>
+__device__ __forceinline__ float pair_term(float o_re, float o_im, float n_re, float n_im) {
+    const float q_re = o_re - n_re;
+    if (!CPLX) return fabsf(q_re);
+    const float q_im = o_im - n_im;
+    return __builtin_amdgcn_sqrtf(q_re * q_re + q_im * q_im);
+}
+
+template <bool CPLX>
 __global__ __launch_bounds__(256) void k_pair_fwd(PairArgs a) {
-    __shared__ float Os[2][PT][PPITCH];
-    __shared__ float Ns[2][PT][PPITCH];
-    const int tid = threadIdx.x, tj = tid & 31, ti = tid >> 5;
+    __shared__ __attribute__((aligned(16))) float Os[CPLX ? 2 : 1][PT][PPITCH];
+    __shared__ __attribute__((aligned(16))) float Ns[CPLX ? 2 : 1][PT][PPITCH];
+    const int tid = threadIdx.x, tj = tid & 15, ti = tid >> 4;  // pairs (2 ti + {0,1}, 2 tj + {0,1}) of the tile
     const int j0 = blockIdx.x * PT, i0 = blockIdx.y * PT, c = blockIdx.z;
     const int NC = CPLX ? a.D / 2 : a.D;  // coordinates
     const float* Oc = a.O + (int64_t)c * a.g * a.D;
     const float* Nc = a.Nst + (int64_t)c * a.k * a.D;
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
     const int lr = tid >> 3, lc = 4 * (tid & 7);
     for (int c0 = 0; c0 < NC; c0 += PCK) {
         const bool cok = c0 + lc < NC;  // NC is a multiple of 4
@@ -46,128 +56,165 @@ __global__ __launch_bounds__(256) void k_pair_fwd(PairArgs a) {
             float4 vo = make_float4(0.f, 0.f, 0.f, 0.f), vn = vo;
             if (cok && i0 + lr < a.g) vo = ld4(Oc + (int64_t)(i0 + lr) * a.D + part * NC + c0 + lc);
             if (cok && j0 + lr < a.k) vn = ld4(Nc + (int64_t)(j0 + lr) * a.D + part * NC + c0 + lc);
-            Os[part][lr][lc] = vo.x; Os[part][lr][lc + 1] = vo.y; Os[part][lr][lc + 2] = vo.z; Os[part][lr][lc + 3] = vo.w;
-            Ns[part][lr][lc] = vn.x; Ns[part][lr][lc + 1] = vn.y; Ns[part][lr][lc + 2] = vn.z; Ns[part][lr][lc + 3] = vn.w;
+            st4(&Os[part][lr][lc], vo);
+            st4(&Ns[part][lr][lc], vn);
         }
         __syncthreads();
         // the 32 terms of this step are summed on their own and then added to the running total: the partial
         // sums stay small, which keeps the fp32 rounding of a 200- or 400-term sum near that of a pairwise sum
-        float part[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-        for (int cc = 0; cc < PCK; ++cc) {
-            const float n_re = Ns[0][tj][cc];
-            const float n_im = CPLX ? Ns[1][tj][cc] : 0.f;
+        float part[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const float q_re = Os[0][ti + 8 * s][cc] - n_re;
+        for (int cc = 0; cc < PCK; cc += 4) {
+            float o_re[2][4], o_im[2][4], n_re[2][4], n_im[2][4];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const float4 vo = ld4(&Os[0][2 * ti + u][cc]), vn = ld4(&Ns[0][2 * tj + u][cc]);
+                o_re[u][0] = vo.x; o_re[u][1] = vo.y; o_re[u][2] = vo.z; o_re[u][3] = vo.w;
+                n_re[u][0] = vn.x; n_re[u][1] = vn.y; n_re[u][2] = vn.z; n_re[u][3] = vn.w;
                 if (CPLX) {
-                    const float q_im = Os[1][ti + 8 * s][cc] - n_im;
-                    part[s] += sqrtf(q_re * q_re + q_im * q_im);
+                    const float4 wo = ld4(&Os[CPLX ? 1 : 0][2 * ti + u][cc]), wn = ld4(&Ns[CPLX ? 1 : 0][2 * tj + u][cc]);
+                    o_im[u][0] = wo.x; o_im[u][1] = wo.y; o_im[u][2] = wo.z; o_im[u][3] = wo.w;
+                    n_im[u][0] = wn.x; n_im[u][1] = wn.y; n_im[u][2] = wn.z; n_im[u][3] = wn.w;
                 } else {
-                    part[s] += fabsf(q_re);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { o_im[u][e] = 0.f; n_im[u][e] = 0.f; }
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) part[u][q] += pair_term<CPLX>(o_re[u][e], o_im[u][e], n_re[q][e], n_im[q][e]);
                 }
             }
         }
 #pragma unroll
-        for (int s = 0; s < 4; ++s) acc[s] += part[s];
+        for (int u = 0; u < 2; ++u) { acc[u][0] += part[u][0]; acc[u][1] += part[u][1]; }
         __syncthreads();
     }
     // padded coordinates hold zeros on both sides and contribute |0 - 0| = 0
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int i = i0 + ti + 8 * s, j = j0 + tj;
-        if (i < a.g && j < a.k) a.S[((int64_t)c * a.g + i) * a.ld_s + j] = a.gamma - acc[s];
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int i = i0 + 2 * ti + u, j = j0 + 2 * tj + q;
+            if (i < a.g && j < a.k) a.S[((int64_t)c * a.g + i) * a.ld_s + j] = a.gamma - acc[u][q];
+        }
     }
 }
 
-// direction of (o - n): unit complex number, or sign for real coordinates; 0 where o == n
-template <bool CPLX>
-__device__ __forceinline__ void direction(float q_re, float q_im, float& e_re, float& e_im) {
-    if (CPLX) {
-        const float m2 = q_re * q_re + q_im * q_im;
-        const float inv = m2 > 0.f ? __builtin_amdgcn_rsqf(m2) : 0.f;
-        e_re = q_re * inv;
-        e_im = q_im * inv;
-    } else {
-        e_re = (float)((q_re > 0.f) - (q_re < 0.f));
-        e_im = 0.f;
-    }
-}
-
-constexpr int BT = 8;     // rows per backward workgroup
-constexpr int BW = 256;   // coefficients staged per step
+constexpr int BR = 4;        // rows per thread in the backward kernel
+constexpr int BT = 2 * BR;   // rows per backward workgroup: two thread groups of BR rows each
+constexpr int BW = 128;      // coefficients staged per step and row
 
 // blockIdx.x < n_i_tiles: dL/do for positives i0..i0+7 (sum over the chunk's k negatives)
 // else               : gradient rows of negatives j0..j0+7 (sum over the chunk's g positives)
-template <bool CPLX>
-__global__ __launch_bounds__(256) void k_pair_bwd(PairArgs a, int n_i_tiles) {
-    __shared__ float Ws[BW][BT];
-    const int tid = threadIdx.x, c = blockIdx.y;
+// Thread (group, coordinate): group 0 owns rows r0..r0+3, group 1 rows r0+4..r0+7; blockDim = 2 * coordinates per pass
+// rounded up to whole waves.  d psi / d o = -dir(o - n), d psi / d n = +dir(o - n), dir = unit complex number (sign
+// for real coordinates), 0 where o == n.
+template <bool CPLX, bool FOR_O>
+__device__ __forceinline__ void pair_bwd_rows(const PairArgs& a, int c, int r0, int cpp, float (*Ws)[BT]) {
+    const int tid = threadIdx.x;
     const int NC = CPLX ? a.D / 2 : a.D;
     const float* Oc = a.O + (int64_t)c * a.g * a.D;
     const float* Nc = a.Nst + (int64_t)c * a.k * a.D;
     const float* Wc = a.S + (int64_t)c * a.g * a.ld_s;
-    const bool for_o = (int)blockIdx.x < n_i_tiles;
-    const int r0 = (for_o ? blockIdx.x : blockIdx.x - n_i_tiles) * BT;
-    const int n_own = for_o ? a.g : a.k;      // rows on my side
-    const int n_other = for_o ? a.k : a.g;    // rows I sum over
-    const float* own = for_o ? Oc : Nc;
-    const float* other = for_o ? Nc : Oc;
-    const float sgn = for_o ? -1.f : 1.f;     // d psi/d o = -dir(o - n), d psi/d n = +dir(o - n)
+    const int n_own = FOR_O ? a.g : a.k;      // rows on my side
+    const int n_other = FOR_O ? a.k : a.g;    // rows I sum over
+    const float* own = FOR_O ? Oc : Nc;
+    const float* other = FOR_O ? Nc : Oc;
+    const int grp = tid >= cpp ? 1 : 0, lc = tid - grp * cpp;
+    const int rg = r0 + grp * BR;             // first row of my group
 
-    for (int cb = 0; cb < NC; cb += 256) {
-        const int cc = cb + tid;
-        const bool act = cc < NC;
-        float x_re[BT], x_im[BT], g_re[BT], g_im[BT];
+    for (int cb = 0; cb < NC; cb += cpp) {
+        const int cc = cb + lc;
+        const bool act = lc < cpp && tid < 2 * cpp && cc < NC;
+        const int ccs = act ? cc : 0;         // always a valid column
+        float x_re[BR], x_im[BR], g_re[BR], g_im[BR];
 #pragma unroll
-        for (int s = 0; s < BT; ++s) {
-            const bool ok = act && r0 + s < n_own;
-            x_re[s] = ok ? own[(int64_t)(r0 + s) * a.D + cc] : 0.f;
-            x_im[s] = (ok && CPLX) ? own[(int64_t)(r0 + s) * a.D + NC + cc] : 0.f;
+        for (int s = 0; s < BR; ++s) {
+            const bool ok = act && rg + s < n_own;
+            x_re[s] = ok ? own[(int64_t)(rg + s) * a.D + cc] : 0.f;
+            x_im[s] = (ok && CPLX) ? own[(int64_t)(rg + s) * a.D + NC + cc] : 0.f;
             g_re[s] = 0.f;
             g_im[s] = 0.f;
         }
         for (int m0 = 0; m0 < n_other; m0 += BW) {
             __syncthreads();
-            // stage W[i][j] for my 8 rows against the next BW rows of the other side
-            for (int e = tid; e < BW * BT; e += 256) {
-                const int mm = e / BT, s = e % BT;
+            // stage W[i][j] for the 8 rows of this workgroup against the next BW rows of the other side
+            for (int e = tid; e < BW * BT; e += blockDim.x) {
+                const int mm = FOR_O ? e % BW : e / BT, s = FOR_O ? e / BW : e % BT;  // lanes along the contiguous index
                 float wv = 0.f;
                 if (m0 + mm < n_other && r0 + s < n_own) {
-                    const int i = for_o ? r0 + s : m0 + mm, j = for_o ? m0 + mm : r0 + s;
+                    const int i = FOR_O ? r0 + s : m0 + mm, j = FOR_O ? m0 + mm : r0 + s;
                     wv = Wc[(int64_t)i * a.ld_s + j];
                 }
-                Ws[mm][s] = wv;
+                Ws[mm][s] = FOR_O ? -wv : wv;
             }
             __syncthreads();
             const int lim = min(BW, n_other - m0);
-            if (act) {
-                for (int mm = 0; mm < lim; ++mm) {
-                    const float y_re = other[(int64_t)(m0 + mm) * a.D + cc];
-                    const float y_im = CPLX ? other[(int64_t)(m0 + mm) * a.D + NC + cc] : 0.f;
+            const float* yp = other + (int64_t)m0 * a.D + ccs;
+            // eight rows of the other side per round, and the loads of the next round go out before this round is
+            // worked on, so that the arithmetic of one round covers the latency of the next one's loads
+            constexpr int RU = 8;
+            float y_re[RU], y_im[RU];
 #pragma unroll
-                    for (int s = 0; s < BT; ++s) {
-                        // o - n with o on my side (for_o) or on the other side
-                        const float q_re = for_o ? x_re[s] - y_re : y_re - x_re[s];
-                        const float q_im = for_o ? x_im[s] - y_im : y_im - x_im[s];
-                        float e_re, e_im;
-                        direction<CPLX>(q_re, q_im, e_re, e_im);
-                        const float wv = Ws[mm][s] * sgn;
-                        g_re[s] += wv * e_re;
-                        if (CPLX) g_im[s] += wv * e_im;
+            for (int u = 0; u < RU; ++u) {
+                const int row = u < lim ? u : lim - 1;
+                y_re[u] = yp[(int64_t)row * a.D];
+                y_im[u] = CPLX ? yp[(int64_t)row * a.D + NC] : 0.f;
+            }
+            for (int mm = 0; mm < lim; mm += RU) {
+                float z_re[RU], z_im[RU];
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    const int row = mm + RU + u < lim ? mm + RU + u : lim - 1;
+                    z_re[u] = yp[(int64_t)row * a.D];
+                    z_im[u] = CPLX ? yp[(int64_t)row * a.D + NC] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    if (mm + u < lim) {
+                        const float4 w4 = ld4(&Ws[mm + u][grp * BR]);
+                        const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+                        for (int s = 0; s < BR; ++s) {
+                            // o - n with o on my side (FOR_O) or on the other side
+                            const float q_re = FOR_O ? x_re[s] - y_re[u] : y_re[u] - x_re[s];
+                            if (CPLX) {
+                                const float q_im = FOR_O ? x_im[s] - y_im[u] : y_im[u] - x_im[s];
+                                // w / |q|; q = 0 gives w * 2^63 * 0 = 0
+                                const float t = wv[s] * __builtin_amdgcn_rsqf(fmaxf(q_re * q_re + q_im * q_im, 1e-38f));
+                                g_re[s] = fmaf(t, q_re, g_re[s]);
+                                g_im[s] = fmaf(t, q_im, g_im[s]);
+                            } else {
+                                g_re[s] += q_re > 0.f ? wv[s] : (q_re < 0.f ? -wv[s] : 0.f);
+                            }
+                        }
                     }
                 }
+#pragma unroll
+                for (int u = 0; u < RU; ++u) { y_re[u] = z_re[u]; y_im[u] = z_im[u]; }
             }
         }
-        float* dst = for_o ? a.GO + (int64_t)c * a.g * a.D : a.Gneg + (int64_t)c * a.k * a.D;
+        float* dst = FOR_O ? a.GO + (int64_t)c * a.g * a.D : a.Gneg + (int64_t)c * a.k * a.D;
 #pragma unroll
-        for (int s = 0; s < BT; ++s) {
-            if (act && r0 + s < n_own) {
-                dst[(int64_t)(r0 + s) * a.D + cc] = g_re[s];
-                if (CPLX) dst[(int64_t)(r0 + s) * a.D + NC + cc] = g_im[s];
+        for (int s = 0; s < BR; ++s) {
+            if (act && rg + s < n_own) {
+                dst[(int64_t)(rg + s) * a.D + cc] = g_re[s];
+                if (CPLX) dst[(int64_t)(rg + s) * a.D + NC + cc] = g_im[s];
             }
         }
     }
+}
+
+template <bool CPLX>
+__global__ __launch_bounds__(1024) void k_pair_bwd(PairArgs a, int n_i_tiles, int cpp) {
+    __shared__ __attribute__((aligned(16))) float Ws[BW][BT];
+    const int c = blockIdx.y;
+    if ((int)blockIdx.x < n_i_tiles) pair_bwd_rows<CPLX, true>(a, c, blockIdx.x * BT, cpp, Ws);
+    else pair_bwd_rows<CPLX, false>(a, c, (blockIdx.x - n_i_tiles) * BT, cpp, Ws);
 }
 
 }  // namespace
@@ -186,6 +233,10 @@ void kge_pair_neg_backward(kge_ctx* c, int b, int k, int gsz, hipStream_t st) {
     a.GO = c->GO; a.Gneg = c->Gent + (int64_t)2 * b * a.D;
     const int n_i_tiles = (gsz + BT - 1) / BT, n_j_tiles = (k + BT - 1) / BT;
     const dim3 grid(n_i_tiles + n_j_tiles, b / gsz);
-    if (c->cfg.model == KGE_ROTATE) KGE_LAUNCH(c, k_pair_bwd<true>, grid, dim3(256), 0, st, a, n_i_tiles);
-    else KGE_LAUNCH(c, k_pair_bwd<false>, grid, dim3(256), 0, st, a, n_i_tiles);
+    // coordinates per pass: all of them if two thread groups of that size fit a workgroup, else 512
+    const int nc = c->cfg.model == KGE_ROTATE ? a.D / 2 : a.D;
+    const int cpp = nc <= 512 ? nc : 512;
+    const dim3 block((2 * cpp + 63) / 64 * 64);
+    if (c->cfg.model == KGE_ROTATE) KGE_LAUNCH(c, k_pair_bwd<true>, grid, block, 0, st, a, n_i_tiles, cpp);
+    else KGE_LAUNCH(c, k_pair_bwd<false>, grid, block, 0, st, a, n_i_tiles, cpp);
 }
