@@ -38,33 +38,46 @@ __device__ __forceinline__ float pair_term(float o_re, float o_im, float n_re, f
     return __builtin_amdgcn_sqrtf(q_re * q_re + q_im * q_im);
 }
 
+// 512 threads: both halves of the workgroup hold the same 2x2 blocks of pairs, the first half sums coordinates 0..15 of
+// every staged step, the second 16..31 (twice the waves for the same LDS traffic); their sums meet at the end.
 template <bool CPLX>
-__global__ __launch_bounds__(256) void k_pair_fwd(PairArgs a) {
+__global__ __launch_bounds__(512) void k_pair_fwd(PairArgs a) {
     __shared__ __attribute__((aligned(16))) float Os[CPLX ? 2 : 1][PT][PPITCH];
     __shared__ __attribute__((aligned(16))) float Ns[CPLX ? 2 : 1][PT][PPITCH];
-    const int tid = threadIdx.x, tj = tid & 15, ti = tid >> 4;  // pairs (2 ti + {0,1}, 2 tj + {0,1}) of the tile
+    __shared__ float halves[256][4];
+    const int half = threadIdx.x >> 8, tid = threadIdx.x & 255;
+    const int tj = tid & 15, ti = tid >> 4;  // pairs (2 ti + {0,1}, 2 tj + {0,1}) of the tile
     const int j0 = blockIdx.x * PT, i0 = blockIdx.y * PT, c = blockIdx.z;
     const int NC = CPLX ? a.D / 2 : a.D;  // coordinates
     const float* Oc = a.O + (int64_t)c * a.g * a.D;
     const float* Nc = a.Nst + (int64_t)c * a.k * a.D;
     float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
     const int lr = tid >> 3, lc = 4 * (tid & 7);
-    for (int c0 = 0; c0 < NC; c0 += PCK) {
-        const bool cok = c0 + lc < NC;  // NC is a multiple of 4
+    // one thread stages one 16-byte piece per step (and per part): the first half of the workgroup the positives,
+    // the second the negatives.  The piece for the next step is asked for before this step's arithmetic starts.
+    const float* src = half == 0 ? Oc + (int64_t)(i0 + lr) * a.D : Nc + (int64_t)(j0 + lr) * a.D;
+    const bool rok = half == 0 ? i0 + lr < a.g : j0 + lr < a.k;
+    float (*dst)[PT][PPITCH] = half == 0 ? Os : Ns;
+    float4 nxt[CPLX ? 2 : 1];
+    auto fetch = [&](int c0) {
 #pragma unroll
         for (int part = 0; part < (CPLX ? 2 : 1); ++part) {
-            float4 vo = make_float4(0.f, 0.f, 0.f, 0.f), vn = vo;
-            if (cok && i0 + lr < a.g) vo = ld4(Oc + (int64_t)(i0 + lr) * a.D + part * NC + c0 + lc);
-            if (cok && j0 + lr < a.k) vn = ld4(Nc + (int64_t)(j0 + lr) * a.D + part * NC + c0 + lc);
-            st4(&Os[part][lr][lc], vo);
-            st4(&Ns[part][lr][lc], vn);
+            nxt[part] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (rok && c0 + lc < NC) nxt[part] = ld4(src + part * NC + c0 + lc);  // NC is a multiple of 4
         }
+    };
+    fetch(0);
+    for (int c0 = 0; c0 < NC; c0 += PCK) {
+#pragma unroll
+        for (int part = 0; part < (CPLX ? 2 : 1); ++part) st4(&dst[part][lr][lc], nxt[part]);
+        if (c0 + PCK < NC) fetch(c0 + PCK);
         __syncthreads();
         // the 32 terms of this step are summed on their own and then added to the running total: the partial
         // sums stay small, which keeps the fp32 rounding of a 200- or 400-term sum near that of a pairwise sum
         float part[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
 #pragma unroll
-        for (int cc = 0; cc < PCK; cc += 4) {
+        for (int cq = 0; cq < PCK / 2; cq += 4) {
+            const int cc = cq + half * (PCK / 2);
             float o_re[2][4], o_im[2][4], n_re[2][4], n_im[2][4];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
@@ -94,6 +107,12 @@ __global__ __launch_bounds__(256) void k_pair_fwd(PairArgs a) {
         __syncthreads();
     }
     // padded coordinates hold zeros on both sides and contribute |0 - 0| = 0
+    if (half == 1) {
+        halves[tid][0] = acc[0][0]; halves[tid][1] = acc[0][1]; halves[tid][2] = acc[1][0]; halves[tid][3] = acc[1][1];
+    }
+    __syncthreads();
+    if (half == 1) return;
+    acc[0][0] += halves[tid][0]; acc[0][1] += halves[tid][1]; acc[1][0] += halves[tid][2]; acc[1][1] += halves[tid][3];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
@@ -223,8 +242,8 @@ void kge_pair_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     PairArgs a = {};
     a.O = c->O; a.Nst = c->Nst; a.S = out; a.ld_s = ld_out; a.g = gsz; a.k = k; a.D = c->cfg.ent_dim; a.gamma = gamma;
     const dim3 grid((k + PT - 1) / PT, (gsz + PT - 1) / PT, b / gsz);
-    if (c->cfg.model == KGE_ROTATE) KGE_LAUNCH(c, k_pair_fwd<true>, grid, dim3(256), 0, st, a);
-    else KGE_LAUNCH(c, k_pair_fwd<false>, grid, dim3(256), 0, st, a);
+    if (c->cfg.model == KGE_ROTATE) KGE_LAUNCH(c, k_pair_fwd<true>, grid, dim3(512), 0, st, a);
+    else KGE_LAUNCH(c, k_pair_fwd<false>, grid, dim3(512), 0, st, a);
 }
 
 void kge_pair_neg_backward(kge_ctx* c, int b, int k, int gsz, hipStream_t st) {
