@@ -123,17 +123,19 @@ __global__ __launch_bounds__(512) void k_pair_fwd(PairArgs a) {
     }
 }
 
-constexpr int BR = 4;        // rows per thread in the backward kernel
-constexpr int BT = 2 * BR;   // rows per backward workgroup: two thread groups of BR rows each
+constexpr int BT_MAX = 16;   // most rows per backward workgroup: two thread groups of up to 8 rows each
 constexpr int BW = 128;      // coefficients staged per step and row
 
-// blockIdx.x < n_i_tiles: dL/do for positives i0..i0+7 (sum over the chunk's k negatives)
-// else               : gradient rows of negatives j0..j0+7 (sum over the chunk's g positives)
-// Thread (group, coordinate): group 0 owns rows r0..r0+3, group 1 rows r0+4..r0+7; blockDim = 2 * coordinates per pass
-// rounded up to whole waves.  d psi / d o = -dir(o - n), d psi / d n = +dir(o - n), dir = unit complex number (sign
+// blockIdx.x < n_i_tiles: dL/do for 2 BR_O positives (sum over the chunk's k negatives)
+// else               : gradient rows of 2 BR_N negatives (sum over the chunk's g positives)
+// Thread (group, coordinate): group 0 owns rows r0..r0+BR-1, group 1 the next BR; blockDim = 2 * coordinates per pass
+// rounded up to whole waves.  A workgroup's running time goes with BR * (rows it sums over), so the side that sums
+// over fewer rows takes 8 rows per thread and the other 4 when the chunk is lopsided (k >= 2g or g >= 2k): all
+// workgroups of a launch then run about equally long.  d psi / d o = -dir(o - n), d psi / d n = +dir(o - n), dir = unit complex number (sign
 // for real coordinates), 0 where o == n.
-template <bool CPLX, bool FOR_O>
-__device__ __forceinline__ void pair_bwd_rows(const PairArgs& a, int c, int r0, int cpp, float (*Ws)[BT]) {
+template <bool CPLX, bool FOR_O, int BR>
+__device__ __forceinline__ void pair_bwd_rows(const PairArgs& a, int c, int r0, int cpp, float (*Ws)[BT_MAX]) {
+    constexpr int BT = 2 * BR;
     const int tid = threadIdx.x;
     const int NC = CPLX ? a.D / 2 : a.D;
     const float* Oc = a.O + (int64_t)c * a.g * a.D;
@@ -195,8 +197,12 @@ __device__ __forceinline__ void pair_bwd_rows(const PairArgs& a, int c, int r0, 
 #pragma unroll
                 for (int u = 0; u < RU; ++u) {
                     if (mm + u < lim) {
-                        const float4 w4 = ld4(&Ws[mm + u][grp * BR]);
-                        const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
+                        float wv[BR];
+#pragma unroll
+                        for (int s4 = 0; s4 < BR; s4 += 4) {
+                            const float4 w4 = ld4(&Ws[mm + u][grp * BR + s4]);
+                            wv[s4] = w4.x; wv[s4 + 1] = w4.y; wv[s4 + 2] = w4.z; wv[s4 + 3] = w4.w;
+                        }
 #pragma unroll
                         for (int s = 0; s < BR; ++s) {
                             // o - n with o on my side (FOR_O) or on the other side
@@ -228,12 +234,22 @@ __device__ __forceinline__ void pair_bwd_rows(const PairArgs& a, int c, int r0, 
     }
 }
 
-template <bool CPLX>
+template <bool CPLX, int BR_O, int BR_N>
 __global__ __launch_bounds__(1024) void k_pair_bwd(PairArgs a, int n_i_tiles, int cpp) {
-    __shared__ __attribute__((aligned(16))) float Ws[BW][BT];
+    __shared__ __attribute__((aligned(16))) float Ws[BW][BT_MAX];
     const int c = blockIdx.y;
-    if ((int)blockIdx.x < n_i_tiles) pair_bwd_rows<CPLX, true>(a, c, blockIdx.x * BT, cpp, Ws);
-    else pair_bwd_rows<CPLX, false>(a, c, (blockIdx.x - n_i_tiles) * BT, cpp, Ws);
+    if ((int)blockIdx.x < n_i_tiles) pair_bwd_rows<CPLX, true, BR_O>(a, c, blockIdx.x * 2 * BR_O, cpp, Ws);
+    else pair_bwd_rows<CPLX, false, BR_N>(a, c, (blockIdx.x - n_i_tiles) * 2 * BR_N, cpp, Ws);
+}
+
+template <bool CPLX>
+void launch_pair_bwd(kge_ctx* c, const PairArgs& a, int chunks, int cpp, dim3 block, hipStream_t st) {
+    const int br_o = a.g >= 2 * a.k ? 8 : 4, br_n = a.k >= 2 * a.g ? 8 : 4;
+    const int n_i_tiles = (a.g + 2 * br_o - 1) / (2 * br_o), n_j_tiles = (a.k + 2 * br_n - 1) / (2 * br_n);
+    const dim3 grid(n_i_tiles + n_j_tiles, chunks);
+    if (br_o == 8) KGE_LAUNCH(c, (k_pair_bwd<CPLX, 8, 4>), grid, block, 0, st, a, n_i_tiles, cpp);
+    else if (br_n == 8) KGE_LAUNCH(c, (k_pair_bwd<CPLX, 4, 8>), grid, block, 0, st, a, n_i_tiles, cpp);
+    else KGE_LAUNCH(c, (k_pair_bwd<CPLX, 4, 4>), grid, block, 0, st, a, n_i_tiles, cpp);
 }
 
 }  // namespace
@@ -250,12 +266,10 @@ void kge_pair_neg_backward(kge_ctx* c, int b, int k, int gsz, hipStream_t st) {
     PairArgs a = {};
     a.O = c->O; a.Nst = c->Nst; a.S = c->S; a.ld_s = c->ld_s; a.g = gsz; a.k = k; a.D = c->cfg.ent_dim;
     a.GO = c->GO; a.Gneg = c->Gent + (int64_t)2 * b * a.D;
-    const int n_i_tiles = (gsz + BT - 1) / BT, n_j_tiles = (k + BT - 1) / BT;
-    const dim3 grid(n_i_tiles + n_j_tiles, b / gsz);
     // coordinates per pass: all of them if two thread groups of that size fit a workgroup, else 512
     const int nc = c->cfg.model == KGE_ROTATE ? a.D / 2 : a.D;
     const int cpp = nc <= 512 ? nc : 512;
     const dim3 block((2 * cpp + 63) / 64 * 64);
-    if (c->cfg.model == KGE_ROTATE) KGE_LAUNCH(c, k_pair_bwd<true>, grid, block, 0, st, a, n_i_tiles, cpp);
-    else KGE_LAUNCH(c, k_pair_bwd<false>, grid, block, 0, st, a, n_i_tiles, cpp);
+    if (c->cfg.model == KGE_ROTATE) launch_pair_bwd<true>(c, a, b / gsz, cpp, block, st);
+    else launch_pair_bwd<false>(c, a, b / gsz, cpp, block, st);
 }
