@@ -17,11 +17,13 @@
 // order at the end, so results do not depend on scheduling.  Operands may be stored K-contiguous ("KC":
 // [rows][K]) or row-contiguous ("MC": [K][rows]); both are read from memory as they lie.
 //
-// What is fused into the backward launch (one launch computes dO and dN; their tiles run side by side):
-//   * with uniform negative weights W is an elementwise function of the stored score, so it is formed while the
-//     A operand is loaded (no separate loss kernel, no W matrix in memory); the tiles of dO that own column
-//     block 0 also add up softplus(f-) for the loss value, and TransE-L2's rowsum(W) / colsum(W) fall out of the
-//     same loads;
+// What is fused (uniform negative weights):
+//   * W is then an elementwise function of the score, so the forward epilogue, which holds every score exactly
+//     once, stores W instead of the score and adds up softplus(f-) for the loss value (no separate loss kernel).
+//     (Forming W inside the backward tiles instead was measured: every element is then transformed in 26 tiles,
+//     and those instructions, not memory, set the pace of the launch.)
+//   * one backward launch computes dO and dN; their tiles run side by side; TransE-L2's rowsum(W) / colsum(W)
+//     fall out of the operand fragments;
 //   * for TransE-L2 and DistMult the chain rule from dL/do to the head, tail and relation gradient rows is
 //     elementwise, so the dO epilogue writes those rows directly (no dL/do array, no separate chain kernel);
 //     the rows it needs for that are fetched before the K loop starts.
@@ -33,7 +35,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 enum { EPI_PLAIN = 0, EPI_L2_FWD = 1, EPI_L2_DO = 2, EPI_L2_DN = 3, EPI_CHAIN_L2 = 4, EPI_CHAIN_DM = 5 };
-enum { TF_NONE = 0, TF_DOT = 1, TF_L2 = 2 };  // how the A operand is derived from what is stored
+enum { OUT_SCORE = 0, OUT_DIST = 1, OUT_W = 2 };  // what the forward launch stores (see kge_gemm_neg_score)
 
 struct GemmArgs {
     const float* A;
@@ -49,11 +51,11 @@ struct GemmArgs {
     int ldx;
     int64_t sX;
     float gamma;
-    int store_dist;      // EPI_L2_FWD: store the distance instead of gamma - distance
+    int out_mode;        // forward: OUT_SCORE, OUT_DIST (TransE-L2: the distance) or OUT_W (backward coefficients)
     int gx, gy, tiles;   // tiles along N, along M, and in total (over all chunks); set by the launchers
     // A-operand transform (uniform negative weights): W = wk * sigmoid(f) [/ distance]
     float wk;            // 1 / (k b)
-    float* neg_loss_part;  // [tiles along M, all chunks] sum of wk * softplus(f-) over the tile's rows
+    float* neg_loss_part;  // [forward tiles] OUT_W: sum of wk * softplus(f-) over the tile
     // chain-rule epilogues
     StepIds ids;
     const float* E;
@@ -72,19 +74,21 @@ constexpr int REGION = TILE * KC_PITCH;      // floats per staged operand block
 
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
 
-// W from a stored score (TF_DOT) or distance (TF_L2); optionally accumulates softplus(f).
-// Every W element is formed once per tile that reads it (a dozen times per step in all), so this uses the
-// hardware exp2 / log2 / reciprocal (1 ulp each; the argument scaling costs another few ulp at |f| ~ 10), which
-// keeps W within about 1e-6 relative: the same size as the rounding of the fp32 products it is multiplied into.
-template <int TF, bool LOSS>
-__device__ __forceinline__ float w_from_stored(float raw, float gamma, float wk, float& loss) {
-    const float f = TF == TF_L2 ? gamma - raw : raw;
-    const float e = __builtin_amdgcn_exp2f(-fabsf(f) * 1.4426950408889634f);  // exp(-|f|) in (0, 1]
-    const float sig = (f >= 0.f ? 1.f : e) * __builtin_amdgcn_rcpf(1.f + e);
-    if (LOSS) loss += fmaxf(f, 0.f) + __builtin_amdgcn_logf(1.f + e) * 0.6931471805599453f;
-    const float coef = wk * sig;
-    if (TF == TF_L2) return raw > 0.f ? coef * __builtin_amdgcn_rcpf(raw) : 0.f;
-    return coef;
+// Backward coefficient of a negative score f with uniform weight wk: wk * sigmoid(f) = d/df [wk softplus(f)];
+// adds softplus(f) to loss.  Runs once per score, in the forward epilogue.  FAST: the hardware exp2 / log2 /
+// reciprocal (1 ulp each; about 1e-6 relative in W, the size of the rounding of the fp32 products W goes into).
+// With bf16 operands W is rounded to bf16 afterwards, and which neighbour a value rounds to should not hinge on
+// those last bits, so that path uses the accurate functions.
+template <bool FAST>
+__device__ __forceinline__ float w_and_loss(float f, float wk, float& loss) {
+    if (FAST) {
+        const float e = __builtin_amdgcn_exp2f(-fabsf(f) * 1.4426950408889634f);  // exp(-|f|) in (0, 1]
+        loss += fmaxf(f, 0.f) + __builtin_amdgcn_logf(1.f + e) * 0.6931471805599453f;
+        return wk * ((f >= 0.f ? 1.f : e) * __builtin_amdgcn_rcpf(1.f + e));
+    }
+    const float e = expf(-fabsf(f));
+    loss += fmaxf(f, 0.f) + log1pf(e);
+    return wk * ((f >= 0.f ? 1.f : e) / (1.f + e));
 }
 
 // Loads 32x32 blocks of one operand into registers (zero-filled outside the matrix).  The per-lane row pointers
@@ -144,9 +148,9 @@ struct BlockLoader {
         const bool kin = k0 + major0 + 8 * it < K;
         return kin && (e == 0 ? any : (e == 1 ? m1 : (e == 2 ? m2 : m3)));
     }
-    // Elements outside the matrix become `fill` (0 for a plain operand; for an operand that still goes through
-    // w_from_stored, the value that function maps to W = 0 and loss 0).
-    __device__ __forceinline__ void mask(int kb, float4 (&reg)[4], float fill) const {
+    // Elements outside the matrix become 0.
+    __device__ __forceinline__ void mask(int kb, float4 (&reg)[4]) const {
+        const float fill = 0.f;
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             reg[it].x = valid(kb, it, 0) ? reg[it].x : fill;
@@ -203,11 +207,11 @@ __device__ __forceinline__ int xcd_tile(int q, int per_xcd) { return (blockIdx.x
 // BF: both operands are rounded to bf16 on their way from LDS to the matrix unit (after the W transform, so W is
 // rounded too) and multiplied by v_mfma_f32_32x32x16_bf16 with fp32 accumulation; the TransE-L2 correction terms
 // then use the rounded o / n rows and the sums of the rounded W.
-template <int NW, bool A_KC, bool B_KC, int TF, int EPI, bool IS_DO, bool BF>
+template <int NW, bool A_KC, bool B_KC, int EPI, bool IS_DO, bool BF>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*lds)[2][REGION]) {
     constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM;
     constexpr bool WANT_ASUM = EPI == EPI_L2_DO || EPI == EPI_L2_DN || EPI == EPI_CHAIN_L2;
-    constexpr bool WANT_LOSS = TF != TF_NONE && IS_DO;  // the dO tiles of column block 0 add up the loss
+    constexpr bool IS_FWD = A_KC && B_KC;  // only the forward product has both operands K-contiguous
     constexpr int NE = TILE * TILE / (NW * 64);           // output elements per thread
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int n0 = (tile % g.gx) * TILE, mt = (tile / g.gx) % g.gy, m0 = mt * TILE, c = tile / (g.gx * g.gy);
@@ -249,8 +253,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     float a_sum = 0.f;  // sum over this lane's K-values of A[m = lane%32][.]  (rowsum / colsum of W)
-    float loss = 0.f;
-    const bool loss_tile = WANT_LOSS && n0 == 0;
 
     const int nblk = (g.K + TILE - 1) / TILE;
     float4 ra[4], rb[4];
@@ -264,9 +266,8 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         lb.issue(kb, rb);
     }
     while (kb < nblk) {
-        // a stored score of -inf / distance of +inf gives W = 0 and no loss: the fill for elements outside W
-        la.mask(kb, ra, TF == TF_NONE ? 0.f : (TF == TF_DOT ? -INFINITY : INFINITY));
-        lb.mask(kb, rb, 0.f);
+        la.mask(kb, ra);
+        lb.mask(kb, rb);
         lds_store<A_KC>(As, lane, ra);
         lds_store<B_KC>(Bs, lane, rb);
         const int nxt = kb + NW;
@@ -283,13 +284,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
                 float fa[8], fb[8];
                 lds_frag8<A_KC>(As, lane, m, fa);
                 lds_frag8<B_KC>(Bs, lane, m, fb);
-                if (TF != TF_NONE) {
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) {
-                        if (loss_tile) fa[t] = w_from_stored<TF, true>(fa[t], g.gamma, g.wk, loss);
-                        else { float unused = 0.f; fa[t] = w_from_stored<TF, false>(fa[t], g.gamma, g.wk, unused); }
-                    }
-                }
                 bf16x8 pa, pb;
 #pragma unroll
                 for (int t = 0; t < 8; ++t) { pa[t] = (__bf16)fa[t]; pb[t] = (__bf16)fb[t]; }
@@ -305,14 +299,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
                 float fa[4], fb[4];
                 lds_frag<A_KC>(As, lane, q, fa);
                 lds_frag<B_KC>(Bs, lane, q, fb);
-                if (TF != TF_NONE) {  // every element of the block is read by exactly one lane here
-    #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        if (loss_tile) fa[t] = w_from_stored<TF, true>(fa[t], g.gamma, g.wk, loss);
-                        else { float unused = 0.f; fa[t] = w_from_stored<TF, false>(fa[t], g.gamma, g.wk, unused); }
-                    }
-                }
-    #pragma unroll
+#pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[t], fb[t], acc, 0, 0, 0);
                     if (WANT_ASUM) a_sum += fa[t];
@@ -334,18 +321,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         a_sum += __shfl_xor(a_sum, 32, 64);
         if (lane < 32) Bs[lane] = a_sum;
     }
-    if (WANT_LOSS) {
-        loss = wave_sum(loss);
-        if (lane == 0) Bs[32] = loss;
-    }
     __syncthreads();
-    if (WANT_LOSS && loss_tile && threadIdx.x == 0) {
-        float s = 0.f;
-#pragma unroll
-        for (int ww = 0; ww < NW; ++ww) s += lds[ww][1][32];
-        g.neg_loss_part[c * g.gy + mt] = s * g.wk;
-    }
     float* C = g.C + c * g.sC;
+    float loss = 0.f;  // OUT_W: softplus(f-) of this thread's elements
 #pragma unroll
     for (int it = 0; it < NE; ++it) {
         const int e = threadIdx.x + it * NW * 64;
@@ -362,11 +340,16 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             for (int ww = 0; ww < NW; ++ww) rs += lds[ww][1][i];
         }
         if (EPI == EPI_PLAIN) {
-            C[(int64_t)gm * g.ldc + gn] = s;
+            C[(int64_t)gm * g.ldc + gn] = (IS_FWD && g.out_mode == OUT_W) ? w_and_loss<!BF>(s, g.wk, loss) : s;
         } else if (EPI == EPI_L2_FWD) {
             const float d2 = g.rowv[c * g.s_rowv + gm] + g.colv[c * g.s_colv + gn] - 2.f * s;
             const float d = sqrtf(fmaxf(d2, 0.f));
-            C[(int64_t)gm * g.ldc + gn] = g.store_dist ? d : g.gamma - d;
+            float out = g.out_mode == OUT_DIST ? d : g.gamma - d;
+            if (g.out_mode == OUT_W) {  // W = w sigmoid(f) / |o - n|, 0 where the distance is 0
+                const float coef = w_and_loss<!BF>(g.gamma - d, g.wk, loss);
+                out = d > 0.f ? (BF ? coef / d : coef * __builtin_amdgcn_rcpf(d)) : 0.f;
+            }
+            C[(int64_t)gm * g.ldc + gn] = out;
         } else if (EPI == EPI_L2_DO || EPI == EPI_L2_DN) {
             const float xv = g.X[c * g.sX + (int64_t)gm * g.ldx + gn];
             C[(int64_t)gm * g.ldc + gn] = s - rs * (BF ? round_bf16(xv) : xv);
@@ -384,6 +367,19 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             g.Grel[(int64_t)bi * g.D + gn] = go * e_a[it];
         }
     }
+    if (IS_FWD && g.out_mode == OUT_W) {
+        // negative part of the loss: this tile's sum of w softplus(f-), in a fixed order
+        loss = wave_sum(loss);
+        __syncthreads();  // the partial tiles in LDS have been read
+        if (lane == 0) lds[w][1][0] = loss;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < NW; ++ww) t += lds[ww][1][0];
+            g.neg_loss_part[tile] = t * g.wk;
+        }
+    }
 }
 
 template <int NW, int EPI, bool BF>
@@ -391,22 +387,22 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_fwd(GemmArgs g) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
     const int tile = xcd_tile(blockIdx.x >> 3, gridDim.x >> 3);
     if (tile >= g.tiles) return;
-    gemm_tile<NW, true, true, TF_NONE, EPI, false, BF>(g, tile, lds);
+    gemm_tile<NW, true, true, EPI, false, BF>(g, tile, lds);
 }
 
 // dN tiles first (their K is the chunk size, they run longest), then dO tiles; each XCD gets its share of both.
 // Held to 128 registers so that four waves fit on every SIMD (two 8-wave workgroups per CU): all tiles of the
 // Freebase-scale step are then resident at once instead of running in two rounds.
-template <int NW, int TF, int EPI_O, int EPI_N, bool BF>
+template <int NW, int EPI_O, int EPI_N, bool BF>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_gemm_bwd(GemmArgs gO, GemmArgs gN, int per_xcd_n, int per_xcd_o) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
     const int q = blockIdx.x >> 3;
     if (q < per_xcd_n) {
         const int tile = xcd_tile(q, per_xcd_n);
-        if (tile < gN.tiles) gemm_tile<NW, false, false, TF, EPI_N, false, BF>(gN, tile, lds);
+        if (tile < gN.tiles) gemm_tile<NW, false, false, EPI_N, false, BF>(gN, tile, lds);
     } else {
         const int tile = xcd_tile(q - per_xcd_n, per_xcd_o);
-        if (tile < gO.tiles) gemm_tile<NW, true, false, TF, EPI_O, true, BF>(gO, tile, lds);
+        if (tile < gO.tiles) gemm_tile<NW, true, false, EPI_O, true, BF>(gO, tile, lds);
     }
 }
 
@@ -435,7 +431,7 @@ void launch_fwd(kge_ctx* c, GemmArgs g, int chunks, hipStream_t st) {
     else KGE_LAUNCH(c, (k_gemm_fwd<16, EPI, BF>), grid, dim3(1024), 0, st, g);
 }
 
-template <int TF, int EPI_O, int EPI_N, bool BF>
+template <int EPI_O, int EPI_N, bool BF>
 void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st) {
     set_tiling(gO, chunks);
     set_tiling(gN, chunks);
@@ -444,15 +440,16 @@ void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st
     const int nblk = ((gO.K > gN.K ? gO.K : gN.K) + TILE - 1) / TILE;
     // at most 8 waves: 74 KB of LDS per workgroup, so two workgroups share a CU
     const int nw = pick_nw(gO.tiles + gN.tiles, nblk, 8);
-    if (nw == 4) KGE_LAUNCH(c, (k_gemm_bwd<4, TF, EPI_O, EPI_N, BF>), grid, dim3(256), 0, st, gO, gN, per_n, per_o);
-    else KGE_LAUNCH(c, (k_gemm_bwd<8, TF, EPI_O, EPI_N, BF>), grid, dim3(512), 0, st, gO, gN, per_n, per_o);
+    if (nw == 4) KGE_LAUNCH(c, (k_gemm_bwd<4, EPI_O, EPI_N, BF>), grid, dim3(256), 0, st, gO, gN, per_n, per_o);
+    else KGE_LAUNCH(c, (k_gemm_bwd<8, EPI_O, EPI_N, BF>), grid, dim3(512), 0, st, gO, gN, per_n, per_o);
 }
 
 }  // namespace
 
-// S_c = O_c N_c^T with the model's epilogue.  dist_mode: TransE-L2 stores the distance (training path) instead
-// of the score (kge_score path).
-void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* out, int ld_out, int dist_mode,
+// S_c = O_c N_c^T with the model's epilogue.  out_mode: 0 the scores (kge_score path); 1 what the loss kernel wants
+// (TransE-L2: the distances, else the scores); 2 the backward coefficients W of uniformly weighted negatives, with
+// the tiles' loss sums in neg_loss_part (training steps without a loss kernel).
+void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* out, int ld_out, int out_mode,
                         hipStream_t st) {
     const int D = c->cfg.ent_dim;
     GemmArgs g = {};
@@ -461,7 +458,8 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     g.lda = D; g.ldb = D; g.ldc = ld_out;
     g.sA = (int64_t)gsz * D; g.sB = (int64_t)k * D; g.sC = (int64_t)gsz * ld_out;
     g.rowv = c->o_n2; g.colv = c->n_n2; g.s_rowv = gsz; g.s_colv = k;
-    g.gamma = gamma; g.store_dist = dist_mode;
+    g.gamma = gamma; g.out_mode = out_mode;
+    g.wk = 1.f / ((float)k * (float)b); g.neg_loss_part = c->neg_loss_part;
     const int chunks = b / gsz;
     const bool bf = c->cfg.gemm_input == 1;
     if (c->cfg.model == KGE_TRANSE_L2) {
@@ -473,15 +471,14 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     }
 }
 
-// With bf16 operands W is rounded to bf16, and which neighbour a value rounds to should not hinge on the few-ulp
-// error of the fast exp2 / reciprocal used when W is formed on the fly: there the loss kernel forms W (accurate
-// functions, once per element) and the products only round it.
-bool kge_gemm_backward_forms_w(const kge_ctx* c) { return c->cfg.adv_temperature == 0.f && c->cfg.gemm_input == 0; }
+// Uniform negative weights: the forward launch stores W and the loss sums, and no loss kernel runs.
+bool kge_gemm_backward_forms_w(const kge_ctx* c) { return c->cfg.adv_temperature == 0.f; }
 bool kge_gemm_backward_does_chain(const kge_ctx* c) {
     return c->cfg.model == KGE_TRANSE_L2 || c->cfg.model == KGE_DISTMULT;
 }
-int kge_gemm_loss_parts(const kge_ctx* c, int b, int gsz) {
-    return kge_gemm_backward_forms_w(c) ? (b / gsz) * ((gsz + TILE - 1) / TILE) : 0;
+int kge_gemm_loss_parts(const kge_ctx* c, int b, int k, int gsz) {
+    const int k_tiles = (k + TILE - 1) / TILE;
+    return kge_gemm_backward_forms_w(c) ? (b / gsz) * ((gsz + TILE - 1) / TILE) * k_tiles : 0;
 }
 
 // dO_c = W_c N_c (- rowsum(W) o)  and  dN_c = W_c^T O_c (- colsum(W) n) in one launch.  dN goes straight into the
@@ -498,7 +495,7 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
     g.lda = c->ld_s; g.ldb = D; g.ldc = D;
     g.sA = (int64_t)gsz * c->ld_s; g.sB = (int64_t)k * D; g.sC = (int64_t)gsz * D;
     g.X = c->O; g.ldx = D; g.sX = (int64_t)gsz * D;
-    g.gamma = gamma; g.wk = 1.f / ((float)k * (float)b); g.neg_loss_part = c->neg_loss_part;
+    g.gamma = gamma;
     g.ids = ids; g.E = E; g.R = R; g.cpos = c->cpos; g.inv_dpos = c->inv_dpos; g.Gent = c->Gent; g.Grel = c->Grel;
     g.b = b; g.D = D; g.n_ent = c->cfg.num_entities; g.n_rel = c->cfg.num_relations;
 
@@ -509,22 +506,14 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
     q.sA = (int64_t)gsz * c->ld_s; q.sB = (int64_t)gsz * D; q.sC = (int64_t)k * D;
     q.X = c->Nst; q.ldx = D; q.sX = (int64_t)k * D;
 
-    const bool tf = kge_gemm_backward_forms_w(c);
     const bool bf = c->cfg.gemm_input == 1;
-#define KGE_BWD(TF, EO, EN)                                             \
-    do {                                                                \
-        if (bf) launch_bwd<TF, EO, EN, true>(c, g, q, chunks, st);      \
-        else launch_bwd<TF, EO, EN, false>(c, g, q, chunks, st);        \
+#define KGE_BWD(EO, EN)                                           \
+    do {                                                          \
+        if (bf) launch_bwd<EO, EN, true>(c, g, q, chunks, st);    \
+        else launch_bwd<EO, EN, false>(c, g, q, chunks, st);      \
     } while (0)
-    if (model == KGE_TRANSE_L2) {
-        if (tf) KGE_BWD(TF_L2, EPI_CHAIN_L2, EPI_L2_DN);
-        else KGE_BWD(TF_NONE, EPI_CHAIN_L2, EPI_L2_DN);
-    } else if (model == KGE_DISTMULT) {
-        if (tf) KGE_BWD(TF_DOT, EPI_CHAIN_DM, EPI_PLAIN);
-        else KGE_BWD(TF_NONE, EPI_CHAIN_DM, EPI_PLAIN);
-    } else {
-        if (tf) KGE_BWD(TF_DOT, EPI_PLAIN, EPI_PLAIN);
-        else KGE_BWD(TF_NONE, EPI_PLAIN, EPI_PLAIN);
-    }
+    if (model == KGE_TRANSE_L2) KGE_BWD(EPI_CHAIN_L2, EPI_L2_DN);
+    else if (model == KGE_DISTMULT) KGE_BWD(EPI_CHAIN_DM, EPI_PLAIN);
+    else KGE_BWD(EPI_PLAIN, EPI_PLAIN);
 #undef KGE_BWD
 }

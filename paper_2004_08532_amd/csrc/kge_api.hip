@@ -107,7 +107,8 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
     }
     {
         ProfScope p(c, KGE_PROF_SCORE);
-        if (is_gemm_model(c->cfg.model)) kge_gemm_neg_score(c, B, K, G, gamma, c->S, c->ld_s, 1, st);
+        if (is_gemm_model(c->cfg.model))
+            kge_gemm_neg_score(c, B, K, G, gamma, c->S, c->ld_s, kge_gemm_backward_forms_w(c) ? 2 : 1, st);
         else kge_pair_neg_score(c, B, K, G, gamma, c->S, c->ld_s, st);
     }
     // The matrix-product models fold the loss (uniform weights) and the chain rule (TransE-L2, DistMult) into
@@ -115,7 +116,7 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
     const bool gemm = is_gemm_model(c->cfg.model);
     const bool run_loss = !(gemm && kge_gemm_backward_forms_w(c));
     const bool run_chain = !(gemm && kge_gemm_backward_does_chain(c));
-    const int n_loss_parts = gemm ? kge_gemm_loss_parts(c, B, G) : 0;
+    const int n_loss_parts = gemm ? kge_gemm_loss_parts(c, B, K, G) : 0;
     if (run_loss) {
         ProfScope p(c, KGE_PROF_LOSS);
         kge_launch_loss(c, B, K, gamma, st);
@@ -247,7 +248,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t o_Ge = take(EK * D * 4), o_Gr = take(B * Dr * 4);
     const size_t o_fpos = take(B * 4), o_on2 = take(B * 4), o_nn2 = take(NR * 4), o_cpos = take(B * 4);
     const size_t o_rl = take(B * 4), o_wrs = take(B * 4), o_idp = take(B * 4);
-    const size_t o_nlp = take((B / 32 + cfg->max_chunks + 1) * 4);
+    const size_t o_nlp = take((B / 32 + cfg->max_chunks + 1) * ((size_t)cfg->max_neg_per_chunk / 32 + 1) * 4);
     const size_t o_ek0 = take(EK * 4), o_ek1 = take(EK * 4), o_ep0 = take(EK * 4), o_ep1 = take(EK * 4);
     const size_t o_rk0 = take(B * 4), o_rk1 = take(B * 4), o_rp0 = take(B * 4), o_rp1 = take(B * 4);
     const size_t o_flags = take(256), o_step = take(256);

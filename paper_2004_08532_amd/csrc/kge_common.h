@@ -39,7 +39,7 @@ struct kge_ctx {
     float* row_loss; // [max_batch]          loss terms of positive i, already divided by b
     float* w_rowsum; // [max_batch]          sum_j W_ij       (TransE-L2, self-adversarial path)
     float* inv_dpos; // [max_batch]          1 / |o_i - c_i|  (TransE-L2)
-    float* neg_loss_part;  // [max_batch/32 + max_chunks]  negative-side loss sums written by the backward launch
+    float* neg_loss_part;  // [forward tiles]  negative-side loss sums written by the forward launch
     uint32_t* ekey[2];  // entity sort ping-pong: keys
     uint32_t* epos[2];  //                        positions in the key list
     uint32_t* rkey[2];  // relation sort ping-pong
@@ -129,9 +129,9 @@ void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st);
 // a5: dL/do and the gradient rows of the corrupting entities
 void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const StepIds& ids, int k, int g, float gamma,
                            hipStream_t st);
-bool kge_gemm_backward_forms_w(const kge_ctx* c);     // W is formed inside the backward launch (no k_loss)
+bool kge_gemm_backward_forms_w(const kge_ctx* c);     // the forward launch stores W and the loss sums (no k_loss)
 bool kge_gemm_backward_does_chain(const kge_ctx* c);  // the backward launch writes the positives' gradient rows
-int kge_gemm_loss_parts(const kge_ctx* c, int b, int g);
+int kge_gemm_loss_parts(const kge_ctx* c, int b, int k, int g);  // loss sums the forward launch leaves in neg_loss_part
 void kge_pair_neg_backward(kge_ctx* c, int b, int k, int g, hipStream_t st);
 // a5: positive-pair term and chain rule through phi -> gradient rows of heads, tails and relations
 void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
