@@ -34,6 +34,7 @@ class Workload:
     lr: float
     adv_temperature: float = 0.0
     bf16_inputs: bool = False
+    loss: str = "logistic"   # logistic | ranking (the two losses of Sec. 2)
     steps: int = 20
     seed: int = 0
 

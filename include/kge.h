@@ -44,6 +44,13 @@ typedef enum {
 /* Which entity of each positive is replaced to form its negatives (Sec. 2: only entities are corrupted). */
 typedef enum { KGE_NEG_TAIL = 0, KGE_NEG_HEAD = 1 } kge_neg_side;
 
+/* The two training losses of Sec. 2.  With b positives, k negatives per positive and weights w_ij (see
+ * adv_temperature):
+ *   logistic:  L = (1/b) sum_i [ log(1 + exp(-f+_i)) + sum_j w_ij log(1 + exp(f-_ij)) ]
+ *   ranking:   L = (1/b) sum_i sum_j w_ij max(0, gamma - f+_i + f-_ij)      (gamma of the call is the margin; the
+ *              gamma inside the distance scores cancels in f- - f+; sub-gradient 0 at the kink) */
+typedef enum { KGE_LOSS_LOGISTIC = 0, KGE_LOSS_RANKING = 1 } kge_loss;
+
 typedef enum {
     KGE_OK = 0,
     KGE_ERR_INVALID_ARG = -1, /* null pointer, size out of range, b not a multiple of chunk, bad enum   */
@@ -69,6 +76,7 @@ typedef struct {
     float adv_temperature;     /* 0: negatives weigh 1/k each; > 0: softmax(temperature * score) weights  */
     int32_t validate_indices;  /* != 0: kge_train_step / kge_score range-check ids on the device and the  */
                                /* next kge_check_indices call reports the result                          */
+    int32_t loss;              /* kge_loss                                                                */
 } kge_config;
 
 /* Create a context and its workspace on cfg->device.  (host) cfg, (host) out.  The workspace is sized from
@@ -87,7 +95,8 @@ void kge_destroy(kge_ctx* ctx);
  *   h, r, t [b]: int64 ids of the positive triples.
  *   neg [(b / chunk) * k]: int64 corrupting entity ids; positives chunk*c .. chunk*c + chunk - 1 share
  *   neg[c*k .. c*k + k - 1].  neg_side says whether they replace the tail or the head.
- *   Loss (Sec. 2, logistic loss with y = +1 on positives and -1 on negatives):
+ *   Loss (Sec. 2, logistic loss with y = +1 on positives and -1 on negatives, unless cfg.loss selects the
+ *   pairwise ranking loss, see kge_loss):
  *       L = (1/b) sum_i [ log(1 + exp(-f+_i)) + sum_j w_ij log(1 + exp(f-_ij)) ],
  *   w_ij = 1/k, or softmax_j(adv_temperature * f-_ij) held constant in the backward pass.
  *   Update: for every distinct row that occurs among h, t, neg (entities) or r (relations), with g the sum of

@@ -19,6 +19,7 @@ _LIB = os.path.join(_HERE, "libkge_oracle.so")
 
 TRANSE_L2, TRANSE_L1, DISTMULT, COMPLEX, ROTATE = 0, 1, 2, 3, 4
 NEG_TAIL, NEG_HEAD = 0, 1
+LOSS_IDS = {"logistic": 0, "ranking": 1}
 MODEL_IDS = {"transe_l2": TRANSE_L2, "transe_l1": TRANSE_L1, "distmult": DISTMULT, "complex": COMPLEX,
              "rotate": ROTATE}
 
@@ -34,7 +35,7 @@ def build(force: bool = False) -> str:
 class _Params(ctypes.Structure):
     _fields_ = [("model", ctypes.c_int32), ("ent_dim", ctypes.c_int32), ("rel_dim", ctypes.c_int32),
                 ("neg_side", ctypes.c_int32), ("tables_f64", ctypes.c_int32), ("bf16_inputs", ctypes.c_int32),
-                ("rotate_squared", ctypes.c_int32), ("split_form", ctypes.c_int32),
+                ("rotate_squared", ctypes.c_int32), ("split_form", ctypes.c_int32), ("loss", ctypes.c_int32),
                 ("gamma", ctypes.c_double), ("adv_temperature", ctypes.c_double)]
 
 
@@ -70,14 +71,14 @@ def _ids(a) -> np.ndarray:
 
 
 def _params(model, ent_dim, rel_dim, neg_side, gamma, adv_temperature=0.0, tables_f64=False, bf16_inputs=False,
-            rotate_squared=False, split_form=False) -> _Params:
+            rotate_squared=False, split_form=False, loss="logistic") -> _Params:
     m = MODEL_IDS[model] if isinstance(model, str) else int(model)
     return _Params(m, int(ent_dim), int(rel_dim), int(neg_side), int(tables_f64), int(bf16_inputs),
-                   int(rotate_squared), int(split_form), float(gamma), float(adv_temperature))
+                   int(rotate_squared), int(split_form), LOSS_IDS[loss], float(gamma), float(adv_temperature))
 
 
 def loss_and_grad(model, E, R, h, r, t, neg, k, chunk, neg_side, gamma, adv_temperature=0.0, w_fixed=None,
-                  want_grad=True, bf16_inputs=False, rotate_squared=False, split_form=False):
+                  want_grad=True, bf16_inputs=False, rotate_squared=False, split_form=False, loss="logistic"):
     """Loss, scores, weights and (dense) gradients of one mini-batch.
 
     E, R: float32 or float64 2-D arrays.  Returns a dict with ``loss`` (float), ``pos`` [b], ``neg`` [b,k],
@@ -92,7 +93,7 @@ def loss_and_grad(model, E, R, h, r, t, neg, k, chunk, neg_side, gamma, adv_temp
     b = h.shape[0]
     assert neg.shape[0] == (b // chunk) * k
     p = _params(model, E.shape[1], R.shape[1], neg_side, gamma, adv_temperature, f64, bf16_inputs, rotate_squared,
-                split_form)
+                split_form, loss)
     loss = ctypes.c_double(0.0)
     pos = np.zeros(b, np.float64)
     negs = np.zeros((b, k), np.float64)
@@ -149,7 +150,8 @@ def adagrad_rows(table, state, ids, grad, lr, eps, rowwise=False):
 
 
 def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr, eps=1e-10, adv_temperature=0.0,
-               dense=False, bf16_inputs=False, rotate_squared=False, want_scores=False, report=False, rowwise=False):
+               dense=False, bf16_inputs=False, rotate_squared=False, want_scores=False, report=False, rowwise=False,
+               loss="logistic"):
     """One step, in place on float32 E, SE, R, SR.  Returns loss (and scores when asked).
 
     report=True (touched-rows mode) returns ``(loss, rep)`` where rep holds, for the distinct rows of the step,
@@ -161,7 +163,8 @@ def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr,
     h, r, t, neg = _ids(h), _ids(r), _ids(t), _ids(neg).reshape(-1)
     b = h.shape[0]
     assert neg.shape[0] == (b // chunk) * k
-    p = _params(model, E.shape[1], R.shape[1], neg_side, gamma, adv_temperature, False, bf16_inputs, rotate_squared)
+    p = _params(model, E.shape[1], R.shape[1], neg_side, gamma, adv_temperature, False, bf16_inputs, rotate_squared,
+                False, loss)
     loss = ctypes.c_double(0.0)
     pos = np.zeros(b, np.float64) if want_scores else None
     negs = np.zeros((b, k), np.float64) if want_scores else None

@@ -11,6 +11,7 @@
  *   - joint negative sampling: positives are grouped into consecutive sets of size g and all members of a
  *     set share the same k corrupting entities                                               [Sec. 3.3]
  *   - the logistic loss  log(1 + exp(-y f))  with y = +1 on positives and -1 on negatives    [Sec. 2]
+ *   - or the pairwise ranking loss  max(0, gamma - f(positive) + f(negative))                [Sec. 2]
  *   - the gradients of that loss with respect to every embedding row that took part          [Sec. 3.1 step 3]
  *   - the update of exactly those rows by Adagrad                                            [Sec. 3.1 step 4]
  *
@@ -28,6 +29,10 @@
  *     phases in radians
  *   - loss = (1/b) sum_i [ softplus(-f+_i) + sum_j w_ij softplus(f-_ij) ],  w_ij = 1/k, or the softmax over
  *     j of (adv_temperature * f-_ij) treated as a constant when adv_temperature > 0
+ *   - ranking loss = (1/b) sum_i sum_j w_ij max(0, gamma - f+_i + f-_ij): every positive is paired with its own k
+ *     negatives, with the same weights and the same 1/b as the logistic loss; its margin is the gamma that the
+ *     distance models also carry inside f (where it cancels: gamma + dist+ - dist-); the sub-gradient at the kink
+ *     (margin term exactly 0) is 0
  *   - the optimizer is element-wise Adagrad:  S += g^2 ; theta -= lr * g / (sqrt(S) + eps), where g is the
  *     sum of all contributions to that row within the step
  *   - where a norm or modulus is exactly zero its sub-gradient is taken to be zero
@@ -48,6 +53,7 @@
 
 enum { KO_TRANSE_L2 = 0, KO_TRANSE_L1 = 1, KO_DISTMULT = 2, KO_COMPLEX = 3, KO_ROTATE = 4 };
 enum { KO_NEG_TAIL = 0, KO_NEG_HEAD = 1 };
+enum { KO_LOSS_LOGISTIC = 0, KO_LOSS_RANKING = 1 };
 
 typedef struct {
     int32_t model;
@@ -58,6 +64,7 @@ typedef struct {
     int32_t bf16_inputs;     /* see header comment */
     int32_t rotate_squared;  /* RotatE as printed in Table 1: gamma - sum_j |h_j r_j - t_j|^2 */
     int32_t split_form;      /* evaluate negatives through the Sec. 3.3 split without any rounding (tests) */
+    int32_t loss;            /* KO_LOSS_LOGISTIC or KO_LOSS_RANKING (the two losses of Sec. 2) */
     double gamma;
     double adv_temperature;
 } ko_params;
@@ -426,7 +433,9 @@ static void add_rows(double *acc, int64_t slot, int dim, const double *v) {
  * pos_score [b], neg_score [b*k], w_out [b*k] : outputs, each may be NULL.
  * dE / dR : NULL (no gradients wanted) or zero-initialised [n_slots * dim] accumulators; row s of dE
  * belongs to entity ent_ids[s] (ascending list), or to entity s when ent_ids == NULL.
- * aE / aR : NULL or accumulators of the same shape for the condition measure of grad_triple_mag.
+ * aE / aR : NULL or accumulators of the same shape for the condition measure of grad_triple_mag.  With the
+ *           ranking loss a pair whose margin term lies within 2e-5 * max(1, |f+|, |f-|) of the kink (fp32 scores
+ *           may put it on the other side) adds 2^20 times what switching it on or off would change.
  * mE / mR : NULL or arrays of the same shape that receive, per element, the largest grad_triple_mag measure of a
  *           single (positive, negative) pair: how much one backward coefficient weighs in that element (the tests
  *           bound with it what a coefficient that rounds to the neighbouring bfloat16 value can change).
@@ -488,9 +497,22 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
         }
         if (w_out) for (int64_t j = 0; j < k; ++j) w_out[i * k + j] = w[j];
 
-        /* logistic loss: y = +1 for the positive, y = -1 for each negative */
-        double li = softplus(-fpos);
-        for (int64_t j = 0; j < k; ++j) li += w[j] * softplus(fneg[j]);
+        double li, cpos;
+        if (p->loss == KO_LOSS_RANKING) {
+            /* pairwise ranking loss: the positive against each of its negatives, margin gamma */
+            double active = 0.0;
+            li = 0.0;
+            for (int64_t j = 0; j < k; ++j) {
+                const double m = p->gamma - fpos + fneg[j];
+                if (m > 0) { li += w[j] * m; active += w[j]; }
+            }
+            cpos = -active / (double)b;
+        } else {
+            /* logistic loss: y = +1 for the positive, y = -1 for each negative */
+            li = softplus(-fpos);
+            for (int64_t j = 0; j < k; ++j) li += w[j] * softplus(fneg[j]);
+            cpos = -sigmoid(-fpos) / (double)b; /* d/df softplus(-f) / b */
+        }
         total += li / (double)b;
 
         if (!dE) continue;
@@ -501,7 +523,6 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
         /* every triple's contribution is formed in scratch rows (th, tr, tt) and then added to the rows'
          * accumulators; the optional aE / aR receive the magnitudes of the terms involved (a condition
          * measure used by the parity tests, not part of the method) */
-        const double cpos = -sigmoid(-fpos) / (double)b; /* d/df softplus(-f) / b */
         memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
         grad_triple(p, hv, rv, tv, cpos, th, tr, tt);
         add_rows(dE, sh, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, st, De, tt);
@@ -513,6 +534,17 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
             if (sn < 0) { rc = -2; break; }
             double cneg = w[j] * sigmoid(fneg[j]) / (double)b; /* d/df softplus(f) * w / b */
             fetch_row(E, f64, n, De, nv);
+            if (p->loss == KO_LOSS_RANKING) {
+                const double m = p->gamma - fpos + fneg[j];
+                cneg = m > 0 ? w[j] / (double)b : 0.0;
+                double big = fabs(fpos) > fabs(fneg[j]) ? fabs(fpos) : fabs(fneg[j]);
+                if (aE && fabs(m) <= 2e-5 * (big > 1 ? big : 1)) { /* undecided in fp32: see aE above */
+                    const double flip = 1048576.0 * w[j] / (double)b;
+                    grad_triple_mag(p, hv, rv, tv, flip, aE + sh * De, aR + sr * Dr, aE + st * De);
+                    if (head_side) grad_triple_mag(p, nv, rv, tv, flip, aE + sn * De, aR + sr * Dr, aE + st * De);
+                    else grad_triple_mag(p, hv, rv, nv, flip, aE + sh * De, aR + sr * Dr, aE + sn * De);
+                }
+            }
             memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
             if (aE) {
                 if (head_side) grad_triple_mag(p, nv, rv, tv, cneg, aE + sn * De, aR + sr * Dr, aE + st * De);

@@ -20,6 +20,7 @@ KGE_TRANSE_L2, KGE_TRANSE_L1, KGE_DISTMULT, KGE_COMPLEX, KGE_ROTATE = 0, 1, 2, 3
 KGE_NEG_TAIL, KGE_NEG_HEAD = 0, 1
 KGE_OK, KGE_ERR_INVALID_ARG, KGE_ERR_UNSUPPORTED, KGE_ERR_WORKSPACE, KGE_ERR_DEVICE, KGE_ERR_INDEX_RANGE = \
     0, -1, -2, -3, -4, -5
+LOSS_IDS = {"logistic": 0, "ranking": 1}
 MODEL_IDS = {"transe_l2": KGE_TRANSE_L2, "transe_l1": KGE_TRANSE_L1, "distmult": KGE_DISTMULT,
              "complex": KGE_COMPLEX, "rotate": KGE_ROTATE}
 
@@ -42,7 +43,7 @@ class kge_config(ctypes.Structure):
                 ("max_batch", ctypes.c_int32), ("max_neg_per_chunk", ctypes.c_int32), ("max_chunks", ctypes.c_int32),
                 ("gemm_input", ctypes.c_int32), ("adagrad_mode", ctypes.c_int32),
                 ("adagrad_eps", ctypes.c_float), ("adv_temperature", ctypes.c_float),
-                ("validate_indices", ctypes.c_int32)]
+                ("validate_indices", ctypes.c_int32), ("loss", ctypes.c_int32)]
 
 
 class KgeError(RuntimeError):
@@ -239,7 +240,7 @@ class KgeContext:
 
     def __init__(self, model, num_entities, num_relations, ent_dim, rel_dim=None, max_batch=1024,
                  max_neg_per_chunk=256, max_chunks=None, device=0, gemm_input=0, adv_temperature=0.0,
-                 adagrad_eps=0.0, validate_indices=False, adagrad_mode=0):
+                 adagrad_eps=0.0, validate_indices=False, adagrad_mode=0, loss="logistic"):
         m = MODEL_IDS[model] if isinstance(model, str) else int(model)
         if rel_dim is None:
             rel_dim = ent_dim // 2 if m == KGE_ROTATE else ent_dim
@@ -248,7 +249,8 @@ class KgeContext:
         self.cfg = kge_config(m, int(device), int(num_entities), int(num_relations), int(ent_dim), int(rel_dim),
                               int(max_batch), int(max_neg_per_chunk), int(max_chunks), int(gemm_input),
                               int(adagrad_mode),
-                              float(adagrad_eps), float(adv_temperature), int(bool(validate_indices)))
+                              float(adagrad_eps), float(adv_temperature), int(bool(validate_indices)),
+                              LOSS_IDS[loss])
         self.ctx = kge_create(self.cfg)
 
     def train_step(self, ent, ent_state, rel, rel_state, h, r, t, neg, k, chunk, neg_side, gamma, lr, loss_out=None,

@@ -471,8 +471,11 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     }
 }
 
-// Uniform negative weights: the forward launch stores W and the loss sums, and no loss kernel runs.
-bool kge_gemm_backward_forms_w(const kge_ctx* c) { return c->cfg.adv_temperature == 0.f; }
+// Logistic loss with uniform negative weights: the forward launch stores W and the loss sums, and no loss kernel
+// runs.  (The ranking loss couples a positive with all of its negatives, so it always takes the loss kernel.)
+bool kge_gemm_backward_forms_w(const kge_ctx* c) {
+    return c->cfg.adv_temperature == 0.f && c->cfg.loss == KGE_LOSS_LOGISTIC;
+}
 bool kge_gemm_backward_does_chain(const kge_ctx* c) {
     return c->cfg.model == KGE_TRANSE_L2 || c->cfg.model == KGE_DISTMULT;
 }

@@ -1,4 +1,4 @@
-// Logistic loss (paper Sec. 2) on the positive and negative scores, its derivatives, and the chain rule from
+// Logistic or pairwise ranking loss (paper Sec. 2) on the positive and negative scores, its derivatives, and the chain rule from
 // dL/do back to the head / tail / relation rows (the back-propagation half of Sec. 3.1 step 3).
 //
 // k_loss: one wavefront per positive.  The k negative scores of the row are read by the 64 lanes, the optional
@@ -6,6 +6,8 @@
 // coefficient matrix W that the backward products consume:
 //     W_ij = w_ij * sigmoid(f-_ij) / b               (DistMult, ComplEx, RotatE, TransE-L1)
 //     W_ij = w_ij * sigmoid(f-_ij) / (b * dist_ij)    (TransE-L2, so that dO = W N - rowsum(W) o)
+// Ranking loss max(0, gamma - f+_i + f-_ij): sigmoid(f-_ij) is replaced by the indicator of a positive margin term,
+// and dL/df+_i = -sum_j w_ij [term > 0] / b comes out of the same pass over the row.
 // k_chain: one wavefront per positive.  Adds the positive pair's own term to dL/do, pushes it through
 // o = phi(a, r) and writes the three gradient rows of the positive (kept entity, replaced entity, relation).
 #include "kge_common.h"
@@ -25,6 +27,7 @@ struct LossArgs {
     const float* fpos;
     float gamma, alpha;
     int is_dist;  // TransE-L2 training path: S holds distances, score = gamma - S
+    int ranking;  // pairwise ranking loss instead of the logistic loss
     int bf16;
     float* cpos;
     float* row_loss;
@@ -54,13 +57,21 @@ __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
         }
         z = wave_sum(zz);
     }
-    float li = 0.f, rs = 0.f;
+    float li = 0.f, rs = 0.f, active = 0.f;
     for (int j = lane; j < k; j += 64) {
         const float raw = s[j];
         const float f = a.is_dist ? a.gamma - raw : raw;
         const float w = a.alpha > 0.f ? expf(a.alpha * f - mx) / z : 1.f / (float)k;
-        li += w * softplusf_(f);
-        float coef = w * sigmoidf_(f) * invb;
+        float coef;
+        if (a.ranking) {
+            const float m = a.gamma - fp + f;
+            li += w * fmaxf(m, 0.f);
+            coef = m > 0.f ? w * invb : 0.f;
+            active += m > 0.f ? w : 0.f;
+        } else {
+            li += w * softplusf_(f);
+            coef = w * sigmoidf_(f) * invb;
+        }
         if (a.is_dist) coef = raw > 0.f ? coef / raw : 0.f;
         if (a.bf16) coef = round_bf16(coef);  // what the product kernels multiply with
         s[j] = coef;
@@ -68,9 +79,10 @@ __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
     }
     li = wave_sum(li);
     rs = wave_sum(rs);
+    if (a.ranking) active = wave_sum(active);
     if (lane == 0) {
-        a.row_loss[i] = (softplusf_(-fp) + li) * invb;
-        a.cpos[i] = -sigmoidf_(-fp) * invb;
+        a.row_loss[i] = a.ranking ? li * invb : (softplusf_(-fp) + li) * invb;
+        a.cpos[i] = a.ranking ? -active * invb : -sigmoidf_(-fp) * invb;
         a.w_rowsum[i] = rs;
     }
 }
@@ -251,7 +263,7 @@ void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st) {
     LossArgs a;
     a.S = c->S; a.ld_s = c->ld_s; a.b = b; a.k = k; a.fpos = c->fpos; a.gamma = gamma;
     a.alpha = c->cfg.adv_temperature; a.is_dist = c->cfg.model == KGE_TRANSE_L2;
-    a.bf16 = c->cfg.gemm_input;
+    a.bf16 = c->cfg.gemm_input; a.ranking = c->cfg.loss == KGE_LOSS_RANKING;
     a.cpos = c->cpos; a.row_loss = c->row_loss; a.w_rowsum = c->w_rowsum;
     KGE_LAUNCH(c, k_loss, dim3((b + 3) / 4), dim3(256), 0, st, a);
 }

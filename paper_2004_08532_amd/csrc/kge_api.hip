@@ -219,6 +219,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     if ((int64_t)cfg->max_chunks * cfg->max_neg_per_chunk + 2ll * cfg->max_batch > (1 << 24))
         return fail(nullptr, KGE_ERR_INVALID_ARG, "more than 2^24 entity keys per step%s");
     if (cfg->adagrad_mode != 0 && cfg->adagrad_mode != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "adagrad_mode must be 0 or 1%s");
+    if (cfg->loss != KGE_LOSS_LOGISTIC && cfg->loss != KGE_LOSS_RANKING) return fail(nullptr, KGE_ERR_INVALID_ARG, "loss must be 0 (logistic) or 1 (ranking)%s");
     if (cfg->gemm_input != 0 && cfg->gemm_input != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "gemm_input must be 0 or 1%s");
     if (cfg->gemm_input != 0 && cfg->gemm_input != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "gemm_input must be 0 or 1%s");
     if (cfg->gemm_input == 1 && !is_gemm_model(cfg->model))

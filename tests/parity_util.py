@@ -95,7 +95,7 @@ class Pair:
         self.ctx = kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
                                   max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks,
                                   gemm_input=int(w.bf16_inputs), adv_temperature=w.adv_temperature,
-                                  validate_indices=validate, adagrad_mode=int(rowwise))
+                                  validate_indices=validate, adagrad_mode=int(rowwise), loss=w.loss)
         self.loss = torch.zeros(1, dtype=torch.float32, device="cuda")
         self.floor = graphs.init_bound(w.gamma, w.ent_dim)
         self.eps = 1e-10
@@ -123,7 +123,7 @@ class Pair:
         torch.cuda.synchronize()
         want = oracle.train_step(w.model, self.E, self.SE, self.R, self.SR, h, r, t, neg, k, w.chunk, side, w.gamma,
                                  w.lr, eps=self.eps, adv_temperature=w.adv_temperature, bf16_inputs=w.bf16_inputs,
-                                 report=report, rowwise=self.rowwise)
+                                 report=report, rowwise=self.rowwise, loss=w.loss)
         return float(self.loss.item()), want
 
     # -- one step from identical tables, every touched element checked, then tables re-synchronised ----------

@@ -85,6 +85,40 @@ def test_ragged_shapes_every_model(kge, model, alpha):
         p.close()
 
 
+# margins at which roughly half of the (positive, negative) pairs of the ragged workload are active at its
+# initialisation (score differences there: ~0.1 for the distance models, ~1e-3 for the products)
+RANKING_MARGIN = {"transe_l2": 0.03, "transe_l1": 0.3, "distmult": 3e-4, "complex": 3e-4, "rotate": 0.3}
+
+
+@pytest.mark.parametrize("alpha", [0.0, 1.0])
+@pytest.mark.parametrize("model", MODELS)
+def test_pairwise_ranking_loss_every_model(kge, model, alpha):
+    """The second loss of Sec. 2.  Whether a pair's margin term is clipped is decided by fp32 scores on the device;
+    the oracle widens the allowance of the elements that a pair within the score tolerance of the kink feeds."""
+    w = ragged(model, adv_temperature=alpha, loss="ranking", gamma=RANKING_MARGIN[model])
+    bs = configs.BatchStream(w)
+    E, R = configs.init_tables(w.scaled(gamma=6.0))  # tables as in the other ragged tests, whatever the margin
+    p = Pair(w, kge, E=E, R=R)
+    try:
+        h, r, t, neg, side = bs.step(0)
+        opos, oneg = oracle.scores(model, p.E, p.R, h, r, t, neg, w.neg_per_chunk, w.chunk, side, w.gamma)
+        active = (w.gamma - opos[:, None] + oneg > 0).mean()
+        assert 0.1 < active < 0.9, active  # the test means to exercise both branches
+        run_steps(p, bs, w.steps)
+    finally:
+        p.close()
+
+
+def test_pairwise_ranking_loss_bf16_operands(kge):
+    w = ragged("transe_l2", loss="ranking", gamma=RANKING_MARGIN["transe_l2"], bf16_inputs=True)
+    E, R = configs.init_tables(w.scaled(gamma=6.0))
+    p = Pair(w, kge, E=E, R=R)
+    try:
+        run_steps(p, configs.BatchStream(w), w.steps)
+    finally:
+        p.close()
+
+
 def test_tiny_config_20_steps(kge):
     """Configuration 'tiny': TransE-L2, dim 64, b 256, g 32, k 64, 20 steps: every step checked element by
     element, then the same 20 steps free-running from the same seed."""
@@ -434,6 +468,8 @@ def test_host_detected_errors_leave_everything_untouched(kge):
         assert torch.equal(p.dE, E0) and torch.equal(p.dSE, S0)
         with pytest.raises(kge.KgeError):
             kge.KgeContext("rotate", 10, 2, 30)  # ent_dim not a multiple of 8
+        with pytest.raises(KeyError):
+            kge.KgeContext("distmult", 10, 2, 32, loss="hinge")  # unknown loss name
     finally:
         p.close()
 
