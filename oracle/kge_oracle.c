@@ -6,7 +6,7 @@
  * build, load or call it.  It shares no code, header, table or helper with the GPU library.
  *
  * What it computes (paper sections in brackets):
- *   - the score of a triple (h, r, t) for TransE (L1 or L2), DistMult, ComplEx and RotatE   [Table 1]
+ *   - the score of a triple (h, r, t) for TransE (L1 or L2), DistMult, ComplEx, RotatE and RESCAL  [Table 1]
  *   - negatives obtained by replacing the head or the tail of a positive triple              [Sec. 2]
  *   - joint negative sampling: positives are grouped into consecutive sets of size g and all members of a
  *     set share the same k corrupting entities                                               [Sec. 3.3]
@@ -26,7 +26,7 @@
  *   - RotatE uses gamma - sum_j |h_j r_j - t_j| (modulus per complex coordinate); the literally printed
  *     squared norm is available through rotate_squared
  *   - a row of ComplEx / RotatE entities is [real parts | imaginary parts]; a RotatE relation row holds
- *     phases in radians
+ *     phases in radians; a RESCAL relation row holds the D x D matrix M_r row by row (rel_dim = D * D)
  *   - loss = (1/b) sum_i [ softplus(-f+_i) + sum_j w_ij softplus(f-_ij) ],  w_ij = 1/k, or the softmax over
  *     j of (adv_temperature * f-_ij) treated as a constant when adv_temperature > 0
  *   - ranking loss = (1/b) sum_i sum_j w_ij max(0, gamma - f+_i + f-_ij): every positive is paired with its own k
@@ -51,7 +51,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { KO_TRANSE_L2 = 0, KO_TRANSE_L1 = 1, KO_DISTMULT = 2, KO_COMPLEX = 3, KO_ROTATE = 4 };
+enum { KO_TRANSE_L2 = 0, KO_TRANSE_L1 = 1, KO_DISTMULT = 2, KO_COMPLEX = 3, KO_ROTATE = 4, KO_RESCAL = 5 };
 enum { KO_NEG_TAIL = 0, KO_NEG_HEAD = 1 };
 enum { KO_LOSS_LOGISTIC = 0, KO_LOSS_RANKING = 1 };
 
@@ -150,6 +150,10 @@ static double score_triple(const ko_params *p, const double *h, const double *r,
         }
         return p->gamma - acc;
     }
+    case KO_RESCAL: /* h^T M t, M[a][c] = r[a * D + c] */
+        for (int a = 0; a < D; ++a)
+            for (int c = 0; c < D; ++c) acc += h[a] * r[(int64_t)a * D + c] * t[c];
+        return acc;
     default: return NAN;
     }
 }
@@ -219,6 +223,15 @@ static void grad_triple(const ko_params *p, const double *h, const double *r, co
         }
         return;
     }
+    case KO_RESCAL:
+        for (int a = 0; a < D; ++a)
+            for (int c = 0; c < D; ++c) {
+                const double m = r[(int64_t)a * D + c];
+                gh[a] += coef * m * t[c];
+                gt[c] += coef * h[a] * m;
+                gr[(int64_t)a * D + c] += coef * h[a] * t[c];
+            }
+        return;
     default: return;
     }
 }
@@ -290,6 +303,15 @@ static void grad_triple_mag(const ko_params *p, const double *h, const double *r
         }
         return;
     }
+    case KO_RESCAL:
+        for (int a = 0; a < D; ++a)
+            for (int c = 0; c < D; ++c) {
+                const double m = fabs(r[(int64_t)a * D + c]);
+                mh[a] += ac * m * fabs(t[c]);
+                mt[c] += ac * fabs(h[a]) * m;
+                mr[(int64_t)a * D + c] += ac * fabs(h[a] * t[c]);
+            }
+        return;
     default: return;
     }
 }
@@ -317,6 +339,14 @@ static void split_o(const ko_params *p, const double *a, const double *r, double
             o[C + j] = a[j] * rim + a[C + j] * rre;
         }
         break;
+    case KO_RESCAL: /* tail side: h^T M n = (M^T h) . n ; head side: n^T M t = n . (M t) */
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        for (int x = 0; x < D; ++x)
+            for (int c = 0; c < D; ++c) {
+                if (head) o[x] += r[(int64_t)x * D + c] * a[c];
+                else o[c] += a[x] * r[(int64_t)x * D + c];
+            }
+        break;
     }
 }
 
@@ -331,7 +361,7 @@ static double pair_score(const ko_params *p, const double *o, const double *x) {
     case KO_TRANSE_L1:
         for (int d = 0; d < D; ++d) acc += fabs(o[d] - x[d]);
         return p->gamma - acc;
-    case KO_DISTMULT: case KO_COMPLEX:
+    case KO_DISTMULT: case KO_COMPLEX: case KO_RESCAL:
         for (int d = 0; d < D; ++d) acc += o[d] * x[d];
         return acc;
     case KO_ROTATE:
@@ -360,7 +390,7 @@ static void pair_grad(const ko_params *p, const double *o, const double *x, doub
     case KO_TRANSE_L1:
         for (int d = 0; d < D; ++d) { double u = o[d] - x[d]; double e = (u > 0) - (u < 0); go[d] -= coef * e; gx[d] += coef * e; }
         return;
-    case KO_DISTMULT: case KO_COMPLEX:
+    case KO_DISTMULT: case KO_COMPLEX: case KO_RESCAL:
         for (int d = 0; d < D; ++d) { go[d] += coef * x[d]; gx[d] += coef * o[d]; }
         return;
     case KO_ROTATE:
@@ -414,6 +444,14 @@ static void split_o_backward(const ko_params *p, const double *a, const double *
             gr[j] += head ? -d_th : d_th;
         }
         break;
+    case KO_RESCAL:
+        for (int x = 0; x < D; ++x)
+            for (int c = 0; c < D; ++c) {
+                const double m = r[(int64_t)x * D + c];
+                if (head) { ga[c] += go[x] * m; gr[(int64_t)x * D + c] += go[x] * a[c]; }  /* o = M a */
+                else { ga[x] += m * go[c]; gr[(int64_t)x * D + c] += a[x] * go[c]; }        /* o = M^T a */
+            }
+        break;
     }
 }
 
@@ -449,6 +487,7 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
                  const int64_t *rel_ids, int64_t n_rel_slots, double *dR, double *aR, double *mE, double *mR) {
     if (b <= 0 || chunk <= 0 || b % chunk != 0 || k < 0) return -1;
     if ((p->model == KO_COMPLEX || p->model == KO_ROTATE) && (p->ent_dim % 2)) return -1;
+    if (p->model == KO_RESCAL && p->rel_dim != p->ent_dim * p->ent_dim) return -1;
     const int De = p->ent_dim, Dr = p->rel_dim, f64 = p->tables_f64;
     const int head_side = p->neg_side == KO_NEG_HEAD;
     const int use_split = p->bf16_inputs || p->split_form;

@@ -7,12 +7,12 @@ import pytest
 
 import oracle
 
-MODELS = ["transe_l2", "transe_l1", "distmult", "complex", "rotate"]
+MODELS = ["transe_l2", "transe_l1", "distmult", "complex", "rotate", "rescal"]
 LN2 = math.log(2.0)
 
 
 def _problem(model, rng, n_ent=7, n_rel=3, D=6, b=4, chunk=2, k=3):
-    Dr = D // 2 if model == "rotate" else D
+    Dr = D // 2 if model == "rotate" else (D * D if model == "rescal" else D)
     E = rng.normal(size=(n_ent, D))
     R = rng.uniform(-math.pi, math.pi, size=(n_rel, Dr)) if model == "rotate" else rng.normal(size=(n_rel, Dr))
     h = rng.integers(0, n_ent, b)

@@ -9,7 +9,7 @@ import pytest
 import oracle
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "hand_scores.txt")
-MODELS = ["transe_l2", "transe_l1", "distmult", "complex", "rotate"]
+MODELS = ["transe_l2", "transe_l1", "distmult", "complex", "rotate", "rescal"]
 
 
 def _vec(txt):
@@ -46,7 +46,7 @@ def test_hand_worked_scores(row):
 
 
 def _rand_problem(model, rng, n_ent=23, n_rel=5, D=8, b=12, chunk=4, k=5):
-    Dr = D // 2 if model == "rotate" else D
+    Dr = D // 2 if model == "rotate" else (D * D if model == "rescal" else D)
     E = rng.normal(size=(n_ent, D))
     R = rng.uniform(-math.pi, math.pi, size=(n_rel, Dr)) if model == "rotate" else rng.normal(size=(n_rel, Dr))
     h = rng.integers(0, n_ent, b)
@@ -67,6 +67,9 @@ def _split_scores_numpy(model, E, R, h, r, t, neg, chunk, k, side, gamma):
         o = a - rr if side == 1 else a + rr
     elif model == "distmult":
         o = a * rr
+    elif model == "rescal":  # h^T M n = (M^T h) . n ;  n^T M t = n . (M t)
+        M = rr.reshape(b, D, D)
+        o = np.einsum("bxc,bc->bx", M, a) if side == 1 else np.einsum("bx,bxc->bc", a, M)
     else:
         if model == "rotate":
             rc = np.cos(rr) + 1j * np.sin(rr)
@@ -79,7 +82,7 @@ def _split_scores_numpy(model, E, R, h, r, t, neg, chunk, k, side, gamma):
     for c in range(b // chunk):
         Oc = o[c * chunk:(c + 1) * chunk]
         Nc = E[neg[c]]
-        if model in ("distmult", "complex"):
+        if model in ("distmult", "complex", "rescal"):
             S = Oc @ Nc.T
         elif model == "transe_l2":
             d2 = (Oc * Oc).sum(1)[:, None] + (Nc * Nc).sum(1)[None, :] - 2.0 * (Oc @ Nc.T)
@@ -184,3 +187,24 @@ def test_complex_reduces_to_distmult_for_real_embeddings():
     pd, nd = oracle.scores("distmult", Er, Rr, h, r, t, neg, 2, 3, 0, 0.0)
     np.testing.assert_allclose(pc, pd, atol=1e-13)
     np.testing.assert_allclose(nc, nd, atol=1e-13)
+
+
+def test_rescal_with_diagonal_matrices_is_distmult():
+    """M_r = diag(r) turns h^T M_r t into DistMult's sum_d h_d r_d t_d: scores, loss and the entity gradients coincide,
+    and the diagonal of dL/dM_r is DistMult's relation gradient (off-diagonal entries are h_a t_c terms, not zero)."""
+    rng = np.random.default_rng(11)
+    E, R, h, r, t, neg, chunk, k = _rand_problem("distmult", rng)
+    D = E.shape[1]
+    Rm = np.zeros((R.shape[0], D * D))
+    for i in range(R.shape[0]):
+        Rm[i] = np.diag(R[i]).reshape(-1)
+    for side in (0, 1):
+        for loss in ("logistic", "ranking"):
+            a = oracle.loss_and_grad("distmult", E, R, h, r, t, neg, k, chunk, side, 0.4, loss=loss)
+            m = oracle.loss_and_grad("rescal", E, Rm, h, r, t, neg, k, chunk, side, 0.4, loss=loss)
+            np.testing.assert_allclose(m["pos"], a["pos"], rtol=1e-12, atol=1e-12)
+            np.testing.assert_allclose(m["neg"], a["neg"], rtol=1e-12, atol=1e-12)
+            assert abs(m["loss"] - a["loss"]) < 1e-12
+            np.testing.assert_allclose(m["dE"], a["dE"], rtol=1e-10, atol=1e-12)
+            diag = m["dR"].reshape(-1, D, D)[:, np.arange(D), np.arange(D)]
+            np.testing.assert_allclose(diag, a["dR"], rtol=1e-10, atol=1e-12)
