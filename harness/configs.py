@@ -17,7 +17,7 @@ from . import graphs, sampler
 @dataclasses.dataclass(frozen=True)
 class Workload:
     name: str
-    model: str               # transe_l2 | transe_l1 | distmult | complex | rotate
+    model: str               # transe_l2 | transe_l1 | distmult | complex | rotate | rescal
     n_entities: int
     n_relations: int
     n_triples: int           # size of the synthetic triple list (0: positives are drawn directly, not stored)
@@ -51,6 +51,8 @@ TINY = Workload("tiny", "transe_l2", 1_000, 20, 10_000, 1.1, None, 64, 64, 256, 
 SMALL_DISTMULT = Workload("small-distmult", "distmult", 14_951, 1_345, 483_142, 1.0, 1.2, 400, 400, 1024, 128, 256,
                           "uniform", "alternate", 12.0, 0.1, steps=471)
 SMALL_COMPLEX = SMALL_DISTMULT.scaled(name="small-complex", model="complex")
+# RESCAL at the same graph and batch shape, rows of 200 floats: a relation row is a 200 x 200 matrix
+SMALL_RESCAL = SMALL_DISTMULT.scaled(name="small-rescal", model="rescal", ent_dim=200, rel_dim=200 * 200)
 MEDIUM = Workload("medium", "rotate", 2_500_000, 800, 16_000_000, 0.9, None, 400, 200, 1024, 128, 256, "degree",
                   "tail", 12.0, 0.1, adv_temperature=1.0, steps=1000)
 LARGE = Workload("large", "transe_l2", 5_000_000, 800, 20_000_000, 0.9, None, 400, 400, 2048, 256, 1024, "uniform",
@@ -59,7 +61,8 @@ FREEBASE_TRANSE = Workload("freebase-transe_l2", "transe_l2", 86_054_151, 14_824
                            200, "uniform", "tail", 12.0, 0.1, steps=100_000)
 FREEBASE_COMPLEX = FREEBASE_TRANSE.scaled(name="freebase-complex", model="complex")
 
-ALL = {w.name: w for w in (TINY, SMALL_DISTMULT, SMALL_COMPLEX, MEDIUM, LARGE, FREEBASE_TRANSE, FREEBASE_COMPLEX)}
+ALL = {w.name: w for w in (TINY, SMALL_DISTMULT, SMALL_COMPLEX, SMALL_RESCAL, MEDIUM, LARGE, FREEBASE_TRANSE,
+                           FREEBASE_COMPLEX)}
 
 
 class BatchStream:

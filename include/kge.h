@@ -38,7 +38,8 @@ typedef enum {
     KGE_TRANSE_L1 = 1,
     KGE_DISTMULT = 2,
     KGE_COMPLEX = 3,
-    KGE_ROTATE = 4
+    KGE_ROTATE = 4,
+    KGE_RESCAL = 5 /* h^T M_r t: a relation row is the ent_dim x ent_dim matrix M_r, row by row */
 } kge_model;
 
 /* Which entity of each positive is replaced to form its negatives (Sec. 2: only entities are corrupted). */
@@ -66,7 +67,8 @@ typedef struct {
     int64_t num_entities;      /* rows of the entity table   (< 2^32)                                     */
     int64_t num_relations;     /* rows of the relation table (< 2^32)                                     */
     int32_t ent_dim;           /* floats per entity row: multiple of 4 (8 for ComplEx / RotatE), <= 1024  */
-    int32_t rel_dim;           /* floats per relation row: ent_dim, or ent_dim/2 for RotatE               */
+    int32_t rel_dim;           /* floats per relation row: ent_dim; ent_dim/2 for RotatE; ent_dim^2 for   */
+                               /* RESCAL                                                                  */
     int32_t max_batch;         /* largest b a call may pass                                               */
     int32_t max_neg_per_chunk; /* largest k                                                               */
     int32_t max_chunks;        /* largest b / chunk                                                       */
@@ -173,7 +175,9 @@ enum {
     KGE_PROF_CHAIN = 4,    /* chain rule to head / tail / relation rows */
     KGE_PROF_SORT = 5,     /* (id, position) sort, on its own stream    */
     KGE_PROF_UPDATE = 6,   /* segment sum + sparse Adagrad              */
-    KGE_PROF_SLOTS = 7
+    KGE_PROF_PHI = 7,      /* RESCAL: o = M_r^T h or M_r t              */
+    KGE_PROF_REL_UPDATE = 8, /* RESCAL: update of the relation matrices */
+    KGE_PROF_SLOTS = 9
 };
 int kge_profile(kge_ctx* ctx, int32_t enable);
 int kge_profile_read(kge_ctx* ctx, double* ms_out, int64_t* steps_out);

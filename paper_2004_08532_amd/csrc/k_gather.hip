@@ -189,7 +189,15 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
     for (int it = 0; it < NV; ++it) {
         const int v = lane + it * 64;
         if (v >= nvec) continue;
-        if constexpr (!CPLX) {
+        if constexpr (MODEL == KGE_RESCAL) {
+            // o_i = M_r^T h or M_r t is already in staging (k_rescal); the positive's score is o . c
+            const float4 Oo = ld4(po + 4 * v), Cc = ld4(pc + 4 * v);
+            acc += Oo.x * Cc.x + Oo.y * Cc.y + Oo.z * Cc.z + Oo.w * Cc.w;
+            if (a.bf16) {
+                const float n0 = round_bf16(Oo.x), n1 = round_bf16(Oo.y), n2 = round_bf16(Oo.z), n3 = round_bf16(Oo.w);
+                on += n0 * n0 + n1 * n1 + n2 * n2 + n3 * n3;
+            }
+        } else if constexpr (!CPLX) {
             const float4 A = ld4(pa + 4 * v), Rr = ld4(pr + 4 * v), Cc = ld4(pc + 4 * v);
             const float av[4] = {A.x, A.y, A.z, A.w}, rv[4] = {Rr.x, Rr.y, Rr.z, Rr.w}, cv[4] = {Cc.x, Cc.y, Cc.z, Cc.w};
             float ov[4];
@@ -301,6 +309,7 @@ void launch_model(kge_ctx* c, GatherArgs& a, int nv, int rows, bool with_keys, c
     case KGE_TRANSE_L1: launch_nv<KGE_TRANSE_L1, THREADS>(c, a, nv, grid, lds, st); break;
     case KGE_DISTMULT: launch_nv<KGE_DISTMULT, THREADS>(c, a, nv, grid, lds, st); break;
     case KGE_COMPLEX: launch_nv<KGE_COMPLEX, THREADS>(c, a, nv, grid, lds, st); break;
+    case KGE_RESCAL: launch_nv<KGE_RESCAL, THREADS>(c, a, nv, grid, lds, st); break;
     default: launch_nv<KGE_ROTATE, THREADS>(c, a, nv, grid, lds, st); break;
     }
 }

@@ -42,19 +42,6 @@ struct UpdateArgs {
 
 __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 
-// S += g^2 ; x -= lr * g / (sqrt(S) + eps), with the hardware square root and reciprocal (1 ulp each): the update
-// is a step of size <= lr, so their 1e-7 relative error is far below the accuracy of g itself.
-__device__ __forceinline__ float adagrad1(float g, float& s, float lr, float eps) {
-    s = fmaf(g, g, s);
-    return lr * g * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(s) + eps);
-}
-__device__ __forceinline__ void adagrad4(float4 g, float4& x, float4& s, float lr, float eps) {
-    x.x -= adagrad1(g.x, s.x, lr, eps);
-    x.y -= adagrad1(g.y, s.y, lr, eps);
-    x.z -= adagrad1(g.z, s.z, lr, eps);
-    x.w -= adagrad1(g.w, s.w, lr, eps);
-}
-
 // Workgroup barrier that orders LDS traffic only: global loads that are still in flight stay in flight across it.
 __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -273,8 +260,9 @@ void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, con
     a.G[0] = c->Gent; a.G[1] = c->Grel;
     a.key[0] = c->ekey[c->ebuf]; a.key[1] = c->rkey[c->rbuf];
     a.pos[0] = c->epos[c->ebuf]; a.pos[1] = c->rpos[c->rbuf];
-    a.n[0] = n_ent_keys; a.n[1] = n_rel_keys;
-    a.tiles[0] = (n_ent_keys + TILE_R - 1) / TILE_R; a.tiles[1] = (n_rel_keys + TILE_R - 1) / TILE_R;
+    // (RESCAL's relation rows are D x D matrices whose gradients are never materialised: k_rescal_update)
+    a.n[0] = n_ent_keys; a.n[1] = c->cfg.model == KGE_RESCAL ? 0 : n_rel_keys;
+    a.tiles[0] = (n_ent_keys + TILE_R - 1) / TILE_R; a.tiles[1] = (a.n[1] + TILE_R - 1) / TILE_R;
     a.D[0] = c->cfg.ent_dim; a.D[1] = c->cfg.rel_dim;
     a.lr = lr; a.eps = c->eps; a.row_loss = c->row_loss; a.b = b; a.loss_out = loss_out;
     a.neg_loss_part = c->neg_loss_part; a.n_loss_parts = n_loss_parts;

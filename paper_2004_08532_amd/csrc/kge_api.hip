@@ -24,7 +24,7 @@ int fail(kge_ctx* c, int code, const char* fmt, const char* detail = "") {
         if (e_ != hipSuccess) return fail((c), KGE_ERR_DEVICE, #call ": %s", hipGetErrorString(e_)); \
     } while (0)
 
-bool is_gemm_model(int m) { return m == KGE_TRANSE_L2 || m == KGE_DISTMULT || m == KGE_COMPLEX; }
+bool is_gemm_model(int m) { return m == KGE_TRANSE_L2 || m == KGE_DISTMULT || m == KGE_COMPLEX || m == KGE_RESCAL; }
 
 __global__ void k_validate(StepIds ids, int64_t n_ent, int64_t n_rel, int* flag) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -67,6 +67,7 @@ int check_batch(kge_ctx* c, const void* ent, const void* rel, const int64_t* h, 
 void forward(kge_ctx* c, const float* ent, const float* rel, const StepIds& ids, int k, int chunk, float gamma,
              float* pos_out, float* neg_out, int ld_out, int dist_mode, hipStream_t st) {
     if (c->cfg.validate_indices) launch_validate(c, ids, st);
+    if (c->cfg.model == KGE_RESCAL) kge_launch_rescal_phi(c, ent, rel, ids, st);
     kge_launch_gather(c, ent, rel, ids, gamma, pos_out, false, st);
     if (neg_out && k > 0) {
         if (is_gemm_model(c->cfg.model)) kge_gemm_neg_score(c, ids.b, k, chunk, gamma, neg_out, ld_out, dist_mode, st);
@@ -101,6 +102,10 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
         KGE_HIP(c, hipEventRecord(c->ev_join, c->side_stream));
     }
     if (c->cfg.validate_indices) launch_validate(c, ids, st);
+    if (c->cfg.model == KGE_RESCAL) {
+        ProfScope p(c, KGE_PROF_PHI);
+        kge_launch_rescal_phi(c, ent, rel, ids, st);
+    }
     {
         ProfScope p(c, KGE_PROF_GATHER);
         kge_launch_gather(c, ent, rel, ids, gamma, nullptr, !long_lists, st);
@@ -128,9 +133,14 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
     }
     if (run_chain) {
         ProfScope p(c, KGE_PROF_CHAIN);
-        kge_launch_chain(c, ent, rel, ids, st);
+        if (c->cfg.model == KGE_RESCAL) kge_launch_rescal_chain(c, ent, rel, ids, st);
+        else kge_launch_chain(c, ent, rel, ids, st);
     }
     if (long_lists) KGE_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
+    if (c->cfg.model == KGE_RESCAL) {
+        ProfScope p(c, KGE_PROF_REL_UPDATE);
+        kge_launch_rescal_update(c, rel, rel_state, ids, lr, st);
+    }
     {
         ProfScope p(c, KGE_PROF_UPDATE);
         kge_launch_update(c, ent, ent_state, rel, rel_state, ids, lr, n_loss_parts, st);
@@ -141,7 +151,7 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
         for (int s = 0; s < KGE_PROF_SLOTS; ++s) {
             float ms = 0.f;
             if ((s == KGE_PROF_SORT && !long_lists) || (s == KGE_PROF_LOSS && !run_loss) ||
-                (s == KGE_PROF_CHAIN && !run_chain))
+                (s == KGE_PROF_CHAIN && !run_chain) || ((s == KGE_PROF_PHI || s == KGE_PROF_REL_UPDATE) && c->cfg.model != KGE_RESCAL))
                 continue;  // that kernel did not run in this configuration
             if (hipEventElapsedTime(&ms, c->prof_ev[s][0], c->prof_ev[s][1]) == hipSuccess) c->prof_ms[s] += ms;
         }
@@ -205,12 +215,14 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     if (!cfg || !out) return fail(nullptr, KGE_ERR_INVALID_ARG, "null argument%s");
     *out = nullptr;
     const int m = cfg->model;
-    if (m < KGE_TRANSE_L2 || m > KGE_ROTATE) return fail(nullptr, KGE_ERR_INVALID_ARG, "unknown model%s");
+    if (m < KGE_TRANSE_L2 || m > KGE_RESCAL) return fail(nullptr, KGE_ERR_INVALID_ARG, "unknown model%s");
     const bool cplx = m == KGE_COMPLEX || m == KGE_ROTATE;
     if (cfg->ent_dim <= 0 || cfg->ent_dim > 1024 || cfg->ent_dim % (cplx ? 8 : 4) != 0)
         return fail(nullptr, KGE_ERR_INVALID_ARG, "ent_dim must be a multiple of 4 (8 for ComplEx/RotatE), at most 1024%s");
-    if (cfg->rel_dim != (m == KGE_ROTATE ? cfg->ent_dim / 2 : cfg->ent_dim))
-        return fail(nullptr, KGE_ERR_INVALID_ARG, "rel_dim must be ent_dim (ent_dim/2 for RotatE)%s");
+    if (cfg->rel_dim != (m == KGE_ROTATE ? cfg->ent_dim / 2 : (m == KGE_RESCAL ? cfg->ent_dim * cfg->ent_dim : cfg->ent_dim)))
+        return fail(nullptr, KGE_ERR_INVALID_ARG, "rel_dim must be ent_dim (ent_dim/2 for RotatE, ent_dim^2 for RESCAL)%s");
+    if (m == KGE_RESCAL && (cfg->adagrad_mode != 0 || cfg->gemm_input != 0))
+        return fail(nullptr, KGE_ERR_UNSUPPORTED, "RESCAL runs with element-wise Adagrad state and fp32 operands only%s");
     if (cfg->num_entities <= 0 || cfg->num_relations <= 0 || cfg->num_entities >= (1ll << 32) ||
         cfg->num_relations >= (1ll << 32))
         return fail(nullptr, KGE_ERR_INVALID_ARG, "table row counts must be in [1, 2^32)%s");
@@ -220,7 +232,6 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
         return fail(nullptr, KGE_ERR_INVALID_ARG, "more than 2^24 entity keys per step%s");
     if (cfg->adagrad_mode != 0 && cfg->adagrad_mode != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "adagrad_mode must be 0 or 1%s");
     if (cfg->loss != KGE_LOSS_LOGISTIC && cfg->loss != KGE_LOSS_RANKING) return fail(nullptr, KGE_ERR_INVALID_ARG, "loss must be 0 (logistic) or 1 (ranking)%s");
-    if (cfg->gemm_input != 0 && cfg->gemm_input != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "gemm_input must be 0 or 1%s");
     if (cfg->gemm_input != 0 && cfg->gemm_input != 1) return fail(nullptr, KGE_ERR_INVALID_ARG, "gemm_input must be 0 or 1%s");
     if (cfg->gemm_input == 1 && !is_gemm_model(cfg->model))
         return fail(nullptr, KGE_ERR_UNSUPPORTED, "bf16 operands exist for the matrix-product models only (TransE-L2, DistMult, ComplEx)%s");
@@ -246,7 +257,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
     const size_t o_O = take(B * D * 4), o_N = take(NR * D * 4), o_S = take(B * c->ld_s * 4), o_GO = take(B * D * 4);
-    const size_t o_Ge = take(EK * D * 4), o_Gr = take(B * Dr * 4);
+    const size_t o_Ge = take(EK * D * 4), o_Gr = take(B * (m == KGE_RESCAL ? 2 * D : Dr) * 4);  // RESCAL keeps two factor rows per positive
     const size_t o_fpos = take(B * 4), o_on2 = take(B * 4), o_nn2 = take(NR * 4), o_cpos = take(B * 4);
     const size_t o_rl = take(B * 4), o_wrs = take(B * 4), o_idp = take(B * 4);
     const size_t o_nlp = take((B / 32 + cfg->max_chunks + 1) * ((size_t)cfg->max_neg_per_chunk / 32 + 1) * 4);
@@ -493,7 +504,7 @@ int kge_profile_read(kge_ctx* c, double* ms_out, int64_t* steps_out) {
 }
 
 const char* kge_profile_slot_name(int32_t slot) {
-    static const char* names[KGE_PROF_SLOTS] = {"gather", "neg_score", "loss", "neg_backward", "chain", "sort", "update"};
+    static const char* names[KGE_PROF_SLOTS] = {"gather", "neg_score", "loss", "neg_backward", "chain", "sort", "update", "phi", "rel_update"};
     return slot >= 0 && slot < KGE_PROF_SLOTS ? names[slot] : "";
 }
 

@@ -135,6 +135,11 @@ int kge_gemm_loss_parts(const kge_ctx* c, int b, int k, int g);  // loss sums th
 void kge_pair_neg_backward(kge_ctx* c, int b, int k, int g, hipStream_t st);
 // a5: positive-pair term and chain rule through phi -> gradient rows of heads, tails and relations
 void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
+// RESCAL: o_i from the kept entity and the relation's matrix (before the gather launch); chain rule through it
+void kge_launch_rescal_phi(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
+void kge_launch_rescal_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
+// RESCAL, a7 for the relation matrices: gradient of a distinct relation formed from the factor rows, then Adagrad
+void kge_launch_rescal_update(kge_ctx* c, float* R, float* SR, const StepIds& ids, float lr, hipStream_t st);
 // a6: sort (id, position) of the entity and relation key lists
 void kge_launch_sort(kge_ctx* c, const StepIds& ids, hipStream_t st);
 // a7: per distinct row, sum its gradient rows and apply Adagrad; also reduces the loss terms
@@ -201,6 +206,19 @@ __device__ __forceinline__ float wave_max(float v) {
 __device__ __forceinline__ float4 ld4(const float* p) { return *reinterpret_cast<const float4*>(p); }
 __device__ __forceinline__ void st4(float* p, float4 v) { *reinterpret_cast<float4*>(p) = v; }
 __device__ __forceinline__ float4 f4(float x) { return make_float4(x, x, x, x); }
+
+// Adagrad: S += g^2 ; x -= lr * g / (sqrt(S) + eps), with the hardware square root and reciprocal (1 ulp each): the
+// update is a step of size <= lr, so their 1e-7 relative error is far below the accuracy of g itself.
+__device__ __forceinline__ float adagrad1(float g, float& s, float lr, float eps) {
+    s = fmaf(g, g, s);
+    return lr * g * __builtin_amdgcn_rcpf(__builtin_amdgcn_sqrtf(s) + eps);
+}
+__device__ __forceinline__ void adagrad4(float4 g, float4& x, float4& s, float lr, float eps) {
+    x.x -= adagrad1(g.x, s.x, lr, eps);
+    x.y -= adagrad1(g.y, s.y, lr, eps);
+    x.z -= adagrad1(g.z, s.z, lr, eps);
+    x.w -= adagrad1(g.w, s.w, lr, eps);
+}
 
 // fp32 -> bf16 -> fp32, round to nearest even (the hardware conversion of gfx950)
 __device__ __forceinline__ float round_bf16(float x) { return (float)(__bf16)x; }

@@ -9,7 +9,7 @@ from parity_util import EMB_TOL, SCORE_TOL, Pair, dev, rel_err
 
 pytestmark = pytest.mark.gpu
 
-MODELS = ["transe_l2", "transe_l1", "distmult", "complex", "rotate"]
+MODELS = ["transe_l2", "transe_l1", "distmult", "complex", "rotate", "rescal"]
 
 
 @pytest.fixture(scope="module")
@@ -22,7 +22,7 @@ def ragged(model, **kw):
     """A small workload whose sizes are multiples of nothing convenient: several 32x32 tiles with ragged tails
     in every dimension, k not a multiple of 4, rows of 72 floats (a ragged K-block)."""
     base = dict(name="ragged-" + model, model=model, n_entities=517, n_relations=11, n_triples=4000, s_entity=1.0,
-                s_relation=None, ent_dim=72, rel_dim=36 if model == "rotate" else 72, batch=90, chunk=45,
+                s_relation=None, ent_dim=72, rel_dim={"rotate": 36, "rescal": 72 * 72}.get(model, 72), batch=90, chunk=45,
                 neg_per_chunk=37, neg_mode="uniform", side_mode="alternate", gamma=6.0, lr=0.1, steps=4, seed=5)
     base.update(kw)
     return configs.Workload(**base)
@@ -87,7 +87,8 @@ def test_ragged_shapes_every_model(kge, model, alpha):
 
 # margins at which roughly half of the (positive, negative) pairs of the ragged workload are active at its
 # initialisation (score differences there: ~0.1 for the distance models, ~1e-3 for the products)
-RANKING_MARGIN = {"transe_l2": 0.03, "transe_l1": 0.3, "distmult": 3e-4, "complex": 3e-4, "rotate": 0.3}
+RANKING_MARGIN = {"transe_l2": 0.03, "transe_l1": 0.3, "distmult": 3e-4, "complex": 3e-4, "rotate": 0.3,
+                  "rescal": 2e-3}
 
 
 @pytest.mark.parametrize("alpha", [0.0, 1.0])
@@ -113,6 +114,17 @@ def test_pairwise_ranking_loss_bf16_operands(kge):
     w = ragged("transe_l2", loss="ranking", gamma=RANKING_MARGIN["transe_l2"], bf16_inputs=True)
     E, R = configs.init_tables(w.scaled(gamma=6.0))
     p = Pair(w, kge, E=E, R=R)
+    try:
+        run_steps(p, configs.BatchStream(w), w.steps)
+    finally:
+        p.close()
+
+
+def test_rescal_relations_that_fill_half_of_the_batch(kge):
+    """Two relations over 640 positives: the runs of equal relation ids are longer than one look-back round of the
+    matrix update (256 entries), and every positive's matrix gradient (an outer product) lands in one of two rows."""
+    w = ragged("rescal", n_relations=2, ent_dim=64, rel_dim=64 * 64, batch=640, chunk=64, neg_per_chunk=32, steps=2)
+    p = Pair(w, kge)
     try:
         run_steps(p, configs.BatchStream(w), w.steps)
     finally:
