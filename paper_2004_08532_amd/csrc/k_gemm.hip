@@ -27,69 +27,13 @@
 //   * for TransE-L2 and DistMult the chain rule from dL/do to the head, tail and relation gradient rows is
 //     elementwise, so the dO epilogue writes those rows directly (no dL/do array, no separate chain kernel);
 //     the rows it needs for that are fetched before the K loop starts.
-#include "kge_common.h"
+#include "k_gemm_shared.h"
 
 namespace {
-
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
-enum { EPI_PLAIN = 0, EPI_L2_FWD = 1, EPI_L2_DO = 2, EPI_L2_DN = 3, EPI_CHAIN_L2 = 4, EPI_CHAIN_DM = 5 };
-enum { OUT_SCORE = 0, OUT_DIST = 1, OUT_W = 2 };  // what the forward launch stores (see kge_gemm_neg_score)
-
-struct GemmArgs {
-    const float* A;
-    const float* B;
-    float* C;
-    int M, N, K;
-    int lda, ldb, ldc;
-    int64_t sA, sB, sC;  // chunk strides (floats)
-    const float* rowv;   // EPI_L2_FWD: |o|^2 per row (chunk stride s_rowv)
-    const float* colv;   // EPI_L2_FWD: |n|^2 per column (chunk stride s_colv)
-    int64_t s_rowv, s_colv;
-    const float* X;      // [M x ldx] operand of the TransE-L2 correction term (o rows for dO, n rows for dN)
-    int ldx;
-    int64_t sX;
-    float gamma;
-    int out_mode;        // forward: OUT_SCORE, OUT_DIST (TransE-L2: the distance) or OUT_W (backward coefficients)
-    int gx, gy, tiles;   // tiles along N, along M, and in total (over all chunks); set by the launchers
-    // A-operand transform (uniform negative weights): W = wk * sigmoid(f) [/ distance]
-    float wk;            // 1 / (k b)
-    float* neg_loss_part;  // [forward tiles] OUT_W: sum of wk * softplus(f-) over the tile
-    // chain-rule epilogues
-    StepIds ids;
-    const float* E;
-    const float* R;
-    const float* cpos;
-    const float* inv_dpos;
-    float* Gent;
-    float* Grel;
-    int b, D;
-    int64_t n_ent, n_rel;
-};
 
 constexpr int TILE = 32;
 constexpr int KC_PITCH = 36;                 // floats; 16-byte aligned rows, conflict-free 128-bit reads
 constexpr int REGION = TILE * KC_PITCH;      // floats per staged operand block
-
-__device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
-
-// Backward coefficient of a negative score f with uniform weight wk: wk * sigmoid(f) = d/df [wk softplus(f)];
-// adds softplus(f) to loss.  Runs once per score, in the forward epilogue.  FAST: the hardware exp2 / log2 /
-// reciprocal (1 ulp each; about 1e-6 relative in W, the size of the rounding of the fp32 products W goes into).
-// With bf16 operands W is rounded to bf16 afterwards, and which neighbour a value rounds to should not hinge on
-// those last bits, so that path uses the accurate functions.
-template <bool FAST>
-__device__ __forceinline__ float w_and_loss(float f, float wk, float& loss) {
-    if (FAST) {
-        const float e = __builtin_amdgcn_exp2f(-fabsf(f) * 1.4426950408889634f);  // exp(-|f|) in (0, 1]
-        loss += fmaxf(f, 0.f) + __builtin_amdgcn_logf(1.f + e) * 0.6931471805599453f;
-        return wk * ((f >= 0.f ? 1.f : e) * __builtin_amdgcn_rcpf(1.f + e));
-    }
-    const float e = expf(-fabsf(f));
-    loss += fmaxf(f, 0.f) + log1pf(e);
-    return wk * ((f >= 0.f ? 1.f : e) / (1.f + e));
-}
 
 // Loads 32x32 blocks of one operand into registers (zero-filled outside the matrix).  The per-lane row pointers
 // and edge masks are set up once.  Loads are branch-free: the four loads of a block are issued unconditionally
@@ -184,30 +128,8 @@ __device__ __forceinline__ void lds_frag(const float* region, int lane, int q, f
     }
 }
 
-// bf16 operands: the eight K-values a lane feeds to MFMA m = 0, 1 of a 32-wide K block:
-// kk = 16 m + 8 * (lane / 32) + 0..7, for row lane % 32.
-template <bool KC>
-__device__ __forceinline__ void lds_frag8(const float* region, int lane, int m, float (&f)[8]) {
-    const int rw = lane & 31, kk = 16 * m + 8 * (lane >> 5);
-    if (KC) {
-        const float4 u = ld4(region + rw * KC_PITCH + kk), v = ld4(region + rw * KC_PITCH + kk + 4);
-        f[0] = u.x; f[1] = u.y; f[2] = u.z; f[3] = u.w; f[4] = v.x; f[5] = v.y; f[6] = v.z; f[7] = v.w;
-    } else {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) f[t] = region[(kk + t) * TILE + rw];
-    }
-}
-
-// Workgroups are handed to the 8 XCDs round-robin by linear id, and every XCD has its own L2.  Each XCD gets a
-// contiguous range of tiles (row-major, column tiles fastest), so the tiles that share an A row-block run on one
-// XCD and re-read it from that L2 instead of from memory.  q = index of the workgroup within its XCD.
-__device__ __forceinline__ int xcd_tile(int q, int per_xcd) { return (blockIdx.x & 7) * per_xcd + q; }
-
 // One 32x32 output tile: K loop, cross-wave sum, epilogue.
-// BF: both operands are rounded to bf16 on their way from LDS to the matrix unit (after the W transform, so W is
-// rounded too) and multiplied by v_mfma_f32_32x32x16_bf16 with fp32 accumulation; the TransE-L2 correction terms
-// then use the rounded o / n rows and the sums of the rounded W.
-template <int NW, bool A_KC, bool B_KC, int EPI, bool IS_DO, bool BF>
+template <int NW, bool A_KC, bool B_KC, int EPI, bool IS_DO>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*lds)[2][REGION]) {
     constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM;
     constexpr bool WANT_ASUM = EPI == EPI_L2_DO || EPI == EPI_L2_DN || EPI == EPI_CHAIN_L2;
@@ -278,32 +200,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        if (BF) {
 #pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                float fa[8], fb[8];
-                lds_frag8<A_KC>(As, lane, m, fa);
-                lds_frag8<B_KC>(Bs, lane, m, fb);
-                bf16x8 pa, pb;
+        for (int q = 0; q < 4; ++q) {
+            float fa[4], fb[4];
+            lds_frag<A_KC>(As, lane, q, fa);
+            lds_frag<B_KC>(Bs, lane, q, fb);
 #pragma unroll
-                for (int t = 0; t < 8; ++t) { pa[t] = (__bf16)fa[t]; pb[t] = (__bf16)fb[t]; }
-                if (WANT_ASUM) {
-#pragma unroll
-                    for (int t = 0; t < 8; ++t) a_sum += (float)pa[t];
-                }
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, pb, acc, 0, 0, 0);
-            }
-        } else {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                float fa[4], fb[4];
-                lds_frag<A_KC>(As, lane, q, fa);
-                lds_frag<B_KC>(Bs, lane, q, fb);
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[t], fb[t], acc, 0, 0, 0);
-                    if (WANT_ASUM) a_sum += fa[t];
-                }
+            for (int t = 0; t < 4; ++t) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[t], fb[t], acc, 0, 0, 0);
+                if (WANT_ASUM) a_sum += fa[t];
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -340,23 +245,23 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             for (int ww = 0; ww < NW; ++ww) rs += lds[ww][1][i];
         }
         if (EPI == EPI_PLAIN) {
-            C[(int64_t)gm * g.ldc + gn] = (IS_FWD && g.out_mode == OUT_W) ? w_and_loss<!BF>(s, g.wk, loss) : s;
+            C[(int64_t)gm * g.ldc + gn] = (IS_FWD && g.out_mode == OUT_W) ? w_and_loss<true>(s, g.wk, loss) : s;
         } else if (EPI == EPI_L2_FWD) {
             const float d2 = g.rowv[c * g.s_rowv + gm] + g.colv[c * g.s_colv + gn] - 2.f * s;
             const float d = sqrtf(fmaxf(d2, 0.f));
             float out = g.out_mode == OUT_DIST ? d : g.gamma - d;
             if (g.out_mode == OUT_W) {  // W = w sigmoid(f) / |o - n|, 0 where the distance is 0
-                const float coef = w_and_loss<!BF>(g.gamma - d, g.wk, loss);
-                out = d > 0.f ? (BF ? coef / d : coef * __builtin_amdgcn_rcpf(d)) : 0.f;
+                const float coef = w_and_loss<true>(g.gamma - d, g.wk, loss);
+                out = d > 0.f ? coef * __builtin_amdgcn_rcpf(d) : 0.f;
             }
             C[(int64_t)gm * g.ldc + gn] = out;
         } else if (EPI == EPI_L2_DO || EPI == EPI_L2_DN) {
             const float xv = g.X[c * g.sX + (int64_t)gm * g.ldx + gn];
-            C[(int64_t)gm * g.ldc + gn] = s - rs * (BF ? round_bf16(xv) : xv);
+            C[(int64_t)gm * g.ldc + gn] = s - rs * xv;
         } else if (EPI == EPI_CHAIN_L2) {
             // dL/do = W n - rowsum(W) o  +  dL/df+ * d(gamma - |o - c|)/do
             const float dir = (e_o[it] - e_c[it]) * e_inv[it];
-            const float go = s - rs * (BF ? round_bf16(e_o[it]) : e_o[it]) - e_cp[it] * dir;
+            const float go = s - rs * e_o[it] - e_cp[it] * dir;
             g.Gent[(int64_t)(e_head ? g.b + bi : bi) * g.D + gn] = go;
             g.Gent[(int64_t)(e_head ? bi : g.b + bi) * g.D + gn] = e_cp[it] * dir;
             g.Grel[(int64_t)bi * g.D + gn] = e_head ? -go : go;
@@ -382,27 +287,27 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     }
 }
 
-template <int NW, int EPI, bool BF>
+template <int NW, int EPI>
 __global__ __launch_bounds__(NW * 64) void k_gemm_fwd(GemmArgs g) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
     const int tile = xcd_tile(blockIdx.x >> 3, gridDim.x >> 3);
     if (tile >= g.tiles) return;
-    gemm_tile<NW, true, true, EPI, false, BF>(g, tile, lds);
+    gemm_tile<NW, true, true, EPI, false>(g, tile, lds);
 }
 
 // dN tiles first (their K is the chunk size, they run longest), then dO tiles; each XCD gets its share of both.
 // Held to 128 registers so that four waves fit on every SIMD (two 8-wave workgroups per CU): all tiles of the
 // Freebase-scale step are then resident at once instead of running in two rounds.
-template <int NW, int EPI_O, int EPI_N, bool BF>
+template <int NW, int EPI_O, int EPI_N>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_gemm_bwd(GemmArgs gO, GemmArgs gN, int per_xcd_n, int per_xcd_o) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
     const int q = blockIdx.x >> 3;
     if (q < per_xcd_n) {
         const int tile = xcd_tile(q, per_xcd_n);
-        if (tile < gN.tiles) gemm_tile<NW, false, false, EPI_N, false, BF>(gN, tile, lds);
+        if (tile < gN.tiles) gemm_tile<NW, false, false, EPI_N, false>(gN, tile, lds);
     } else {
         const int tile = xcd_tile(q - per_xcd_n, per_xcd_o);
-        if (tile < gO.tiles) gemm_tile<NW, true, false, EPI_O, true, BF>(gO, tile, lds);
+        if (tile < gO.tiles) gemm_tile<NW, true, false, EPI_O, true>(gO, tile, lds);
     }
 }
 
@@ -421,17 +326,17 @@ void set_tiling(GemmArgs& g, int chunks) {
     g.tiles = g.gx * g.gy * chunks;
 }
 
-template <int EPI, bool BF>
+template <int EPI>
 void launch_fwd(kge_ctx* c, GemmArgs g, int chunks, hipStream_t st) {
     set_tiling(g, chunks);
     const dim3 grid(8 * ((g.tiles + 7) / 8));
     const int nw = pick_nw(g.tiles, (g.K + TILE - 1) / TILE, 16);
-    if (nw == 4) KGE_LAUNCH(c, (k_gemm_fwd<4, EPI, BF>), grid, dim3(256), 0, st, g);
-    else if (nw == 8) KGE_LAUNCH(c, (k_gemm_fwd<8, EPI, BF>), grid, dim3(512), 0, st, g);
-    else KGE_LAUNCH(c, (k_gemm_fwd<16, EPI, BF>), grid, dim3(1024), 0, st, g);
+    if (nw == 4) KGE_LAUNCH(c, (k_gemm_fwd<4, EPI>), grid, dim3(256), 0, st, g);
+    else if (nw == 8) KGE_LAUNCH(c, (k_gemm_fwd<8, EPI>), grid, dim3(512), 0, st, g);
+    else KGE_LAUNCH(c, (k_gemm_fwd<16, EPI>), grid, dim3(1024), 0, st, g);
 }
 
-template <int EPI_O, int EPI_N, bool BF>
+template <int EPI_O, int EPI_N>
 void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st) {
     set_tiling(gO, chunks);
     set_tiling(gN, chunks);
@@ -440,8 +345,8 @@ void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st
     const int nblk = ((gO.K > gN.K ? gO.K : gN.K) + TILE - 1) / TILE;
     // at most 8 waves: 74 KB of LDS per workgroup, so two workgroups share a CU
     const int nw = pick_nw(gO.tiles + gN.tiles, nblk, 8);
-    if (nw == 4) KGE_LAUNCH(c, (k_gemm_bwd<4, EPI_O, EPI_N, BF>), grid, dim3(256), 0, st, gO, gN, per_n, per_o);
-    else KGE_LAUNCH(c, (k_gemm_bwd<8, EPI_O, EPI_N, BF>), grid, dim3(512), 0, st, gO, gN, per_n, per_o);
+    if (nw == 4) KGE_LAUNCH(c, (k_gemm_bwd<4, EPI_O, EPI_N>), grid, dim3(256), 0, st, gO, gN, per_n, per_o);
+    else KGE_LAUNCH(c, (k_gemm_bwd<8, EPI_O, EPI_N>), grid, dim3(512), 0, st, gO, gN, per_n, per_o);
 }
 
 }  // namespace
@@ -462,13 +367,10 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     g.wk = 1.f / ((float)k * (float)b); g.neg_loss_part = c->neg_loss_part;
     const int chunks = b / gsz;
     const bool bf = c->cfg.gemm_input == 1;
-    if (c->cfg.model == KGE_TRANSE_L2) {
-        if (bf) launch_fwd<EPI_L2_FWD, true>(c, g, chunks, st);
-        else launch_fwd<EPI_L2_FWD, false>(c, g, chunks, st);
-    } else {
-        if (bf) launch_fwd<EPI_PLAIN, true>(c, g, chunks, st);
-        else launch_fwd<EPI_PLAIN, false>(c, g, chunks, st);
-    }
+    const int epi = c->cfg.model == KGE_TRANSE_L2 ? EPI_L2_FWD : EPI_PLAIN;
+    if (bf) kge_gemm_bf_forward(c, &g, epi, chunks, st);
+    else if (epi == EPI_L2_FWD) launch_fwd<EPI_L2_FWD>(c, g, chunks, st);
+    else launch_fwd<EPI_PLAIN>(c, g, chunks, st);
 }
 
 // Logistic loss with uniform negative weights: the forward launch stores W and the loss sums, and no loss kernel
@@ -510,10 +412,10 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
     q.X = c->Nst; q.ldx = D; q.sX = (int64_t)k * D;
 
     const bool bf = c->cfg.gemm_input == 1;
-#define KGE_BWD(EO, EN)                                           \
-    do {                                                          \
-        if (bf) launch_bwd<EO, EN, true>(c, g, q, chunks, st);    \
-        else launch_bwd<EO, EN, false>(c, g, q, chunks, st);      \
+#define KGE_BWD(EO, EN)                                                     \
+    do {                                                                    \
+        if (bf) kge_gemm_bf_backward(c, &g, &q, EO, EN, chunks, st);        \
+        else launch_bwd<EO, EN>(c, g, q, chunks, st);                \
     } while (0)
     if (model == KGE_TRANSE_L2) KGE_BWD(EPI_CHAIN_L2, EPI_L2_DN);
     else if (model == KGE_DISTMULT) KGE_BWD(EPI_CHAIN_DM, EPI_PLAIN);

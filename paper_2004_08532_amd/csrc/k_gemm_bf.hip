@@ -1,0 +1,303 @@
+// The chunked negative-scoring products (Sec. 3.3 of the paper) and their backward with bf16 operands and fp32
+// accumulation: S_c = O_c N_c^T, dO_c = W_c N_c, dN_c = W_c^T O_c with the same epilogues as the fp32 path.
+//
+// Shapes here are the large ones (thousands of positives and corrupting rows per step), so the limit is not
+// latency but how often an operand row is pulled from L2 into a CU: a 32x32 tile per workgroup re-reads every row
+// once per 32 columns of output.  A workgroup therefore owns a 64x64 output tile over the whole K range (no
+// split over K, no cross-wave sum); its four waves hold one 32x32 quarter each.  Per K block of 64 the 256 threads
+// load the two 64x64 fp32 operand blocks (16-byte loads, the next two blocks in flight while this one is multiplied), round
+// them to bf16 (the hardware's round-to-nearest-even conversion, two values per instruction) and lay them out in LDS
+// K-contiguous, whatever their orientation in memory, so that every v_mfma_f32_32x32x16_bf16 operand is one
+// 16-byte LDS read.  Operands that are stored with K along rows ("MC": N_c in dO, W_c and O_c in dN) are
+// transposed for free on the way: a thread loads the same four columns of two adjacent K rows and packs the
+// pairs.  LDS is double-buffered: one workgroup barrier per K block.
+#include "k_gemm_shared.h"
+
+namespace {
+
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int BT = 64;            // output tile edge
+constexpr int BK = 64;            // K block
+constexpr int PITCH = BK + 8;     // bf16 per LDS row: 144 bytes, an odd multiple of 16 (conflict-free 16-byte reads)
+constexpr int PITCH_W = PITCH / 2;
+constexpr int THREADS = 256;
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ void lds_barrier() {  // orders LDS traffic only: global loads stay in flight across it
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Stages 64 (rows) x 64 (K) blocks of one operand: fp32 in memory -> registers -> bf16 in LDS as [row][k].
+// Element (row, kk) of the operand lies at base[row * ld + kk] (KC) or base[kk * ld + row] (MC).  Everything
+// outside the matrix (rows >= R, kk >= K) becomes 0.  Loads are unconditional, from clamped addresses, and masked
+// afterwards.  16-byte loads may run past R or K up to the next multiple of 4, which the row pitch covers.
+template <bool KC>
+struct Stager {
+    const float* base;
+    const float* p;  // MC: row 0 at the thread's first column
+    const float* pr[4];  // KC: start of the thread's four rows
+    int ld, K, R;
+    int r;           // KC: the first of the thread's four rows in the tile (the others follow at + 16); MC: its first
+                     // row (of 4 consecutive ones)
+    int k;           // KC: first of its 4 K values; MC: first of its two K pairs (2 * kp; the second is 32 + 2 * kp)
+    bool okr[4];
+    // KC: 16 consecutive lanes read 256 consecutive bytes of one row (whole cache lines per request)
+    __device__ __forceinline__ void init(const float* base_, int ld_, int r0, int R_, int K_, int t) {
+        base = base_; ld = ld_; K = K_; R = R_;
+        if (KC) {
+            r = t >> 4;
+            k = 4 * (t & 15);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                okr[q] = r0 + r + 16 * q < R;
+                pr[q] = base + (int64_t)(okr[q] ? r0 + r + 16 * q : 0) * ld;
+            }
+            p = base;
+        } else {
+            r = 4 * (t & 15);
+            k = 2 * (t >> 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) okr[e] = r0 + r + e < R;
+            p = base + (okr[0] ? r0 + r : 0);
+        }
+    }
+    __device__ __forceinline__ void issue(int kb, float4 (&reg)[4]) const {
+        const int k0 = kb * BK + k;
+        if (KC) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) reg[q] = ld4(pr[q] + (k0 < K ? k0 : 0));
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int kk = k0 + (q >> 1) * 32 + (q & 1);
+                reg[q] = ld4(kk < K ? p + (int64_t)kk * ld : base);
+            }
+        }
+    }
+    __device__ __forceinline__ void store(int kb, const float4 (&reg)[4], __bf16* lds) const {
+        const int k0 = kb * BK + k;
+        if (KC) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float v[4] = {reg[q].x, reg[q].y, reg[q].z, reg[q].w};
+                float m[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) m[e] = (okr[q] && k0 + e < K) ? v[e] : 0.f;
+                *reinterpret_cast<uint2*>(lds + (r + 16 * q) * PITCH + k) = make_uint2(pack2(m[0], m[1]), pack2(m[2], m[3]));
+            }
+        } else {
+            uint32_t* l32 = reinterpret_cast<uint32_t*>(lds);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int kk = k0 + 32 * h;
+                const float lo[4] = {reg[2 * h].x, reg[2 * h].y, reg[2 * h].z, reg[2 * h].w};
+                const float hi[4] = {reg[2 * h + 1].x, reg[2 * h + 1].y, reg[2 * h + 1].z, reg[2 * h + 1].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float a = (okr[e] && kk < K) ? lo[e] : 0.f;
+                    const float b = (okr[e] && kk + 1 < K) ? hi[e] : 0.f;
+                    l32[(r + e) * PITCH_W + (k >> 1) + 16 * h] = pack2(a, b);
+                }
+            }
+        }
+    }
+};
+
+// One 64x64 output tile.  EPI as in the fp32 path.  A_KC / B_KC: orientation of the operands in memory.
+template <bool A_KC, bool B_KC, int EPI>
+__device__ __forceinline__ void bf_tile(const GemmArgs& g, int tile, __bf16 (*lds)[2][BT * PITCH]) {
+    constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM;
+    constexpr bool WANT_ASUM = EPI == EPI_L2_DO || EPI == EPI_L2_DN || EPI == EPI_CHAIN_L2;
+    constexpr bool IS_FWD = A_KC && B_KC;
+    const int t = threadIdx.x, w = t >> 6, lane = t & 63;
+    const int n0 = (tile % g.gx) * BT, mt = (tile / g.gx) % g.gy, m0 = mt * BT, c = tile / (g.gx * g.gy);
+    const float* A = g.A + c * g.sA;
+    const float* B = g.B + c * g.sB;
+    const int wm = 32 * (w >> 1), wn = 32 * (w & 1);  // this wave's quarter of the tile
+
+    floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    float a_sum = 0.f;  // sum over K of the rounded A[row wm + lane % 32][.], this lane's half of the K values
+
+    Stager<A_KC> sa;
+    Stager<B_KC> sb;
+    sa.init(A, g.lda, m0, g.M, g.K, t);
+    sb.init(B, g.ldb, n0, g.N, g.K, t);
+    const int nblk = (g.K + BK - 1) / BK, last = nblk - 1;
+    // Two K blocks of loads are in flight: while block kb is multiplied, kb + 1 is on its way in one register set
+    // and kb + 2 in the other (few workgroups share a CU at these shapes, so the latency has to be covered here).
+    // Blocks past the end are clamped to the last one (loaded again, never stored) rather than branched around.
+    float4 ra0[4], rb0[4], ra1[4], rb1[4];
+    sa.issue(0, ra0);
+    sb.issue(0, rb0);
+    sa.issue(1 < nblk ? 1 : last, ra1);
+    sb.issue(1 < nblk ? 1 : last, rb1);
+    auto multiply = [&](const __bf16* As, const __bf16* Bs) {
+        // lane feeds row (column) lane % 32 of its quarter and K values 16 s + 8 (lane / 32) .. + 7 of MFMA s
+        const __bf16* ap = As + (wm + (lane & 31)) * PITCH + 8 * (lane >> 5);
+        const __bf16* bp = Bs + (wn + (lane & 31)) * PITCH + 8 * (lane >> 5);
+#pragma unroll
+        for (int s = 0; s < BK / 16; ++s) {
+            const bf16x8 pa = *reinterpret_cast<const bf16x8*>(ap + 16 * s);
+            const bf16x8 pb = *reinterpret_cast<const bf16x8*>(bp + 16 * s);
+            if (WANT_ASUM) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a_sum += (float)pa[e];
+            }
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pa, pb, acc, 0, 0, 0);
+        }
+    };
+    for (int kb = 0; kb < nblk; kb += 2) {
+        sa.store(kb, ra0, lds[0][0]);
+        sb.store(kb, rb0, lds[0][1]);
+        sa.issue(kb + 2 < nblk ? kb + 2 : last, ra0);
+        sb.issue(kb + 2 < nblk ? kb + 2 : last, rb0);
+        lds_barrier();
+        multiply(lds[0][0], lds[0][1]);
+        if (kb + 1 >= nblk) break;
+        sa.store(kb + 1, ra1, lds[1][0]);
+        sb.store(kb + 1, rb1, lds[1][1]);
+        sa.issue(kb + 3 < nblk ? kb + 3 : last, ra1);
+        sb.issue(kb + 3 < nblk ? kb + 3 : last, rb1);
+        lds_barrier();
+        multiply(lds[1][0], lds[1][1]);
+    }
+
+    // ---- epilogue, straight from the accumulators: register v of lane l holds C[8 (v/4) + 4 (l/32) + v%4][l%32]
+    // of the wave's quarter
+    float* rs_lds = reinterpret_cast<float*>(lds[0][0]) + 32 * w;  // row sums of A for the quarter's 32 rows
+    if (WANT_ASUM) {
+        a_sum += __shfl_xor(a_sum, 32, 64);
+        lds_barrier();  // every wave is done reading the operand blocks
+        if (lane < 32) rs_lds[lane] = a_sum;
+        lds_barrier();
+    }
+    StepView sv;
+    bool head = false;
+    if (CHAIN) {
+        sv = step_view(g.ids);
+        head = sv.side == KGE_NEG_HEAD;
+    }
+    float* C = g.C + c * g.sC;
+    float loss = 0.f;
+    const int gn = n0 + wn + (lane & 31);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int i = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int gm = m0 + wm + i;
+        if (gm >= g.M || gn >= g.N) continue;
+        const float s = acc[v];
+        const float rs = WANT_ASUM ? rs_lds[i] : 0.f;
+        const int bi = c * g.M + gm;  // index of the positive in the mini-batch (chain epilogues)
+        if (EPI == EPI_PLAIN) {
+            C[(int64_t)gm * g.ldc + gn] = (IS_FWD && g.out_mode == OUT_W) ? w_and_loss<false>(s, g.wk, loss) : s;
+        } else if (EPI == EPI_L2_FWD) {
+            const float d2 = g.rowv[c * g.s_rowv + gm] + g.colv[c * g.s_colv + gn] - 2.f * s;
+            const float d = __builtin_amdgcn_sqrtf(fmaxf(d2, 0.f));  // 1 ulp
+            float out = g.out_mode == OUT_DIST ? d : g.gamma - d;
+            if (g.out_mode == OUT_W) {  // W = w sigmoid(f) / |o - n|, 0 where the distance is 0
+                const float coef = w_and_loss<false>(g.gamma - d, g.wk, loss);
+                out = d > 0.f ? coef * rcp_refined(d) : 0.f;
+            }
+            C[(int64_t)gm * g.ldc + gn] = out;
+        } else if (EPI == EPI_L2_DO || EPI == EPI_L2_DN) {
+            const float xv = g.X[c * g.sX + (int64_t)gm * g.ldx + gn];
+            C[(int64_t)gm * g.ldc + gn] = s - rs * round_bf16(xv);
+        } else {
+            const int64_t hid = clamp_id(sv.h[bi], g.n_ent), tid = clamp_id(sv.t[bi], g.n_ent);
+            const int64_t aid = head ? tid : hid, cid = head ? hid : tid;
+            const float e_o = g.X[(int64_t)bi * g.ldx + gn];
+            const float e_c = g.E[cid * g.D + gn];
+            const float e_cp = g.cpos[bi];
+            float* ga = g.Gent + (int64_t)(head ? g.b + bi : bi) * g.D + gn;
+            float* gc = g.Gent + (int64_t)(head ? bi : g.b + bi) * g.D + gn;
+            float* gr = g.Grel + (int64_t)bi * g.D + gn;
+            if (EPI == EPI_CHAIN_L2) {
+                // dL/do = W n - rowsum(W) o  +  dL/df+ * d(gamma - |o - c|)/do
+                const float dir = (e_o - e_c) * g.inv_dpos[bi];
+                const float go = s - rs * round_bf16(e_o) - e_cp * dir;
+                *ga = go;
+                *gc = e_cp * dir;
+                *gr = head ? -go : go;
+            } else {  // EPI_CHAIN_DM: o = a * r, psi = o . x
+                const int64_t rid = clamp_id(sv.r[bi], g.n_rel);
+                const float go = s + e_cp * e_c;
+                *ga = go * g.R[rid * g.D + gn];
+                *gc = e_cp * e_o;
+                *gr = go * g.E[aid * g.D + gn];
+            }
+        }
+    }
+    if (IS_FWD && g.out_mode == OUT_W) {
+        // negative part of the loss, one sum per 32x32 quarter that lies inside the matrix, indexed as the 32x32
+        // tiling of the fp32 path indexes its tiles
+        loss = wave_sum(loss);
+        const int q_m = (m0 + wm) / 32, q_n = (n0 + wn) / 32;
+        const int qx = (g.N + 31) / 32, qy = (g.M + 31) / 32;
+        if (lane == 0 && m0 + wm < g.M && n0 + wn < g.N) g.neg_loss_part[(c * qy + q_m) * qx + q_n] = loss * g.wk;
+    }
+}
+
+template <int EPI>
+__global__ __launch_bounds__(THREADS) void k_gemm_bf_fwd(GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) __bf16 lds[2][2][BT * PITCH];
+    const int tile = xcd_tile(blockIdx.x >> 3, gridDim.x >> 3);
+    if (tile >= g.tiles) return;
+    bf_tile<true, true, EPI>(g, tile, lds);
+}
+
+// dO tiles first: their K is the number of corrupting rows per chunk, the longer loop at these shapes
+template <int EPI_O, int EPI_N>
+__global__ __launch_bounds__(THREADS) void k_gemm_bf_bwd(GemmArgs gO, GemmArgs gN, int per_xcd_o, int per_xcd_n) {
+    __shared__ __attribute__((aligned(16))) __bf16 lds[2][2][BT * PITCH];
+    const int q = blockIdx.x >> 3;
+    if (q < per_xcd_o) {
+        const int tile = xcd_tile(q, per_xcd_o);
+        if (tile < gO.tiles) bf_tile<true, false, EPI_O>(gO, tile, lds);
+    } else {
+        const int tile = xcd_tile(q - per_xcd_o, per_xcd_n);
+        if (tile < gN.tiles) bf_tile<false, false, EPI_N>(gN, tile, lds);
+    }
+}
+
+void set_tiling(GemmArgs& g, int chunks) {
+    g.gx = (g.N + BT - 1) / BT;
+    g.gy = (g.M + BT - 1) / BT;
+    g.tiles = g.gx * g.gy * chunks;
+}
+
+template <int EPI_O, int EPI_N>
+void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st) {
+    set_tiling(gO, chunks);
+    set_tiling(gN, chunks);
+    const int per_o = (gO.tiles + 7) / 8, per_n = (gN.tiles + 7) / 8;
+    KGE_LAUNCH(c, (k_gemm_bf_bwd<EPI_O, EPI_N>), dim3(8 * (per_o + per_n)), dim3(THREADS), 0, st, gO, gN, per_o, per_n);
+}
+
+}  // namespace
+
+void kge_gemm_bf_forward(kge_ctx* c, const void* args, int epi, int chunks, hipStream_t st) {
+    GemmArgs g = *static_cast<const GemmArgs*>(args);
+    set_tiling(g, chunks);
+    const dim3 grid(8 * ((g.tiles + 7) / 8));
+    if (epi == EPI_L2_FWD) KGE_LAUNCH(c, k_gemm_bf_fwd<EPI_L2_FWD>, grid, dim3(THREADS), 0, st, g);
+    else KGE_LAUNCH(c, k_gemm_bf_fwd<EPI_PLAIN>, grid, dim3(THREADS), 0, st, g);
+}
+
+void kge_gemm_bf_backward(kge_ctx* c, const void* args_o, const void* args_n, int epi_o, int epi_n, int chunks,
+                          hipStream_t st) {
+    const GemmArgs gO = *static_cast<const GemmArgs*>(args_o), gN = *static_cast<const GemmArgs*>(args_n);
+    if (epi_o == EPI_CHAIN_L2 && epi_n == EPI_L2_DN) launch_bwd<EPI_CHAIN_L2, EPI_L2_DN>(c, gO, gN, chunks, st);
+    else if (epi_o == EPI_CHAIN_DM && epi_n == EPI_PLAIN) launch_bwd<EPI_CHAIN_DM, EPI_PLAIN>(c, gO, gN, chunks, st);
+    else launch_bwd<EPI_PLAIN, EPI_PLAIN>(c, gO, gN, chunks, st);
+}
