@@ -30,6 +30,7 @@ struct GatherArgs {
     float* row_loss;  // softplus(-f+_i) / b
     int rank_blocks;         // blocks [0, rank_blocks) order the key lists, the others gather rows
     int ent_rank_blocks;     // the first ent_rank_blocks of them order the entity key list, the rest the relation keys
+    uint64_t bucket_mul;     // long entity lists: bucket of an id = (id * bucket_mul) >> 32 (0: brute-force blocks)
     KeyList ent, rel;
 };
 
@@ -122,6 +123,87 @@ __device__ __forceinline__ void rank_block(const KeyList& l, int blk, uint32_t* 
     }
 }
 
+// Long lists (RANK_LONG_LIST keys and more): brute force would compare every key with every other (1.5e8 comparisons
+// for 12,288 keys, which set the duration of the whole launch).  Here a block of 1024 threads ranks 1024 keys with
+// work linear in the list.  The id range [0, n_ids) is cut into RANK_BUCKETS equal slices, so buckets are ordered
+// like the ids they hold.  Every block (1) counts the keys per bucket with LDS atomics, (2) turns the counts into
+// offsets, (3) drops one word per key into its bucket's stretch of LDS, in whatever order the atomics hand out:
+// (id - first id of the bucket) << 14 | position, so that the words of a bucket compare like (id, position) pairs,
+// and (4) ranks its own 1024 keys: offset of the key's bucket + the number of smaller words in that bucket.  The
+// result does not depend on the order inside the buckets.  Needs positions below 2^14 (lists end at 14,336 keys) and
+// buckets narrower than 2^18 ids (tables of up to 134 M rows; larger ones keep the brute-force blocks).
+constexpr int RANK_BUCKETS = 512;
+constexpr int RANK_POS_BITS = 14;
+__host__ __device__ constexpr size_t bucketed_lds_words(int n) { return (size_t)n + 3 * RANK_BUCKETS + 16; }
+inline bool bucketed_ranking_fits(int64_t n_ids) { return n_ids / RANK_BUCKETS + 2 < (1 << (32 - RANK_POS_BITS)); }
+
+__device__ __forceinline__ void rank_block_bucketed(const KeyList& l, int blk, uint64_t bucket_mul, uint32_t* lds) {
+    constexpr int T = 1024, MAXK = KGE_RANK_MAX_KEYS / T;  // keys per thread: position u * T + tid
+    const int tid = threadIdx.x, n = l.n;
+    uint32_t* word = lds;                               // [n] one word per key, bucket after bucket
+    int* cnt = reinterpret_cast<int*>(lds + n);         // [RANK_BUCKETS]
+    int* off = cnt + RANK_BUCKETS;                      // [RANK_BUCKETS] exclusive prefix of cnt
+    uint32_t* first = reinterpret_cast<uint32_t*>(off + RANK_BUCKETS);  // [RANK_BUCKETS] smallest id of the bucket
+    int* wave_tot = reinterpret_cast<int*>(first + RANK_BUCKETS);       // [8]
+    if (tid < RANK_BUCKETS) {
+        cnt[tid] = 0;
+        // bucket(id) = (id * bucket_mul) >> 32 >= tid  <=>  id >= ceil((tid << 32) / bucket_mul)
+        first[tid] = (uint32_t)((((uint64_t)tid << 32) + bucket_mul - 1) / bucket_mul);
+    }
+    const int64_t step = l.step_ptr ? *l.step_ptr : 0;
+    int64_t raw[MAXK];
+#pragma unroll
+    for (int u = 0; u < MAXK; ++u) {
+        const int p = u * T + tid;
+        raw[u] = *key_address(l, step, p < n ? p : 0);
+    }
+    __syncthreads();
+    uint32_t key[MAXK];
+    int bucket[MAXK], slot[MAXK];
+#pragma unroll
+    for (int u = 0; u < MAXK; ++u) {
+        key[u] = clamp_key(l, raw[u]);
+        bucket[u] = (int)(((uint64_t)key[u] * bucket_mul) >> 32);
+        slot[u] = u * T + tid < n ? atomicAdd(&cnt[bucket[u]], 1) : 0;
+    }
+    __syncthreads();
+    if (tid < RANK_BUCKETS) {  // exclusive prefix over the bucket counts: scan inside the 8 waves, then across them
+        const int c = cnt[tid];
+        int inc = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(inc, o, 64);
+            if ((tid & 63) >= o) inc += v;
+        }
+        if ((tid & 63) == 63) wave_tot[tid >> 6] = inc;
+        off[tid] = inc - c;
+    }
+    __syncthreads();
+    if (tid < RANK_BUCKETS) {
+        int before = 0;
+        for (int w = 0; w < (tid >> 6); ++w) before += wave_tot[w];
+        off[tid] += before;
+    }
+    __syncthreads();
+    uint32_t mine_word = 0;
+    int mine_bucket = 0;
+#pragma unroll
+    for (int u = 0; u < MAXK; ++u) {
+        const uint32_t wd = ((key[u] - first[bucket[u]]) << RANK_POS_BITS) | (uint32_t)(u * T + tid);
+        if (u * T + tid < n) word[off[bucket[u]] + slot[u]] = wd;
+        if (u == blk) { mine_word = wd; mine_bucket = bucket[u]; }  // this block ranks positions blk * T + tid
+    }
+    __syncthreads();
+    const int mine = blk * T + tid;
+    if (mine >= n) return;
+    const int lo = off[mine_bucket], hi = lo + cnt[mine_bucket];
+    int before = lo;
+#pragma unroll 4
+    for (int j = lo; j < hi; ++j) before += word[j] < mine_word ? 1 : 0;
+    l.key[0][before] = (mine_word >> RANK_POS_BITS) + first[mine_bucket];
+    l.pos[0][before] = (uint32_t)mine;
+}
+
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
 
 // NV = 16-byte vectors per lane: ceil(D/4/64) for the real models, ceil(D/8/64) (re, im) pairs for the complex ones.
@@ -132,8 +214,12 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
     // the rank blocks come first: they run longest and need nothing but the ids
     if ((int)blockIdx.x < a.rank_blocks) {
         const int rb = blockIdx.x;
-        if (rb < a.ent_rank_blocks) rank_block<THREADS>(a.ent, rb, rank_keys);
-        else rank_block<THREADS>(a.rel, rb - a.ent_rank_blocks, rank_keys);
+        if (rb < a.ent_rank_blocks) {
+            if (THREADS == 1024 && a.bucket_mul != 0) rank_block_bucketed(a.ent, rb, a.bucket_mul, rank_keys);
+            else rank_block<THREADS>(a.ent, rb, rank_keys);
+        } else {
+            rank_block<THREADS>(a.rel, rb - a.ent_rank_blocks, rank_keys);
+        }
         return;
     }
     const int lane = threadIdx.x & 63;
@@ -296,9 +382,18 @@ void launch_model(kge_ctx* c, GatherArgs& a, int nv, int rows, bool with_keys, c
     if (with_keys) {
         constexpr int ITEMS = RankShape<THREADS>::ITEMS;
         kge_make_key_lists(c, ids, &a.ent, &a.rel);
-        a.ent_rank_blocks = (a.ent.n + ITEMS - 1) / ITEMS;
+        a.bucket_mul = 0;
+        if (THREADS == 1024 && bucketed_ranking_fits(a.ent.n_ids)) {  // long entity list: 1024 keys per block
+            a.ent_rank_blocks = (a.ent.n + 1023) / 1024;
+            a.bucket_mul = ((uint64_t)RANK_BUCKETS << 32) / (uint64_t)a.ent.n_ids;
+            lds = sizeof(uint32_t) * bucketed_lds_words(a.ent.n);
+            const size_t rel_lds = sizeof(uint32_t) * (size_t)((a.rel.n + 3) & ~3);
+            if (rel_lds > lds) lds = rel_lds;
+        } else {
+            a.ent_rank_blocks = (a.ent.n + ITEMS - 1) / ITEMS;
+            lds = sizeof(uint32_t) * (size_t)((a.ent.n + 3) & ~3);  // the entity list is the longer one
+        }
         rank_blocks = a.ent_rank_blocks + (a.rel.n + ITEMS - 1) / ITEMS;
-        lds = sizeof(uint32_t) * (size_t)((a.ent.n + 3) & ~3);  // the entity list is the longer one
         c->ebuf = 0;
         c->rbuf = 0;
     }

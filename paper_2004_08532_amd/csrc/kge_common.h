@@ -119,7 +119,7 @@ void kge_make_key_lists(kge_ctx* c, const StepIds& ids, KeyList* ent, KeyList* r
 // KGE_RANK_MAX_KEYS keys; longer lists go through kge_launch_sort)
 void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds& ids, float gamma, float* pos_out,
                        bool with_keys, hipStream_t st);
-constexpr int KGE_RANK_MAX_KEYS = 16384;
+constexpr int KGE_RANK_MAX_KEYS = 14336;  // 14 * 1024: positions fit 14 bits, the list and its tables fit 64 KB of LDS
 // a3: negative scores of every chunk into out[b x ld_out]: matrix-product models / elementwise-reduce models
 void kge_gemm_neg_score(kge_ctx* c, int b, int k, int g, float gamma, float* out, int ld_out, int dist_mode,
                         hipStream_t st);

@@ -323,6 +323,21 @@ def test_long_key_lists_take_the_radix_sort_path(kge):
         p.close()
 
 
+@pytest.mark.parametrize("n_entities", [401, 200_003])
+def test_key_lists_of_medium_length_take_the_bucketed_ranking(kge, n_entities):
+    """Between 6,144 and 14,336 entity keys the gather launch ranks them bucket by bucket.  With 401 entities every id
+    occurs about 20 times (ties are broken by position, buckets hold one id each and some are empty); with 200,003
+    most ids are distinct and a bucket holds a few hundred different ids."""
+    w = ragged("distmult", n_entities=n_entities, ent_dim=16, rel_dim=16, batch=768, chunk=64, neg_per_chunk=550,
+               steps=2)
+    assert 6144 <= 2 * w.batch + w.n_chunks * w.neg_per_chunk <= 14336
+    p = Pair(w, kge)
+    try:
+        run_steps(p, configs.BatchStream(w), 2, check_dedup_at=(0, 1))
+    finally:
+        p.close()
+
+
 @pytest.mark.parametrize("model", MODELS)
 def test_evaluation_ranks_and_metrics(kge, model):
     """Link-prediction evaluation: the rank of every positive among 2 x 150 sampled candidates (both sides), then
