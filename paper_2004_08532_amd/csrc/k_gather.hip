@@ -38,7 +38,7 @@ struct GatherArgs {
 // rank blocks keep the whole key list in (dynamic) LDS, and every block of a launch is given the same amount; with
 // a long list the blocks are large, so that the LDS of a gather block is spread over 16 row-gathering waves and
 // does not limit how many of them a CU holds, and so that fewer blocks load the list.
-constexpr int RANK_LONG_LIST = 6144;  // keys from which on the large blocks are used (measured: 4096 keys are still faster with the small ones)
+constexpr int RANK_LONG_LIST = 6144;  // keys from which on the 1024-thread blocks are used (measured: lists of 2,200 and 4,096 keys are 4-5 us faster with the small brute-force blocks)
 template <int THREADS> struct RankShape {
     static constexpr int R = THREADS == 256 ? 1 : 2;     // keys ranked by one 32-thread group
     static constexpr int ITEMS = (THREADS / 32) * R;     // keys ranked per block
