@@ -521,11 +521,22 @@ def test_index_validation_reports_out_of_range_ids_without_touching_memory_outsi
         p.close()
 
 
-def test_train_steps_graph_replay_equals_step_by_step(kge):
+REPLAY_VARIANTS = {
+    "transe_l2": {},
+    "rescal": dict(model="rescal", ent_dim=32, rel_dim=32 * 32),
+    "rotate-ranking-adversarial": dict(model="rotate", rel_dim=32, loss="ranking", gamma=0.5, adv_temperature=1.0),
+    "complex-bf16": dict(model="complex", bf16_inputs=True),
+}
+
+
+@pytest.mark.parametrize("variant", list(REPLAY_VARIANTS), ids=list(REPLAY_VARIANTS))
+def test_train_steps_graph_replay_equals_step_by_step(kge, variant):
     """kge_train_steps replays captured graphs; the result must equal kge_train_step called once per step, bit for
     bit, on every replay: first use (capture), reuse with new ids in the same buffers, a step count that is not a
-    multiple of the unroll factor, with eager work and synchronisation in between."""
-    w = configs.TINY.scaled(name="tiny-replay", side_mode="alternate")
+    multiple of the unroll factor, with eager work and synchronisation in between.  The variants take every kernel
+    of the library through a replayed graph once (fused and separate loss / chain kernels, pair kernels, the RESCAL
+    kernels, the bf16 products)."""
+    w = configs.TINY.scaled(name="tiny-replay", side_mode="alternate", **REPLAY_VARIANTS[variant])
     bs = configs.BatchStream(w)
     E0, R0 = configs.init_tables(w)
     stream = torch.cuda.Stream()
@@ -537,7 +548,8 @@ def test_train_steps_graph_replay_equals_step_by_step(kge):
 
     def make_ctx():
         return kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
-                              max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks)
+                              max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks, loss=w.loss,
+                              adv_temperature=w.adv_temperature, gemm_input=int(w.bf16_inputs))
 
     # step by step
     ctx = make_ctx()
