@@ -21,6 +21,9 @@ struct GatherArgs {
     int64_t n_ent, n_rel;
     float* O;
     float* Nst;
+    uint16_t* Obf;  // bf16 operands: o_i and the corrupting rows as the products read them (row pitch ld_bf);
+    uint16_t* Nbf;  // Nst is then not written
+    int ld_bf;
     float* fpos;
     float* pos_out;
     float* o_n2;
@@ -206,6 +209,14 @@ __device__ __forceinline__ void rank_block_bucketed(const KeyList& l, int blk, u
 
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
 
+// four floats -> four bf16 (round to nearest even), stored as 8 bytes
+__device__ __forceinline__ void st4_bf16(uint16_t* p, float x0, float x1, float x2, float x3) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 a, b;
+    a[0] = (__bf16)x0; a[1] = (__bf16)x1; b[0] = (__bf16)x2; b[1] = (__bf16)x3;
+    *reinterpret_cast<uint2*>(p) = make_uint2(__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b));
+}
+
 // NV = 16-byte vectors per lane: ceil(D/4/64) for the real models, ceil(D/8/64) (re, im) pairs for the complex ones.
 template <int MODEL, int NV, int THREADS>
 __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
@@ -249,7 +260,8 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) xv[e] = round_bf16(xv[e]);
                 }
-                st4(dst + 4 * v, x);
+                if (a.bf16) st4_bf16(a.Nbf + (int64_t)j * a.ld_bf + 4 * v, x.x, x.y, x.z, x.w);
+                else st4(dst + 4 * v, x);
                 nn += xv[0] * xv[0] + xv[1] * xv[1] + xv[2] * xv[2] + xv[3] * xv[3];
             }
         }
@@ -293,6 +305,7 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
                 else ov[e] = head ? av[e] - rv[e] : av[e] + rv[e];
             }
             st4(po + 4 * v, make_float4(ov[0], ov[1], ov[2], ov[3]));
+            if (a.bf16) st4_bf16(a.Obf + (int64_t)i * a.ld_bf + 4 * v, ov[0], ov[1], ov[2], ov[3]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (MODEL == KGE_DISTMULT) acc += ov[e] * cv[e];
@@ -332,6 +345,10 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
             }
             st4(po + 4 * v, make_float4(ore[0], ore[1], ore[2], ore[3]));
             st4(po + im_off + 4 * v, make_float4(oim[0], oim[1], oim[2], oim[3]));
+            if (a.bf16) {
+                st4_bf16(a.Obf + (int64_t)i * a.ld_bf + 4 * v, ore[0], ore[1], ore[2], ore[3]);
+                st4_bf16(a.Obf + (int64_t)i * a.ld_bf + im_off + 4 * v, oim[0], oim[1], oim[2], oim[3]);
+            }
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (MODEL == KGE_COMPLEX) acc += ore[e] * cre[e] + oim[e] * cim[e];
@@ -419,6 +436,7 @@ void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds
     a.b = b; a.n_neg = n_neg; a.D = c->cfg.ent_dim; a.Dr = c->cfg.rel_dim;
     a.bf16 = c->cfg.gemm_input;
     a.gamma = gamma; a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
+    a.Obf = c->Obf; a.Nbf = c->Nbf; a.ld_bf = c->ld_bf;
     a.O = c->O; a.Nst = c->Nst; a.fpos = c->fpos; a.pos_out = pos_out; a.o_n2 = c->o_n2; a.n_n2 = c->n_n2;
     a.cpos = c->cpos; a.inv_dpos = c->inv_dpos; a.row_loss = c->row_loss;
     const int model = c->cfg.model;

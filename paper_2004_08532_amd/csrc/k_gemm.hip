@@ -368,7 +368,12 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     const int chunks = b / gsz;
     const bool bf = c->cfg.gemm_input == 1;
     const int epi = c->cfg.model == KGE_TRANSE_L2 ? EPI_L2_FWD : EPI_PLAIN;
-    if (bf) kge_gemm_bf_forward(c, &g, epi, chunks, st);
+    if (bf) {  // the operands as the gather launch rounded them
+        g.A = reinterpret_cast<const float*>(c->Obf); g.B = reinterpret_cast<const float*>(c->Nbf);
+        g.lda = c->ld_bf; g.ldb = c->ld_bf;
+        g.sA = (int64_t)gsz * c->ld_bf; g.sB = (int64_t)k * c->ld_bf;
+        kge_gemm_bf_forward(c, &g, epi, chunks, st);
+    }
     else if (epi == EPI_L2_FWD) launch_fwd<EPI_L2_FWD>(c, g, chunks, st);
     else launch_fwd<EPI_PLAIN>(c, g, chunks, st);
 }
@@ -412,6 +417,11 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
     q.X = c->Nst; q.ldx = D; q.sX = (int64_t)k * D;
 
     const bool bf = c->cfg.gemm_input == 1;
+    if (bf) {  // N_c and O_c (the B operands) and the rows of the dN correction term as bf16
+        g.B = reinterpret_cast<const float*>(c->Nbf); g.ldb = c->ld_bf; g.sB = (int64_t)k * c->ld_bf;
+        q.B = reinterpret_cast<const float*>(c->Obf); q.ldb = c->ld_bf; q.sB = (int64_t)gsz * c->ld_bf;
+        q.X = reinterpret_cast<const float*>(c->Nbf); q.ldx = c->ld_bf; q.sX = (int64_t)k * c->ld_bf;
+    }
 #define KGE_BWD(EO, EN)                                                     \
     do {                                                                    \
         if (bf) kge_gemm_bf_backward(c, &g, &q, EO, EN, chunks, st);        \

@@ -1,16 +1,18 @@
 // The chunked negative-scoring products (Sec. 3.3 of the paper) and their backward with bf16 operands and fp32
 // accumulation: S_c = O_c N_c^T, dO_c = W_c N_c, dN_c = W_c^T O_c with the same epilogues as the fp32 path.
 //
-// Shapes here are the large ones (thousands of positives and corrupting rows per step), so the limit is not
-// latency but how often an operand row is pulled from L2 into a CU: a 32x32 tile per workgroup re-reads every row
-// once per 32 columns of output.  A workgroup therefore owns a 64x64 output tile over the whole K range (no
-// split over K, no cross-wave sum); its four waves hold one 32x32 quarter each.  Per K block of 64 the 256 threads
-// load the two 64x64 fp32 operand blocks (16-byte loads, the next two blocks in flight while this one is multiplied), round
-// them to bf16 (the hardware's round-to-nearest-even conversion, two values per instruction) and lay them out in LDS
-// K-contiguous, whatever their orientation in memory, so that every v_mfma_f32_32x32x16_bf16 operand is one
-// 16-byte LDS read.  Operands that are stored with K along rows ("MC": N_c in dO, W_c and O_c in dN) are
-// transposed for free on the way: a thread loads the same four columns of two adjacent K rows and packs the
-// pairs.  LDS is double-buffered: one workgroup barrier per K block.
+// Shapes here are the large ones (thousands of positives and corrupting rows per step), where a 32x32 tile per
+// workgroup pulls every operand row from L2 into a CU once per 32 columns of output, and that path is the limit.  A
+// workgroup therefore owns a 64x64 output tile over the whole K range (no split over K, no cross-wave sum); its four
+// waves hold one 32x32 quarter each.  Per K block of 64 the 256 threads load the two 64x64 operand blocks (whole
+// cache lines per request, the next two blocks in flight while this one is multiplied) and lay them out in LDS as
+// bf16, K-contiguous whatever their
+// orientation in memory, so that every v_mfma_f32_32x32x16_bf16 operand is one 16-byte LDS read.  The o rows and the
+// corrupting rows arrive as bf16 (the gather launch rounds them once); the coefficients W are fp32 in memory and are
+// rounded here (the hardware's round-to-nearest-even conversion, two values per instruction).  Operands that are
+// stored with K along rows ("MC": N_c in dO, W_c and O_c in dN) are transposed on the way: a thread loads the same
+// four columns of two adjacent K rows and packs the pairs.  LDS is double-buffered: one workgroup barrier per K
+// block.
 #include "k_gemm_shared.h"
 
 namespace {
@@ -29,6 +31,12 @@ __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
     v[1] = (__bf16)hi;
     return __builtin_bit_cast(uint32_t, v);
 }
+
+// Position (in 4-byte words) of word `word` of tile row `row` in LDS.  The groups of four words (one 16-byte MFMA
+// operand) of a row are permuted by the row's group of eight: the 16-byte reads stay free of bank conflicts, and the
+// transposing 4-byte writes of the MC operands, which hit rows four apart, spread over the banks (2 lanes per bank
+// instead of 8).
+__device__ __forceinline__ int lds_word(int row, int word) { return row * PITCH_W + (word ^ (4 * ((row >> 3) & 7))); }
 
 __device__ __forceinline__ void lds_barrier() {  // orders LDS traffic only: global loads stay in flight across it
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
@@ -50,6 +58,7 @@ struct Stager {
                      // row (of 4 consecutive ones)
     int k;           // KC: first of its 4 K values; MC: first of its two K pairs (2 * kp; the second is 32 + 2 * kp)
     bool okr[4];
+    struct Reg { float4 v[4]; };
     // KC: 16 consecutive lanes read 256 consecutive bytes of one row (whole cache lines per request)
     __device__ __forceinline__ void init(const float* base_, int ld_, int r0, int R_, int K_, int t) {
         base = base_; ld = ld_; K = K_; R = R_;
@@ -70,7 +79,8 @@ struct Stager {
             p = base + (okr[0] ? r0 + r : 0);
         }
     }
-    __device__ __forceinline__ void issue(int kb, float4 (&reg)[4]) const {
+    __device__ __forceinline__ void issue(int kb, Reg& rg) const {
+        float4 (&reg)[4] = rg.v;
         const int k0 = kb * BK + k;
         if (KC) {
 #pragma unroll
@@ -83,7 +93,8 @@ struct Stager {
             }
         }
     }
-    __device__ __forceinline__ void store(int kb, const float4 (&reg)[4], __bf16* lds) const {
+    __device__ __forceinline__ void store(int kb, const Reg& rg, __bf16* lds) const {
+        const float4 (&reg)[4] = rg.v;
         const int k0 = kb * BK + k;
         if (KC) {
 #pragma unroll
@@ -92,7 +103,8 @@ struct Stager {
                 float m[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) m[e] = (okr[q] && k0 + e < K) ? v[e] : 0.f;
-                *reinterpret_cast<uint2*>(lds + (r + 16 * q) * PITCH + k) = make_uint2(pack2(m[0], m[1]), pack2(m[2], m[3]));
+                *reinterpret_cast<uint2*>(reinterpret_cast<uint32_t*>(lds) + lds_word(r + 16 * q, k >> 1)) =
+                    make_uint2(pack2(m[0], m[1]), pack2(m[2], m[3]));
             }
         } else {
             uint32_t* l32 = reinterpret_cast<uint32_t*>(lds);
@@ -105,51 +117,146 @@ struct Stager {
                 for (int e = 0; e < 4; ++e) {
                     const float a = (okr[e] && kk < K) ? lo[e] : 0.f;
                     const float b = (okr[e] && kk + 1 < K) ? hi[e] : 0.f;
-                    l32[(r + e) * PITCH_W + (k >> 1) + 16 * h] = pack2(a, b);
+                    l32[lds_word(r + e, (k >> 1) + 16 * h)] = pack2(a, b);
                 }
             }
         }
     }
 };
 
-// One 64x64 output tile.  EPI as in the fp32 path.  A_KC / B_KC: orientation of the operands in memory.
-template <bool A_KC, bool B_KC, int EPI>
+// The same for an operand that the gather launch has already rounded to bf16 (the o rows and the corrupting rows; row
+// pitch a multiple of 8 elements): half the bytes from L2, no conversion.  KC: 8 consecutive lanes read the 128 bytes
+// that a row has in the K block and copy them; MC: 16 consecutive lanes read 128 consecutive bytes of one K row, and the
+// 16-bit halves of two adjacent K rows are interleaved.
+template <bool KC>
+struct StagerBF {
+    const uint16_t* base;
+    const uint16_t* p;
+    const uint16_t* pr[2];
+    int ld, K, R, r, k;
+    bool okr[4];
+    struct Reg { uint4 v[2]; };  // KC: two rows x 8 K values; MC: (v[0].xy, v[0].zw, v[1].xy, v[1].zw) = 4 K rows x 4 columns
+    __device__ __forceinline__ void init(const float* base_, int ld_, int r0, int R_, int K_, int t) {
+        base = reinterpret_cast<const uint16_t*>(base_); ld = ld_; K = K_; R = R_;
+        if (KC) {
+            r = t >> 3;
+            k = 8 * (t & 7);
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                okr[q] = r0 + r + 32 * q < R;
+                pr[q] = base + (int64_t)(okr[q] ? r0 + r + 32 * q : 0) * ld;
+            }
+            p = base;
+        } else {
+            r = 4 * (t & 15);
+            k = 2 * (t >> 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) okr[e] = r0 + r + e < R;
+            p = base + (okr[0] ? r0 + r : 0);
+        }
+    }
+    __device__ __forceinline__ void issue(int kb, Reg& rg) const {
+        const int k0 = kb * BK + k;
+        if (KC) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) rg.v[q] = *reinterpret_cast<const uint4*>(pr[q] + (k0 < K ? k0 : 0));
+        } else {
+            uint2 x[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int kk = k0 + (q >> 1) * 32 + (q & 1);
+                x[q] = *reinterpret_cast<const uint2*>(kk < K ? p + (int64_t)kk * ld : base);
+            }
+            rg.v[0] = make_uint4(x[0].x, x[0].y, x[1].x, x[1].y);
+            rg.v[1] = make_uint4(x[2].x, x[2].y, x[3].x, x[3].y);
+        }
+    }
+    __device__ __forceinline__ void store(int kb, const Reg& rg, __bf16* lds) const {
+        const int k0 = kb * BK + k;
+        if (KC) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                // K is a multiple of 4, so a pair of values is inside the matrix or outside as a whole
+                uint4 w = rg.v[q];
+                w.x = (okr[q] && k0 < K) ? w.x : 0u;
+                w.y = (okr[q] && k0 + 2 < K) ? w.y : 0u;
+                w.z = (okr[q] && k0 + 4 < K) ? w.z : 0u;
+                w.w = (okr[q] && k0 + 6 < K) ? w.w : 0u;
+                *reinterpret_cast<uint4*>(reinterpret_cast<uint32_t*>(lds) + lds_word(r + 32 * q, k >> 1)) = w;
+            }
+        } else {
+            uint32_t* l32 = reinterpret_cast<uint32_t*>(lds);
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int kk = k0 + 32 * h;
+                // lo: K row kk, hi: K row kk + 1; each holds columns (0, 1) in .x / .z and (2, 3) in .y / .w
+                const uint32_t lo01 = rg.v[h].x, lo23 = rg.v[h].y, hi01 = rg.v[h].z, hi23 = rg.v[h].w;
+                const uint32_t lo[4] = {lo01 & 0xffffu, lo01 >> 16, lo23 & 0xffffu, lo23 >> 16};
+                const uint32_t hi[4] = {hi01 << 16, hi01 & 0xffff0000u, hi23 << 16, hi23 & 0xffff0000u};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t a = (okr[e] && kk < K) ? lo[e] : 0u;
+                    const uint32_t b = (okr[e] && kk + 1 < K) ? hi[e] : 0u;
+                    l32[lds_word(r + e, (k >> 1) + 16 * h)] = a | b;
+                }
+            }
+        }
+    }
+};
+
+template <bool KC, bool SRC_BF> struct StagerSel { typedef Stager<KC> type; };
+template <bool KC> struct StagerSel<KC, true> { typedef StagerBF<KC> type; };
+
+// One 64x64 output tile.  EPI as in the fp32 path.  A_KC / B_KC: orientation of the operands in memory; A_BF / B_BF:
+// the operand is stored as bf16 (g.A / g.B then point at 16-bit elements, strides and pitches counted in elements).
+template <bool A_KC, bool B_KC, int EPI, bool A_BF, bool B_BF>
 __device__ __forceinline__ void bf_tile(const GemmArgs& g, int tile, __bf16 (*lds)[2][BT * PITCH]) {
     constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM;
-    constexpr bool WANT_ASUM = EPI == EPI_L2_DO || EPI == EPI_L2_DN || EPI == EPI_CHAIN_L2;
+    constexpr bool WANT_ASUM = EPI == EPI_L2_DN || EPI == EPI_CHAIN_L2;
     constexpr bool IS_FWD = A_KC && B_KC;
+    static_assert(EPI != EPI_L2_DO, "with bf16 operands dL/do of TransE-L2 goes through the chain-rule epilogue");
     const int t = threadIdx.x, w = t >> 6, lane = t & 63;
     const int n0 = (tile % g.gx) * BT, mt = (tile / g.gx) % g.gy, m0 = mt * BT, c = tile / (g.gx * g.gy);
-    const float* A = g.A + c * g.sA;
-    const float* B = g.B + c * g.sB;
+    // (a bf16 operand: the pointer is to 2-byte elements, chunk strides are counted in elements)
+    const float* A = A_BF ? reinterpret_cast<const float*>(reinterpret_cast<const uint16_t*>(g.A) + c * g.sA) : g.A + c * g.sA;
+    const float* B = B_BF ? reinterpret_cast<const float*>(reinterpret_cast<const uint16_t*>(g.B) + c * g.sB) : g.B + c * g.sB;
     const int wm = 32 * (w >> 1), wn = 32 * (w & 1);  // this wave's quarter of the tile
 
     floatx16 acc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-    float a_sum = 0.f;  // sum over K of the rounded A[row wm + lane % 32][.], this lane's half of the K values
+    // sum over K of the rounded A[row wm + lane % 32][.], this lane's half of the K values.  (Taking the row sums from
+    // a second MFMA against a matrix of ones instead was measured: the extra matrix instructions cost more than these
+    // conversions and additions.)
+    float a_sum = 0.f;
 
-    Stager<A_KC> sa;
-    Stager<B_KC> sb;
+    typedef typename StagerSel<A_KC, A_BF>::type SA;
+    typedef typename StagerSel<B_KC, B_BF>::type SB;
+    SA sa;
+    SB sb;
     sa.init(A, g.lda, m0, g.M, g.K, t);
     sb.init(B, g.ldb, n0, g.N, g.K, t);
     const int nblk = (g.K + BK - 1) / BK, last = nblk - 1;
     // Two K blocks of loads are in flight: while block kb is multiplied, kb + 1 is on its way in one register set
-    // and kb + 2 in the other (few workgroups share a CU at these shapes, so the latency has to be covered here).
-    // Blocks past the end are clamped to the last one (loaded again, never stored) rather than branched around.
-    float4 ra0[4], rb0[4], ra1[4], rb1[4];
+    // and kb + 2 in the other.  Blocks past the end are clamped to the last one (loaded again, never stored) rather
+    // than branched around.  (Splitting the K range over two groups of waves that add their partial tiles at the end
+    // was measured and is slower: the launches are bound by what a CU can pull and convert per unit of time, not by
+    // the length of a tile's loop.)
+    typename SA::Reg ra0, ra1;
+    typename SB::Reg rb0, rb1;
     sa.issue(0, ra0);
     sb.issue(0, rb0);
     sa.issue(1 < nblk ? 1 : last, ra1);
     sb.issue(1 < nblk ? 1 : last, rb1);
     auto multiply = [&](const __bf16* As, const __bf16* Bs) {
         // lane feeds row (column) lane % 32 of its quarter and K values 16 s + 8 (lane / 32) .. + 7 of MFMA s
-        const __bf16* ap = As + (wm + (lane & 31)) * PITCH + 8 * (lane >> 5);
-        const __bf16* bp = Bs + (wn + (lane & 31)) * PITCH + 8 * (lane >> 5);
+        const uint32_t* a32 = reinterpret_cast<const uint32_t*>(As);
+        const uint32_t* b32 = reinterpret_cast<const uint32_t*>(Bs);
+        const int ra = wm + (lane & 31), rb = wn + (lane & 31), w0 = 4 * (lane >> 5);
 #pragma unroll
         for (int s = 0; s < BK / 16; ++s) {
-            const bf16x8 pa = *reinterpret_cast<const bf16x8*>(ap + 16 * s);
-            const bf16x8 pb = *reinterpret_cast<const bf16x8*>(bp + 16 * s);
+            const bf16x8 pa = *reinterpret_cast<const bf16x8*>(a32 + lds_word(ra, w0 + 8 * s));
+            const bf16x8 pb = *reinterpret_cast<const bf16x8*>(b32 + lds_word(rb, w0 + 8 * s));
             if (WANT_ASUM) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a_sum += (float)pa[e];
@@ -210,9 +317,10 @@ __device__ __forceinline__ void bf_tile(const GemmArgs& g, int tile, __bf16 (*ld
                 out = d > 0.f ? coef * rcp_refined(d) : 0.f;
             }
             C[(int64_t)gm * g.ldc + gn] = out;
-        } else if (EPI == EPI_L2_DO || EPI == EPI_L2_DN) {
-            const float xv = g.X[c * g.sX + (int64_t)gm * g.ldx + gn];
-            C[(int64_t)gm * g.ldc + gn] = s - rs * round_bf16(xv);
+        } else if (EPI == EPI_L2_DN) {
+            // the rows of the correction term are the bf16 rows that went into the products
+            const uint16_t xb = reinterpret_cast<const uint16_t*>(g.X)[c * g.sX + (int64_t)gm * g.ldx + gn];
+            C[(int64_t)gm * g.ldc + gn] = s - rs * __builtin_bit_cast(float, (uint32_t)xb << 16);
         } else {
             const int64_t hid = clamp_id(sv.h[bi], g.n_ent), tid = clamp_id(sv.t[bi], g.n_ent);
             const int64_t aid = head ? tid : hid, cid = head ? hid : tid;
@@ -250,23 +358,23 @@ __device__ __forceinline__ void bf_tile(const GemmArgs& g, int tile, __bf16 (*ld
 
 template <int EPI>
 __global__ __launch_bounds__(THREADS) void k_gemm_bf_fwd(GemmArgs g) {
-    __shared__ __attribute__((aligned(16))) __bf16 lds[2][2][BT * PITCH];
+    __shared__ __attribute__((aligned(16))) __bf16 lds[2][2][BT * PITCH];  // [buffer][operand]
     const int tile = xcd_tile(blockIdx.x >> 3, gridDim.x >> 3);
     if (tile >= g.tiles) return;
-    bf_tile<true, true, EPI>(g, tile, lds);
+    bf_tile<true, true, EPI, true, true>(g, tile, lds);
 }
 
 // dO tiles first: their K is the number of corrupting rows per chunk, the longer loop at these shapes
 template <int EPI_O, int EPI_N>
 __global__ __launch_bounds__(THREADS) void k_gemm_bf_bwd(GemmArgs gO, GemmArgs gN, int per_xcd_o, int per_xcd_n) {
-    __shared__ __attribute__((aligned(16))) __bf16 lds[2][2][BT * PITCH];
+    __shared__ __attribute__((aligned(16))) __bf16 lds[2][2][BT * PITCH];  // [buffer][operand]
     const int q = blockIdx.x >> 3;
     if (q < per_xcd_o) {
         const int tile = xcd_tile(q, per_xcd_o);
-        if (tile < gO.tiles) bf_tile<true, false, EPI_O>(gO, tile, lds);
+        if (tile < gO.tiles) bf_tile<true, false, EPI_O, false, true>(gO, tile, lds);
     } else {
         const int tile = xcd_tile(q - per_xcd_o, per_xcd_n);
-        if (tile < gN.tiles) bf_tile<false, false, EPI_N>(gN, tile, lds);
+        if (tile < gN.tiles) bf_tile<false, false, EPI_N, false, true>(gN, tile, lds);
     }
 }
 

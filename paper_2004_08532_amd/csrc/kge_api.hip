@@ -264,6 +264,9 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t o_ek0 = take(EK * 4), o_ek1 = take(EK * 4), o_ep0 = take(EK * 4), o_ep1 = take(EK * 4);
     const size_t o_rk0 = take(B * 4), o_rk1 = take(B * 4), o_rp0 = take(B * 4), o_rp1 = take(B * 4);
     const size_t o_flags = take(256), o_step = take(256);
+    c->ld_bf = (cfg->ent_dim + 7) / 8 * 8;
+    const bool bf = cfg->gemm_input == 1;
+    const size_t o_Obf = take(bf ? B * c->ld_bf * 2 + 64 : 0), o_Nbf = take(bf ? NR * c->ld_bf * 2 + 64 : 0);
     c->ws_bytes = (int64_t)off;
 
     hipError_t e = hipMalloc(&c->ws_base, off);
@@ -282,6 +285,8 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->epos[0] = (uint32_t*)(base + o_ep0); c->epos[1] = (uint32_t*)(base + o_ep1);
     c->rkey[0] = (uint32_t*)(base + o_rk0); c->rkey[1] = (uint32_t*)(base + o_rk1);
     c->rpos[0] = (uint32_t*)(base + o_rp0); c->rpos[1] = (uint32_t*)(base + o_rp1);
+    c->Obf = bf ? (uint16_t*)(base + o_Obf) : nullptr;
+    c->Nbf = bf ? (uint16_t*)(base + o_Nbf) : nullptr;
     c->flags = (int*)(base + o_flags);
     c->step_counter = (int64_t*)(base + o_step);
 

@@ -28,6 +28,9 @@ struct kge_ctx {
 
     float* O;        // [max_batch x D]      o_i
     float* Nst;      // [max_neg_rows x D]   gathered corrupting rows, chunk after chunk
+    uint16_t* Obf;   // bf16 operands only: o_i and the corrupting rows rounded to bf16, row pitch ld_bf (the products
+    uint16_t* Nbf;   // read these; Nst is then not written)
+    int ld_bf;       // D rounded up to 8
     float* S;        // [max_batch x ld_s]   negative scores, then backward coefficients W
     float* GO;       // [max_batch x D]      dL/do_i
     float* Gent;     // [max_ent_keys x D]   gradient rows in key order: heads | tails | corrupting rows
