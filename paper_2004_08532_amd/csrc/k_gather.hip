@@ -31,6 +31,7 @@ struct GatherArgs {
     float* cpos;      // dL/df+_i = -sigmoid(-f+_i) / b
     float* inv_dpos;  // TransE-L2: 1 / |o_i - c_i| (0 if the distance is 0)
     float* row_loss;  // softplus(-f+_i) / b
+    int32_t* rank_out;  // evaluation with ranks counted by the forward launch: set to 1 here (else null)
     int rank_blocks;         // blocks [0, rank_blocks) order the key lists, the others gather rows
     int ent_rank_blocks;     // the first ent_rank_blocks of them order the entity key list, the rest the relation keys
     uint64_t bucket_mul;     // long entity lists: bucket of an id = (id * bucket_mul) >> 32 (0: brute-force blocks)
@@ -368,6 +369,7 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
         else f = acc;
         a.fpos[i] = f;
         if (a.pos_out) a.pos_out[i] = f;
+        if (a.rank_out) a.rank_out[i] = 1;
         if (MODEL == KGE_TRANSE_L2) {
             a.o_n2[i] = on;
             a.inv_dpos[i] = acc > 0.f ? 1.f / sqrtf(acc) : 0.f;
@@ -438,7 +440,7 @@ void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds
     a.gamma = gamma; a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
     a.Obf = c->Obf; a.Nbf = c->Nbf; a.ld_bf = c->ld_bf;
     a.O = c->O; a.Nst = c->Nst; a.fpos = c->fpos; a.pos_out = pos_out; a.o_n2 = c->o_n2; a.n_n2 = c->n_n2;
-    a.cpos = c->cpos; a.inv_dpos = c->inv_dpos; a.row_loss = c->row_loss;
+    a.cpos = c->cpos; a.inv_dpos = c->inv_dpos; a.row_loss = c->row_loss; a.rank_out = c->rank_out;
     const int model = c->cfg.model;
     const bool cplx = model == KGE_COMPLEX || model == KGE_ROTATE;
     const int nvec = cplx ? a.D / 8 : a.D / 4;

@@ -234,6 +234,23 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         const int e = threadIdx.x + it * NW * 64;
         const int i = e >> 5, j = e & 31;
         const int gm = m0 + i, gn = n0 + j;
+        if (IS_FWD && g.out_mode == OUT_RANK) {
+            // evaluation: nothing is stored; rank_i = 1 + #{j : f-_ij > f+_i}.  The 32 consecutive lanes that hold the
+            // row's columns of this tile count them and add the count to the row's rank (integer atomics, any order).
+            const bool in = gm < g.M && gn < g.N;
+            const int row = gm < g.M ? gm : 0, col = gn < g.N ? gn : 0;
+            float f = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < NW; ++ww) f += lds[ww][0][e];
+            if (EPI == EPI_L2_FWD) {
+                const float d2 = g.rowv[c * g.s_rowv + row] + g.colv[c * g.s_colv + col] - 2.f * f;
+                f = g.gamma - sqrtf(fmaxf(d2, 0.f));
+            }
+            const unsigned long long m = __ballot(in && f > g.fpos[c * g.M + row]);
+            const int cnt = __popcll(lane < 32 ? (m & 0xffffffffull) : (m >> 32));
+            if ((lane & 31) == 0 && gm < g.M && cnt > 0) atomicAdd(&g.rank[c * g.M + gm], cnt);
+            continue;
+        }
         if (gm >= g.M || gn >= g.N) continue;
         const int bi = c * g.M + gm;  // index of the positive in the mini-batch (chain epilogues)
         float s = 0.f;
@@ -353,7 +370,8 @@ void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st
 
 // S_c = O_c N_c^T with the model's epilogue.  out_mode: 0 the scores (kge_score path); 1 what the loss kernel wants
 // (TransE-L2: the distances, else the scores); 2 the backward coefficients W of uniformly weighted negatives, with
-// the tiles' loss sums in neg_loss_part (training steps without a loss kernel).
+// the tiles' loss sums in neg_loss_part (training steps without a loss kernel); 3 nothing is stored, the ranks of the
+// positives are counted into c->rank_out (only where kge_gemm_forward_can_rank says so).
 void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* out, int ld_out, int out_mode,
                         hipStream_t st) {
     const int D = c->cfg.ent_dim;
@@ -365,6 +383,7 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     g.rowv = c->o_n2; g.colv = c->n_n2; g.s_rowv = gsz; g.s_colv = k;
     g.gamma = gamma; g.out_mode = out_mode;
     g.wk = 1.f / ((float)k * (float)b); g.neg_loss_part = c->neg_loss_part;
+    g.fpos = c->fpos; g.rank = c->rank_out;
     const int chunks = b / gsz;
     const bool bf = c->cfg.gemm_input == 1;
     const int epi = c->cfg.model == KGE_TRANSE_L2 ? EPI_L2_FWD : EPI_PLAIN;
@@ -377,6 +396,9 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     else if (epi == EPI_L2_FWD) launch_fwd<EPI_L2_FWD>(c, g, chunks, st);
     else launch_fwd<EPI_PLAIN>(c, g, chunks, st);
 }
+
+// Evaluation: can the forward launch count the ranks itself (out_mode 3) instead of storing the scores?
+bool kge_gemm_forward_can_rank(const kge_ctx* c) { return c->cfg.gemm_input == 0; }
 
 // Logistic loss with uniform negative weights: the forward launch stores W and the loss sums, and no loss kernel
 // runs.  (The ranking loss couples a positive with all of its negatives, so it always takes the loss kernel.)

@@ -9,7 +9,8 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 enum { EPI_PLAIN = 0, EPI_L2_FWD = 1, EPI_L2_DO = 2, EPI_L2_DN = 3, EPI_CHAIN_L2 = 4, EPI_CHAIN_DM = 5 };
-enum { OUT_SCORE = 0, OUT_DIST = 1, OUT_W = 2 };  // what the forward launch stores (see kge_gemm_neg_score)
+// what the forward launch leaves behind (see kge_gemm_neg_score); OUT_RANK: nothing but the ranks of the positives
+enum { OUT_SCORE = 0, OUT_DIST = 1, OUT_W = 2, OUT_RANK = 3 };
 
 struct GemmArgs {
     const float* A;
@@ -30,6 +31,8 @@ struct GemmArgs {
     // A-operand transform (uniform negative weights): W = wk * sigmoid(f) [/ distance]
     float wk;            // 1 / (k b)
     float* neg_loss_part;  // [forward tiles] OUT_W: sum of wk * softplus(f-) over the tile
+    const float* fpos;     // OUT_RANK: scores of the positives
+    int32_t* rank;         // OUT_RANK: [b], set to 1 beforehand; gets + #{j : f-_ij > f+_i}
     // chain-rule epilogues
     StepIds ids;
     const float* E;

@@ -445,8 +445,15 @@ int kge_rank(kge_ctx* c, const float* ent, const float* rel,
     KGE_HIP(c, hipSetDevice(c->cfg.device));
     const StepIds ids = direct_ids(h, r, t, (int)b, neg, (int)((b / chunk) * k), neg_side, nullptr);
     hipStream_t st = (hipStream_t)hip_stream;
-    forward(c, ent, rel, ids, (int)k, (int)chunk, gamma, nullptr, c->S, c->ld_s, 0, st);
-    kge_launch_rank(c, (int)b, (int)k, rank_out, st);
+    if (is_gemm_model(c->cfg.model) && kge_gemm_forward_can_rank(c)) {
+        // the gather launch sets every rank to 1, the forward launch adds the candidates that score higher
+        c->rank_out = rank_out;
+        forward(c, ent, rel, ids, (int)k, (int)chunk, gamma, nullptr, c->S, c->ld_s, 3, st);
+        c->rank_out = nullptr;
+    } else {
+        forward(c, ent, rel, ids, (int)k, (int)chunk, gamma, nullptr, c->S, c->ld_s, 0, st);
+        kge_launch_rank(c, (int)b, (int)k, rank_out, st);
+    }
     KGE_HIP(c, hipGetLastError());
     return KGE_OK;
 }

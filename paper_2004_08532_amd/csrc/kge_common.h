@@ -48,6 +48,8 @@ struct kge_ctx {
     uint32_t* rkey[2];  // relation sort ping-pong
     uint32_t* rpos[2];
     int* flags;         // [0]: an id was out of range
+    int32_t* rank_out;  // kge_rank: where the running call wants the ranks (the gather launch sets them to 1, the
+                        // forward launch counts); null otherwise
 
     int ebuf, rbuf;                 // which ping-pong half holds the sorted result
     int64_t last_ent_keys, last_rel_keys;  // sizes of the last train step's key lists (0: none yet)
@@ -132,6 +134,7 @@ void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st);
 // a5: dL/do and the gradient rows of the corrupting entities
 void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const StepIds& ids, int k, int g, float gamma,
                            hipStream_t st);
+bool kge_gemm_forward_can_rank(const kge_ctx* c);  // evaluation without storing the scores (fp32 products)
 bool kge_gemm_backward_forms_w(const kge_ctx* c);     // the forward launch stores W and the loss sums (no k_loss)
 bool kge_gemm_backward_does_chain(const kge_ctx* c);  // the backward launch writes the positives' gradient rows
 int kge_gemm_loss_parts(const kge_ctx* c, int b, int k, int g);  // loss sums the forward launch leaves in neg_loss_part

@@ -131,6 +131,18 @@ def test_rescal_relations_that_fill_half_of_the_batch(kge):
         p.close()
 
 
+def test_training_shapes_with_thousands_of_tiles(kge):
+    """A score matrix of 1035 x 1219 per step (three chunks): thousands of 32 x 32 tiles, four waves per tile, ragged
+    edges in every dimension."""
+    for model in ("transe_l2", "distmult"):
+        w = ragged(model, n_entities=3001, batch=1035, chunk=345, neg_per_chunk=1219, steps=2)
+        p = Pair(w, kge)
+        try:
+            run_steps(p, configs.BatchStream(w), w.steps)
+        finally:
+            p.close()
+
+
 def test_tiny_config_20_steps(kge):
     """Configuration 'tiny': TransE-L2, dim 64, b 256, g 32, k 64, 20 steps: every step checked element by
     element, then the same 20 steps free-running from the same seed."""
@@ -338,14 +350,23 @@ def test_key_lists_of_medium_length_take_the_bucketed_ranking(kge, n_entities):
         p.close()
 
 
+EVAL_SHAPES = {  # "wide": a thousand candidates per positive, two chunks, ragged tiles
+    "narrow": dict(batch=180, chunk=60, neg_per_chunk=150),
+    "wide": dict(batch=1000, chunk=500, neg_per_chunk=1030),
+}
+
+
+@pytest.mark.parametrize("shape", list(EVAL_SHAPES))
 @pytest.mark.parametrize("model", MODELS)
-def test_evaluation_ranks_and_metrics(kge, model):
-    """Link-prediction evaluation: the rank of every positive among 2 x 150 sampled candidates (both sides), then
+def test_evaluation_ranks_and_metrics(kge, model, shape):
+    """Link-prediction evaluation: the rank of every positive among sampled candidates (both sides), then
     Hit@k / MR / MRR.  A rank is an integer decided by comparing fp32 scores; candidates whose oracle score lies
     within the score tolerance of the positive's could fall on either side, so the rank must lie between the
     counts with those candidates excluded and included, and equals the oracle's rank when there are none.  The
     metrics kernel is checked exactly against the oracle's formulas on the device's own ranks."""
-    w = ragged(model, n_entities=2003, batch=180, chunk=60, neg_per_chunk=150, name="eval-" + model)
+    if shape == "wide" and model == "rescal":
+        pytest.skip("the oracle needs minutes for a million pairs of 72 x 72 matrices; the products are DistMult's")
+    w = ragged(model, n_entities=2003, name="eval-" + model, **EVAL_SHAPES[shape])
     # tables eight times the initialisation range: scores of an untrained model at the usual range lie so close
     # together that most ranks would hinge on differences below the score tolerance
     E, R = configs.init_tables(w)
@@ -371,7 +392,8 @@ def test_evaluation_ranks_and_metrics(kge, model):
             assert np.array_equal(got[clear], oracle.ranks(opos, oneg)[clear])
             unambiguous += int(clear.sum())
             all_ranks.append(dr)
-        assert unambiguous >= 0.9 * 2 * w.batch
+        # (with a thousand candidates per positive more ranks have a candidate within the tolerance of the positive)
+        assert unambiguous >= (0.9 if shape == "narrow" else 0.4) * 2 * w.batch
         ranks = torch.cat(all_ranks)
         m = torch.zeros(5, dtype=torch.float64, device="cuda")
         kge.kge_rank_metrics(ranks, m)
