@@ -143,6 +143,19 @@ def test_training_shapes_with_thousands_of_tiles(kge):
             p.close()
 
 
+@pytest.mark.parametrize("b,g,k", [(1, 1, 1), (3, 1, 2), (2, 2, 1)])
+@pytest.mark.parametrize("model", MODELS)
+def test_smallest_batches(kge, model, b, g, k):
+    """One positive with one negative; chunks of a single positive; a chunk with a single negative: every launch
+    is a fraction of one tile, every key list a handful of keys."""
+    w = ragged(model, batch=b, chunk=g, neg_per_chunk=k, steps=2)
+    p = Pair(w, kge)
+    try:
+        run_steps(p, configs.BatchStream(w), w.steps, check_dedup_at=(0, 1))
+    finally:
+        p.close()
+
+
 def test_tiny_config_20_steps(kge):
     """Configuration 'tiny': TransE-L2, dim 64, b 256, g 32, k 64, 20 steps: every step checked element by
     element, then the same 20 steps free-running from the same seed."""
