@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--workload", default="freebase-transe_l2")
     ap.add_argument("--entities", type=int, default=0, help="override the entity count (debugging)")
     ap.add_argument("--profile-steps", type=int, default=500)
-    ap.add_argument("--cpu-steps", type=int, default=8)
+    ap.add_argument("--cpu-steps", type=int, default=48)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rowwise-state", action="store_true",
                     help="Adagrad with one accumulator per row (adagrad_mode 1) instead of the element-wise state")

@@ -31,10 +31,72 @@ struct LossArgs {
     int bf16;
     float* cpos;
     float* row_loss;
-    float* w_rowsum;
 };
 
+// VPL: values per lane (the row's k scores live in registers: one pass over memory in, one out; all loads of a row
+// are in flight together and every exponential is taken once).
+template <int VPL>
 __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= a.b) return;
+    float* s = a.S + (int64_t)i * a.ld_s;
+    const float invb = 1.f / (float)a.b;
+    const float fp = a.fpos[i];
+    const int k = a.k;
+
+    float raw[VPL], f[VPL], e[VPL];
+#pragma unroll
+    for (int u = 0; u < VPL; ++u) {
+        const int j = lane + 64 * u;
+        raw[u] = s[j < k ? j : 0];
+    }
+    float mx = -INFINITY, z = 1.f;
+#pragma unroll
+    for (int u = 0; u < VPL; ++u) {
+        f[u] = a.is_dist ? a.gamma - raw[u] : raw[u];
+        if (lane + 64 * u < k) mx = fmaxf(mx, a.alpha * f[u]);
+    }
+    if (a.alpha > 0.f) {
+        mx = wave_max(mx);
+        float zz = 0.f;
+#pragma unroll
+        for (int u = 0; u < VPL; ++u) {
+            e[u] = expf(a.alpha * f[u] - mx);
+            if (lane + 64 * u < k) zz += e[u];
+        }
+        z = wave_sum(zz);
+    }
+    float li = 0.f, active = 0.f;
+#pragma unroll
+    for (int u = 0; u < VPL; ++u) {
+        const int j = lane + 64 * u;
+        if (j >= k) continue;
+        const float w = a.alpha > 0.f ? e[u] / z : 1.f / (float)k;
+        float coef;
+        if (a.ranking) {
+            const float m = a.gamma - fp + f[u];
+            li += w * fmaxf(m, 0.f);
+            coef = m > 0.f ? w * invb : 0.f;
+            active += m > 0.f ? w : 0.f;
+        } else {
+            li += w * softplusf_(f[u]);
+            coef = w * sigmoidf_(f[u]) * invb;
+        }
+        if (a.is_dist) coef = raw[u] > 0.f ? coef / raw[u] : 0.f;
+        if (a.bf16) coef = round_bf16(coef);  // what the product kernels multiply with
+        s[j] = coef;
+    }
+    li = wave_sum(li);
+    if (a.ranking) active = wave_sum(active);
+    if (lane == 0) {
+        a.row_loss[i] = a.ranking ? li * invb : (softplusf_(-fp) + li) * invb;
+        a.cpos[i] = a.ranking ? -active * invb : -sigmoidf_(-fp) * invb;
+    }
+}
+
+// rows longer than 1024 scores: the same with three passes over memory
+__global__ __launch_bounds__(256) void k_loss_long(LossArgs a) {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (i >= a.b) return;
@@ -57,7 +119,7 @@ __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
         }
         z = wave_sum(zz);
     }
-    float li = 0.f, rs = 0.f, active = 0.f;
+    float li = 0.f, active = 0.f;
     for (int j = lane; j < k; j += 64) {
         const float raw = s[j];
         const float f = a.is_dist ? a.gamma - raw : raw;
@@ -73,17 +135,14 @@ __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
             coef = w * sigmoidf_(f) * invb;
         }
         if (a.is_dist) coef = raw > 0.f ? coef / raw : 0.f;
-        if (a.bf16) coef = round_bf16(coef);  // what the product kernels multiply with
+        if (a.bf16) coef = round_bf16(coef);
         s[j] = coef;
-        rs += coef;
     }
     li = wave_sum(li);
-    rs = wave_sum(rs);
     if (a.ranking) active = wave_sum(active);
     if (lane == 0) {
         a.row_loss[i] = a.ranking ? li * invb : (softplusf_(-fp) + li) * invb;
         a.cpos[i] = a.ranking ? -active * invb : -sigmoidf_(-fp) * invb;
-        a.w_rowsum[i] = rs;
     }
 }
 
@@ -264,8 +323,12 @@ void kge_launch_loss(kge_ctx* c, int b, int k, float gamma, hipStream_t st) {
     a.S = c->S; a.ld_s = c->ld_s; a.b = b; a.k = k; a.fpos = c->fpos; a.gamma = gamma;
     a.alpha = c->cfg.adv_temperature; a.is_dist = c->cfg.model == KGE_TRANSE_L2;
     a.bf16 = c->cfg.gemm_input; a.ranking = c->cfg.loss == KGE_LOSS_RANKING;
-    a.cpos = c->cpos; a.row_loss = c->row_loss; a.w_rowsum = c->w_rowsum;
-    KGE_LAUNCH(c, k_loss, dim3((b + 3) / 4), dim3(256), 0, st, a);
+    a.cpos = c->cpos; a.row_loss = c->row_loss;
+    const dim3 grid((b + 3) / 4);
+    const int vpl = (k + 63) / 64;
+    if (vpl <= 4) KGE_LAUNCH(c, k_loss<4>, grid, dim3(256), 0, st, a);
+    else if (vpl <= 16) KGE_LAUNCH(c, k_loss<16>, grid, dim3(256), 0, st, a);
+    else KGE_LAUNCH(c, k_loss_long, grid, dim3(256), 0, st, a);
 }
 
 void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st) {

@@ -259,7 +259,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t o_O = take(B * D * 4), o_N = take(NR * D * 4), o_S = take(B * c->ld_s * 4), o_GO = take(B * D * 4);
     const size_t o_Ge = take(EK * D * 4), o_Gr = take(B * (m == KGE_RESCAL ? 2 * D : Dr) * 4);  // RESCAL keeps two factor rows per positive
     const size_t o_fpos = take(B * 4), o_on2 = take(B * 4), o_nn2 = take(NR * 4), o_cpos = take(B * 4);
-    const size_t o_rl = take(B * 4), o_wrs = take(B * 4), o_idp = take(B * 4);
+    const size_t o_rl = take(B * 4), o_idp = take(B * 4);
     const size_t o_nlp = take((B / 32 + cfg->max_chunks + 1) * ((size_t)cfg->max_neg_per_chunk / 32 + 1) * 4);
     const size_t o_ek0 = take(EK * 4), o_ek1 = take(EK * 4), o_ep0 = take(EK * 4), o_ep1 = take(EK * 4);
     const size_t o_rk0 = take(B * 4), o_rk1 = take(B * 4), o_rp0 = take(B * 4), o_rp1 = take(B * 4);
@@ -279,7 +279,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->O = (float*)(base + o_O); c->Nst = (float*)(base + o_N); c->S = (float*)(base + o_S);
     c->GO = (float*)(base + o_GO); c->Gent = (float*)(base + o_Ge); c->Grel = (float*)(base + o_Gr);
     c->fpos = (float*)(base + o_fpos); c->o_n2 = (float*)(base + o_on2); c->n_n2 = (float*)(base + o_nn2);
-    c->cpos = (float*)(base + o_cpos); c->row_loss = (float*)(base + o_rl); c->w_rowsum = (float*)(base + o_wrs);
+    c->cpos = (float*)(base + o_cpos); c->row_loss = (float*)(base + o_rl);
     c->inv_dpos = (float*)(base + o_idp); c->neg_loss_part = (float*)(base + o_nlp);
     c->ekey[0] = (uint32_t*)(base + o_ek0); c->ekey[1] = (uint32_t*)(base + o_ek1);
     c->epos[0] = (uint32_t*)(base + o_ep0); c->epos[1] = (uint32_t*)(base + o_ep1);

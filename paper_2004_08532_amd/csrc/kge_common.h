@@ -40,7 +40,6 @@ struct kge_ctx {
     float* n_n2;     // [max_neg_rows]       |n_j|^2          (TransE-L2)
     float* cpos;     // [max_batch]          dL/df+_i
     float* row_loss; // [max_batch]          loss terms of positive i, already divided by b
-    float* w_rowsum; // [max_batch]          sum_j W_ij       (TransE-L2, self-adversarial path)
     float* inv_dpos; // [max_batch]          1 / |o_i - c_i|  (TransE-L2)
     float* neg_loss_part;  // [forward tiles]  negative-side loss sums written by the forward launch
     uint32_t* ekey[2];  // entity sort ping-pong: keys

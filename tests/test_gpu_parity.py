@@ -339,7 +339,9 @@ def test_zero_distance_pairs_have_zero_gradient(kge):
 def test_long_key_lists_take_the_radix_sort_path(kge):
     """More entity keys per step than the rank blocks take: the key lists are sorted by the radix kernel on the second stream
     instead of the rank blocks of the gather launch."""
-    w = ragged("distmult", n_entities=3001, ent_dim=16, rel_dim=16, batch=512, chunk=64, neg_per_chunk=2000, steps=2)
+    # (self-adversarial weights: rows of 2000 scores also take the loss kernel's variant for long rows)
+    w = ragged("distmult", n_entities=3001, ent_dim=16, rel_dim=16, batch=512, chunk=64, neg_per_chunk=2000, steps=2,
+               adv_temperature=1.0)
     assert 2 * w.batch + w.n_chunks * w.neg_per_chunk > 16384  # far above the switch-over
     p = Pair(w, kge)
     try:
@@ -353,8 +355,9 @@ def test_key_lists_of_medium_length_take_the_bucketed_ranking(kge, n_entities):
     """Between 6,144 and 14,336 entity keys the gather launch ranks them bucket by bucket.  With 401 entities every id
     occurs about 20 times (ties are broken by position, buckets hold one id each and some are empty); with 200,003
     most ids are distinct and a bucket holds a few hundred different ids."""
+    # (one of the two with self-adversarial weights: rows of 550 scores, 9 per lane of the loss kernel)
     w = ragged("distmult", n_entities=n_entities, ent_dim=16, rel_dim=16, batch=768, chunk=64, neg_per_chunk=550,
-               steps=2)
+               steps=2, adv_temperature=1.0 if n_entities == 401 else 0.0)
     assert 6144 <= 2 * w.batch + w.n_chunks * w.neg_per_chunk <= 14336
     p = Pair(w, kge)
     try:
