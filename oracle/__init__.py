@@ -17,11 +17,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "kge_oracle.c")
 _LIB = os.path.join(_HERE, "libkge_oracle.so")
 
-TRANSE_L2, TRANSE_L1, DISTMULT, COMPLEX, ROTATE, RESCAL = 0, 1, 2, 3, 4, 5
+TRANSE_L2, TRANSE_L1, DISTMULT, COMPLEX, ROTATE, RESCAL, TRANSR = 0, 1, 2, 3, 4, 5, 6
 NEG_TAIL, NEG_HEAD = 0, 1
 LOSS_IDS = {"logistic": 0, "ranking": 1}
 MODEL_IDS = {"transe_l2": TRANSE_L2, "transe_l1": TRANSE_L1, "distmult": DISTMULT, "complex": COMPLEX,
-             "rotate": ROTATE, "rescal": RESCAL}
+             "rotate": ROTATE, "rescal": RESCAL, "transr": TRANSR}
 
 
 def build(force: bool = False) -> str:

@@ -6,7 +6,7 @@
  * build, load or call it.  It shares no code, header, table or helper with the GPU library.
  *
  * What it computes (paper sections in brackets):
- *   - the score of a triple (h, r, t) for TransE (L1 or L2), DistMult, ComplEx, RotatE and RESCAL  [Table 1]
+ *   - the score of a triple (h, r, t) for TransE (L1 or L2), TransR, DistMult, ComplEx, RotatE and RESCAL  [Table 1]
  *   - negatives obtained by replacing the head or the tail of a positive triple              [Sec. 2]
  *   - joint negative sampling: positives are grouped into consecutive sets of size g and all members of a
  *     set share the same k corrupting entities                                               [Sec. 3.3]
@@ -26,7 +26,10 @@
  *   - RotatE uses gamma - sum_j |h_j r_j - t_j| (modulus per complex coordinate); the literally printed
  *     squared norm is available through rotate_squared
  *   - a row of ComplEx / RotatE entities is [real parts | imaginary parts]; a RotatE relation row holds
- *     phases in radians; a RESCAL relation row holds the D x D matrix M_r row by row (rel_dim = D * D)
+ *     phases in radians; a RESCAL relation row holds the D x D matrix M_r row by row (rel_dim = D * D); a TransR
+ *     relation row holds the translation r (D numbers) followed by the D x D projection M_r row by row
+ *     (rel_dim = D + D * D: relations live in a space of the entities' dimension)
+ *   - TransR is used as printed in Table 1, with the squared norm: f = gamma - |M_r h + r - M_r t|_2^2
  *   - loss = (1/b) sum_i [ softplus(-f+_i) + sum_j w_ij softplus(f-_ij) ],  w_ij = 1/k, or the softmax over
  *     j of (adv_temperature * f-_ij) treated as a constant when adv_temperature > 0
  *   - ranking loss = (1/b) sum_i sum_j w_ij max(0, gamma - f+_i + f-_ij): every positive is paired with its own k
@@ -51,7 +54,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-enum { KO_TRANSE_L2 = 0, KO_TRANSE_L1 = 1, KO_DISTMULT = 2, KO_COMPLEX = 3, KO_ROTATE = 4, KO_RESCAL = 5 };
+enum { KO_TRANSE_L2 = 0, KO_TRANSE_L1 = 1, KO_DISTMULT = 2, KO_COMPLEX = 3, KO_ROTATE = 4, KO_RESCAL = 5, KO_TRANSR = 6 };
 enum { KO_NEG_TAIL = 0, KO_NEG_HEAD = 1 };
 enum { KO_LOSS_LOGISTIC = 0, KO_LOSS_RANKING = 1 };
 
@@ -154,6 +157,15 @@ static double score_triple(const ko_params *p, const double *h, const double *r,
         for (int a = 0; a < D; ++a)
             for (int c = 0; c < D; ++c) acc += h[a] * r[(int64_t)a * D + c] * t[c];
         return acc;
+    case KO_TRANSR: { /* u = M h + r - M t, M[a][c] = r[D + a * D + c]; gamma - |u|^2 */
+        const double *M = r + D;
+        for (int a = 0; a < D; ++a) {
+            double u = r[a];
+            for (int c = 0; c < D; ++c) u += M[(int64_t)a * D + c] * (h[c] - t[c]);
+            acc += u * u;
+        }
+        return p->gamma - acc;
+    }
     default: return NAN;
     }
 }
@@ -232,6 +244,21 @@ static void grad_triple(const ko_params *p, const double *h, const double *r, co
                 gr[(int64_t)a * D + c] += coef * h[a] * t[c];
             }
         return;
+    case KO_TRANSR: { /* f = gamma - sum_a u_a^2, u = M (h - t) + r:  df/du_a = -2 u_a */
+        const double *M = r + D;
+        for (int a = 0; a < D; ++a) {
+            double u = r[a];
+            for (int c = 0; c < D; ++c) u += M[(int64_t)a * D + c] * (h[c] - t[c]);
+            const double e = -2.0 * u * coef;
+            gr[a] += e;
+            for (int c = 0; c < D; ++c) {
+                gh[c] += e * M[(int64_t)a * D + c];
+                gt[c] -= e * M[(int64_t)a * D + c];
+                gr[D + (int64_t)a * D + c] += e * (h[c] - t[c]);
+            }
+        }
+        return;
+    }
     default: return;
     }
 }
@@ -312,6 +339,21 @@ static void grad_triple_mag(const ko_params *p, const double *h, const double *r
                 mr[(int64_t)a * D + c] += ac * fabs(h[a] * t[c]);
             }
         return;
+    case KO_TRANSR: { /* magnitudes of the terms of u_a, times the factors they are multiplied with */
+        const double *M = r + D;
+        for (int a = 0; a < D; ++a) {
+            double T = fabs(r[a]);
+            for (int c = 0; c < D; ++c) T += fabs(M[(int64_t)a * D + c]) * (fabs(h[c]) + fabs(t[c]));
+            const double e = 2.0 * T * ac;
+            mr[a] += e;
+            for (int c = 0; c < D; ++c) {
+                mh[c] += e * fabs(M[(int64_t)a * D + c]);
+                mt[c] += e * fabs(M[(int64_t)a * D + c]);
+                mr[D + (int64_t)a * D + c] += e * (fabs(h[c]) + fabs(t[c]));
+            }
+        }
+        return;
+    }
     default: return;
     }
 }
@@ -488,6 +530,8 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
     if (b <= 0 || chunk <= 0 || b % chunk != 0 || k < 0) return -1;
     if ((p->model == KO_COMPLEX || p->model == KO_ROTATE) && (p->ent_dim % 2)) return -1;
     if (p->model == KO_RESCAL && p->rel_dim != p->ent_dim * p->ent_dim) return -1;
+    if (p->model == KO_TRANSR && p->rel_dim != p->ent_dim + p->ent_dim * p->ent_dim) return -1;
+    if (p->model == KO_TRANSR && (p->bf16_inputs || p->split_form)) return -1; /* its pairs do not split into (o, n) */
     const int De = p->ent_dim, Dr = p->rel_dim, f64 = p->tables_f64;
     const int head_side = p->neg_side == KO_NEG_HEAD;
     const int use_split = p->bf16_inputs || p->split_form;

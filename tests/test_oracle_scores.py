@@ -208,3 +208,23 @@ def test_rescal_with_diagonal_matrices_is_distmult():
             np.testing.assert_allclose(m["dE"], a["dE"], rtol=1e-10, atol=1e-12)
             diag = m["dR"].reshape(-1, D, D)[:, np.arange(D), np.arange(D)]
             np.testing.assert_allclose(diag, a["dR"], rtol=1e-10, atol=1e-12)
+
+
+def test_transr_with_identity_projections_is_the_squared_transe_distance():
+    """M_r = identity: gamma - f_TransR = |h + r - t|^2 = (gamma - f_TransE-L2)^2, for positives and negatives on both
+    sides; and projecting both entities with the same matrix makes the score invariant under a common shift of h and t
+    (M (h + s) - M (t + s) = M h - M t), whatever the matrix."""
+    rng = np.random.default_rng(12)
+    E, R, h, r, t, neg, chunk, k = _rand_problem("transe_l2", rng)
+    D = E.shape[1]
+    Rt = np.concatenate([R, np.tile(np.eye(D).reshape(-1), (R.shape[0], 1))], axis=1)
+    for side in (0, 1):
+        p2, n2 = oracle.scores("transe_l2", E, R, h, r, t, neg, k, chunk, side, 3.0)
+        pr, nr = oracle.scores("transr", E, Rt, h, r, t, neg, k, chunk, side, 3.0)
+        np.testing.assert_allclose(3.0 - pr, (3.0 - p2) ** 2, rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(3.0 - nr, (3.0 - n2) ** 2, rtol=1e-12, atol=1e-12)
+    Rm = np.concatenate([R, rng.normal(size=(R.shape[0], D * D))], axis=1)
+    a = oracle.scores("transr", E, Rm, h, r, t, neg, k, chunk, 0, 3.0)
+    b = oracle.scores("transr", E + rng.normal(size=(1, D)), Rm, h, r, t, neg, k, chunk, 0, 3.0)
+    np.testing.assert_allclose(a[0], b[0], rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(a[1], b[1], rtol=1e-10, atol=1e-10)
