@@ -68,15 +68,17 @@ def algorithmic_work(w, h, r, t, neg, rowwise=False):
     pair_fwd = {"rotate": 6.0, "transe_l1": 3.0}.get(w.model)
     pair_bwd = {"rotate": 2 * 9.0, "transe_l1": 2 * 3.0}.get(w.model)
     coords = D // 2 if w.model == "rotate" else D
-    rescal = w.model == "rescal"  # relation rows are D x D matrices, read by their own kernels (phi, chain)
+    rescal = w.model in ("rescal", "transr")  # relation rows hold D x D matrices, read by their own kernels
+    transr = w.model == "transr"  # three products batched over the positives, 2 b k D^2 flops each
     return {
         "gather": {"bytes": 4.0 * ((2 * b + C * k) * D + (0 if rescal else b * Dr)) + 4.0 * (b + C * k) * D},
         "phi": {"bytes": 4.0 * b * (Dr + 2 * D)},
         "rel_update": {"bytes": ur * 16.0 * Dr + 8.0 * b * D},
         "update": {"bytes": ue * (8.0 * D + 8.0 if rowwise else 16.0 * D) + n_keys * 4.0 * D +
                             (0 if rescal else ur * (8.0 * Dr + 8.0 if rowwise else 16.0 * Dr) + b * 4.0 * Dr)},
-        "neg_score": {"flops": pair_fwd * b * k * coords if pair_fwd else 2.0 * b * k * D},
-        "neg_backward": {"flops": pair_bwd * b * k * coords if pair_bwd else 4.0 * b * k * D},
+        "neg_score": {"flops": pair_fwd * b * k * coords if pair_fwd else 2.0 * b * k * D * (D if transr else 1)},
+        "neg_backward": {"flops": pair_bwd * b * k * coords if pair_bwd else
+                         (2.0 * b * k * D * D if transr else 4.0 * b * k * D)},
         "chain": {"bytes": 4.0 * (8 * b * D + b * Dr) if rescal else 4.0 * (6 * b * D + 2 * b * Dr)},
         "loss": {"bytes": 8.0 * b * k},
         "sort": {"bytes": 8.0 * (n_keys + b)},
@@ -192,7 +194,7 @@ def main():
         ms, nsteps = ctx.profile_read()
         ctx.profile(False)
         work = algorithmic_work(w, h[W + K:], r[W + K:], t[W + K:], neg[W + K:], args.rowwise_state)
-        gemm = w.model in ("transe_l2", "distmult", "complex", "rescal")
+        gemm = w.model in ("transe_l2", "distmult", "complex", "rescal", "transr")
         for name, total_ms in ms.items():
             avg_us = 1e3 * total_ms / max(nsteps, 1)
             ent = {"avg_us": avg_us}

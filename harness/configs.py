@@ -17,7 +17,7 @@ from . import graphs, sampler
 @dataclasses.dataclass(frozen=True)
 class Workload:
     name: str
-    model: str               # transe_l2 | transe_l1 | distmult | complex | rotate | rescal
+    model: str               # transe_l2 | transe_l1 | distmult | complex | rotate | rescal | transr
     n_entities: int
     n_relations: int
     n_triples: int           # size of the synthetic triple list (0: positives are drawn directly, not stored)
@@ -53,6 +53,8 @@ SMALL_DISTMULT = Workload("small-distmult", "distmult", 14_951, 1_345, 483_142, 
 SMALL_COMPLEX = SMALL_DISTMULT.scaled(name="small-complex", model="complex")
 # RESCAL at the same graph and batch shape, rows of 200 floats: a relation row is a 200 x 200 matrix
 SMALL_RESCAL = SMALL_DISTMULT.scaled(name="small-rescal", model="rescal", ent_dim=200, rel_dim=200 * 200)
+# TransR at the same graph and batch shape, rows of 100 floats: a relation row is a translation and a 100 x 100 matrix
+SMALL_TRANSR = SMALL_DISTMULT.scaled(name="small-transr", model="transr", ent_dim=100, rel_dim=100 + 100 * 100)
 MEDIUM = Workload("medium", "rotate", 2_500_000, 800, 16_000_000, 0.9, None, 400, 200, 1024, 128, 256, "degree",
                   "tail", 12.0, 0.1, adv_temperature=1.0, steps=1000)
 LARGE = Workload("large", "transe_l2", 5_000_000, 800, 20_000_000, 0.9, None, 400, 400, 2048, 256, 1024, "uniform",
@@ -61,7 +63,7 @@ FREEBASE_TRANSE = Workload("freebase-transe_l2", "transe_l2", 86_054_151, 14_824
                            200, "uniform", "tail", 12.0, 0.1, steps=100_000)
 FREEBASE_COMPLEX = FREEBASE_TRANSE.scaled(name="freebase-complex", model="complex")
 
-ALL = {w.name: w for w in (TINY, SMALL_DISTMULT, SMALL_COMPLEX, SMALL_RESCAL, MEDIUM, LARGE, FREEBASE_TRANSE,
+ALL = {w.name: w for w in (TINY, SMALL_DISTMULT, SMALL_COMPLEX, SMALL_RESCAL, SMALL_TRANSR, MEDIUM, LARGE, FREEBASE_TRANSE,
                            FREEBASE_COMPLEX)}
 
 

@@ -39,7 +39,9 @@ typedef enum {
     KGE_DISTMULT = 2,
     KGE_COMPLEX = 3,
     KGE_ROTATE = 4,
-    KGE_RESCAL = 5 /* h^T M_r t: a relation row is the ent_dim x ent_dim matrix M_r, row by row */
+    KGE_RESCAL = 5, /* h^T M_r t: a relation row is the ent_dim x ent_dim matrix M_r, row by row */
+    KGE_TRANSR = 6  /* gamma - |M_r h + r - M_r t|^2 (squared, as Table 1 prints it): a relation row is the
+                       translation r (ent_dim floats) followed by the ent_dim x ent_dim matrix M_r, row by row */
 } kge_model;
 
 /* Which entity of each positive is replaced to form its negatives (Sec. 2: only entities are corrupted). */
@@ -68,7 +70,7 @@ typedef struct {
     int64_t num_relations;     /* rows of the relation table (< 2^32)                                     */
     int32_t ent_dim;           /* floats per entity row: multiple of 4 (8 for ComplEx / RotatE), <= 1024  */
     int32_t rel_dim;           /* floats per relation row: ent_dim; ent_dim/2 for RotatE; ent_dim^2 for   */
-                               /* RESCAL                                                                  */
+                               /* RESCAL; ent_dim + ent_dim^2 for TransR                                  */
     int32_t max_batch;         /* largest b a call may pass                                               */
     int32_t max_neg_per_chunk; /* largest k                                                               */
     int32_t max_chunks;        /* largest b / chunk                                                       */

@@ -16,13 +16,13 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("KGE_LIBRARY", os.path.join(_HERE, "libkge.so"))  # KGE_LIBRARY: another build of the same library
 
-KGE_TRANSE_L2, KGE_TRANSE_L1, KGE_DISTMULT, KGE_COMPLEX, KGE_ROTATE, KGE_RESCAL = 0, 1, 2, 3, 4, 5
+KGE_TRANSE_L2, KGE_TRANSE_L1, KGE_DISTMULT, KGE_COMPLEX, KGE_ROTATE, KGE_RESCAL, KGE_TRANSR = 0, 1, 2, 3, 4, 5, 6
 KGE_NEG_TAIL, KGE_NEG_HEAD = 0, 1
 KGE_OK, KGE_ERR_INVALID_ARG, KGE_ERR_UNSUPPORTED, KGE_ERR_WORKSPACE, KGE_ERR_DEVICE, KGE_ERR_INDEX_RANGE = \
     0, -1, -2, -3, -4, -5
 LOSS_IDS = {"logistic": 0, "ranking": 1}
 MODEL_IDS = {"transe_l2": KGE_TRANSE_L2, "transe_l1": KGE_TRANSE_L1, "distmult": KGE_DISTMULT,
-             "complex": KGE_COMPLEX, "rotate": KGE_ROTATE, "rescal": KGE_RESCAL}
+             "complex": KGE_COMPLEX, "rotate": KGE_ROTATE, "rescal": KGE_RESCAL, "transr": KGE_TRANSR}
 
 EXPORTS = ("kge_create", "kge_destroy", "kge_train_step", "kge_train_steps", "kge_score", "kge_get_dedup",
            "kge_check_indices", "kge_last_error", "kge_workspace_bytes", "kge_profile", "kge_profile_read",
@@ -243,7 +243,8 @@ class KgeContext:
                  adagrad_eps=0.0, validate_indices=False, adagrad_mode=0, loss="logistic"):
         m = MODEL_IDS[model] if isinstance(model, str) else int(model)
         if rel_dim is None:
-            rel_dim = ent_dim // 2 if m == KGE_ROTATE else (ent_dim * ent_dim if m == KGE_RESCAL else ent_dim)
+            rel_dim = {KGE_ROTATE: ent_dim // 2, KGE_RESCAL: ent_dim * ent_dim,
+                       KGE_TRANSR: ent_dim + ent_dim * ent_dim}.get(m, ent_dim)
         if max_chunks is None:
             max_chunks = max_batch
         self.cfg = kge_config(m, int(device), int(num_entities), int(num_relations), int(ent_dim), int(rel_dim),

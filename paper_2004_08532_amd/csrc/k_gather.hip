@@ -274,6 +274,7 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
     }
 
     // ---- a positive: rows a (kept entity), r, c (the entity that the negatives replace)
+    if constexpr (MODEL == KGE_TRANSR) return;  // k_transr_phi has done the positives (they need the matrix)
     const int i = row;
     const int64_t hid = clamp_id(sv.h[i], a.n_ent), tid = clamp_id(sv.t[i], a.n_ent);
     const int64_t rid = clamp_id(sv.r[i], a.n_rel);
@@ -424,6 +425,7 @@ void launch_model(kge_ctx* c, GatherArgs& a, int nv, int rows, bool with_keys, c
     case KGE_DISTMULT: launch_nv<KGE_DISTMULT, THREADS>(c, a, nv, grid, lds, st); break;
     case KGE_COMPLEX: launch_nv<KGE_COMPLEX, THREADS>(c, a, nv, grid, lds, st); break;
     case KGE_RESCAL: launch_nv<KGE_RESCAL, THREADS>(c, a, nv, grid, lds, st); break;
+    case KGE_TRANSR: launch_nv<KGE_TRANSR, THREADS>(c, a, nv, grid, lds, st); break;
     default: launch_nv<KGE_ROTATE, THREADS>(c, a, nv, grid, lds, st); break;
     }
 }

@@ -129,7 +129,7 @@ __device__ __forceinline__ void lds_frag(const float* region, int lane, int q, f
 }
 
 // One 32x32 output tile: K loop, cross-wave sum, epilogue.
-template <int NW, bool A_KC, bool B_KC, int EPI, bool IS_DO>
+template <int NW, bool A_KC, bool B_KC, int EPI, bool IS_DO, int IND = IND_NONE>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*lds)[2][REGION]) {
     constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM;
     constexpr bool WANT_ASUM = EPI == EPI_L2_DO || EPI == EPI_L2_DN || EPI == EPI_CHAIN_L2;
@@ -139,6 +139,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     const int n0 = (tile % g.gx) * TILE, mt = (tile / g.gx) % g.gy, m0 = mt * TILE, c = tile / (g.gx * g.gy);
     const float* A = g.A + c * g.sA;
     const float* B = g.B + c * g.sB;
+    if (IND == IND_CHUNK_REL) A = g.A + (c / g.ind_g) * g.sA;
+    if (IND == IND_CHUNK_REL || IND == IND_ITEM_REL) {
+        const StepView sv = step_view(g.ids);
+        B = g.B + clamp_id(sv.r[c], g.n_rel) * g.sB + g.b_off;
+    }
+    if (IND == IND_ITEM_CHUNK) B = g.B + (c / g.ind_g) * g.sB;
     float* As = lds[w][0];
     float* Bs = lds[w][1];
 
@@ -328,6 +334,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4)))
     }
 }
 
+// One plain product per batch item, operands found as IND says (the TransR products).
+template <int NW, bool A_KC, bool B_KC, int IND>
+__global__ __launch_bounds__(NW * 64) void k_gemm_one(GemmArgs g) {
+    __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
+    const int tile = xcd_tile(blockIdx.x >> 3, gridDim.x >> 3);
+    if (tile >= g.tiles) return;
+    gemm_tile<NW, A_KC, B_KC, EPI_PLAIN, false, IND>(g, tile, lds);
+}
+
 // Number of K-splitting waves per tile.  With few tiles every K-block gets its own wave (one round of memory
 // latency, all SIMDs of the CU busy); with thousands of tiles four waves per tile keep the cross-wave sum cheap.
 int pick_nw(int tiles, int nblk, int cap) {
@@ -351,6 +366,16 @@ void launch_fwd(kge_ctx* c, GemmArgs g, int chunks, hipStream_t st) {
     if (nw == 4) KGE_LAUNCH(c, (k_gemm_fwd<4, EPI>), grid, dim3(256), 0, st, g);
     else if (nw == 8) KGE_LAUNCH(c, (k_gemm_fwd<8, EPI>), grid, dim3(512), 0, st, g);
     else KGE_LAUNCH(c, (k_gemm_fwd<16, EPI>), grid, dim3(1024), 0, st, g);
+}
+
+template <bool A_KC, bool B_KC, int IND>
+void launch_one(kge_ctx* c, GemmArgs g, int items, hipStream_t st) {
+    set_tiling(g, items);
+    g.out_mode = OUT_SCORE;
+    const dim3 grid(8 * ((g.tiles + 7) / 8));
+    const int nw = pick_nw(g.tiles, (g.K + TILE - 1) / TILE, 8);
+    if (nw == 4) KGE_LAUNCH(c, (k_gemm_one<4, A_KC, B_KC, IND>), grid, dim3(256), 0, st, g);
+    else KGE_LAUNCH(c, (k_gemm_one<8, A_KC, B_KC, IND>), grid, dim3(512), 0, st, g);
 }
 
 template <int EPI_O, int EPI_N>
@@ -453,4 +478,41 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
     else if (model == KGE_DISTMULT) KGE_BWD(EPI_CHAIN_DM, EPI_PLAIN);
     else KGE_BWD(EPI_PLAIN, EPI_PLAIN);
 #undef KGE_BWD
+}
+
+// ---- TransR: f = gamma - |M_r h + r - M_r t|^2 (Table 1).  Every positive i has its own projection matrix M_i (D x D,
+// behind the D numbers of r in its relation row), so the products are batched over positives:
+//   P_i = N_c M_i^T   [k x D]  projections of the chunk's corrupting rows              (forward)
+//   T_i = U_i M_i     [k x D]  with U_i = dL/dP_i; summed over the chunk's positives -> gradient rows of the negatives
+//   G_i = U_i^T N_c   [D x D]  the negatives' share of dL/dM_i
+void kge_gemm_transr_project(kge_ctx* c, const float* R, const StepIds& ids, int k, int gsz, float* P, hipStream_t st) {
+    const int D = c->cfg.ent_dim;
+    GemmArgs g = {};
+    g.A = c->Nst; g.B = R; g.C = P;
+    g.M = k; g.N = D; g.K = D; g.lda = D; g.ldb = D; g.ldc = D;
+    g.sA = (int64_t)k * D; g.sB = c->cfg.rel_dim; g.sC = (int64_t)k * D;
+    g.ids = ids; g.n_rel = c->cfg.num_relations; g.ind_g = gsz; g.b_off = D;
+    launch_one<true, true, IND_CHUNK_REL>(c, g, ids.b, st);
+}
+
+void kge_gemm_transr_back_project(kge_ctx* c, const float* R, const StepIds& ids, int k, const float* U, float* T,
+                                  hipStream_t st) {
+    const int D = c->cfg.ent_dim;
+    GemmArgs g = {};
+    g.A = U; g.B = R; g.C = T;
+    g.M = k; g.N = D; g.K = D; g.lda = D; g.ldb = D; g.ldc = D;
+    g.sA = (int64_t)k * D; g.sB = c->cfg.rel_dim; g.sC = (int64_t)k * D;
+    g.ids = ids; g.n_rel = c->cfg.num_relations; g.ind_g = 1; g.b_off = D;
+    launch_one<true, false, IND_ITEM_REL>(c, g, ids.b, st);
+}
+
+void kge_gemm_transr_matrix_grad(kge_ctx* c, const StepIds& ids, int k, int gsz, const float* U, float* GM,
+                                 hipStream_t st) {
+    const int D = c->cfg.ent_dim;
+    GemmArgs g = {};
+    g.A = U; g.B = c->Nst; g.C = GM;
+    g.M = D; g.N = D; g.K = k; g.lda = D; g.ldb = D; g.ldc = D;
+    g.sA = (int64_t)k * D; g.sB = (int64_t)k * D; g.sC = (int64_t)D * D;
+    g.ids = ids; g.n_rel = c->cfg.num_relations; g.ind_g = gsz;
+    launch_one<false, false, IND_ITEM_CHUNK>(c, g, ids.b, st);
 }

@@ -43,6 +43,15 @@ struct GemmArgs {
     float* Grel;
     int b, D;
     int64_t n_ent, n_rel;
+    // batches whose items are positives rather than chunks (TransR: every positive has its own projection matrix)
+    int ind_g;       // positives per chunk: item i uses chunk i / ind_g of the operand that is stored per chunk
+    int64_t b_off;   // offset of the matrix inside a relation row
+};
+// how the operands of batch item i are found (IND of gemm_tile)
+enum { IND_NONE = 0,      // A + i sA, B + i sB
+       IND_CHUNK_REL = 1, // A + (i / ind_g) sA (per chunk), B + r_i sB + b_off (the positive's relation row)
+       IND_ITEM_REL = 2,  // A + i sA,                       B + r_i sB + b_off
+       IND_ITEM_CHUNK = 3 // A + i sA,                       B + (i / ind_g) sB
 };
 
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }

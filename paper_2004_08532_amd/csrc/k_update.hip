@@ -260,8 +260,8 @@ void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, con
     a.G[0] = c->Gent; a.G[1] = c->Grel;
     a.key[0] = c->ekey[c->ebuf]; a.key[1] = c->rkey[c->rbuf];
     a.pos[0] = c->epos[c->ebuf]; a.pos[1] = c->rpos[c->rbuf];
-    // (RESCAL's relation rows are D x D matrices whose gradients are never materialised: k_rescal_update)
-    a.n[0] = n_ent_keys; a.n[1] = c->cfg.model == KGE_RESCAL ? 0 : n_rel_keys;
+    // (relation rows that hold D x D matrices have their own update kernels: k_rescal_update, k_transr_update)
+    a.n[0] = n_ent_keys; a.n[1] = (c->cfg.model == KGE_RESCAL || c->cfg.model == KGE_TRANSR) ? 0 : n_rel_keys;
     a.tiles[0] = (n_ent_keys + TILE_R - 1) / TILE_R; a.tiles[1] = (a.n[1] + TILE_R - 1) / TILE_R;
     a.D[0] = c->cfg.ent_dim; a.D[1] = c->cfg.rel_dim;
     a.lr = lr; a.eps = c->eps; a.row_loss = c->row_loss; a.b = b; a.loss_out = loss_out;

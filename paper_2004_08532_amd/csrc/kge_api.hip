@@ -68,10 +68,17 @@ void forward(kge_ctx* c, const float* ent, const float* rel, const StepIds& ids,
              float* pos_out, float* neg_out, int ld_out, int dist_mode, hipStream_t st) {
     if (c->cfg.validate_indices) launch_validate(c, ids, st);
     if (c->cfg.model == KGE_RESCAL) kge_launch_rescal_phi(c, ent, rel, ids, st);
+    if (c->cfg.model == KGE_TRANSR) kge_transr_phi(c, ent, rel, ids, gamma, pos_out, st);
     kge_launch_gather(c, ent, rel, ids, gamma, pos_out, false, st);
     if (neg_out && k > 0) {
-        if (is_gemm_model(c->cfg.model)) kge_gemm_neg_score(c, ids.b, k, chunk, gamma, neg_out, ld_out, dist_mode, st);
-        else kge_pair_neg_score(c, ids.b, k, chunk, gamma, neg_out, ld_out, st);
+        if (c->cfg.model == KGE_TRANSR) {
+            kge_gemm_transr_project(c, rel, ids, k, chunk, kge_transr_projections(c), st);
+            kge_transr_score(c, ids, k, gamma, neg_out, ld_out, st);
+        } else if (is_gemm_model(c->cfg.model)) {
+            kge_gemm_neg_score(c, ids.b, k, chunk, gamma, neg_out, ld_out, dist_mode, st);
+        } else {
+            kge_pair_neg_score(c, ids.b, k, chunk, gamma, neg_out, ld_out, st);
+        }
     }
 }
 
@@ -85,6 +92,54 @@ struct ProfScope {
     }
     ~ProfScope() { c->launch_ev0 = nullptr; c->launch_ev1 = nullptr; }
 };
+
+// TransR after its phi and gather launches: the three batched products with the elementwise steps between them.
+// Profile slots: neg_score = the projection product, loss, neg_backward = the back-projection product, chain,
+// rel_update, update; the small kernels between them are not timed separately.
+int enqueue_transr_rest(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state, const StepIds& ids,
+                        int K, int G, float gamma, float lr, bool long_lists, hipStream_t st) {
+    float* P = kge_transr_projections(c);
+    {
+        ProfScope p(c, KGE_PROF_SCORE);
+        kge_gemm_transr_project(c, rel, ids, K, G, P, st);
+    }
+    kge_transr_score(c, ids, K, gamma, c->S, c->ld_s, st);
+    {
+        ProfScope p(c, KGE_PROF_LOSS);
+        kge_launch_loss(c, ids.b, K, gamma, st);
+    }
+    kge_transr_dp(c, ids, K, st);
+    {
+        ProfScope p(c, KGE_PROF_BACKWARD);
+        kge_gemm_transr_back_project(c, rel, ids, K, P, kge_transr_back_projections(c), st);
+    }
+    kge_transr_reduce(c, ids, K, G, st);
+    kge_gemm_transr_matrix_grad(c, ids, K, G, P, kge_transr_matrix_grads(c), st);
+    {
+        ProfScope p(c, KGE_PROF_CHAIN);
+        kge_transr_chain(c, ent, rel, ids, st);
+    }
+    if (long_lists) KGE_HIP(c, hipStreamWaitEvent(st, c->ev_join, 0));
+    {
+        ProfScope p(c, KGE_PROF_REL_UPDATE);
+        kge_transr_update(c, rel, rel_state, ids, lr, st);
+    }
+    {
+        ProfScope p(c, KGE_PROF_UPDATE);
+        kge_launch_update(c, ent, ent_state, rel, rel_state, ids, lr, 0, st);
+    }
+    KGE_HIP(c, hipGetLastError());
+    if (c->prof_on) {
+        KGE_HIP(c, hipStreamSynchronize(st));
+        for (int s = 0; s < KGE_PROF_SLOTS; ++s) {
+            float ms = 0.f;
+            if (s == KGE_PROF_SORT && !long_lists) continue;
+            if (hipEventElapsedTime(&ms, c->prof_ev[s][0], c->prof_ev[s][1]) == hipSuccess) c->prof_ms[s] += ms;
+        }
+        c->prof_steps += 1;
+    }
+    return KGE_OK;
+}
 
 int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state, const StepIds& ids, int K,
                  int G, float gamma, float lr, hipStream_t st) {
@@ -106,10 +161,15 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
         ProfScope p(c, KGE_PROF_PHI);
         kge_launch_rescal_phi(c, ent, rel, ids, st);
     }
+    if (c->cfg.model == KGE_TRANSR) {
+        ProfScope p(c, KGE_PROF_PHI);
+        kge_transr_phi(c, ent, rel, ids, gamma, nullptr, st);
+    }
     {
         ProfScope p(c, KGE_PROF_GATHER);
         kge_launch_gather(c, ent, rel, ids, gamma, nullptr, !long_lists, st);
     }
+    if (c->cfg.model == KGE_TRANSR) return enqueue_transr_rest(c, ent, ent_state, rel, rel_state, ids, K, G, gamma, lr, long_lists, st);
     {
         ProfScope p(c, KGE_PROF_SCORE);
         if (is_gemm_model(c->cfg.model))
@@ -215,14 +275,16 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     if (!cfg || !out) return fail(nullptr, KGE_ERR_INVALID_ARG, "null argument%s");
     *out = nullptr;
     const int m = cfg->model;
-    if (m < KGE_TRANSE_L2 || m > KGE_RESCAL) return fail(nullptr, KGE_ERR_INVALID_ARG, "unknown model%s");
+    if (m < KGE_TRANSE_L2 || m > KGE_TRANSR) return fail(nullptr, KGE_ERR_INVALID_ARG, "unknown model%s");
     const bool cplx = m == KGE_COMPLEX || m == KGE_ROTATE;
     if (cfg->ent_dim <= 0 || cfg->ent_dim > 1024 || cfg->ent_dim % (cplx ? 8 : 4) != 0)
         return fail(nullptr, KGE_ERR_INVALID_ARG, "ent_dim must be a multiple of 4 (8 for ComplEx/RotatE), at most 1024%s");
-    if (cfg->rel_dim != (m == KGE_ROTATE ? cfg->ent_dim / 2 : (m == KGE_RESCAL ? cfg->ent_dim * cfg->ent_dim : cfg->ent_dim)))
-        return fail(nullptr, KGE_ERR_INVALID_ARG, "rel_dim must be ent_dim (ent_dim/2 for RotatE, ent_dim^2 for RESCAL)%s");
-    if (m == KGE_RESCAL && (cfg->adagrad_mode != 0 || cfg->gemm_input != 0))
-        return fail(nullptr, KGE_ERR_UNSUPPORTED, "RESCAL runs with element-wise Adagrad state and fp32 operands only%s");
+    const int sq = cfg->ent_dim * cfg->ent_dim;
+    const int want_rel = m == KGE_ROTATE ? cfg->ent_dim / 2 : (m == KGE_RESCAL ? sq : (m == KGE_TRANSR ? cfg->ent_dim + sq : cfg->ent_dim));
+    if (cfg->rel_dim != want_rel)
+        return fail(nullptr, KGE_ERR_INVALID_ARG, "rel_dim must be ent_dim (ent_dim/2 for RotatE, ent_dim^2 for RESCAL, ent_dim + ent_dim^2 for TransR)%s");
+    if ((m == KGE_RESCAL || m == KGE_TRANSR) && (cfg->adagrad_mode != 0 || cfg->gemm_input != 0))
+        return fail(nullptr, KGE_ERR_UNSUPPORTED, "RESCAL and TransR run with element-wise Adagrad state and fp32 operands only%s");
     if (cfg->num_entities <= 0 || cfg->num_relations <= 0 || cfg->num_entities >= (1ll << 32) ||
         cfg->num_relations >= (1ll << 32))
         return fail(nullptr, KGE_ERR_INVALID_ARG, "table row counts must be in [1, 2^32)%s");
@@ -267,6 +329,9 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->ld_bf = (cfg->ent_dim + 7) / 8 * 8;
     const bool bf = cfg->gemm_input == 1;
     const size_t o_Obf = take(bf ? B * c->ld_bf * 2 + 64 : 0), o_Nbf = take(bf ? NR * c->ld_bf * 2 + 64 : 0);
+    const bool transr = m == KGE_TRANSR;
+    const size_t proj = transr ? B * (size_t)(cfg->max_neg_per_chunk > 0 ? cfg->max_neg_per_chunk : 1) * D * 4 : 0;
+    const size_t o_PP = take(transr ? B * D * 4 : 0), o_P3 = take(proj), o_T3 = take(proj);
     c->ws_bytes = (int64_t)off;
 
     hipError_t e = hipMalloc(&c->ws_base, off);
@@ -287,6 +352,9 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->rpos[0] = (uint32_t*)(base + o_rp0); c->rpos[1] = (uint32_t*)(base + o_rp1);
     c->Obf = bf ? (uint16_t*)(base + o_Obf) : nullptr;
     c->Nbf = bf ? (uint16_t*)(base + o_Nbf) : nullptr;
+    c->PP = transr ? (float*)(base + o_PP) : nullptr;
+    c->P3 = transr ? (float*)(base + o_P3) : nullptr;
+    c->T3 = transr ? (float*)(base + o_T3) : nullptr;
     c->flags = (int*)(base + o_flags);
     c->step_counter = (int64_t*)(base + o_step);
 

@@ -32,6 +32,9 @@ struct kge_ctx {
     uint16_t* Nbf;   // read these; Nst is then not written)
     int ld_bf;       // D rounded up to 8
     float* S;        // [max_batch x ld_s]   negative scores, then backward coefficients W
+    float* PP;       // TransR: [max_batch x D] p_i = M_i c_i
+    float* P3;       // TransR: [max_batch x max_neg_per_chunk x D] projections of the corrupting rows, then dL/dP
+    float* T3;       // TransR: the same shape, U_i M_i
     float* GO;       // [max_batch x D]      dL/do_i
     float* Gent;     // [max_ent_keys x D]   gradient rows in key order: heads | tails | corrupting rows
     float* Grel;     // [max_batch x Dr]     gradient rows of the relations
@@ -145,6 +148,22 @@ void kge_launch_rescal_phi(kge_ctx* c, const float* E, const float* R, const Ste
 void kge_launch_rescal_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
 // RESCAL, a7 for the relation matrices: gradient of a distinct relation formed from the factor rows, then Adagrad
 void kge_launch_rescal_update(kge_ctx* c, float* R, float* SR, const StepIds& ids, float lr, hipStream_t st);
+// TransR: the steps around its batched products (k_transr.hip) and the products (k_gemm.hip)
+void kge_transr_phi(kge_ctx* c, const float* E, const float* R, const StepIds& ids, float gamma, float* pos_out,
+                    hipStream_t st);
+void kge_transr_score(kge_ctx* c, const StepIds& ids, int k, float gamma, float* out, int ld_out, hipStream_t st);
+void kge_transr_dp(kge_ctx* c, const StepIds& ids, int k, hipStream_t st);
+void kge_transr_reduce(kge_ctx* c, const StepIds& ids, int k, int g, hipStream_t st);
+void kge_transr_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
+void kge_transr_update(kge_ctx* c, float* R, float* SR, const StepIds& ids, float lr, hipStream_t st);
+float* kge_transr_projections(kge_ctx* c);
+float* kge_transr_back_projections(kge_ctx* c);
+float* kge_transr_matrix_grads(kge_ctx* c);
+void kge_gemm_transr_project(kge_ctx* c, const float* R, const StepIds& ids, int k, int g, float* P, hipStream_t st);
+void kge_gemm_transr_back_project(kge_ctx* c, const float* R, const StepIds& ids, int k, const float* U, float* T,
+                                  hipStream_t st);
+void kge_gemm_transr_matrix_grad(kge_ctx* c, const StepIds& ids, int k, int g, const float* U, float* GM,
+                                 hipStream_t st);
 // a6: sort (id, position) of the entity and relation key lists
 void kge_launch_sort(kge_ctx* c, const StepIds& ids, hipStream_t st);
 // a7: per distinct row, sum its gradient rows and apply Adagrad; also reduces the loss terms

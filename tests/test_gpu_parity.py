@@ -9,7 +9,7 @@ from parity_util import EMB_TOL, SCORE_TOL, Pair, dev, rel_err
 
 pytestmark = pytest.mark.gpu
 
-MODELS = ["transe_l2", "transe_l1", "distmult", "complex", "rotate", "rescal"]
+MODELS = ["transe_l2", "transe_l1", "distmult", "complex", "rotate", "rescal", "transr"]
 
 
 @pytest.fixture(scope="module")
@@ -22,7 +22,7 @@ def ragged(model, **kw):
     """A small workload whose sizes are multiples of nothing convenient: several 32x32 tiles with ragged tails
     in every dimension, k not a multiple of 4, rows of 72 floats (a ragged K-block)."""
     base = dict(name="ragged-" + model, model=model, n_entities=517, n_relations=11, n_triples=4000, s_entity=1.0,
-                s_relation=None, ent_dim=72, rel_dim={"rotate": 36, "rescal": 72 * 72}.get(model, 72), batch=90, chunk=45,
+                s_relation=None, ent_dim=72, rel_dim={"rotate": 36, "rescal": 72 * 72, "transr": 72 + 72 * 72}.get(model, 72), batch=90, chunk=45,
                 neg_per_chunk=37, neg_mode="uniform", side_mode="alternate", gamma=6.0, lr=0.1, steps=4, seed=5)
     base.update(kw)
     return configs.Workload(**base)
@@ -88,7 +88,7 @@ def test_ragged_shapes_every_model(kge, model, alpha):
 # margins at which roughly half of the (positive, negative) pairs of the ragged workload are active at its
 # initialisation (score differences there: ~0.1 for the distance models, ~1e-3 for the products)
 RANKING_MARGIN = {"transe_l2": 0.03, "transe_l1": 0.3, "distmult": 3e-4, "complex": 3e-4, "rotate": 0.3,
-                  "rescal": 2e-3}
+                  "rescal": 2e-3, "transr": 0.02}
 
 
 @pytest.mark.parametrize("alpha", [0.0, 1.0])
@@ -380,8 +380,8 @@ def test_evaluation_ranks_and_metrics(kge, model, shape):
     within the score tolerance of the positive's could fall on either side, so the rank must lie between the
     counts with those candidates excluded and included, and equals the oracle's rank when there are none.  The
     metrics kernel is checked exactly against the oracle's formulas on the device's own ranks."""
-    if shape == "wide" and model == "rescal":
-        pytest.skip("the oracle needs minutes for a million pairs of 72 x 72 matrices; the products are DistMult's")
+    if shape == "wide" and model in ("rescal", "transr"):
+        pytest.skip("the oracle needs minutes for a million pairs of 72 x 72 matrices")
     w = ragged(model, n_entities=2003, name="eval-" + model, **EVAL_SHAPES[shape])
     # tables eight times the initialisation range: scores of an untrained model at the usual range lie so close
     # together that most ranks would hinge on differences below the score tolerance
@@ -562,6 +562,7 @@ def test_index_validation_reports_out_of_range_ids_without_touching_memory_outsi
 REPLAY_VARIANTS = {
     "transe_l2": {},
     "rescal": dict(model="rescal", ent_dim=32, rel_dim=32 * 32),
+    "transr": dict(model="transr", ent_dim=32, rel_dim=32 + 32 * 32),
     "rotate-ranking-adversarial": dict(model="rotate", rel_dim=32, loss="ranking", gamma=0.5, adv_temperature=1.0),
     "complex-bf16": dict(model="complex", bf16_inputs=True),
 }
