@@ -120,10 +120,12 @@ def test_pairwise_ranking_loss_bf16_operands(kge):
         p.close()
 
 
-def test_rescal_relations_that_fill_half_of_the_batch(kge):
+@pytest.mark.parametrize("model", ["rescal", "transr"])
+def test_matrix_relations_that_fill_half_of_the_batch(kge, model):
     """Two relations over 640 positives: the runs of equal relation ids are longer than one look-back round of the
-    matrix update (256 entries), and every positive's matrix gradient (an outer product) lands in one of two rows."""
-    w = ragged("rescal", n_relations=2, ent_dim=64, rel_dim=64 * 64, batch=640, chunk=64, neg_per_chunk=32, steps=2)
+    matrix update (256 entries), and every positive's matrix gradient lands in one of two rows."""
+    w = ragged(model, n_relations=2, ent_dim=64, rel_dim=64 * 64 + (64 if model == "transr" else 0), batch=640, chunk=64,
+               neg_per_chunk=32, steps=2)
     p = Pair(w, kge)
     try:
         run_steps(p, configs.BatchStream(w), w.steps)
