@@ -157,12 +157,34 @@ struct ChainArgs {
     const float* cpos;
     float* Gent;
     float* Grel;
+    // after the tiled backward of RotatE / TransE-L1: dL/do_i is the sum of go_parts rows go_stride floats apart, and
+    // the workgroups from chain_blocks on add up the partial gradient rows of the corrupting entities
+    int go_parts;
+    int64_t go_stride;
+    int chain_blocks;
+    PartialRows rest;
 };
+
+// sum of `parts` 16-byte pieces `stride` floats apart, in order
+__device__ __forceinline__ float4 ld4_parts(const float* p, int parts, int64_t stride) {
+    float4 s = ld4(p);
+    for (int q = 1; q < parts; ++q) {
+        const float4 v = ld4(p + q * stride);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+    return s;
+}
 
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
 
 template <int MODEL, int NV>
 __global__ __launch_bounds__(256) void k_chain(ChainArgs a) {
+    if ((int)blockIdx.x >= a.chain_blocks) {  // partial rows of the corrupting entities -> their gradient rows
+        const int64_t step = (int64_t)(gridDim.x - a.chain_blocks) * 256;
+        for (int64_t e = (int64_t)(blockIdx.x - a.chain_blocks) * 256 + threadIdx.x; e < a.rest.n4; e += step)
+            st4(a.rest.out + 4 * e, ld4_parts(a.rest.src + 4 * e, a.rest.parts, a.rest.stride));
+        return;
+    }
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (i >= a.b) return;
@@ -210,7 +232,7 @@ __global__ __launch_bounds__(256) void k_chain(ChainArgs a) {
         for (int it = 0; it < NV; ++it) {
             const int v = lane + it * 64;
             if (v >= nvec) continue;
-            const float4 G = ld4(pg + 4 * v);
+            const float4 G = ld4_parts(pg + 4 * v, a.go_parts, a.go_stride);
             const float ov[4] = {Ov[it].x, Ov[it].y, Ov[it].z, Ov[it].w};
             const float cv[4] = {Cv[it].x, Cv[it].y, Cv[it].z, Cv[it].w};
             const float gv[4] = {G.x, G.y, G.z, G.w};
@@ -247,7 +269,8 @@ __global__ __launch_bounds__(256) void k_chain(ChainArgs a) {
             if (v >= nvec) continue;
             const float4 Ore = ld4(po + 4 * v), Oim = ld4(po + im_off + 4 * v);
             const float4 Cre = ld4(pc + 4 * v), Cim = ld4(pc + im_off + 4 * v);
-            const float4 Gre = ld4(pg + 4 * v), Gim = ld4(pg + im_off + 4 * v);
+            const float4 Gre = ld4_parts(pg + 4 * v, a.go_parts, a.go_stride);
+            const float4 Gim = ld4_parts(pg + im_off + 4 * v, a.go_parts, a.go_stride);
             const float4 Are = ld4(pa + 4 * v), Aim = ld4(pa + im_off + 4 * v);
             const float ore[4] = {Ore.x, Ore.y, Ore.z, Ore.w}, oim[4] = {Oim.x, Oim.y, Oim.z, Oim.w};
             const float cre[4] = {Cre.x, Cre.y, Cre.z, Cre.w}, cim[4] = {Cim.x, Cim.y, Cim.z, Cim.w};
@@ -337,11 +360,17 @@ void kge_launch_chain(kge_ctx* c, const float* E, const float* R, const StepIds&
     a.E = E; a.R = R; a.ids = ids; a.b = b; a.D = c->cfg.ent_dim; a.Dr = c->cfg.rel_dim;
     a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations;
     a.O = c->O; a.GO = c->GO; a.cpos = c->cpos; a.Gent = c->Gent; a.Grel = c->Grel;
+    a.go_parts = 1; a.go_stride = 0;
+    if (c->go_partial.parts > 1) { a.GO = c->go_partial.src; a.go_parts = c->go_partial.parts; a.go_stride = c->go_partial.stride; }
+    a.chain_blocks = (b + 3) / 4;
+    a.rest = c->neg_partial;
+    int rest_blocks = 0;  // 16 bytes per thread, up to four rounds
+    if (a.rest.parts > 1) rest_blocks = (int)((a.rest.n4 + 1023) / 1024);
     const int model = c->cfg.model;
     const bool cplx = model == KGE_COMPLEX || model == KGE_ROTATE;
     const int nvec = cplx ? a.D / 8 : a.D / 4;
     const int nv = (nvec + 63) / 64;
-    const dim3 grid((b + 3) / 4);
+    const dim3 grid(a.chain_blocks + rest_blocks);
     switch (model) {
     case KGE_TRANSE_L2: launch_chain_nv<KGE_TRANSE_L2>(c, a, nv, grid, st); break;
     case KGE_TRANSE_L1: launch_chain_nv<KGE_TRANSE_L1>(c, a, nv, grid, st); break;

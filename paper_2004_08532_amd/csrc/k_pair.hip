@@ -9,9 +9,18 @@
 // LDS at a time; a thread accumulates a 2x2 block of pairs and reads four coordinates of a row with one 16-byte
 // LDS load, so one load serves eight pair terms.  The modulus uses the hardware square root (1 ulp).
 // Backward: threads own coordinates instead of pairs, so the sums over j (for dL/do_i) and over i (for the
-// gradient row of corrupting entity j) stay in registers: one kind of workgroup walks all k negatives for 8
-// positives, the other walks all g positives for 8 negatives; a workgroup is two groups of threads with 4 rows
-// each, so that rows of 200 coordinates fill its wavefronts.  Nothing is accumulated with atomics.
+// gradient row of corrupting entity j) stay in registers.  Both sums are made of the same terms
+// W_ij dir(o_i - n_j) with opposite signs, and a term costs a reciprocal square root, so it should be formed once:
+//   k_pair_bwd_tile  (chunks of up to 128 positives) a workgroup owns 16 positives x a range of negatives; a thread
+//                    keeps its coordinate of the 16 o rows and of their 16 running sums in registers, walks the
+//                    negatives that fall to its thread group, and adds every term to both sides.  What a workgroup
+//                    can sum is partial (over its negatives for dL/do, over its 16 positives for a corrupting row):
+//                    the partial rows go to a scratch area and the chain launch (k_chain) adds them in a fixed order.
+//   k_pair_bwd       (longer chunks, where that would be too many partial rows) one kind of workgroup walks all k
+//                    negatives for 8 positives, the other walks all g positives for 8 negatives, each forming every
+//                    term for itself; a workgroup is two groups of threads with 4 rows each, so that rows of 200
+//                    coordinates fill its wavefronts.
+// Nothing is accumulated with atomics.
 #include "kge_common.h"
 
 namespace {
@@ -242,6 +251,124 @@ __global__ __launch_bounds__(1024) void k_pair_bwd(PairArgs a, int n_i_tiles, in
     else pair_bwd_rows<CPLX, false, BR_N>(a, c, (blockIdx.x - n_i_tiles) * 2 * BR_N, cpp, Ws);
 }
 
+// ---- the tile form of the backward
+constexpr int TI = 16;          // positives per workgroup: their coordinate and running sum stay in registers
+constexpr int NG = 5;           // thread groups per workgroup: 5 x 200 coordinates fill 16 wavefronts
+constexpr int TJB = 8 * NG;     // negatives per staged block of W, dealt round-robin to the groups
+constexpr int WPITCH = TI + 4;  // floats per staged row of W^T
+constexpr int TILE_CPP = 1024 / NG;  // most coordinates per pass
+constexpr int MAX_PARTS = KGE_PAIR_MAX_PARTS;  // most partial rows per gradient row
+
+struct PairTileArgs {
+    int n_i_tiles, tj;     // i-tiles per chunk; negatives per workgroup
+    int cpp;               // coordinates per pass
+    float* dstO;           // dL/do rows or their partial rows: [j-tile][b x D]
+    float* dstN;           // gradient rows of the corrupting entities or their partial rows: [i-tile][C*k x D]
+    int64_t strideO, strideN;  // floats between consecutive partials (0: the final rows are written directly)
+};
+
+// Thread (group, coordinate).  Held to 128 registers: 16 wavefronts per CU, four on every SIMD.
+template <bool CPLX>
+__global__ __launch_bounds__(1024) void k_pair_bwd_tile(PairArgs a, PairTileArgs t) {
+    __shared__ __attribute__((aligned(16))) float Ws[TJB][WPITCH];  // W^T of the block: [negative][positive]
+    __shared__ float2 Gs[TI][TILE_CPP];                             // another group's sums for dL/do
+    const int tid = threadIdx.x, cpp = t.cpp;
+    const int grp = tid / cpp, lc = tid - grp * cpp;
+    const int it = blockIdx.x % t.n_i_tiles, jt = blockIdx.x / t.n_i_tiles, c = blockIdx.y;
+    const int i0 = it * TI, jb0 = jt * t.tj, jb1 = min(jb0 + t.tj, a.k);
+    const int NC = CPLX ? a.D / 2 : a.D;
+    const float* Oc = a.O + (int64_t)c * a.g * a.D;
+    const float* Nc = a.Nst + (int64_t)c * a.k * a.D;
+    const float* Wc = a.S + (int64_t)c * a.g * a.ld_s;
+    float* dN = t.dstN + it * t.strideN + (int64_t)c * a.k * a.D;
+    float* dO = t.dstO + jt * t.strideO + (int64_t)c * a.g * a.D;
+
+    for (int cb = 0; cb < NC; cb += cpp) {
+        const int cc = cb + lc;
+        const bool act = grp < NG && cc < NC;
+        float x_re[TI], x_im[TI], g_re[TI], g_im[TI];
+#pragma unroll
+        for (int s = 0; s < TI; ++s) {
+            const bool ok = act && i0 + s < a.g;
+            x_re[s] = ok ? Oc[(int64_t)(i0 + s) * a.D + cc] : 0.f;
+            x_im[s] = (ok && CPLX) ? Oc[(int64_t)(i0 + s) * a.D + NC + cc] : 0.f;
+            g_re[s] = 0.f;
+            g_im[s] = 0.f;
+        }
+        for (int j0 = jb0; j0 < jb1; j0 += TJB) {
+            const int jn = min(TJB, jb1 - j0);  // negatives in this block
+            __syncthreads();
+            // W of the block, transposed; 0 for positives outside the chunk, so that such pairs add nothing
+            for (int e = tid; e < jn * TI; e += blockDim.x) {
+                const int jj = e % jn, ii = e / jn;
+                Ws[jj][ii] = i0 + ii < a.g ? Wc[(int64_t)(i0 + ii) * a.ld_s + j0 + jj] : 0.f;
+            }
+            __syncthreads();
+            if (grp >= jn || !act) continue;  // (the barriers above are outside of this)
+            float y_re = Nc[(int64_t)(j0 + grp) * a.D + cc], y_im = CPLX ? Nc[(int64_t)(j0 + grp) * a.D + NC + cc] : 0.f;
+            for (int jj = grp; jj < jn; jj += NG) {
+                const int j = j0 + jj;
+                const int jnx = jj + NG < jn ? j + NG : j;  // the next row is asked for before this one is worked on
+                const float z_re = Nc[(int64_t)jnx * a.D + cc], z_im = CPLX ? Nc[(int64_t)jnx * a.D + NC + cc] : 0.f;
+                float n_re = 0.f, n_im = 0.f;
+#pragma unroll
+                for (int s4 = 0; s4 < TI; s4 += 4) {
+                    const float4 w4 = ld4(&Ws[jj][s4]);
+                    const float wv[4] = {w4.x, w4.y, w4.z, w4.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int s = s4 + e;
+                        const float q_re = x_re[s] - y_re;  // o - n
+                        if (CPLX) {
+                            const float q_im = x_im[s] - y_im;
+                            // w / |q|; q = 0 gives a finite factor times 0
+                            const float f = wv[e] * __builtin_amdgcn_rsqf(fmaf(q_im, q_im, fmaf(q_re, q_re, 1.2e-38f)));
+                            g_re[s] = fmaf(-f, q_re, g_re[s]);
+                            g_im[s] = fmaf(-f, q_im, g_im[s]);
+                            n_re = fmaf(f, q_re, n_re);
+                            n_im = fmaf(f, q_im, n_im);
+                        } else {
+                            const float v = q_re > 0.f ? wv[e] : (q_re < 0.f ? -wv[e] : 0.f);
+                            g_re[s] -= v;
+                            n_re += v;
+                        }
+                    }
+                }
+                dN[(int64_t)j * a.D + cc] = n_re;
+                if (CPLX) dN[(int64_t)j * a.D + NC + cc] = n_im;
+                y_re = z_re;
+                y_im = z_im;
+            }
+        }
+        // dL/do: the other groups' sums are added to the first group's, in group order
+        for (int o = 1; o < NG; ++o) {
+            __syncthreads();
+            if (grp == o && act) {
+#pragma unroll
+                for (int s = 0; s < TI; ++s) Gs[s][lc] = make_float2(g_re[s], g_im[s]);
+            }
+            __syncthreads();
+            if (grp == 0 && act) {
+#pragma unroll
+                for (int s = 0; s < TI; ++s) {
+                    const float2 v = Gs[s][lc];
+                    g_re[s] += v.x;
+                    g_im[s] += v.y;
+                }
+            }
+        }
+        if (grp == 0 && act) {
+#pragma unroll
+            for (int s = 0; s < TI; ++s) {
+                if (i0 + s < a.g) {
+                    dO[(int64_t)(i0 + s) * a.D + cc] = g_re[s];
+                    if (CPLX) dO[(int64_t)(i0 + s) * a.D + NC + cc] = g_im[s];
+                }
+            }
+        }
+    }
+}
+
 template <bool CPLX>
 void launch_pair_bwd(kge_ctx* c, const PairArgs& a, int chunks, int cpp, dim3 block, hipStream_t st) {
     const int br_o = a.g >= 2 * a.k ? 8 : 4, br_n = a.k >= 2 * a.g ? 8 : 4;
@@ -266,6 +393,34 @@ void kge_pair_neg_backward(kge_ctx* c, int b, int k, int gsz, hipStream_t st) {
     PairArgs a = {};
     a.O = c->O; a.Nst = c->Nst; a.S = c->S; a.ld_s = c->ld_s; a.g = gsz; a.k = k; a.D = c->cfg.ent_dim;
     a.GO = c->GO; a.Gneg = c->Gent + (int64_t)2 * b * a.D;
+    const int nc_all = c->cfg.model == KGE_ROTATE ? a.D / 2 : a.D;
+    const int chunks = b / gsz, n_i_tiles = (gsz + TI - 1) / TI;
+    if (n_i_tiles <= MAX_PARTS && c->pair_part_o) {
+        // the tile form.  Enough workgroups for the chip, at most MAX_PARTS ranges of negatives per chunk
+        int pj = (256 + chunks * n_i_tiles - 1) / (chunks * n_i_tiles);
+        pj = pj > MAX_PARTS ? MAX_PARTS : pj;
+        pj = pj > (k + NG - 1) / NG ? (k + NG - 1) / NG : pj;  // at least one negative per thread group
+        PairTileArgs t;
+        t.n_i_tiles = n_i_tiles;
+        t.tj = (k + pj - 1) / pj;
+        pj = (k + t.tj - 1) / t.tj;
+        const int passes = (nc_all + TILE_CPP - 1) / TILE_CPP;
+        t.cpp = (nc_all + passes - 1) / passes;
+        const int64_t rows_o = (int64_t)b * a.D, rows_n = (int64_t)chunks * k * a.D;
+        t.dstO = pj > 1 ? c->pair_part_o : a.GO;
+        t.strideO = pj > 1 ? rows_o : 0;
+        t.dstN = n_i_tiles > 1 ? c->pair_part_n : a.Gneg;
+        t.strideN = n_i_tiles > 1 ? rows_n : 0;
+        const dim3 grid(n_i_tiles * pj, chunks), block((NG * t.cpp + 63) / 64 * 64);
+        if (c->cfg.model == KGE_ROTATE) KGE_LAUNCH(c, k_pair_bwd_tile<true>, grid, block, 0, st, a, t);
+        else KGE_LAUNCH(c, k_pair_bwd_tile<false>, grid, block, 0, st, a, t);
+        // the chain launch that follows adds up the partial rows
+        c->go_partial = {c->pair_part_o, a.GO, pj, rows_o, rows_o / 4};
+        c->neg_partial = {c->pair_part_n, a.Gneg, n_i_tiles, rows_n, rows_n / 4};
+        return;
+    }
+    c->go_partial = {};
+    c->neg_partial = {};
     // coordinates per pass: all of them if two thread groups of that size fit a workgroup, else 512
     const int nc = c->cfg.model == KGE_ROTATE ? a.D / 2 : a.D;
     const int cpp = nc <= 512 ? nc : 512;

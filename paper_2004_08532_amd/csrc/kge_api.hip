@@ -332,6 +332,8 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const bool transr = m == KGE_TRANSR;
     const size_t proj = transr ? B * (size_t)(cfg->max_neg_per_chunk > 0 ? cfg->max_neg_per_chunk : 1) * D * 4 : 0;
     const size_t o_PP = take(transr ? B * D * 4 : 0), o_P3 = take(proj), o_T3 = take(proj);
+    const bool pair_model = m == KGE_ROTATE || m == KGE_TRANSE_L1;
+    const size_t o_ppo = take(pair_model ? KGE_PAIR_MAX_PARTS * B * D * 4 : 0), o_ppn = take(pair_model ? KGE_PAIR_MAX_PARTS * NR * D * 4 : 0);
     c->ws_bytes = (int64_t)off;
 
     hipError_t e = hipMalloc(&c->ws_base, off);
@@ -355,6 +357,8 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->PP = transr ? (float*)(base + o_PP) : nullptr;
     c->P3 = transr ? (float*)(base + o_P3) : nullptr;
     c->T3 = transr ? (float*)(base + o_T3) : nullptr;
+    c->pair_part_o = pair_model ? (float*)(base + o_ppo) : nullptr;
+    c->pair_part_n = pair_model ? (float*)(base + o_ppn) : nullptr;
     c->flags = (int*)(base + o_flags);
     c->step_counter = (int64_t*)(base + o_step);
 

@@ -15,6 +15,15 @@
 // so that the score of (i, any replacement x) is psi(o_i, x); this is the split of Sec. 3.3
 // (TransE: o = h + r, psi = gamma - |o - x|) carried over to the other models and to head corruption.
 // ---------------------------------------------------------------------------------------------------------
+// Gradient rows that exist as `parts` partial rows, `stride` floats apart, still to be added up (in order) into out.
+struct PartialRows {
+    const float* src;
+    float* out;
+    int parts;       // 0 or 1: nothing to add up
+    int64_t stride;
+    int64_t n4;      // 16-byte pieces per partial
+};
+
 struct kge_ctx {
     kge_config cfg;
     float eps;
@@ -36,6 +45,9 @@ struct kge_ctx {
     float* P3;       // TransR: [max_batch x max_neg_per_chunk x D] projections of the corrupting rows, then dL/dP
     float* T3;       // TransR: the same shape, U_i M_i
     float* GO;       // [max_batch x D]      dL/do_i
+    float* pair_part_o;  // RotatE / TransE-L1: [KGE_PAIR_MAX_PARTS][max_batch x D] partial dL/do rows of the tiled backward
+    PartialRows go_partial, neg_partial;  // what the last backward launch left for the chain launch to add up
+    float* pair_part_n;  //                     [KGE_PAIR_MAX_PARTS][max_neg_rows x D] partial rows of the corrupting entities
     float* Gent;     // [max_ent_keys x D]   gradient rows in key order: heads | tails | corrupting rows
     float* Grel;     // [max_batch x Dr]     gradient rows of the relations
     float* fpos;     // [max_batch]          positive scores
@@ -126,6 +138,7 @@ void kge_make_key_lists(kge_ctx* c, const StepIds& ids, KeyList* ent, KeyList* r
 // KGE_RANK_MAX_KEYS keys; longer lists go through kge_launch_sort)
 void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds& ids, float gamma, float* pos_out,
                        bool with_keys, hipStream_t st);
+constexpr int KGE_PAIR_MAX_PARTS = 8;  // partial rows per gradient row in the tiled backward of RotatE / TransE-L1
 constexpr int KGE_RANK_MAX_KEYS = 14336;  // 14 * 1024: positions fit 14 bits, the list and its tables fit 64 KB of LDS
 // a3: negative scores of every chunk into out[b x ld_out]: matrix-product models / elementwise-reduce models
 void kge_gemm_neg_score(kge_ctx* c, int b, int k, int g, float gamma, float* out, int ld_out, int dist_mode,

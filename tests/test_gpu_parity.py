@@ -145,6 +145,31 @@ def test_training_shapes_with_thousands_of_tiles(kge):
             p.close()
 
 
+PAIR_BACKWARD_SHAPES = {
+    # chunks of up to 128 positives take the backward in which a workgroup owns 16 positives x a range of negatives
+    # and writes partial rows; here with 8 i-tiles of which the last is ragged, and 8 ranges of 22 negatives
+    "tiled": dict(batch=250, chunk=125, neg_per_chunk=173),
+    # rows of 840 floats: the tiled backward walks the coordinates in several passes
+    "tiled-long-rows": dict(batch=80, chunk=40, neg_per_chunk=23, ent_dim=840),
+    # longer chunks would need too many partial rows: workgroups that own rows of one side only
+    "per-side": dict(batch=300, chunk=150, neg_per_chunk=70),
+}
+
+
+@pytest.mark.parametrize("shape", sorted(PAIR_BACKWARD_SHAPES))
+@pytest.mark.parametrize("model", ["rotate", "transe_l1"])
+def test_both_forms_of_the_elementwise_backward(kge, model, shape):
+    kw = dict(PAIR_BACKWARD_SHAPES[shape])
+    if "ent_dim" in kw:
+        kw["rel_dim"] = kw["ent_dim"] // 2 if model == "rotate" else kw["ent_dim"]
+    w = ragged(model, steps=2, **kw)
+    p = Pair(w, kge)
+    try:
+        run_steps(p, configs.BatchStream(w), w.steps)
+    finally:
+        p.close()
+
+
 @pytest.mark.parametrize("b,g,k", [(1, 1, 1), (3, 1, 2), (2, 2, 1)])
 @pytest.mark.parametrize("model", MODELS)
 def test_smallest_batches(kge, model, b, g, k):
