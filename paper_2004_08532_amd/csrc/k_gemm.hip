@@ -26,7 +26,9 @@
 //     fall out of the operand fragments;
 //   * for TransE-L2 and DistMult the chain rule from dL/do to the head, tail and relation gradient rows is
 //     elementwise, so the dO epilogue writes those rows directly (no dL/do array, no separate chain kernel);
-//     the rows it needs for that are fetched before the K loop starts.
+//     the rows it needs for that are fetched before the K loop starts.  ComplEx couples the real and the imaginary
+//     part of a coordinate; its dO tiles take 16 real parts and their 16 imaginary parts as their 32 columns and do
+//     the same.
 #include "k_gemm_shared.h"
 
 namespace {
@@ -63,13 +65,16 @@ struct BlockLoader {
             }
             any = true; m1 = m2 = m3 = true;
         } else {
-            const int gr = r0 + minor;
-            any = gr < rows; m1 = gr + 1 < rows; m2 = gr + 2 < rows; m3 = gr + 3 < rows;
+            init_rows_at(base, r0 + minor, rows);
+        }
+    }
+    // MC: the lane's four consecutive rows start at row gr of a range that ends before row lim
+    __device__ __forceinline__ void init_rows_at(const float* base, int gr, int lim) {
+        any = gr < lim; m1 = gr + 1 < lim; m2 = gr + 2 < lim; m3 = gr + 3 < lim;
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                ok[it] = true;
-                p[it] = base + (int64_t)(major0 + 8 * it) * ld + (any ? gr : 0);
-            }
+        for (int it = 0; it < 4; ++it) {
+            ok[it] = true;
+            p[it] = base + (int64_t)(major0 + 8 * it) * ld + (any ? gr : 0);
         }
     }
     __device__ __forceinline__ void issue(int kb, float4 (&reg)[4]) const {
@@ -131,7 +136,8 @@ __device__ __forceinline__ void lds_frag(const float* region, int lane, int q, f
 // One 32x32 output tile: K loop, cross-wave sum, epilogue.
 template <int NW, bool A_KC, bool B_KC, int EPI, bool IS_DO, int IND = IND_NONE>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*lds)[2][REGION]) {
-    constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM;
+    constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM || EPI == EPI_CHAIN_CX;
+    constexpr bool CX = EPI == EPI_CHAIN_CX;
     constexpr bool WANT_ASUM = EPI == EPI_L2_DO || EPI == EPI_L2_DN || EPI == EPI_CHAIN_L2;
     constexpr bool IS_FWD = A_KC && B_KC;  // only the forward product has both operands K-contiguous
     constexpr int NE = TILE * TILE / (NW * 64);           // output elements per thread
@@ -147,6 +153,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     if (IND == IND_ITEM_CHUNK) B = g.B + (c / g.ind_g) * g.sB;
     float* As = lds[w][0];
     float* Bs = lds[w][1];
+    // ComplEx chain rule: the real and the imaginary part of a coordinate have to meet in one tile, so the tile's
+    // 32 columns are 16 consecutive real parts (columns c0 .. of the [re | im] rows) and the 16 imaginary parts
+    // that belong to them (columns N/2 + c0 ..); the tile index along N counts groups of 16 coordinates.
+    const int c0 = CX ? (tile % g.gx) * (TILE / 2) : 0;
+    auto col_of = [&](int j) { return CX ? (j < TILE / 2 ? c0 + j : g.N / 2 + c0 + j - TILE / 2) : n0 + j; };
+    auto col_in = [&](int j) { return CX ? c0 + (j & (TILE / 2 - 1)) < g.N / 2 : n0 + j < g.N; };
 
     // ---- chain-rule epilogues: fetch what they need now, so that it arrives while the K loop runs
     float e_o[NE], e_c[NE], e_a[NE], e_r[NE], e_cp[NE], e_inv[NE];
@@ -157,17 +169,17 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
 #pragma unroll
         for (int it = 0; it < NE; ++it) {
             const int e = threadIdx.x + it * NW * 64;
-            const int gm = m0 + (e >> 5), gn = n0 + (e & 31);
-            const bool in = gm < g.M && gn < g.N;
+            const int gm = m0 + (e >> 5);
+            const bool in = gm < g.M && col_in(e & 31);
             const int i = c * g.M + (in ? gm : 0);  // index of the positive in the mini-batch
-            const int d = in ? gn : 0;
+            const int d = in ? col_of(e & 31) : 0;
             const int64_t hid = clamp_id(sv.h[i], g.n_ent), tid = clamp_id(sv.t[i], g.n_ent);
             const int64_t aid = e_head ? tid : hid, cid = e_head ? hid : tid;
             e_o[it] = g.X[(int64_t)i * g.ldx + d];
             e_c[it] = g.E[cid * g.D + d];
             e_cp[it] = g.cpos[i];
             e_a[it] = 0.f; e_r[it] = 0.f; e_inv[it] = 0.f;
-            if (EPI == EPI_CHAIN_DM) {
+            if (EPI == EPI_CHAIN_DM || CX) {
                 const int64_t rid = clamp_id(sv.r[i], g.n_rel);
                 e_a[it] = g.E[aid * g.D + d];
                 e_r[it] = g.R[rid * g.D + d];
@@ -188,6 +200,10 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     BlockLoader<B_KC> lb;
     la.init(A, g.lda, m0, g.M, g.K, lane);
     lb.init(B, g.ldb, n0, g.N, g.K, lane);
+    if (CX) {  // the lane's four columns lie inside one half of the tile, and inside one half of the row
+        const int j = 4 * (lane & 7);
+        lb.init_rows_at(B, col_of(j), col_in(j) ? (j < TILE / 2 ? g.N / 2 : g.N) : 0);
+    }
     int kb = w;
     if (kb < nblk) {
         la.issue(kb, ra);
@@ -257,7 +273,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             if ((lane & 31) == 0 && gm < g.M && cnt > 0) atomicAdd(&g.rank[c * g.M + gm], cnt);
             continue;
         }
-        if (gm >= g.M || gn >= g.N) continue;
+        if (gm >= g.M || !col_in(j)) continue;  // (ComplEx: the two lanes of a coordinate stay or go together)
         const int bi = c * g.M + gm;  // index of the positive in the mini-batch (chain epilogues)
         float s = 0.f;
 #pragma unroll
@@ -288,6 +304,24 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             g.Gent[(int64_t)(e_head ? g.b + bi : bi) * g.D + gn] = go;
             g.Gent[(int64_t)(e_head ? bi : g.b + bi) * g.D + gn] = e_cp[it] * dir;
             g.Grel[(int64_t)bi * g.D + gn] = e_head ? -go : go;
+        } else if (CX) {
+            // o = a (r_re + i r_i) with r_i = -r_im when the head is corrupted; psi = o . x over the [re | im] rows.
+            // With go = dL/do: the kept entity gets go * conj(r_re + i r_i), the relation go * conj(a) (imaginary
+            // part negated for the head side), the replaced entity dL/df+ * o.  The other part of the coordinate is
+            // 16 lanes away.
+            const bool im = j >= TILE / 2;
+            const int d = col_of(j);
+            const float go = s + e_cp[it] * e_c[it];
+            const float go_p = __shfl_xor(go, TILE / 2, 64), r_p = __shfl_xor(e_r[it], TILE / 2, 64);
+            const float a_p = __shfl_xor(e_a[it], TILE / 2, 64);
+            const float sgn = e_head ? -1.f : 1.f;
+            // re lane: g_re r_re + g_im r_i,  g_re a_re + g_im a_im
+            // im lane: g_im r_re - g_re r_i,  sgn (g_im a_re - g_re a_im)
+            const float ga = im ? go * r_p - go_p * (sgn * e_r[it]) : go * e_r[it] + go_p * (sgn * r_p);
+            const float gr = im ? sgn * (go * a_p - go_p * e_a[it]) : go * e_a[it] + go_p * a_p;
+            g.Gent[(int64_t)(e_head ? g.b + bi : bi) * g.D + d] = ga;
+            g.Gent[(int64_t)(e_head ? bi : g.b + bi) * g.D + d] = e_cp[it] * e_o[it];
+            g.Grel[(int64_t)bi * g.D + d] = gr;
         } else {  // EPI_CHAIN_DM: o = a * r, psi = o . x
             const float go = s + e_cp[it] * e_c[it];
             g.Gent[(int64_t)(e_head ? g.b + bi : bi) * g.D + gn] = go * e_r[it];
@@ -352,8 +386,9 @@ int pick_nw(int tiles, int nblk, int cap) {
     return nw;
 }
 
-void set_tiling(GemmArgs& g, int chunks) {
+void set_tiling(GemmArgs& g, int chunks, bool coordinate_tiles = false) {
     g.gx = (g.N + TILE - 1) / TILE;
+    if (coordinate_tiles) g.gx = (g.N / 2 + TILE / 2 - 1) / (TILE / 2);  // EPI_CHAIN_CX: 16 complex coordinates per tile
     g.gy = (g.M + TILE - 1) / TILE;
     g.tiles = g.gx * g.gy * chunks;
 }
@@ -380,7 +415,7 @@ void launch_one(kge_ctx* c, GemmArgs g, int items, hipStream_t st) {
 
 template <int EPI_O, int EPI_N>
 void launch_bwd(kge_ctx* c, GemmArgs gO, GemmArgs gN, int chunks, hipStream_t st) {
-    set_tiling(gO, chunks);
+    set_tiling(gO, chunks, EPI_O == EPI_CHAIN_CX);
     set_tiling(gN, chunks);
     const int per_n = (gN.tiles + 7) / 8, per_o = (gO.tiles + 7) / 8;
     const dim3 grid(8 * (per_n + per_o));
@@ -431,7 +466,8 @@ bool kge_gemm_backward_forms_w(const kge_ctx* c) {
     return c->cfg.adv_temperature == 0.f && c->cfg.loss == KGE_LOSS_LOGISTIC;
 }
 bool kge_gemm_backward_does_chain(const kge_ctx* c) {
-    return c->cfg.model == KGE_TRANSE_L2 || c->cfg.model == KGE_DISTMULT;
+    return c->cfg.model == KGE_TRANSE_L2 || c->cfg.model == KGE_DISTMULT ||
+           (c->cfg.model == KGE_COMPLEX && c->cfg.gemm_input == 0);
 }
 int kge_gemm_loss_parts(const kge_ctx* c, int b, int k, int gsz) {
     const int k_tiles = (k + TILE - 1) / TILE;
@@ -440,7 +476,7 @@ int kge_gemm_loss_parts(const kge_ctx* c, int b, int k, int gsz) {
 
 // dO_c = W_c N_c (- rowsum(W) o)  and  dN_c = W_c^T O_c (- colsum(W) n) in one launch.  dN goes straight into the
 // gradient rows of the corrupting entities (key positions 2b ..); dO goes through the chain rule into the
-// gradient rows of the positives (TransE-L2, DistMult) or into GO for k_chain (ComplEx).
+// gradient rows of the positives (TransE-L2, DistMult, ComplEx with fp32 operands) or into GO for k_chain.
 void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const StepIds& ids, int k, int gsz, float gamma,
                            hipStream_t st) {
     const int D = c->cfg.ent_dim, b = ids.b;
@@ -476,6 +512,7 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
     } while (0)
     if (model == KGE_TRANSE_L2) KGE_BWD(EPI_CHAIN_L2, EPI_L2_DN);
     else if (model == KGE_DISTMULT) KGE_BWD(EPI_CHAIN_DM, EPI_PLAIN);
+    else if (model == KGE_COMPLEX && !bf) launch_bwd<EPI_CHAIN_CX, EPI_PLAIN>(c, g, q, chunks, st);
     else KGE_BWD(EPI_PLAIN, EPI_PLAIN);
 #undef KGE_BWD
 }

@@ -8,7 +8,7 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-enum { EPI_PLAIN = 0, EPI_L2_FWD = 1, EPI_L2_DO = 2, EPI_L2_DN = 3, EPI_CHAIN_L2 = 4, EPI_CHAIN_DM = 5 };
+enum { EPI_PLAIN = 0, EPI_L2_FWD = 1, EPI_L2_DO = 2, EPI_L2_DN = 3, EPI_CHAIN_L2 = 4, EPI_CHAIN_DM = 5, EPI_CHAIN_CX = 6 };
 // what the forward launch leaves behind (see kge_gemm_neg_score); OUT_RANK: nothing but the ranks of the positives
 enum { OUT_SCORE = 0, OUT_DIST = 1, OUT_W = 2, OUT_RANK = 3 };
 
