@@ -352,17 +352,20 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_fwd(GemmArgs g) {
     gemm_tile<NW, true, true, EPI, false>(g, tile, lds);
 }
 
-// dN tiles first (their K is the chunk size, they run longest), then dO tiles; each XCD gets its share of both.
+// The tiles with the longer K loop first (dN: K is the chunk size; dO: K is the number of corrupting rows per chunk),
+// then the others; each XCD gets its share of both.
 // Held to 128 registers so that four waves fit on every SIMD (two 8-wave workgroups per CU): all tiles of the
 // Freebase-scale step are then resident at once instead of running in two rounds.
 template <int NW, int EPI_O, int EPI_N>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(4, 4))) void k_gemm_bwd(GemmArgs gO, GemmArgs gN, int per_xcd_n, int per_xcd_o) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
-    const int q = blockIdx.x >> 3;
+    const int per_xcd = per_xcd_n + per_xcd_o;
+    int q = blockIdx.x >> 3;
+    if (gO.K > gN.K) q = q < per_xcd_o ? q + per_xcd_n : q - per_xcd_o;  // dO tiles first
     if (q < per_xcd_n) {
         const int tile = xcd_tile(q, per_xcd_n);
         if (tile < gN.tiles) gemm_tile<NW, false, false, EPI_N, false>(gN, tile, lds);
-    } else {
+    } else if (q < per_xcd) {
         const int tile = xcd_tile(q - per_xcd_n, per_xcd_o);
         if (tile < gO.tiles) gemm_tile<NW, true, false, EPI_O, true>(gO, tile, lds);
     }
