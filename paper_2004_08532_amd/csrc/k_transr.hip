@@ -129,8 +129,37 @@ __global__ __launch_bounds__(RT) void k_transr_phi(TransrArgs a, float* pos_out)
     }
 }
 
-// wave per (positive, negative): S_ij = gamma - |o_i - P_ij|^2
-__global__ __launch_bounds__(RT) void k_transr_score(TransrArgs a, float* out, int ld_out) {
+// Workgroup per positive: S_ij = gamma - |o_i - P_ij|^2.  A row of D floats is D / 4 16-byte pieces; a group of SUB
+// lanes (the power of two that holds them, at most a wave) takes one j at a time, so that short rows do not leave most
+// of a wave idle, and works on four of its j in one round (four loads in flight, then four shuffle reductions).
+template <int SUB>
+__device__ __forceinline__ void transr_score_rows(const TransrArgs& a, float* out, int ld_out) {
+    constexpr int GROUPS = RT / SUB;
+    const int i = blockIdx.x, grp = threadIdx.x / SUB, ln = threadIdx.x % SUB, D = a.D, lanes = D / 4;
+    const bool act = ln < lanes;
+    const float4 ov = act ? ld4(a.O + (int64_t)i * D + 4 * ln) : f4(0.f);
+    const float* P = a.P + (int64_t)i * a.k * D + (act ? 4 * ln : 0);
+    for (int j0 = grp; j0 < a.k; j0 += 4 * GROUPS) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int j = j0 + u * GROUPS;
+            v[u] = ld4(P + (int64_t)(j < a.k ? j : j0) * D);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float d0 = ov.x - v[u].x, d1 = ov.y - v[u].y, d2 = ov.z - v[u].z, d3 = ov.w - v[u].w;
+            float ss = act ? d0 * d0 + d1 * d1 + d2 * d2 + d3 * d3 : 0.f;
+#pragma unroll
+            for (int o = SUB / 2; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+            const int j = j0 + u * GROUPS;
+            if (ln == 0 && j < a.k) out[(int64_t)i * ld_out + j] = a.gamma - ss;
+        }
+    }
+}
+
+// rows of more than 256 floats: a wave per j, up to four pieces per lane
+__device__ __forceinline__ void transr_score_long_rows(const TransrArgs& a, float* out, int ld_out) {
     const int i = blockIdx.x, w = threadIdx.x >> 6, lane = threadIdx.x & 63, D = a.D, lanes = D / 4;
     const float* o = a.O + (int64_t)i * D;
     float4 ov[4];
@@ -153,34 +182,89 @@ __global__ __launch_bounds__(RT) void k_transr_score(TransrArgs a, float* out, i
     }
 }
 
-// thread per 16 bytes of the row: U_ij = 2 W_ij (o_i - P_ij) over P_ij, for j in order; GO_i = - sum_j U_ij
-__global__ __launch_bounds__(RT) void k_transr_dp(TransrArgs a) {
-    const int i = blockIdx.x, v = threadIdx.x, D = a.D;
-    if (4 * v >= D) return;
-    const float4 o = ld4(a.O + (int64_t)i * D + 4 * v);
-    const float* W = a.S + (int64_t)i * a.ld_s;
-    float4 go = f4(0.f);
-    for (int j = 0; j < a.k; ++j) {
-        float* p = a.P + ((int64_t)i * a.k + j) * D + 4 * v;
-        const float4 pv = ld4(p);
-        const float w2 = 2.f * W[j];
-        const float4 u = make_float4(w2 * (o.x - pv.x), w2 * (o.y - pv.y), w2 * (o.z - pv.z), w2 * (o.w - pv.w));
-        st4(p, u);
-        go.x -= u.x; go.y -= u.y; go.z -= u.z; go.w -= u.w;
-    }
-    st4(a.GO + (int64_t)i * D + 4 * v, go);
+__global__ __launch_bounds__(RT) void k_transr_score(TransrArgs a, float* out, int ld_out) {
+    const int lanes = a.D / 4;  // (the same for every thread)
+    if (lanes <= 16) transr_score_rows<16>(a, out, ld_out);
+    else if (lanes <= 32) transr_score_rows<32>(a, out, ld_out);
+    else if (lanes <= 64) transr_score_rows<64>(a, out, ld_out);
+    else transr_score_long_rows(a, out, ld_out);
 }
 
-// workgroup per corrupting row (c, j): its gradient row is the sum of T_i[j] over the positives i of chunk c
-__global__ __launch_bounds__(RT) void k_transr_reduce(TransrArgs a) {
-    const int row = blockIdx.x, c = row / a.k, j = row - c * a.k, v = threadIdx.x, D = a.D;
-    if (4 * v >= D) return;
-    float4 s = f4(0.f);
-    for (int i = c * a.g; i < (c + 1) * a.g; ++i) {
-        const float4 t = ld4(a.T + ((int64_t)i * a.k + j) * D + 4 * v);
-        s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+// Threads (group, 16 bytes of the row); the groups share out the rows they walk, four loads in flight each, and their
+// sums meet in LDS in group order.
+// U_ij = 2 W_ij (o_i - P_ij) over P_ij; GO_i = - sum_j U_ij
+__global__ __launch_bounds__(RT) void k_transr_dp(TransrArgs a) {
+    __shared__ __attribute__((aligned(16))) float4 part[RT];
+    const int i = blockIdx.x, D = a.D, lanes = D / 4, groups = RT / lanes;
+    const int grp = threadIdx.x / lanes, v = threadIdx.x % lanes;
+    const float* W = a.S + (int64_t)i * a.ld_s;
+    float4 go = f4(0.f);
+    if (grp < groups) {
+        const float4 o = ld4(a.O + (int64_t)i * D + 4 * v);
+        float* P = a.P + (int64_t)i * a.k * D + 4 * v;
+        for (int j0 = grp; j0 < a.k; j0 += 4 * groups) {
+            float4 pv[4];
+            float w2[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u * groups < a.k ? j0 + u * groups : j0;
+                pv[u] = ld4(P + (int64_t)j * D);
+                w2[u] = 2.f * W[j];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u * groups;
+                if (j < a.k) {
+                    const float4 q = make_float4(w2[u] * (o.x - pv[u].x), w2[u] * (o.y - pv[u].y), w2[u] * (o.z - pv[u].z),
+                                                 w2[u] * (o.w - pv[u].w));
+                    st4(P + (int64_t)j * D, q);
+                    go.x -= q.x; go.y -= q.y; go.z -= q.z; go.w -= q.w;
+                }
+            }
+        }
     }
-    st4(a.Gent + ((int64_t)2 * a.b + row) * D + 4 * v, s);
+    part[threadIdx.x] = go;
+    __syncthreads();
+    if (grp == 0) {
+        float4 t = part[v];
+        for (int g2 = 1; g2 < groups; ++g2) {
+            const float4 q = part[g2 * lanes + v];
+            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+        }
+        st4(a.GO + (int64_t)i * D + 4 * v, t);
+    }
+}
+
+// workgroup per corrupting row (c, j): its gradient row is the sum of T_i[j] over the positives i of chunk c; the same
+// sharing of the rows among thread groups
+__global__ __launch_bounds__(RT) void k_transr_reduce(TransrArgs a) {
+    __shared__ __attribute__((aligned(16))) float4 part[RT];
+    const int row = blockIdx.x, c = row / a.k, j = row - c * a.k, D = a.D, lanes = D / 4, groups = RT / lanes;
+    const int grp = threadIdx.x / lanes, v = threadIdx.x % lanes;
+    float4 s = f4(0.f);
+    if (grp < groups) {
+        const float* T = a.T + ((int64_t)c * a.g * a.k + j) * D + 4 * v;
+        const int64_t stride = (int64_t)a.k * D;  // from one positive's T_i[j] to the next one's
+        for (int i0 = grp; i0 < a.g; i0 += 4 * groups) {
+            float4 t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t[u] = ld4(T + (i0 + u * groups < a.g ? i0 + u * groups : i0) * stride);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (i0 + u * groups < a.g) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
+            }
+        }
+    }
+    part[threadIdx.x] = s;
+    __syncthreads();
+    if (grp == 0) {
+        float4 t = part[v];
+        for (int g2 = 1; g2 < groups; ++g2) {
+            const float4 q = part[g2 * lanes + v];
+            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
+        }
+        st4(a.Gent + ((int64_t)2 * a.b + row) * D + 4 * v, t);
+    }
 }
 
 __global__ __launch_bounds__(RT) void k_transr_chain(TransrArgs a) {
