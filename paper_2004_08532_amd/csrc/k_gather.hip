@@ -251,11 +251,16 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
         float* dst = a.Nst + (int64_t)j * D;
         float nn = 0.f;
         const int nv4 = D / 4;
+        // every piece of the row is asked for before the first one is used (a load under a branch is waited for
+        // where the branch ends: lanes past the row's end read its first piece instead)
+        float4 xs[CPLX ? 2 * NV : NV];
+#pragma unroll
+        for (int it = 0; it < (CPLX ? 2 * NV : NV); ++it) xs[it] = ld4(src + 4 * (lane + it * 64 < nv4 ? lane + it * 64 : 0));
 #pragma unroll
         for (int it = 0; it < (CPLX ? 2 * NV : NV); ++it) {
             const int v = lane + it * 64;
             if (v < nv4) {
-                float4 x = ld4(src + 4 * v);
+                const float4 x = xs[it];
                 float xv[4] = {x.x, x.y, x.z, x.w};
                 if (a.bf16) {  // the product kernels round their operands to bf16: the norm is that of the rounded row
 #pragma unroll
@@ -285,20 +290,36 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
     float* po = a.O + (int64_t)i * D;
     float acc = 0.f, on = 0.f;
 
+    // all loads first, as for the corrupting rows.  L1 .. L6: the (up to six) 16-byte pieces that piece v of o needs
+    float4 L1[NV], L2[NV], L3[NV], L4[NV], L5[NV], L6[NV];
+#pragma unroll
+    for (int it = 0; it < NV; ++it) {
+        const int vs = lane + it * 64 < nvec ? lane + it * 64 : 0;
+        if constexpr (MODEL == KGE_RESCAL) {
+            L1[it] = ld4(po + 4 * vs); L2[it] = ld4(pc + 4 * vs);
+        } else if constexpr (!CPLX) {
+            L1[it] = ld4(pa + 4 * vs); L2[it] = ld4(pr + 4 * vs); L3[it] = ld4(pc + 4 * vs);
+        } else {
+            L1[it] = ld4(pa + 4 * vs); L2[it] = ld4(pa + im_off + 4 * vs);
+            L3[it] = ld4(pc + 4 * vs); L4[it] = ld4(pc + im_off + 4 * vs);
+            L5[it] = ld4(pr + 4 * vs);
+            if (MODEL != KGE_ROTATE) L6[it] = ld4(pr + im_off + 4 * vs);
+        }
+    }
 #pragma unroll
     for (int it = 0; it < NV; ++it) {
         const int v = lane + it * 64;
         if (v >= nvec) continue;
         if constexpr (MODEL == KGE_RESCAL) {
             // o_i = M_r^T h or M_r t is already in staging (k_rescal); the positive's score is o . c
-            const float4 Oo = ld4(po + 4 * v), Cc = ld4(pc + 4 * v);
+            const float4 Oo = L1[it], Cc = L2[it];
             acc += Oo.x * Cc.x + Oo.y * Cc.y + Oo.z * Cc.z + Oo.w * Cc.w;
             if (a.bf16) {
                 const float n0 = round_bf16(Oo.x), n1 = round_bf16(Oo.y), n2 = round_bf16(Oo.z), n3 = round_bf16(Oo.w);
                 on += n0 * n0 + n1 * n1 + n2 * n2 + n3 * n3;
             }
         } else if constexpr (!CPLX) {
-            const float4 A = ld4(pa + 4 * v), Rr = ld4(pr + 4 * v), Cc = ld4(pc + 4 * v);
+            const float4 A = L1[it], Rr = L2[it], Cc = L3[it];
             const float av[4] = {A.x, A.y, A.z, A.w}, rv[4] = {Rr.x, Rr.y, Rr.z, Rr.w}, cv[4] = {Cc.x, Cc.y, Cc.z, Cc.w};
             float ov[4];
 #pragma unroll
@@ -323,18 +344,18 @@ __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
                 on += nv[0] * nv[0] + nv[1] * nv[1] + nv[2] * nv[2] + nv[3] * nv[3];
             }
         } else {
-            const float4 Are = ld4(pa + 4 * v), Aim = ld4(pa + im_off + 4 * v);
-            const float4 Cre = ld4(pc + 4 * v), Cim = ld4(pc + im_off + 4 * v);
+            const float4 Are = L1[it], Aim = L2[it];
+            const float4 Cre = L3[it], Cim = L4[it];
             const float are[4] = {Are.x, Are.y, Are.z, Are.w}, aim[4] = {Aim.x, Aim.y, Aim.z, Aim.w};
             const float cre[4] = {Cre.x, Cre.y, Cre.z, Cre.w}, cim[4] = {Cim.x, Cim.y, Cim.z, Cim.w};
             float rre[4], rim[4];
             if (MODEL == KGE_ROTATE) {
-                const float4 Th = ld4(pr + 4 * v);
+                const float4 Th = L5[it];
                 const float th[4] = {Th.x, Th.y, Th.z, Th.w};
 #pragma unroll
                 for (int e = 0; e < 4; ++e) sincosf(th[e], &rim[e], &rre[e]);
             } else {
-                const float4 Rre = ld4(pr + 4 * v), Rim = ld4(pr + im_off + 4 * v);
+                const float4 Rre = L5[it], Rim = L6[it];
                 rre[0] = Rre.x; rre[1] = Rre.y; rre[2] = Rre.z; rre[3] = Rre.w;
                 rim[0] = Rim.x; rim[1] = Rim.y; rim[2] = Rim.z; rim[3] = Rim.w;
             }
