@@ -309,7 +309,8 @@ def main():
     torch.cuda.empty_cache()
     others = []
     if args.other_workloads and args.workload == "freebase-transe_l2":
-        for name in ("small-distmult", "small-complex", "medium", "large", "freebase-complex"):
+        for name in ("small-distmult", "small-complex", "medium", "large", "freebase-complex", "small-rescal",
+                     "small-transr"):
             others.append(time_other_workload(kge, torch, configs, name, 2000, 100))
             torch.cuda.empty_cache()
 
