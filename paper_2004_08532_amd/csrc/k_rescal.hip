@@ -70,27 +70,51 @@ __global__ __launch_bounds__(RT) void k_rescal(RescalArgs a) {
             const int q = lane + 64 * it;
             vv[it] = q < lanes ? ld4(vec + 4 * q) : f4(0.f);
         }
-        for (int r = w; r < D; r += RT / 64) {
-            const float* row = M + (int64_t)r * D;
-            float s = 0.f;
+        if (lanes <= 64) {
+            // one piece per lane: four rows per round, so that four loads are in flight (lanes past the row's end
+            // read its first piece and add nothing)
+            const float* Mc = M + (lane < lanes ? 4 * lane : 0);
+            for (int r0 = w; r0 < D; r0 += 4 * (RT / 64)) {
+                float4 m[4];
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int q = lane + 64 * it;
-                if (q < lanes) {
-                    const float4 m = ld4(row + 4 * q);
-                    s += m.x * vv[it].x + m.y * vv[it].y + m.z * vv[it].z + m.w * vv[it].w;
+                for (int u = 0; u < 4; ++u) m[u] = ld4(Mc + (int64_t)(r0 + u * (RT / 64) < D ? r0 + u * (RT / 64) : r0) * D);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    float s = lane < lanes ? m[u].x * vv[0].x + m[u].y * vv[0].y + m[u].z * vv[0].z + m[u].w * vv[0].w : 0.f;
+                    s = wave_sum(s);
+                    const int r = r0 + u * (RT / 64);
+                    if (lane == 0 && r < D) res[r] = s;
                 }
             }
-            s = wave_sum(s);
-            if (lane == 0) res[r] = s;
+        } else {
+            for (int r = w; r < D; r += RT / 64) {
+                const float* row = M + (int64_t)r * D;
+                float s = 0.f;
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int q = lane + 64 * it;
+                    if (q < lanes) {
+                        const float4 m = ld4(row + 4 * q);
+                        s += m.x * vv[it].x + m.y * vv[it].y + m.z * vv[it].z + m.w * vv[it].w;
+                    }
+                }
+                s = wave_sum(s);
+                if (lane == 0) res[r] = s;
+            }
         }
     } else {
         float4 y = f4(0.f);
         if (grp < groups) {
-            for (int r = grp; r < D; r += groups) {
-                const float4 m = ld4(M + (int64_t)r * D + 4 * v);
-                const float s = vec[r];
-                y.x += s * m.x; y.y += s * m.y; y.z += s * m.z; y.w += s * m.w;
+            for (int r0 = grp; r0 < D; r0 += 4 * groups) {  // four rows per round, their loads in flight together
+                float4 m[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) m[u] = ld4(M + (int64_t)(r0 + u * groups < D ? r0 + u * groups : r0) * D + 4 * v);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int r = r0 + u * groups;
+                    const float s = r < D ? vec[r] : 0.f;
+                    y.x += s * m[u].x; y.y += s * m[u].y; y.z += s * m[u].z; y.w += s * m[u].w;
+                }
             }
         }
         part[tid] = y;

@@ -68,8 +68,36 @@ __device__ __forceinline__ Rows rows_of(const TransrArgs& a, int i) {
     return x;
 }
 
-// y1 = M v1, y2 = M v2 (row dots: a wave per matrix row, 16-byte loads, shuffle reduction); v1, v2, y1, y2 in LDS
-__device__ __forceinline__ void row_dots(const float* M, int D, const float* v1, const float* v2, float* y1, float* y2) {
+// y1 = M v1, y2 = M v2; v1, v2, y1, y2 in LDS.  Row dots: a group of SUB lanes (the power of two that holds the row's
+// 16-byte pieces, at most a wave) per matrix row, four rows per round so that four loads are in flight, shuffle
+// reductions inside the group.  Rows of more than 256 floats: a wave per row, up to four pieces per lane.
+template <int SUB>
+__device__ __forceinline__ void row_dots_short(const float* M, int D, const float* v1, const float* v2, float* y1, float* y2) {
+    constexpr int GROUPS = RT / SUB;
+    const int grp = threadIdx.x / SUB, ln = threadIdx.x % SUB, lanes = D / 4;
+    const bool act = ln < lanes;
+    const float4 a1 = act ? ld4(v1 + 4 * ln) : f4(0.f), a2 = act ? ld4(v2 + 4 * ln) : f4(0.f);
+    const float* Mc = M + (act ? 4 * ln : 0);
+    for (int r0 = grp; r0 < D; r0 += 4 * GROUPS) {
+        float4 m[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) m[u] = ld4(Mc + (int64_t)(r0 + u * GROUPS < D ? r0 + u * GROUPS : r0) * D);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float s1 = act ? m[u].x * a1.x + m[u].y * a1.y + m[u].z * a1.z + m[u].w * a1.w : 0.f;
+            float s2 = act ? m[u].x * a2.x + m[u].y * a2.y + m[u].z * a2.z + m[u].w * a2.w : 0.f;
+#pragma unroll
+            for (int o = SUB / 2; o > 0; o >>= 1) {
+                s1 += __shfl_xor(s1, o, 64);
+                s2 += __shfl_xor(s2, o, 64);
+            }
+            const int r = r0 + u * GROUPS;
+            if (ln == 0 && r < D) { y1[r] = s1; y2[r] = s2; }
+        }
+    }
+}
+
+__device__ __forceinline__ void row_dots_long(const float* M, int D, const float* v1, const float* v2, float* y1, float* y2) {
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, lanes = D / 4;
     float4 a1[4], a2[4];
 #pragma unroll
@@ -94,6 +122,14 @@ __device__ __forceinline__ void row_dots(const float* M, int D, const float* v1,
         s2 = wave_sum(s2);
         if (lane == 0) { y1[r] = s1; y2[r] = s2; }
     }
+}
+
+__device__ __forceinline__ void row_dots(const float* M, int D, const float* v1, const float* v2, float* y1, float* y2) {
+    const int lanes = D / 4;  // (the same for every thread)
+    if (lanes <= 16) row_dots_short<16>(M, D, v1, v2, y1, y2);
+    else if (lanes <= 32) row_dots_short<32>(M, D, v1, v2, y1, y2);
+    else if (lanes <= 64) row_dots_short<64>(M, D, v1, v2, y1, y2);
+    else row_dots_long(M, D, v1, v2, y1, y2);
 }
 
 __global__ __launch_bounds__(RT) void k_transr_phi(TransrArgs a, float* pos_out) {
