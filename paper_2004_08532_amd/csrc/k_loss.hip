@@ -165,12 +165,17 @@ struct ChainArgs {
     PartialRows rest;
 };
 
-// sum of `parts` 16-byte pieces `stride` floats apart, in order
+// sum of `parts` (at most KGE_PAIR_MAX_PARTS) 16-byte pieces `stride` floats apart, in order; all of them are asked
+// for before the first is added (a part that does not exist is read from part 0 and left out of the sum)
 __device__ __forceinline__ float4 ld4_parts(const float* p, int parts, int64_t stride) {
-    float4 s = ld4(p);
-    for (int q = 1; q < parts; ++q) {
-        const float4 v = ld4(p + q * stride);
-        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    if (parts <= 1) return ld4(p);  // (the same for every thread)
+    float4 v[KGE_PAIR_MAX_PARTS];
+#pragma unroll
+    for (int q = 0; q < KGE_PAIR_MAX_PARTS; ++q) v[q] = ld4(p + (q < parts ? q : 0) * stride);
+    float4 s = v[0];
+#pragma unroll
+    for (int q = 1; q < KGE_PAIR_MAX_PARTS; ++q) {
+        if (q < parts) { s.x += v[q].x; s.y += v[q].y; s.z += v[q].z; s.w += v[q].w; }
     }
     return s;
 }
