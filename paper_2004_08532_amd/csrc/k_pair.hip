@@ -47,8 +47,8 @@ __device__ __forceinline__ float pair_term(float o_re, float o_im, float n_re, f
     return __builtin_amdgcn_sqrtf(q_re * q_re + q_im * q_im);
 }
 
-// 512 threads: both halves of the workgroup hold the same 2x2 blocks of pairs, the first half sums coordinates 0..15 of
-// every staged step, the second 16..31 (twice the waves for the same LDS traffic); their sums meet at the end.
+// 512 threads: both halves of the workgroup hold the same 2x2 blocks of pairs and take the groups of four coordinates of
+// every staged step in turn (twice the waves for the same LDS traffic); their sums meet at the end.
 template <bool CPLX>
 __global__ __launch_bounds__(512) void k_pair_fwd(PairArgs a) {
     __shared__ __attribute__((aligned(16))) float Os[CPLX ? 2 : 1][PT][PPITCH];
@@ -86,7 +86,10 @@ __global__ __launch_bounds__(512) void k_pair_fwd(PairArgs a) {
         float part[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
 #pragma unroll
         for (int cq = 0; cq < PCK / 2; cq += 4) {
-            const int cc = cq + half * (PCK / 2);
+            // groups of four coordinates go to the two halves in turn, so that a last step with few coordinates is
+            // still shared; (NC is a multiple of 4) what lies past NC is padding
+            const int cc = 2 * cq + 4 * half;
+            if (c0 + cc >= NC) break;
             float o_re[2][4], o_im[2][4], n_re[2][4], n_im[2][4];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
