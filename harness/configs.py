@@ -1,4 +1,4 @@
-"""The five workload configurations and a batch stream built on the graph and index generators.
+"""The workload configurations and a batch stream built on the graph and index generators.
 
 Inputs only: this module draws graphs, ids and initial tables; it evaluates nothing of the method.
 Counts for ``small`` and ``freebase`` are the entity / relation counts of Table 3 of the paper (FB15k and
@@ -55,6 +55,11 @@ SMALL_COMPLEX = SMALL_DISTMULT.scaled(name="small-complex", model="complex")
 SMALL_RESCAL = SMALL_DISTMULT.scaled(name="small-rescal", model="rescal", ent_dim=200, rel_dim=200 * 200)
 # TransR at the same graph and batch shape, rows of 100 floats: a relation row is a translation and a 100 x 100 matrix
 SMALL_TRANSR = SMALL_DISTMULT.scaled(name="small-transr", model="transr", ent_dim=100, rel_dim=100 + 100 * 100)
+# Sec. 6.1.1 / Fig. 3 of the paper compares joint with independent negative sampling for TransE on FB15k: the same
+# graph and batch with chunks of 128 positives sharing 256 corrupting entities, and with every positive drawing its
+# own 256 (chunks of one positive)
+SMALL_TRANSE_JOINT = SMALL_DISTMULT.scaled(name="small-transe_l2-joint", model="transe_l2")
+SMALL_TRANSE_INDEPENDENT = SMALL_TRANSE_JOINT.scaled(name="small-transe_l2-independent", chunk=1)
 MEDIUM = Workload("medium", "rotate", 2_500_000, 800, 16_000_000, 0.9, None, 400, 200, 1024, 128, 256, "degree",
                   "tail", 12.0, 0.1, adv_temperature=1.0, steps=1000)
 LARGE = Workload("large", "transe_l2", 5_000_000, 800, 20_000_000, 0.9, None, 400, 400, 2048, 256, 1024, "uniform",
@@ -63,7 +68,8 @@ FREEBASE_TRANSE = Workload("freebase-transe_l2", "transe_l2", 86_054_151, 14_824
                            200, "uniform", "tail", 12.0, 0.1, steps=100_000)
 FREEBASE_COMPLEX = FREEBASE_TRANSE.scaled(name="freebase-complex", model="complex")
 
-ALL = {w.name: w for w in (TINY, SMALL_DISTMULT, SMALL_COMPLEX, SMALL_RESCAL, SMALL_TRANSR, MEDIUM, LARGE, FREEBASE_TRANSE,
+ALL = {w.name: w for w in (TINY, SMALL_DISTMULT, SMALL_COMPLEX, SMALL_RESCAL, SMALL_TRANSR, SMALL_TRANSE_JOINT,
+                           SMALL_TRANSE_INDEPENDENT, MEDIUM, LARGE, FREEBASE_TRANSE,
                            FREEBASE_COMPLEX)}
 
 

@@ -332,6 +332,8 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const bool transr = m == KGE_TRANSR;
     const size_t proj = transr ? B * (size_t)(cfg->max_neg_per_chunk > 0 ? cfg->max_neg_per_chunk : 1) * D * 4 : 0;
     const size_t o_PP = take(transr ? B * D * 4 : 0), o_P3 = take(proj), o_T3 = take(proj);
+    const size_t sort_slices = (EK + KGE_SORT_SLICE - 1) / KGE_SORT_SLICE + (B + KGE_SORT_SLICE - 1) / KGE_SORT_SLICE;
+    const size_t o_sc = take(sort_slices * 16 * 256 * 4 + 2 * 256 * 4);  // digit counts of every wave + the two lists' digit bases
     const bool pair_model = m == KGE_ROTATE || m == KGE_TRANSE_L1;
     const size_t o_ppo = take(pair_model ? KGE_PAIR_MAX_PARTS * B * D * 4 : 0), o_ppn = take(pair_model ? KGE_PAIR_MAX_PARTS * NR * D * 4 : 0);
     c->ws_bytes = (int64_t)off;
@@ -359,6 +361,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->T3 = transr ? (float*)(base + o_T3) : nullptr;
     c->pair_part_o = pair_model ? (float*)(base + o_ppo) : nullptr;
     c->pair_part_n = pair_model ? (float*)(base + o_ppn) : nullptr;
+    c->sort_counts = (uint32_t*)(base + o_sc);
     c->flags = (int*)(base + o_flags);
     c->step_counter = (int64_t*)(base + o_step);
 

@@ -66,6 +66,7 @@ struct kge_ctx {
                         // forward launch counts); null otherwise
 
     int ebuf, rbuf;                 // which ping-pong half holds the sorted result
+    uint32_t* sort_counts;          // radix sort: digit counts / offsets, [slices of both lists][16 waves][256]
     int64_t last_ent_keys, last_rel_keys;  // sizes of the last train step's key lists (0: none yet)
     hipStream_t side_stream;        // runs the key sort beside the forward/backward kernels
     hipEvent_t ev_fork, ev_join;
@@ -138,6 +139,7 @@ void kge_make_key_lists(kge_ctx* c, const StepIds& ids, KeyList* ent, KeyList* r
 // KGE_RANK_MAX_KEYS keys; longer lists go through kge_launch_sort)
 void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds& ids, float gamma, float* pos_out,
                        bool with_keys, hipStream_t st);
+constexpr int KGE_SORT_SLICE = 4096;  // keys per workgroup of the radix sort of long key lists
 constexpr int KGE_PAIR_MAX_PARTS = 8;  // partial rows per gradient row in the tiled backward of RotatE / TransE-L1
 constexpr int KGE_RANK_MAX_KEYS = 14336;  // 14 * 1024: positions fit 14 bits, the list and its tables fit 64 KB of LDS
 // a3: negative scores of every chunk into out[b x ld_out]: matrix-product models / elementwise-reduce models
