@@ -592,6 +592,8 @@ REPLAY_VARIANTS = {
     "transr": dict(model="transr", ent_dim=32, rel_dim=32 + 32 * 32),
     "rotate-ranking-adversarial": dict(model="rotate", rel_dim=32, loss="ranking", gamma=0.5, adv_temperature=1.0),
     "complex-bf16": dict(model="complex", bf16_inputs=True),
+    # 16,512 entity keys per step: the radix sort on the second stream, forked and joined inside the captured graph
+    "long-key-lists": dict(neg_per_chunk=2000),
 }
 
 
@@ -601,7 +603,7 @@ def test_train_steps_graph_replay_equals_step_by_step(kge, variant):
     bit, on every replay: first use (capture), reuse with new ids in the same buffers, a step count that is not a
     multiple of the unroll factor, with eager work and synchronisation in between.  The variants take every kernel
     of the library through a replayed graph once (fused and separate loss / chain kernels, pair kernels, the RESCAL
-    kernels, the bf16 products)."""
+    kernels, the bf16 products, the sort of long key lists)."""
     w = configs.TINY.scaled(name="tiny-replay", side_mode="alternate", **REPLAY_VARIANTS[variant])
     bs = configs.BatchStream(w)
     E0, R0 = configs.init_tables(w)
