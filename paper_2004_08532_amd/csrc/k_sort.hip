@@ -7,8 +7,10 @@
 // 8 bits per pass, over only as many bits as the table's row count needs, ping-ponging through global memory.  A list
 // is cut into slices of 4096 keys, one workgroup of 1024 threads per slice, and inside a slice every wavefront owns
 // 256 consecutive keys.  A pass is three launches:
-//   k_sort_count    every wavefront counts the digits of its keys           -> counts [slice][wave][digit]
-//   k_sort_offsets  one workgroup per list: exclusive prefix of the counts, digit-major, then slice, then wave
+//   k_sort_count    every wavefront counts the digits of its keys; per slice and digit: the counts of the earlier
+//                   waves, and the slice's total
+//   k_sort_offsets  one workgroup per list: per digit the totals of the earlier slices, and the number of keys with a
+//                   smaller digit
 //   k_sort_scatter  every wavefront walks its keys again in the same order and writes them to their places; equal
 //                   digits inside a 64-key round are ranked with ballots
 // so the sort is stable and equal ids end up ordered by position.  Both lists go through the same launches (the
@@ -26,7 +28,8 @@ constexpr int WAVE_KEYS = SORT_SLICE / SORT_WAVES;  // consecutive keys per wave
 struct SortArgs {
     KeyList list[2];       // entity keys, relation keys
     int slices[2];         // workgroups per list
-    uint32_t* counts[2];   // [slices * SORT_WAVES][256] per list
+    uint32_t* counts[2];   // [slices * SORT_WAVES][256] per list: keys with the digit in the earlier waves of the slice
+    uint32_t* slice_tot[2];  // [slices][256] per list: keys with the digit in the slice, then in the earlier slices
     uint32_t* bases[2];    // [256] per list: number of keys with a smaller digit
     int pass;
 };
@@ -79,28 +82,37 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_count(SortArgs a) {
         if (valid && (peers & lt_mask) == 0) hist[w][d] = hist[w][d] + (uint32_t)__popcll(peers);  // one lane per digit
         __builtin_amdgcn_wave_barrier();
     }
-    uint32_t* out = a.counts[r.which] + ((int64_t)r.slice * SORT_WAVES + w) * 256;
-    for (int e = lane; e < 256; e += 64) out[e] = hist[w][e];
+    __syncthreads();
+    if (tid < 256) {  // thread d: the digit's counts of the 16 waves become exclusive prefixes, their sum the slice's total
+        uint32_t* out = a.counts[r.which] + (int64_t)r.slice * SORT_WAVES * 256 + tid;
+        uint32_t run = 0;
+#pragma unroll
+        for (int ww = 0; ww < SORT_WAVES; ++ww) {
+            out[ww * 256] = run;
+            run += hist[ww][tid];
+        }
+        a.slice_tot[r.which][(int64_t)r.slice * 256 + tid] = run;
+    }
 }
 
-// One workgroup per list, thread d = digit d: the running sum over (slice, wave) of the digit's counts replaces the
-// counts; the exclusive prefix over the digits' totals goes to bases (the scatter adds the two).
+// One workgroup per list, thread d = digit d: the running sum over the slices of the digit's totals replaces the
+// totals; the exclusive prefix over the digits' sums goes to bases (the scatter adds the three parts).
 __global__ __launch_bounds__(256) void k_sort_offsets(SortArgs a) {
     __shared__ uint32_t wave_tot[4];
     const int which = blockIdx.x;
     if (!sort_pass_runs(a, which)) return;
     const int d = threadIdx.x, lane = d & 63, w = d >> 6;
-    uint32_t* cnt = a.counts[which];
-    const int units = a.slices[which] * SORT_WAVES;
+    uint32_t* tot = a.slice_tot[which];
+    const int slices = a.slices[which];
     uint32_t total = 0;
-    for (int u0 = 0; u0 < units; u0 += 8) {  // eight loads in flight
+    for (int u0 = 0; u0 < slices; u0 += 8) {  // eight loads in flight
         uint32_t v[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] = cnt[(int64_t)(u0 + q < units ? u0 + q : u0) * 256 + d];
+        for (int q = 0; q < 8; ++q) v[q] = tot[(int64_t)(u0 + q < slices ? u0 + q : u0) * 256 + d];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
-            if (u0 + q < units) {
-                cnt[(int64_t)(u0 + q) * 256 + d] = total;
+            if (u0 + q < slices) {
+                tot[(int64_t)(u0 + q) * 256 + d] = total;
                 total += v[q];
             }
         }
@@ -131,7 +143,8 @@ __global__ __launch_bounds__(SORT_THREADS) void k_sort_scatter(SortArgs a) {
     uint32_t* kout = l.key[a.pass & 1];
     uint32_t* pout = l.pos[a.pass & 1];
     const uint32_t* in = a.counts[r.which] + ((int64_t)r.slice * SORT_WAVES + w) * 256;
-    for (int e = lane; e < 256; e += 64) offs[w][e] = in[e] + a.bases[r.which][e];
+    const uint32_t* before = a.slice_tot[r.which] + (int64_t)r.slice * 256;
+    for (int e = lane; e < 256; e += 64) offs[w][e] = in[e] + before[e] + a.bases[r.which][e];
     __builtin_amdgcn_wave_barrier();
     for (int base = r.begin; base < r.end; base += 64) {
         const int idx = base + lane;
@@ -227,15 +240,22 @@ void kge_launch_sort(kge_ctx* c, const StepIds& ids, hipStream_t st) {
     for (int w = 0; w < 2; ++w) a.slices[w] = (a.list[w].n + SORT_SLICE - 1) / SORT_SLICE;
     a.counts[0] = c->sort_counts;
     a.counts[1] = c->sort_counts + (int64_t)a.slices[0] * SORT_WAVES * 256;
-    a.bases[0] = a.counts[1] + (int64_t)a.slices[1] * SORT_WAVES * 256;
+    a.slice_tot[0] = a.counts[1] + (int64_t)a.slices[1] * SORT_WAVES * 256;
+    a.slice_tot[1] = a.slice_tot[0] + (int64_t)a.slices[0] * 256;
+    a.bases[0] = a.slice_tot[1] + (int64_t)a.slices[1] * 256;
     a.bases[1] = a.bases[0] + 256;
     const int passes = a.list[0].passes > a.list[1].passes ? a.list[0].passes : a.list[1].passes;
     const dim3 grid(a.slices[0] + a.slices[1]);
+    // while profiling: the first launch takes the scope's start timestamp, the last one its stop timestamp
+    hipEvent_t ev0 = c->launch_ev0, ev1 = c->launch_ev1;
+    c->launch_ev0 = nullptr;
+    c->launch_ev1 = nullptr;
     for (a.pass = 0; a.pass < passes; ++a.pass) {
-        // (while profiling, the first launch of the sort carries the scope's timestamps)
-        KGE_LAUNCH(c, k_sort_count, grid, dim3(SORT_THREADS), 0, st, a);
+        if (a.pass == 0 && ev0) hipExtLaunchKernelGGL(k_sort_count, grid, dim3(SORT_THREADS), 0, st, ev0, nullptr, 0, a);
+        else hipLaunchKernelGGL(k_sort_count, grid, dim3(SORT_THREADS), 0, st, a);
         hipLaunchKernelGGL(k_sort_offsets, dim3(2), dim3(256), 0, st, a);
-        hipLaunchKernelGGL(k_sort_scatter, grid, dim3(SORT_THREADS), 0, st, a);
+        if (a.pass == passes - 1 && ev1) hipExtLaunchKernelGGL(k_sort_scatter, grid, dim3(SORT_THREADS), 0, st, nullptr, ev1, 0, a);
+        else hipLaunchKernelGGL(k_sort_scatter, grid, dim3(SORT_THREADS), 0, st, a);
     }
 }
 

@@ -333,7 +333,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t proj = transr ? B * (size_t)(cfg->max_neg_per_chunk > 0 ? cfg->max_neg_per_chunk : 1) * D * 4 : 0;
     const size_t o_PP = take(transr ? B * D * 4 : 0), o_P3 = take(proj), o_T3 = take(proj);
     const size_t sort_slices = (EK + KGE_SORT_SLICE - 1) / KGE_SORT_SLICE + (B + KGE_SORT_SLICE - 1) / KGE_SORT_SLICE;
-    const size_t o_sc = take(sort_slices * 16 * 256 * 4 + 2 * 256 * 4);  // digit counts of every wave + the two lists' digit bases
+    const size_t o_sc = take(sort_slices * 17 * 256 * 4 + 2 * 256 * 4);  // digit counts per wave and per slice + the two lists' digit bases
     const bool pair_model = m == KGE_ROTATE || m == KGE_TRANSE_L1;
     const size_t o_ppo = take(pair_model ? KGE_PAIR_MAX_PARTS * B * D * 4 : 0), o_ppn = take(pair_model ? KGE_PAIR_MAX_PARTS * NR * D * 4 : 0);
     c->ws_bytes = (int64_t)off;
