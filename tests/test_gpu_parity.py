@@ -145,6 +145,19 @@ def test_training_shapes_with_thousands_of_tiles(kge):
             p.close()
 
 
+@pytest.mark.parametrize("model", ["transe_l2", "complex", "rotate", "transe_l1"])
+def test_independent_negatives(kge, model):
+    """Every positive with corrupting entities of its own (chunks of one positive, the sampling that Sec. 3.3 of the
+    paper replaces): 96 chunks of 200 candidates, 19,392 entity keys per step, so the key lists take the radix sort,
+    and every product tile has one real row."""
+    w = ragged(model, batch=96, chunk=1, neg_per_chunk=200, steps=2)
+    p = Pair(w, kge)
+    try:
+        run_steps(p, configs.BatchStream(w), w.steps)
+    finally:
+        p.close()
+
+
 PAIR_BACKWARD_SHAPES = {
     # chunks of up to 128 positives take the backward in which a workgroup owns 16 positives x a range of negatives
     # and writes partial rows; here with 8 i-tiles of which the last is ragged, and 8 ranges of 22 negatives
