@@ -51,19 +51,19 @@ __device__ __forceinline__ void lds_barrier() {
 
 // ROWWISE: the accumulator is one float per row, fed with the mean of the squared elements of the row's summed
 // gradient:  S += mean_d g_d^2 ;  theta_d -= lr * g_d / (sqrt(S) + eps).
-template <bool ROWWISE, int T>
-__global__ __launch_bounds__(T) void k_update(UpdateArgs a) {
+template <bool ROWWISE>
+__global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
     int tile = blockIdx.x;
     const int tid = threadIdx.x;
-    __shared__ __attribute__((aligned(16))) float4 red[T];
+    __shared__ __attribute__((aligned(16))) float4 red[UPD_THREADS];
     if (tile == a.tiles[0] + a.tiles[1]) {  // ---- loss: fixed-order tree over the b row terms
         float* part = reinterpret_cast<float*>(red);
         float s = 0.f;
-        for (int i = tid; i < a.b; i += T) s += a.row_loss[i];
-        for (int i = tid; i < a.n_loss_parts; i += T) s += a.neg_loss_part[i];
+        for (int i = tid; i < a.b; i += UPD_THREADS) s += a.row_loss[i];
+        for (int i = tid; i < a.n_loss_parts; i += UPD_THREADS) s += a.neg_loss_part[i];
         part[tid] = s;
         __syncthreads();
-        for (int o = T / 2; o > 0; o >>= 1) {
+        for (int o = UPD_THREADS / 2; o > 0; o >>= 1) {
             if (tid < o) part[tid] += part[tid + o];
             __syncthreads();
         }
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(T) void k_update(UpdateArgs a) {
     // keys p0-1 .. p1 and positions p0 .. p1-1 of this tile: the addresses are the same for every thread, and so is
     // everything computed from them below, so it all lives in scalar registers
     __shared__ int lookback;
-    __shared__ uint32_t back_pos[T];
+    __shared__ uint32_t back_pos[UPD_THREADS];
     uint32_t key[TILE_R + 2], gpos[TILE_R];
 #pragma unroll
     for (int j = 0; j < TILE_R + 2; ++j) {
@@ -126,7 +126,7 @@ __global__ __launch_bounds__(T) void k_update(UpdateArgs a) {
         // `lanes` threads, add up the gradient rows of the chunk, LOOKBACK_U rows per thread in flight.  The sums of
         // the row groups go to the walkers through LDS.
         if (!look) return;
-        const int o = tid - walkers, n_look = T - walkers;
+        const int o = tid - walkers, n_look = UPD_THREADS - walkers;
         const int groups = n_look / lanes, grp = o / lanes;
         const bool active = grp < groups;
         if (o == 0) lookback = 1 << 30;
@@ -191,7 +191,7 @@ __global__ __launch_bounds__(T) void k_update(UpdateArgs a) {
         }
         lds_barrier();  // (4)
         if (walker) {
-            const int groups = (T - walkers) / lanes;
+            const int groups = (UPD_THREADS - walkers) / lanes;
             for (int g2 = 0; g2 < groups; ++g2) acc = add4(acc, red[g2 * lanes + v]);
         }
     }
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(T) void k_update(UpdateArgs a) {
     // Row-wise state.  First the summed gradient of every run that ends here (kept in g[j]) and, per walker wave, its
     // sum of squares; one barrier (the helper waves are gone by now, so it is among the walker waves only); then the
     // walker waves' sums are added in wave order to the mean square of the row and the update is applied.
-    __shared__ float row_ss[TILE_R][T / 64];
+    __shared__ float row_ss[TILE_R][UPD_THREADS / 64];
 #pragma unroll
     for (int j = 0; j < TILE_R; ++j) {
         if (need[j]) acc = add4(acc, g[j]);
@@ -267,19 +267,6 @@ void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, con
     a.lr = lr; a.eps = c->eps; a.row_loss = c->row_loss; a.b = b; a.loss_out = loss_out;
     a.neg_loss_part = c->neg_loss_part; a.n_loss_parts = n_loss_parts;
     const int tiles = a.tiles[0] + a.tiles[1];
-    // Workgroups of 512 threads: up to 128 that own the columns of the tile's rows, the rest add up the part of a run
-    // that lies before the tile, and two workgroups share a CU.  Where the tiles are several times the 512 such
-    // workgroups that the chip holds at once, 256 threads (four workgroups per CU) finish the launch sooner (23.3
-    // against 24.6 us at 1793 tiles), although a long run then has a quarter of the threads to add it up (with 641
-    // tiles and runs of hundreds of rows: 23.9 against 16.1 us).
-    const int lanes = (a.D[0] > a.D[1] ? a.D[0] : a.D[1]) / 4, walkers = (lanes + 63) / 64 * 64;
-    int threads = UPD_THREADS;
-    if (tiles > 1024 && walkers + lanes <= 256) threads = 256;
-    if (c->cfg.adagrad_mode == 1) {
-        if (threads == 256) KGE_LAUNCH(c, (k_update<true, 256>), dim3(tiles + 1), dim3(256), 0, st, a);
-        else KGE_LAUNCH(c, (k_update<true, UPD_THREADS>), dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
-    } else {
-        if (threads == 256) KGE_LAUNCH(c, (k_update<false, 256>), dim3(tiles + 1), dim3(256), 0, st, a);
-        else KGE_LAUNCH(c, (k_update<false, UPD_THREADS>), dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
-    }
+    if (c->cfg.adagrad_mode == 1) KGE_LAUNCH(c, k_update<true>, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
+    else KGE_LAUNCH(c, k_update<false>, dim3(tiles + 1), dim3(UPD_THREADS), 0, st, a);
 }
