@@ -78,17 +78,18 @@ struct BlockLoader {
             p[it] = base + (int64_t)(major0 + 8 * it) * ld + (any ? gr : 0);
         }
     }
-    __device__ __forceinline__ void issue(int kb, float4 (&reg)[4]) const {
+    // shift: floats from the operand that init was given to the one that block kb is taken from (IND_CHUNK_SUM)
+    __device__ __forceinline__ void issue(int kb, float4 (&reg)[4], int64_t shift = 0) const {
         const int k0 = kb * 32;
         if (KC) {
             const int gk = k0 + minor;
             const int koff = gk < K ? gk : 0;  // the first 16 bytes of a row are always there
 #pragma unroll
-            for (int it = 0; it < 4; ++it) reg[it] = ld4(p[it] + koff);
+            for (int it = 0; it < 4; ++it) reg[it] = ld4(p[it] + shift + koff);
         } else {
 #pragma unroll
             for (int it = 0; it < 4; ++it)
-                reg[it] = ld4(k0 + major0 + 8 * it < K ? p[it] + (int64_t)k0 * ld : p0_safe);
+                reg[it] = ld4(k0 + major0 + 8 * it < K ? p[it] + shift + (int64_t)k0 * ld : p0_safe);
         }
     }
     // validity of element e (0..3) of register it for K-block kb
@@ -147,11 +148,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     const float* A = g.A + c * g.sA;
     const float* B = g.B + c * g.sB;
     if (IND == IND_CHUNK_REL) A = g.A + (c / g.ind_g) * g.sA;
-    if (IND == IND_CHUNK_REL || IND == IND_ITEM_REL) {
+    if (IND == IND_CHUNK_REL) {
         const StepView sv = step_view(g.ids);
         B = g.B + clamp_id(sv.r[c], g.n_rel) * g.sB + g.b_off;
     }
     if (IND == IND_ITEM_CHUNK) B = g.B + (c / g.ind_g) * g.sB;
+    if (IND == IND_CHUNK_SUM) B = g.B + g.b_off;  // relation 0's matrix; a block is shifted to its positive's relation
     float* As = lds[w][0];
     float* Bs = lds[w][1];
     // ComplEx chain rule: the real and the imaginary part of a coordinate have to meet in one tile, so the tile's
@@ -195,7 +197,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     float a_sum = 0.f;  // sum over this lane's K-values of A[m = lane%32][.]  (rowsum / colsum of W)
 
-    const int nblk = (g.K + TILE - 1) / TILE;
+    const int nblk = (IND == IND_CHUNK_SUM ? g.ind_g : 1) * ((g.K + TILE - 1) / TILE);
     float4 ra[4], rb[4];
     BlockLoader<A_KC> la;
     BlockLoader<B_KC> lb;
@@ -205,20 +207,38 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         const int j = 4 * (lane & 7);
         lb.init_rows_at(B, col_of(j), col_in(j) ? (j < TILE / 2 ? g.N / 2 : g.N) : 0);
     }
-    int kb = w;
+    // IND_CHUNK_SUM: block kb is block kb % bpi of positive kb / bpi of the chunk; where its operands lie is looked up
+    // (the positive's relation id) one round before its loads go out
+    const int bpi = (g.K + TILE - 1) / TILE;
+    const StepView sv_sum = IND == IND_CHUNK_SUM ? step_view(g.ids) : StepView();
+    auto place = [&](int blk, int& kl, int64_t& sa, int64_t& sb) {
+        kl = blk; sa = 0; sb = 0;
+        if (IND == IND_CHUNK_SUM) {
+            const int p = blk / bpi;
+            kl = blk - p * bpi;
+            sa = p * g.sA_item;
+            sb = clamp_id(sv_sum.r[c * g.ind_g + p], g.n_rel) * g.sB;
+        }
+    };
+    int kb = w, kl = 0, kl_n = 0;
+    int64_t sa = 0, sb = 0, sa_n = 0, sb_n = 0;
     if (kb < nblk) {
-        la.issue(kb, ra);
-        lb.issue(kb, rb);
+        place(kb, kl, sa, sb);
+        la.issue(kl, ra, sa);
+        lb.issue(kl, rb, sb);
+        if (kb + NW < nblk) place(kb + NW, kl_n, sa_n, sb_n);
     }
     while (kb < nblk) {
-        la.mask(kb, ra);
-        lb.mask(kb, rb);
+        la.mask(kl, ra);
+        lb.mask(kl, rb);
         lds_store<A_KC>(As, lane, ra);
         lds_store<B_KC>(Bs, lane, rb);
         const int nxt = kb + NW;
         if (nxt < nblk) {  // next block's global loads fly while this block is multiplied
-            la.issue(nxt, ra);
-            lb.issue(nxt, rb);
+            la.issue(kl_n, ra, sa_n);
+            lb.issue(kl_n, rb, sb_n);
+            kl = kl_n;
+            if (nxt + NW < nblk) place(nxt + NW, kl_n, sa_n, sb_n);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -412,15 +432,16 @@ void launch_one(kge_ctx* c, GemmArgs g, int items, hipStream_t st) {
     set_tiling(g, items);
     g.out_mode = OUT_SCORE;
     const dim3 grid(8 * ((g.tiles + 7) / 8));
-    const int nblk = (g.K + TILE - 1) / TILE;
-    int nw = pick_nw(g.tiles, nblk, 8);
+    const int nblk = (IND == IND_CHUNK_SUM ? g.ind_g : 1) * ((g.K + TILE - 1) / TILE);
+    int nw = pick_nw(g.tiles, nblk, IND == IND_CHUNK_SUM ? 16 : 8);
     // thousands of tiles with a short K loop (rows of 100 floats are 4 K-blocks): one wave per tile, which multiplies
     // all the blocks between the tile's set-up and its epilogue, and sixteen tiles share a CU (measured on the
     // FB15k-sized TransR step: 113 us per product against 117 with two waves per tile and 134 with four)
     if (g.tiles >= 1024 && nblk <= 8) nw = 1;
     if (nw == 1) KGE_LAUNCH(c, (k_gemm_one<1, A_KC, B_KC, IND>), grid, dim3(64), 0, st, g);
     else if (nw == 4) KGE_LAUNCH(c, (k_gemm_one<4, A_KC, B_KC, IND>), grid, dim3(256), 0, st, g);
-    else KGE_LAUNCH(c, (k_gemm_one<8, A_KC, B_KC, IND>), grid, dim3(512), 0, st, g);
+    else if (nw == 8) KGE_LAUNCH(c, (k_gemm_one<8, A_KC, B_KC, IND>), grid, dim3(512), 0, st, g);
+    else KGE_LAUNCH(c, (k_gemm_one<16, A_KC, B_KC, IND>), grid, dim3(1024), 0, st, g);
 }
 
 template <int EPI_O, int EPI_N>
@@ -530,7 +551,8 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
 // ---- TransR: f = gamma - |M_r h + r - M_r t|^2 (Table 1).  Every positive i has its own projection matrix M_i (D x D,
 // behind the D numbers of r in its relation row), so the products are batched over positives:
 //   P_i = N_c M_i^T   [k x D]  projections of the chunk's corrupting rows              (forward)
-//   T_i = U_i M_i     [k x D]  with U_i = dL/dP_i; summed over the chunk's positives -> gradient rows of the negatives
+//   sum_i U_i M_i     [k x D]  with U_i = dL/dP_i, over the chunk's positives i: one product per chunk whose K range
+//                              is the concatenation of the positives' D values -> gradient rows of the negatives
 //   G_i = U_i^T N_c   [D x D]  the negatives' share of dL/dM_i
 void kge_gemm_transr_project(kge_ctx* c, const float* R, const StepIds& ids, int k, int gsz, float* P, hipStream_t st) {
     const int D = c->cfg.ent_dim;
@@ -542,15 +564,17 @@ void kge_gemm_transr_project(kge_ctx* c, const float* R, const StepIds& ids, int
     launch_one<true, true, IND_CHUNK_REL>(c, g, ids.b, st);
 }
 
-void kge_gemm_transr_back_project(kge_ctx* c, const float* R, const StepIds& ids, int k, const float* U, float* T,
-                                  hipStream_t st) {
+// dL/dn for the corrupting rows of every chunk in one product per chunk: sum over the chunk's positives i of U_i M_i,
+// i.e. the K range is the concatenation of the positives' D values; out = the gradient rows of the corrupting entities.
+void kge_gemm_transr_back_project_sum(kge_ctx* c, const float* R, const StepIds& ids, int k, int gsz, const float* U,
+                                      float* out, hipStream_t st) {
     const int D = c->cfg.ent_dim;
     GemmArgs g = {};
-    g.A = U; g.B = R; g.C = T;
+    g.A = U; g.B = R; g.C = out;
     g.M = k; g.N = D; g.K = D; g.lda = D; g.ldb = D; g.ldc = D;
-    g.sA = (int64_t)k * D; g.sB = c->cfg.rel_dim; g.sC = (int64_t)k * D;
-    g.ids = ids; g.n_rel = c->cfg.num_relations; g.ind_g = 1; g.b_off = D;
-    launch_one<true, false, IND_ITEM_REL>(c, g, ids.b, st);
+    g.sA = (int64_t)gsz * k * D; g.sA_item = (int64_t)k * D; g.sB = c->cfg.rel_dim; g.sC = (int64_t)k * D;
+    g.ids = ids; g.n_rel = c->cfg.num_relations; g.ind_g = gsz; g.b_off = D;
+    launch_one<true, false, IND_CHUNK_SUM>(c, g, ids.b / gsz, st);
 }
 
 void kge_gemm_transr_matrix_grad(kge_ctx* c, const StepIds& ids, int k, int gsz, const float* U, float* GM,

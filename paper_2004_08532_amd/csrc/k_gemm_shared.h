@@ -45,13 +45,16 @@ struct GemmArgs {
     int64_t n_ent, n_rel;
     // batches whose items are positives rather than chunks (TransR: every positive has its own projection matrix)
     int ind_g;       // positives per chunk: item i uses chunk i / ind_g of the operand that is stored per chunk
+    int64_t sA_item; // IND_CHUNK_SUM: floats from one positive's A block to the next one's
     int64_t b_off;   // offset of the matrix inside a relation row
 };
 // how the operands of batch item i are found (IND of gemm_tile)
 enum { IND_NONE = 0,      // A + i sA, B + i sB
        IND_CHUNK_REL = 1, // A + (i / ind_g) sA (per chunk), B + r_i sB + b_off (the positive's relation row)
-       IND_ITEM_REL = 2,  // A + i sA,                       B + r_i sB + b_off
-       IND_ITEM_CHUNK = 3 // A + i sA,                       B + (i / ind_g) sB
+       IND_ITEM_CHUNK = 2, // A + i sA,                       B + (i / ind_g) sB
+       // batch item = chunk c; the K range is the concatenation, over the chunk's ind_g positives p, of their K values:
+       // A + c sA + p sA_item, B + r_(c ind_g + p) sB + b_off; K counts one positive's share
+       IND_CHUNK_SUM = 3
 };
 
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }

@@ -10,7 +10,7 @@
 //   k_transr_score   S_ij = gamma - |o_i - P_ij|^2 from the projections P_i = N_c M_i^T
 //   (k_loss)         W = dL/df-
 //   k_transr_dp      U_ij = dL/dP_ij = 2 W_ij (o_i - P_ij), in place over P; dL/do_i of the negatives = - sum_j U_ij
-//   k_transr_reduce  gradient rows of the corrupting entities: sum over the chunk's positives of T_i = U_i M_i
+//   (product)        gradient rows of the corrupting entities: sum over the chunk's positives of U_i M_i
 //   k_transr_chain   go = dL/do, gp = dL/dp -> kept entity M^T go, replaced entity M^T gp, translation sigma go,
 //                    matrix += go a^T + gp c^T (on top of the negatives' share U_i^T N_c)
 //   k_transr_update  duplicate reduction and Adagrad for the relation rows [r | M] (Sec. 3.1 step 4): the last sorted
@@ -34,7 +34,6 @@ struct TransrArgs {
     float* PP;       // [b x D]      p_i = M_i c_i
     float* P;        // [b x k x D]  projections, then U
     float* S;        // [b x ld_s]   scores, then W
-    float* T;        // [b x k x D]  U_i M_i
     float* GO;       // [b x D]      dL/do_i from the negatives
     float* fpos;
     float* cpos;
@@ -271,38 +270,6 @@ __global__ __launch_bounds__(RT) void k_transr_dp(TransrArgs a) {
     }
 }
 
-// workgroup per corrupting row (c, j): its gradient row is the sum of T_i[j] over the positives i of chunk c; the same
-// sharing of the rows among thread groups
-__global__ __launch_bounds__(RT) void k_transr_reduce(TransrArgs a) {
-    __shared__ __attribute__((aligned(16))) float4 part[RT];
-    const int row = blockIdx.x, c = row / a.k, j = row - c * a.k, D = a.D, lanes = D / 4, groups = RT / lanes;
-    const int grp = threadIdx.x / lanes, v = threadIdx.x % lanes;
-    float4 s = f4(0.f);
-    if (grp < groups) {
-        const float* T = a.T + ((int64_t)c * a.g * a.k + j) * D + 4 * v;
-        const int64_t stride = (int64_t)a.k * D;  // from one positive's T_i[j] to the next one's
-        for (int i0 = grp; i0 < a.g; i0 += 4 * groups) {
-            float4 t[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) t[u] = ld4(T + (i0 + u * groups < a.g ? i0 + u * groups : i0) * stride);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (i0 + u * groups < a.g) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
-            }
-        }
-    }
-    part[threadIdx.x] = s;
-    __syncthreads();
-    if (grp == 0) {
-        float4 t = part[v];
-        for (int g2 = 1; g2 < groups; ++g2) {
-            const float4 q = part[g2 * lanes + v];
-            t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
-        }
-        st4(a.Gent + ((int64_t)2 * a.b + row) * D + 4 * v, t);
-    }
-}
-
 __global__ __launch_bounds__(RT) void k_transr_chain(TransrArgs a) {
     __shared__ __attribute__((aligned(16))) float go[MAX_D], gp[MAX_D];
     __shared__ __attribute__((aligned(16))) float4 part1[RT], part2[RT];
@@ -422,7 +389,7 @@ TransrArgs make_args(kge_ctx* c, const float* E, const float* R, const StepIds& 
     a.E = E; a.R = R; a.ids = ids; a.b = ids.b; a.D = D; a.k = k; a.g = gsz; a.ld_s = c->ld_s;
     a.n_ent = c->cfg.num_entities; a.n_rel = c->cfg.num_relations; a.rel_dim = c->cfg.rel_dim;
     a.gamma = gamma;
-    a.O = c->O; a.PP = c->PP; a.P = c->P3; a.S = c->S; a.T = c->T3; a.GO = c->GO;
+    a.O = c->O; a.PP = c->PP; a.P = c->P3; a.S = c->S; a.GO = c->GO;
     a.fpos = c->fpos; a.cpos = c->cpos; a.row_loss = c->row_loss;
     a.Gent = c->Gent; a.Gr = c->Grel; a.GM = c->Grel + (int64_t)c->cfg.max_batch * D;
     return a;
@@ -443,17 +410,11 @@ void kge_transr_score(kge_ctx* c, const StepIds& ids, int k, float gamma, float*
 }
 
 float* kge_transr_projections(kge_ctx* c) { return c->P3; }
-float* kge_transr_back_projections(kge_ctx* c) { return c->T3; }
 float* kge_transr_matrix_grads(kge_ctx* c) { return c->Grel + (int64_t)c->cfg.max_batch * c->cfg.ent_dim; }
 
 void kge_transr_dp(kge_ctx* c, const StepIds& ids, int k, hipStream_t st) {
     const TransrArgs a = make_args(c, nullptr, nullptr, ids, k, 1, 0.f);
     KGE_LAUNCH(c, k_transr_dp, dim3(ids.b), dim3(RT), 0, st, a);
-}
-
-void kge_transr_reduce(kge_ctx* c, const StepIds& ids, int k, int gsz, hipStream_t st) {
-    const TransrArgs a = make_args(c, nullptr, nullptr, ids, k, gsz, 0.f);
-    KGE_LAUNCH(c, k_transr_reduce, dim3((ids.b / gsz) * k), dim3(RT), 0, st, a);
 }
 
 void kge_transr_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st) {

@@ -111,9 +111,8 @@ int enqueue_transr_rest(kge_ctx* c, float* ent, float* ent_state, float* rel, fl
     kge_transr_dp(c, ids, K, st);
     {
         ProfScope p(c, KGE_PROF_BACKWARD);
-        kge_gemm_transr_back_project(c, rel, ids, K, P, kge_transr_back_projections(c), st);
+        kge_gemm_transr_back_project_sum(c, rel, ids, K, G, P, c->Gent + (int64_t)2 * ids.b * c->cfg.ent_dim, st);
     }
-    kge_transr_reduce(c, ids, K, G, st);
     kge_gemm_transr_matrix_grad(c, ids, K, G, P, kge_transr_matrix_grads(c), st);
     {
         ProfScope p(c, KGE_PROF_CHAIN);
@@ -331,7 +330,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t o_Obf = take(bf ? B * c->ld_bf * 2 + 64 : 0), o_Nbf = take(bf ? NR * c->ld_bf * 2 + 64 : 0);
     const bool transr = m == KGE_TRANSR;
     const size_t proj = transr ? B * (size_t)(cfg->max_neg_per_chunk > 0 ? cfg->max_neg_per_chunk : 1) * D * 4 : 0;
-    const size_t o_PP = take(transr ? B * D * 4 : 0), o_P3 = take(proj), o_T3 = take(proj);
+    const size_t o_PP = take(transr ? B * D * 4 : 0), o_P3 = take(proj);
     const size_t sort_slices = (EK + KGE_SORT_SLICE - 1) / KGE_SORT_SLICE + (B + KGE_SORT_SLICE - 1) / KGE_SORT_SLICE;
     const size_t o_sc = take(sort_slices * 17 * 256 * 4 + 2 * 256 * 4);  // digit counts per wave and per slice + the two lists' digit bases
     const bool pair_model = m == KGE_ROTATE || m == KGE_TRANSE_L1;
@@ -358,7 +357,6 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->Nbf = bf ? (uint16_t*)(base + o_Nbf) : nullptr;
     c->PP = transr ? (float*)(base + o_PP) : nullptr;
     c->P3 = transr ? (float*)(base + o_P3) : nullptr;
-    c->T3 = transr ? (float*)(base + o_T3) : nullptr;
     c->pair_part_o = pair_model ? (float*)(base + o_ppo) : nullptr;
     c->pair_part_n = pair_model ? (float*)(base + o_ppn) : nullptr;
     c->sort_counts = (uint32_t*)(base + o_sc);

@@ -43,7 +43,6 @@ struct kge_ctx {
     float* S;        // [max_batch x ld_s]   negative scores, then backward coefficients W
     float* PP;       // TransR: [max_batch x D] p_i = M_i c_i
     float* P3;       // TransR: [max_batch x max_neg_per_chunk x D] projections of the corrupting rows, then dL/dP
-    float* T3;       // TransR: the same shape, U_i M_i
     float* GO;       // [max_batch x D]      dL/do_i
     float* pair_part_o;  // RotatE / TransE-L1: [KGE_PAIR_MAX_PARTS][max_batch x D] partial dL/do rows of the tiled backward
     PartialRows go_partial, neg_partial;  // what the last backward launch left for the chain launch to add up
@@ -168,15 +167,13 @@ void kge_transr_phi(kge_ctx* c, const float* E, const float* R, const StepIds& i
                     hipStream_t st);
 void kge_transr_score(kge_ctx* c, const StepIds& ids, int k, float gamma, float* out, int ld_out, hipStream_t st);
 void kge_transr_dp(kge_ctx* c, const StepIds& ids, int k, hipStream_t st);
-void kge_transr_reduce(kge_ctx* c, const StepIds& ids, int k, int g, hipStream_t st);
 void kge_transr_chain(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
 void kge_transr_update(kge_ctx* c, float* R, float* SR, const StepIds& ids, float lr, hipStream_t st);
 float* kge_transr_projections(kge_ctx* c);
-float* kge_transr_back_projections(kge_ctx* c);
 float* kge_transr_matrix_grads(kge_ctx* c);
 void kge_gemm_transr_project(kge_ctx* c, const float* R, const StepIds& ids, int k, int g, float* P, hipStream_t st);
-void kge_gemm_transr_back_project(kge_ctx* c, const float* R, const StepIds& ids, int k, const float* U, float* T,
-                                  hipStream_t st);
+void kge_gemm_transr_back_project_sum(kge_ctx* c, const float* R, const StepIds& ids, int k, int g, const float* U,
+                                      float* out, hipStream_t st);
 void kge_gemm_transr_matrix_grad(kge_ctx* c, const StepIds& ids, int k, int g, const float* U, float* GM,
                                  hipStream_t st);
 // a6: sort (id, position) of the entity and relation key lists
