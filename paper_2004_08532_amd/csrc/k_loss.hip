@@ -20,6 +20,13 @@ __device__ __forceinline__ float sigmoidf_(float x) {
     return e / (1.f + e);
 }
 __device__ __forceinline__ float softplusf_(float x) { return fmaxf(x, 0.f) + log1pf(expf(-fabsf(x))); }
+// Both at once for a negative score, from one exponential, with the hardware exp2 / log2 / reciprocal (1 ulp each,
+// about 1e-6 relative: the size of the rounding of the fp32 products that the results go into)
+__device__ __forceinline__ void softplus_sigmoid(float f, float& sp, float& sg) {
+    const float e = __builtin_amdgcn_exp2f(-fabsf(f) * 1.4426950408889634f);  // exp(-|f|) in (0, 1]
+    sp = fmaxf(f, 0.f) + __builtin_amdgcn_logf(1.f + e) * 0.6931471805599453f;
+    sg = (f >= 0.f ? 1.f : e) * __builtin_amdgcn_rcpf(1.f + e);
+}
 
 struct LossArgs {
     float* S;  // in: negative scores (distances when is_dist); out: W
@@ -62,7 +69,7 @@ __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
         float zz = 0.f;
 #pragma unroll
         for (int u = 0; u < VPL; ++u) {
-            e[u] = expf(a.alpha * f[u] - mx);
+            e[u] = a.bf16 ? expf(a.alpha * f[u] - mx) : __builtin_amdgcn_exp2f((a.alpha * f[u] - mx) * 1.4426950408889634f);
             if (lane + 64 * u < k) zz += e[u];
         }
         z = wave_sum(zz);
@@ -79,9 +86,14 @@ __global__ __launch_bounds__(256) void k_loss(LossArgs a) {
             li += w * fmaxf(m, 0.f);
             coef = m > 0.f ? w * invb : 0.f;
             active += m > 0.f ? w : 0.f;
-        } else {
+        } else if (a.bf16) {  // (W is rounded to bf16 afterwards: the library functions, so that no value sits on the fence)
             li += w * softplusf_(f[u]);
             coef = w * sigmoidf_(f[u]) * invb;
+        } else {
+            float sp, sg;
+            softplus_sigmoid(f[u], sp, sg);
+            li += w * sp;
+            coef = w * sg * invb;
         }
         if (a.is_dist) coef = raw[u] > 0.f ? coef / raw[u] : 0.f;
         if (a.bf16) coef = round_bf16(coef);  // what the product kernels multiply with
