@@ -2,7 +2,9 @@
 
 Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py`` may import this
 package.  It is a ctypes wrapper around ``kge_oracle.c`` (plain C, fp64 arithmetic, one triple and one
-negative at a time) and contains no arithmetic of its own.  It imports nothing from the GPU package.
+negative at a time), which holds all of the training step's arithmetic; the only arithmetic written here is the
+two-line definition of a link-prediction rank and of the Hit@k / MR / MRR averages (``ranks``, ``rank_metrics``,
+paper Sec. 5), in numpy.  It imports nothing from the GPU package.
 """
 from __future__ import annotations
 
@@ -16,6 +18,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "kge_oracle.c")
 _LIB = os.path.join(_HERE, "libkge_oracle.so")
+_LIB_OMP = os.path.join(_HERE, "libkge_oracle_omp.so")
 
 TRANSE_L2, TRANSE_L1, DISTMULT, COMPLEX, ROTATE, RESCAL, TRANSR = 0, 1, 2, 3, 4, 5, 6
 NEG_TAIL, NEG_HEAD = 0, 1
@@ -24,12 +27,21 @@ MODEL_IDS = {"transe_l2": TRANSE_L2, "transe_l1": TRANSE_L1, "distmult": DISTMUL
              "rotate": ROTATE, "rescal": RESCAL, "transr": TRANSR}
 
 
-def build(force: bool = False) -> str:
-    """Compile kge_oracle.c with gcc (no fast-math, no contraction) and return the library path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.run(["gcc", "-O2", "-Wall", "-Wextra", "-ffp-contract=off", "-shared", "-fPIC", "-o", _LIB,
-                        _SRC, "-lm"], check=True)
-    return _LIB
+def compile_oracle(src: str, lib: str, openmp: bool = False) -> str:
+    """gcc, no fast-math, no contraction.  openmp: the all-cores build (timing baseline only)."""
+    subprocess.run(["gcc", "-O2", "-Wall", "-Wextra", "-ffp-contract=off", *(["-fopenmp"] if openmp else []),
+                    "-shared", "-fPIC", "-o", lib, src, "-lm"], check=True)
+    return lib
+
+
+def build(force: bool = False, openmp: bool = False) -> str:
+    """Compile kge_oracle.c and return the library path.  With force both builds are made: the parity oracle
+    (single thread) and the OpenMP build that the benchmark times on all host cores."""
+    for lib, omp in ((_LIB, False), (_LIB_OMP, True)):
+        wanted = force or omp == openmp
+        if wanted and (force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(_SRC)):
+            compile_oracle(_SRC, lib, omp)
+    return _LIB_OMP if openmp else _LIB
 
 
 class _Params(ctypes.Structure):
@@ -40,26 +52,52 @@ class _Params(ctypes.Structure):
 
 
 _lib = None
+_lib_omp = None
 
 
-def _load():
-    global _lib
+def bind(path: str):
+    """Load a build of kge_oracle.c and declare its entry points."""
+    lib = ctypes.CDLL(path)
+    vp, i64, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double
+    lib.ko_round_bf16.restype = dbl
+    lib.ko_round_bf16.argtypes = [dbl]
+    lib.ko_threads.restype = ctypes.c_int
+    lib.ko_threads.argtypes = []
+    lib.ko_loss_grad.restype = ctypes.c_int
+    lib.ko_loss_grad.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, vp, vp, i64, vp, i64, i64, vp,
+                                 vp, vp, vp, vp, vp, i64, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.ko_dedup.restype = i64
+    lib.ko_dedup.argtypes = [vp, i64, vp, vp]
+    lib.ko_adagrad_rows.restype = None
+    lib.ko_adagrad_rows.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, dbl, dbl, ctypes.c_int]
+    lib.ko_train_step.restype = ctypes.c_int
+    lib.ko_train_step.argtypes = [ctypes.POINTER(_Params), vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
+                                  vp, i64, i64, dbl, dbl, ctypes.c_int, ctypes.c_int, vp, vp, vp,
+                                  vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    return lib
+
+
+def _load(openmp: bool = False):
+    global _lib, _lib_omp
+    if openmp:
+        if _lib_omp is None:
+            _lib_omp = bind(build(openmp=True))
+        return _lib_omp
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        vp, i64, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_double
-        lib.ko_loss_grad.restype = ctypes.c_int
-        lib.ko_loss_grad.argtypes = [ctypes.POINTER(_Params), vp, vp, vp, vp, vp, i64, vp, i64, i64, vp,
-                                     vp, vp, vp, vp, vp, i64, vp, vp, vp, i64, vp, vp, vp, vp]
-        lib.ko_dedup.restype = i64
-        lib.ko_dedup.argtypes = [vp, i64, vp, vp]
-        lib.ko_adagrad_rows.restype = None
-        lib.ko_adagrad_rows.argtypes = [vp, vp, vp, i64, ctypes.c_int, vp, dbl, dbl, ctypes.c_int]
-        lib.ko_train_step.restype = ctypes.c_int
-        lib.ko_train_step.argtypes = [ctypes.POINTER(_Params), vp, vp, i64, vp, vp, i64, vp, vp, vp, i64,
-                                      vp, i64, i64, dbl, dbl, ctypes.c_int, ctypes.c_int, vp, vp, vp,
-                                      vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
-        _lib = lib
+        _lib = bind(build())
     return _lib
+
+
+def threads(openmp: bool = False) -> int:
+    """Workers the chosen build spreads a mini-batch over (1 for the parity oracle)."""
+    return int(_load(openmp).ko_threads())
+
+
+def round_bf16(x) -> np.ndarray:
+    """The oracle's bfloat16 rounding (nearest, ties to even, of the value held as float32), element by element."""
+    lib = _load()
+    a = np.asarray(x, dtype=np.float64)
+    return np.array([lib.ko_round_bf16(float(v)) for v in a.reshape(-1)], dtype=np.float64).reshape(a.shape)
 
 
 def _ptr(a: Optional[np.ndarray]):
@@ -151,13 +189,15 @@ def adagrad_rows(table, state, ids, grad, lr, eps, rowwise=False):
 
 def train_step(model, E, SE, R, SR, h, r, t, neg, k, chunk, neg_side, gamma, lr, eps=1e-10, adv_temperature=0.0,
                dense=False, bf16_inputs=False, rotate_squared=False, want_scores=False, report=False, rowwise=False,
-               loss="logistic"):
+               loss="logistic", openmp=False):
     """One step, in place on float32 E, SE, R, SR.  Returns loss (and scores when asked).
 
     report=True (touched-rows mode) returns ``(loss, rep)`` where rep holds, for the distinct rows of the step,
     ``ent_ids``, ``dE`` (their summed gradient rows), ``absE`` (magnitudes of the terms, per element) and ``maxE``
-    (largest share of a single negative pair in that element), and the same for relations: what the tests need to bound rounding effects, not part of the method."""
-    lib = _load()
+    (largest share of a single negative pair in that element), and the same for relations: what the tests need to
+    bound rounding effects, not part of the method.  openmp=True runs the all-cores build (timing baseline; same
+    terms, summed per thread first)."""
+    lib = _load(openmp)
     for a in (E, SE, R, SR):
         assert a.dtype == np.float32 and a.flags.c_contiguous
     h, r, t, neg = _ids(h), _ids(r), _ids(t), _ids(neg).reshape(-1)

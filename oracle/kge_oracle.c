@@ -47,12 +47,23 @@
  *
  * parity pins (tests/test_oracle_*.py): hand-worked scores, central finite differences of the loss,
  * equality of the per-pair scores with the split form of Sec. 3.3 evaluated by numpy matrix products,
- * special values of the loss, the Adagrad closed form, brute-force duplicate counting.
+ * special values of the loss, the Adagrad closed form, brute-force duplicate counting; the bfloat16 rounding
+ * against exact values (ties, the largest finite number, inf / nan) and two independent conversions; the
+ * bf16_inputs branch against the Sec. 3.3 products written out in numpy on operands rounded by one of those; the
+ * condition measure of grad_triple_mag against a hand-worked case, against |gradient| and against float32
+ * re-evaluations of the same gradient under several orders of summation.  Copies of this file with a planted
+ * mistake (truncating rounding, halved measure, unrounded coefficient) are compiled by the tests and must fail.
+ *
+ * Compiled with -fopenmp this file is also the all-cores timing baseline of the benchmark (ko_loss_grad deals
+ * the positives to the threads); the parity oracle is always the build without OpenMP.
  */
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 enum { KO_TRANSE_L2 = 0, KO_TRANSE_L1 = 1, KO_DISTMULT = 2, KO_COMPLEX = 3, KO_ROTATE = 4, KO_RESCAL = 5, KO_TRANSR = 6 };
 enum { KO_NEG_TAIL = 0, KO_NEG_HEAD = 1 };
@@ -116,6 +127,9 @@ static double round_bf16(double x) {
     memcpy(&f, &u, 4);
     return (double)f;
 }
+
+/* the same, callable from the tests that pin it */
+double ko_round_bf16(double x) { return round_bf16(x); }
 
 /* ------------------------------------------------------------------------------------------------ */
 /* Table 1: score of one triple from its three rows                                                   */
@@ -506,6 +520,197 @@ static void add_rows(double *acc, int64_t slot, int dim, const double *v) {
     for (int d = 0; d < dim; ++d) dst[d] += v[d];
 }
 
+/* scratch rows of one worker */
+typedef struct {
+    double *hv, *tv, *nv, *rv, *ov, *go, *th, *tt, *tr, *fneg, *w;
+} ko_scratch;
+
+static int scratch_alloc(ko_scratch *s, int De, int Dr, int64_t k) {
+    const size_t nr = (size_t)(Dr > De ? Dr : De), nk = (size_t)(k > 0 ? k : 1);
+    memset(s, 0, sizeof(*s));
+    s->hv = malloc(sizeof(double) * De); s->tv = malloc(sizeof(double) * De); s->nv = malloc(sizeof(double) * De);
+    s->rv = malloc(sizeof(double) * nr);
+    s->ov = malloc(sizeof(double) * De); s->go = malloc(sizeof(double) * De);
+    s->th = malloc(sizeof(double) * De); s->tt = malloc(sizeof(double) * De);
+    s->tr = malloc(sizeof(double) * nr);
+    s->fneg = malloc(sizeof(double) * nk); s->w = malloc(sizeof(double) * nk);
+    return s->hv && s->tv && s->nv && s->rv && s->ov && s->go && s->th && s->tt && s->tr && s->fneg && s->w;
+}
+
+static void scratch_free(ko_scratch *s) {
+    free(s->hv); free(s->tv); free(s->nv); free(s->rv); free(s->ov); free(s->go); free(s->fneg); free(s->w);
+    free(s->th); free(s->tt); free(s->tr);
+}
+
+/* what ko_loss_grad was asked for, and where a worker adds its results */
+typedef struct {
+    const ko_params *p;
+    const void *E, *R;
+    const int64_t *h, *r, *t, *neg;
+    int64_t b, k, chunk;
+    const double *w_fixed;
+    double *pos_score, *neg_score, *w_out;
+    const int64_t *ent_ids, *rel_ids;
+    int64_t n_ent_slots, n_rel_slots;
+} ko_batch;
+
+typedef struct {
+    double total;                    /* this worker's share of the loss */
+    double *dE, *dR, *aE, *aR, *mE, *mR; /* accumulators (see ko_loss_grad); dE == NULL: no gradients wanted */
+} ko_acc;
+
+/* Positive i with its k negatives: scores, weights, loss term, and (if wanted) every gradient contribution.
+ * Returns 0, or -2 if an id has no slot. */
+static int one_positive(const ko_batch *q, int64_t i, ko_scratch *s, ko_acc *acc) {
+    const ko_params *p = q->p;
+    const int De = p->ent_dim, Dr = p->rel_dim, f64 = p->tables_f64;
+    const int head_side = p->neg_side == KO_NEG_HEAD;
+    const int use_split = p->bf16_inputs || p->split_form;
+    const int64_t b = q->b, k = q->k;
+    const int64_t *h = q->h, *r = q->r, *t = q->t, *neg = q->neg;
+    double *hv = s->hv, *tv = s->tv, *nv = s->nv, *rv = s->rv, *ov = s->ov, *go = s->go;
+    double *th = s->th, *tt = s->tt, *tr = s->tr, *fneg = s->fneg, *w = s->w;
+    double *dE = acc->dE, *dR = acc->dR, *aE = acc->aE, *aR = acc->aR, *mE = acc->mE, *mR = acc->mR;
+
+    const int64_t c = i / q->chunk;
+    fetch_row(q->E, f64, h[i], De, hv);
+    fetch_row(q->R, f64, r[i], Dr, rv);
+    fetch_row(q->E, f64, t[i], De, tv);
+    const double fpos = score_triple(p, hv, rv, tv);
+    if (q->pos_score) q->pos_score[i] = fpos;
+
+    if (use_split) {
+        split_o(p, head_side ? tv : hv, rv, ov);
+        if (p->bf16_inputs) for (int d = 0; d < De; ++d) ov[d] = round_bf16(ov[d]);
+    }
+    /* scores of this positive's k negatives */
+    for (int64_t j = 0; j < k; ++j) {
+        fetch_row(q->E, f64, neg[c * k + j], De, nv);
+        if (use_split) {
+            if (p->bf16_inputs) for (int d = 0; d < De; ++d) nv[d] = round_bf16(nv[d]);
+            fneg[j] = pair_score(p, ov, nv);
+        } else {
+            fneg[j] = head_side ? score_triple(p, nv, rv, tv) : score_triple(p, hv, rv, nv);
+        }
+        if (q->neg_score) q->neg_score[i * k + j] = fneg[j];
+    }
+    /* weights of the negatives: uniform, or softmax of temperature * score (held constant) */
+    if (q->w_fixed) {
+        for (int64_t j = 0; j < k; ++j) w[j] = q->w_fixed[i * k + j];
+    } else if (p->adv_temperature > 0 && k > 0) {
+        double mx = -INFINITY, z = 0.0;
+        for (int64_t j = 0; j < k; ++j) if (p->adv_temperature * fneg[j] > mx) mx = p->adv_temperature * fneg[j];
+        for (int64_t j = 0; j < k; ++j) { w[j] = exp(p->adv_temperature * fneg[j] - mx); z += w[j]; }
+        for (int64_t j = 0; j < k; ++j) w[j] /= z;
+    } else {
+        for (int64_t j = 0; j < k; ++j) w[j] = 1.0 / (double)k;
+    }
+    if (q->w_out) for (int64_t j = 0; j < k; ++j) q->w_out[i * k + j] = w[j];
+
+    double li, cpos;
+    if (p->loss == KO_LOSS_RANKING) {
+        /* pairwise ranking loss: the positive against each of its negatives, margin gamma */
+        double active = 0.0;
+        li = 0.0;
+        for (int64_t j = 0; j < k; ++j) {
+            const double m = p->gamma - fpos + fneg[j];
+            if (m > 0) { li += w[j] * m; active += w[j]; }
+        }
+        cpos = -active / (double)b;
+    } else {
+        /* logistic loss: y = +1 for the positive, y = -1 for each negative */
+        li = softplus(-fpos);
+        for (int64_t j = 0; j < k; ++j) li += w[j] * softplus(fneg[j]);
+        cpos = -sigmoid(-fpos) / (double)b; /* d/df softplus(-f) / b */
+    }
+    acc->total += li / (double)b;
+
+    if (!dE) return 0;
+    const int64_t sh = slot_of(q->ent_ids, q->n_ent_slots, h[i]);
+    const int64_t st = slot_of(q->ent_ids, q->n_ent_slots, t[i]);
+    const int64_t sr = slot_of(q->rel_ids, q->n_rel_slots, r[i]);
+    if (sh < 0 || st < 0 || sr < 0) return -2;
+    /* every triple's contribution is formed in scratch rows (th, tr, tt) and then added to the rows'
+     * accumulators; the optional aE / aR receive the magnitudes of the terms involved (a condition
+     * measure used by the parity tests, not part of the method) */
+    memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
+    grad_triple(p, hv, rv, tv, cpos, th, tr, tt);
+    add_rows(dE, sh, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, st, De, tt);
+    if (aE) grad_triple_mag(p, hv, rv, tv, cpos, aE + sh * De, aR + sr * Dr, aE + st * De);
+    if (use_split) memset(go, 0, sizeof(double) * De);
+    for (int64_t j = 0; j < k; ++j) {
+        const int64_t n = neg[c * k + j];
+        const int64_t sn = slot_of(q->ent_ids, q->n_ent_slots, n);
+        if (sn < 0) return -2;
+        double cneg = w[j] * sigmoid(fneg[j]) / (double)b; /* d/df softplus(f) * w / b */
+        fetch_row(q->E, f64, n, De, nv);
+        if (p->loss == KO_LOSS_RANKING) {
+            const double m = p->gamma - fpos + fneg[j];
+            cneg = m > 0 ? w[j] / (double)b : 0.0;
+            double big = fabs(fpos) > fabs(fneg[j]) ? fabs(fpos) : fabs(fneg[j]);
+            if (aE && fabs(m) <= 2e-5 * (big > 1 ? big : 1)) { /* undecided in fp32: see aE above */
+                const double flip = 1048576.0 * w[j] / (double)b;
+                grad_triple_mag(p, hv, rv, tv, flip, aE + sh * De, aR + sr * Dr, aE + st * De);
+                if (head_side) grad_triple_mag(p, nv, rv, tv, flip, aE + sn * De, aR + sr * Dr, aE + st * De);
+                else grad_triple_mag(p, hv, rv, nv, flip, aE + sh * De, aR + sr * Dr, aE + sn * De);
+            }
+        }
+        memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
+        if (aE) {
+            if (head_side) grad_triple_mag(p, nv, rv, tv, cneg, aE + sn * De, aR + sr * Dr, aE + st * De);
+            else grad_triple_mag(p, hv, rv, nv, cneg, aE + sh * De, aR + sr * Dr, aE + sn * De);
+        }
+        if (mE && mR) { /* this pair's measure alone, then the element-wise maximum */
+            memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
+            if (head_side) grad_triple_mag(p, nv, rv, tv, cneg, tt, tr, th); /* tt: the negative, th: the kept one */
+            else grad_triple_mag(p, hv, rv, nv, cneg, th, tr, tt);
+            const int64_t sk = head_side ? st : sh;
+            for (int d = 0; d < De; ++d) {
+                if (th[d] > mE[sk * De + d]) mE[sk * De + d] = th[d];
+                if (tt[d] > mE[sn * De + d]) mE[sn * De + d] = tt[d];
+            }
+            for (int d = 0; d < Dr; ++d) if (tr[d] > mR[sr * Dr + d]) mR[sr * Dr + d] = tr[d];
+            memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
+        }
+        if (use_split) {
+            if (p->bf16_inputs) {
+                /* the coefficient that multiplies the rounded operands in the backward products */
+                if (p->model == KO_TRANSE_L2) {
+                    double dist = p->gamma - fneg[j];
+                    double wq = dist > 0 ? round_bf16(cneg / dist) : 0.0;
+                    cneg = wq * dist;
+                } else {
+                    cneg = round_bf16(cneg);
+                }
+                for (int d = 0; d < De; ++d) nv[d] = round_bf16(nv[d]);
+            }
+            pair_grad(p, ov, nv, cneg, go, tt);
+            add_rows(dE, sn, De, tt);
+        } else if (head_side) {
+            grad_triple(p, nv, rv, tv, cneg, th, tr, tt); /* (n, r, t) */
+            add_rows(dE, sn, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, st, De, tt);
+        } else {
+            grad_triple(p, hv, rv, nv, cneg, th, tr, tt); /* (h, r, n) */
+            add_rows(dE, sh, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, sn, De, tt);
+        }
+    }
+    if (use_split) {
+        memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr);
+        split_o_backward(p, head_side ? tv : hv, rv, go, th, tr);
+        add_rows(dE, head_side ? st : sh, De, th); add_rows(dR, sr, Dr, tr);
+    }
+    return 0;
+}
+
+/* how many workers ko_loss_grad spreads the positives over: 1 unless this file was compiled with OpenMP */
+int ko_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 /*
  * h, r, t : [b] ids of the positive triples.   neg : [(b / chunk) * k] corrupting entity ids; positives
  * chunk*c .. chunk*(c+1)-1 share neg[c*k .. c*k+k-1]  (Sec. 3.3).
@@ -519,7 +724,12 @@ static void add_rows(double *acc, int64_t slot, int dim, const double *v) {
  * mE / mR : NULL or arrays of the same shape that receive, per element, the largest grad_triple_mag measure of a
  *           single (positive, negative) pair: how much one backward coefficient weighs in that element (the tests
  *           bound with it what a coefficient that rounds to the neighbouring bfloat16 value can change).
- * Returns 0, or -1 on bad arguments, -2 if an id has no slot.
+ * Returns 0, or -1 on bad arguments, -2 if an id has no slot, -3 if memory ran out.
+ *
+ * The parity oracle is this file compiled WITHOUT OpenMP: one worker takes the positives in order.  Compiled with
+ * -fopenmp (the all-cores timing baseline) the positives are dealt to the threads in contiguous blocks, every
+ * thread adds into accumulators of its own, and these are added up in thread order afterwards: the same terms in
+ * another order of summation.
  */
 int ko_loss_grad(const ko_params *p, const void *E, const void *R,
                  const int64_t *h, const int64_t *r, const int64_t *t, int64_t b,
@@ -532,150 +742,66 @@ int ko_loss_grad(const ko_params *p, const void *E, const void *R,
     if (p->model == KO_RESCAL && p->rel_dim != p->ent_dim * p->ent_dim) return -1;
     if (p->model == KO_TRANSR && p->rel_dim != p->ent_dim + p->ent_dim * p->ent_dim) return -1;
     if (p->model == KO_TRANSR && (p->bf16_inputs || p->split_form)) return -1; /* its pairs do not split into (o, n) */
-    const int De = p->ent_dim, Dr = p->rel_dim, f64 = p->tables_f64;
-    const int head_side = p->neg_side == KO_NEG_HEAD;
-    const int use_split = p->bf16_inputs || p->split_form;
-    double *hv = malloc(sizeof(double) * De), *tv = malloc(sizeof(double) * De), *nv = malloc(sizeof(double) * De);
-    double *rv = malloc(sizeof(double) * (Dr > De ? Dr : De));
-    double *ov = malloc(sizeof(double) * De), *go = malloc(sizeof(double) * De);
-    double *th = malloc(sizeof(double) * De), *tt = malloc(sizeof(double) * De);
-    double *tr = malloc(sizeof(double) * (Dr > De ? Dr : De));
-    double *fneg = malloc(sizeof(double) * (k > 0 ? k : 1)), *w = malloc(sizeof(double) * (k > 0 ? k : 1));
-    double total = 0.0;
+    const int De = p->ent_dim, Dr = p->rel_dim;
+    const ko_batch q = { p, E, R, h, r, t, neg, b, k, chunk, w_fixed, pos_score, neg_score, w_out,
+                         ent_ids, rel_ids, n_ent_slots, n_rel_slots };
     int rc = 0;
-
-    for (int64_t i = 0; i < b && rc == 0; ++i) {
-        const int64_t c = i / chunk;
-        fetch_row(E, f64, h[i], De, hv);
-        fetch_row(R, f64, r[i], Dr, rv);
-        fetch_row(E, f64, t[i], De, tv);
-        const double fpos = score_triple(p, hv, rv, tv);
-        if (pos_score) pos_score[i] = fpos;
-
-        if (use_split) {
-            split_o(p, head_side ? tv : hv, rv, ov);
-            if (p->bf16_inputs) for (int d = 0; d < De; ++d) ov[d] = round_bf16(ov[d]);
-        }
-        /* scores of this positive's k negatives */
-        for (int64_t j = 0; j < k; ++j) {
-            fetch_row(E, f64, neg[c * k + j], De, nv);
-            if (use_split) {
-                if (p->bf16_inputs) for (int d = 0; d < De; ++d) nv[d] = round_bf16(nv[d]);
-                fneg[j] = pair_score(p, ov, nv);
-            } else {
-                fneg[j] = head_side ? score_triple(p, nv, rv, tv) : score_triple(p, hv, rv, nv);
+    double total = 0.0;
+#ifdef _OPENMP
+    int nt = omp_get_max_threads();
+    if ((int64_t)nt > b) nt = (int)b;
+    if (nt > 1) {
+        const size_t nE = (size_t)n_ent_slots * De, nR = (size_t)n_rel_slots * Dr;
+        ko_acc *accs = calloc((size_t)nt, sizeof(ko_acc));
+        int *rcs = calloc((size_t)nt, sizeof(int));
+        if (!accs || !rcs) { free(accs); free(rcs); return -3; }
+#pragma omp parallel num_threads(nt)
+        {
+            const int tid = omp_get_thread_num();
+            ko_acc *a = &accs[tid];
+            ko_scratch s;
+            int ok = scratch_alloc(&s, De, Dr, k);
+            if (dE) {
+                a->dE = calloc(nE, sizeof(double)); a->dR = calloc(nR, sizeof(double));
+                ok = ok && a->dE && a->dR;
+                if (aE) { a->aE = calloc(nE, sizeof(double)); a->aR = calloc(nR, sizeof(double)); ok = ok && a->aE && a->aR; }
+                if (mE && mR) { a->mE = calloc(nE, sizeof(double)); a->mR = calloc(nR, sizeof(double)); ok = ok && a->mE && a->mR; }
             }
-            if (neg_score) neg_score[i * k + j] = fneg[j];
+            if (!ok) rcs[tid] = -3;
+            const int64_t lo = b * tid / nt, hi = b * (tid + 1) / nt;
+            for (int64_t i = lo; i < hi && rcs[tid] == 0; ++i) rcs[tid] = one_positive(&q, i, &s, a);
+            scratch_free(&s);
         }
-        /* weights of the negatives: uniform, or softmax of temperature * score (held constant) */
-        if (w_fixed) {
-            for (int64_t j = 0; j < k; ++j) w[j] = w_fixed[i * k + j];
-        } else if (p->adv_temperature > 0 && k > 0) {
-            double mx = -INFINITY, z = 0.0;
-            for (int64_t j = 0; j < k; ++j) if (p->adv_temperature * fneg[j] > mx) mx = p->adv_temperature * fneg[j];
-            for (int64_t j = 0; j < k; ++j) { w[j] = exp(p->adv_temperature * fneg[j] - mx); z += w[j]; }
-            for (int64_t j = 0; j < k; ++j) w[j] /= z;
-        } else {
-            for (int64_t j = 0; j < k; ++j) w[j] = 1.0 / (double)k;
+        for (int tid = 0; tid < nt; ++tid) {
+            ko_acc *a = &accs[tid];
+            if (rcs[tid] != 0 && rc == 0) rc = rcs[tid];
+            total += a->total;
+            if (a->dE && a->dR) {
+                for (size_t x = 0; x < nE; ++x) dE[x] += a->dE[x];
+                for (size_t x = 0; x < nR; ++x) dR[x] += a->dR[x];
+            }
+            if (a->aE && a->aR) {
+                for (size_t x = 0; x < nE; ++x) aE[x] += a->aE[x];
+                for (size_t x = 0; x < nR; ++x) aR[x] += a->aR[x];
+            }
+            if (a->mE && a->mR) {
+                for (size_t x = 0; x < nE; ++x) if (a->mE[x] > mE[x]) mE[x] = a->mE[x];
+                for (size_t x = 0; x < nR; ++x) if (a->mR[x] > mR[x]) mR[x] = a->mR[x];
+            }
+            free(a->dE); free(a->dR); free(a->aE); free(a->aR); free(a->mE); free(a->mR);
         }
-        if (w_out) for (int64_t j = 0; j < k; ++j) w_out[i * k + j] = w[j];
-
-        double li, cpos;
-        if (p->loss == KO_LOSS_RANKING) {
-            /* pairwise ranking loss: the positive against each of its negatives, margin gamma */
-            double active = 0.0;
-            li = 0.0;
-            for (int64_t j = 0; j < k; ++j) {
-                const double m = p->gamma - fpos + fneg[j];
-                if (m > 0) { li += w[j] * m; active += w[j]; }
-            }
-            cpos = -active / (double)b;
-        } else {
-            /* logistic loss: y = +1 for the positive, y = -1 for each negative */
-            li = softplus(-fpos);
-            for (int64_t j = 0; j < k; ++j) li += w[j] * softplus(fneg[j]);
-            cpos = -sigmoid(-fpos) / (double)b; /* d/df softplus(-f) / b */
-        }
-        total += li / (double)b;
-
-        if (!dE) continue;
-        const int64_t sh = slot_of(ent_ids, n_ent_slots, h[i]);
-        const int64_t st = slot_of(ent_ids, n_ent_slots, t[i]);
-        const int64_t sr = slot_of(rel_ids, n_rel_slots, r[i]);
-        if (sh < 0 || st < 0 || sr < 0) { rc = -2; break; }
-        /* every triple's contribution is formed in scratch rows (th, tr, tt) and then added to the rows'
-         * accumulators; the optional aE / aR receive the magnitudes of the terms involved (a condition
-         * measure used by the parity tests, not part of the method) */
-        memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
-        grad_triple(p, hv, rv, tv, cpos, th, tr, tt);
-        add_rows(dE, sh, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, st, De, tt);
-        if (aE) grad_triple_mag(p, hv, rv, tv, cpos, aE + sh * De, aR + sr * Dr, aE + st * De);
-        if (use_split) memset(go, 0, sizeof(double) * De);
-        for (int64_t j = 0; j < k; ++j) {
-            const int64_t n = neg[c * k + j];
-            const int64_t sn = slot_of(ent_ids, n_ent_slots, n);
-            if (sn < 0) { rc = -2; break; }
-            double cneg = w[j] * sigmoid(fneg[j]) / (double)b; /* d/df softplus(f) * w / b */
-            fetch_row(E, f64, n, De, nv);
-            if (p->loss == KO_LOSS_RANKING) {
-                const double m = p->gamma - fpos + fneg[j];
-                cneg = m > 0 ? w[j] / (double)b : 0.0;
-                double big = fabs(fpos) > fabs(fneg[j]) ? fabs(fpos) : fabs(fneg[j]);
-                if (aE && fabs(m) <= 2e-5 * (big > 1 ? big : 1)) { /* undecided in fp32: see aE above */
-                    const double flip = 1048576.0 * w[j] / (double)b;
-                    grad_triple_mag(p, hv, rv, tv, flip, aE + sh * De, aR + sr * Dr, aE + st * De);
-                    if (head_side) grad_triple_mag(p, nv, rv, tv, flip, aE + sn * De, aR + sr * Dr, aE + st * De);
-                    else grad_triple_mag(p, hv, rv, nv, flip, aE + sh * De, aR + sr * Dr, aE + sn * De);
-                }
-            }
-            memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
-            if (aE) {
-                if (head_side) grad_triple_mag(p, nv, rv, tv, cneg, aE + sn * De, aR + sr * Dr, aE + st * De);
-                else grad_triple_mag(p, hv, rv, nv, cneg, aE + sh * De, aR + sr * Dr, aE + sn * De);
-            }
-            if (mE && mR) { /* this pair's measure alone, then the element-wise maximum */
-                memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
-                if (head_side) grad_triple_mag(p, nv, rv, tv, cneg, tt, tr, th); /* tt: the negative, th: the kept one */
-                else grad_triple_mag(p, hv, rv, nv, cneg, th, tr, tt);
-                const int64_t sk = head_side ? st : sh;
-                for (int d = 0; d < De; ++d) {
-                    if (th[d] > mE[sk * De + d]) mE[sk * De + d] = th[d];
-                    if (tt[d] > mE[sn * De + d]) mE[sn * De + d] = tt[d];
-                }
-                for (int d = 0; d < Dr; ++d) if (tr[d] > mR[sr * Dr + d]) mR[sr * Dr + d] = tr[d];
-                memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr); memset(tt, 0, sizeof(double) * De);
-            }
-            if (use_split) {
-                if (p->bf16_inputs) {
-                    /* the coefficient that multiplies the rounded operands in the backward products */
-                    if (p->model == KO_TRANSE_L2) {
-                        double dist = p->gamma - fneg[j];
-                        double wq = dist > 0 ? round_bf16(cneg / dist) : 0.0;
-                        cneg = wq * dist;
-                    } else {
-                        cneg = round_bf16(cneg);
-                    }
-                    for (int d = 0; d < De; ++d) nv[d] = round_bf16(nv[d]);
-                }
-                pair_grad(p, ov, nv, cneg, go, tt);
-                add_rows(dE, sn, De, tt);
-            } else if (head_side) {
-                grad_triple(p, nv, rv, tv, cneg, th, tr, tt); /* (n, r, t) */
-                add_rows(dE, sn, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, st, De, tt);
-            } else {
-                grad_triple(p, hv, rv, nv, cneg, th, tr, tt); /* (h, r, n) */
-                add_rows(dE, sh, De, th); add_rows(dR, sr, Dr, tr); add_rows(dE, sn, De, tt);
-            }
-        }
-        if (use_split && rc == 0) {
-            memset(th, 0, sizeof(double) * De); memset(tr, 0, sizeof(double) * Dr);
-            split_o_backward(p, head_side ? tv : hv, rv, go, th, tr);
-            add_rows(dE, head_side ? st : sh, De, th); add_rows(dR, sr, Dr, tr);
-        }
+        free(accs); free(rcs);
+        if (loss_out) *loss_out = total;
+        return rc;
     }
+#endif
+    ko_scratch s;
+    if (!scratch_alloc(&s, De, Dr, k)) { scratch_free(&s); return -3; }
+    ko_acc acc = { 0.0, dE, dR, aE, aR, mE, mR };
+    for (int64_t i = 0; i < b && rc == 0; ++i) rc = one_positive(&q, i, &s, &acc);
+    total = acc.total;
     if (loss_out) *loss_out = total;
-    free(hv); free(tv); free(nv); free(rv); free(ov); free(go); free(fneg); free(w);
-    free(th); free(tt); free(tr);
+    scratch_free(&s);
     return rc;
 }
 
