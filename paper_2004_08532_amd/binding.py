@@ -26,7 +26,7 @@ MODEL_IDS = {"transe_l2": KGE_TRANSE_L2, "transe_l1": KGE_TRANSE_L1, "distmult":
 
 EXPORTS = ("kge_create", "kge_destroy", "kge_train_step", "kge_train_steps", "kge_score", "kge_get_dedup",
            "kge_check_indices", "kge_last_error", "kge_workspace_bytes", "kge_profile", "kge_profile_read",
-           "kge_profile_slot_name", "kge_sample_steps", "kge_rank", "kge_rank_metrics")
+           "kge_profile_slot_name", "kge_sample_steps", "kge_rank", "kge_rank_metrics", "kge_graph_captures")
 KGE_PROF_SLOTS = 9
 
 
@@ -85,6 +85,8 @@ def _load() -> ctypes.CDLL:
     lib.kge_last_error.argtypes = [vp]
     lib.kge_workspace_bytes.restype = i64
     lib.kge_workspace_bytes.argtypes = [vp]
+    lib.kge_graph_captures.restype = i64
+    lib.kge_graph_captures.argtypes = [vp]
     lib.kge_rank.restype = ctypes.c_int
     lib.kge_rank.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, i32, f32, vp, vp]
     lib.kge_rank_metrics.restype = ctypes.c_int
@@ -176,11 +178,16 @@ def kge_train_step(ctx, ent, ent_state, rel, rel_state, h, r, t, b, neg, k, chun
 
 def kge_train_steps(ctx, ent, ent_state, rel, rel_state, h, r, t, b, neg, k, chunk, neg_sides, n_steps, gamma, lr,
                     hip_stream=None, loss_out=None) -> None:
-    """h, r, t: device int64 [n_steps, b]; neg: device int64 [n_steps, (b/chunk)*k]; neg_sides: host sequence or None."""
+    """h, r, t: device int64 [n_steps, b]; neg: device int64 [n_steps, (b/chunk)*k]; neg_sides: host sequence (a
+    contiguous numpy int32 array is passed as it is) or None."""
     f, i = torch.float32, torch.int64
     sides = None
     if neg_sides is not None:
-        sides = (ctypes.c_int32 * int(n_steps))(*[int(x) for x in neg_sides])
+        import numpy as np
+        keep = np.ascontiguousarray(neg_sides, dtype=np.int32)  # alive until the call returns (it copies them)
+        if keep.shape != (int(n_steps),):
+            raise ValueError("neg_sides must have one entry per step")
+        sides = keep.ctypes.data_as(ctypes.c_void_p)
     rc = _lib.kge_train_steps(ctx, _dev_ptr(ent, f, "ent"), _dev_ptr(ent_state, f, "ent_state"),
                               _dev_ptr(rel, f, "rel"), _dev_ptr(rel_state, f, "rel_state"),
                               _dev_ptr(h, i, "h"), _dev_ptr(r, i, "r"), _dev_ptr(t, i, "t"), int(b),
@@ -233,6 +240,10 @@ def kge_last_error(ctx) -> str:
 
 def kge_workspace_bytes(ctx) -> int:
     return int(_lib.kge_workspace_bytes(ctx))
+
+
+def kge_graph_captures(ctx) -> int:
+    return int(_lib.kge_graph_captures(ctx))
 
 
 class KgeContext:
@@ -294,6 +305,9 @@ class KgeContext:
 
     def workspace_bytes(self) -> int:
         return kge_workspace_bytes(self.ctx)
+
+    def graph_captures(self) -> int:
+        return kge_graph_captures(self.ctx)
 
     def close(self):
         if self.ctx is not None:

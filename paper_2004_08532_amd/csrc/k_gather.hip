@@ -64,13 +64,13 @@ __device__ __forceinline__ void rank_block(const KeyList& l, int blk, uint32_t* 
     const int tid = threadIdx.x, n = l.n;
     const int n4 = (n + 3) & ~3;  // the tail is padded with 0xffffffff, which is larger than any id
     // independent loads are issued before the first is used: one round of memory latency per 4096 keys
-    const int64_t step = l.step_ptr ? *l.step_ptr : 0;
+    const KeySources ks = key_sources(l);
     for (int base = 0; base < n4; base += RANK_LOADS * GATHER_THREADS) {
         int64_t raw[RANK_LOADS];
 #pragma unroll
         for (int u = 0; u < RANK_LOADS; ++u) {
             const int i = base + u * GATHER_THREADS + tid;
-            raw[u] = *key_address(l, step, i < n ? i : 0);  // unconditional: all loads go out together
+            raw[u] = *key_address(l, ks, i < n ? i : 0);  // unconditional: all loads go out together
         }
 #pragma unroll
         for (int u = 0; u < RANK_LOADS; ++u) {
@@ -154,12 +154,12 @@ __device__ __forceinline__ void rank_block_bucketed(const KeyList& l, int blk, u
         // bucket(id) = (id * bucket_mul) >> 32 >= tid  <=>  id >= ceil((tid << 32) / bucket_mul)
         first[tid] = (uint32_t)((((uint64_t)tid << 32) + bucket_mul - 1) / bucket_mul);
     }
-    const int64_t step = l.step_ptr ? *l.step_ptr : 0;
+    const KeySources ks = key_sources(l);
     int64_t raw[MAXK];
 #pragma unroll
     for (int u = 0; u < MAXK; ++u) {
         const int p = u * T + tid;
-        raw[u] = *key_address(l, step, p < n ? p : 0);
+        raw[u] = *key_address(l, ks, p < n ? p : 0);
     }
     __syncthreads();
     uint32_t key[MAXK];

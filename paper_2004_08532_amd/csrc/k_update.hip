@@ -36,8 +36,9 @@ struct UpdateArgs {
     const float* neg_loss_part;  // [n_loss_parts] negative-side loss sums of the backward launch (may be none)
     int n_loss_parts;
     int b;
-    float* loss_out;        // direct mode: this step's scalar; replay mode: one float per step
-    int64_t* step_ptr;      // replay mode: which step is running; advanced here, by the one thread that reads it
+    float* loss_out;        // direct mode: this step's scalar (may be null)
+    StepBlock* blk;         // replay mode: the call's loss array and the running step, advanced here by the one
+                            // thread that reads it
 };
 
 __device__ __forceinline__ float4 add4(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
@@ -68,9 +69,14 @@ __global__ __launch_bounds__(UPD_THREADS) void k_update(UpdateArgs a) {
             __syncthreads();
         }
         if (tid == 0) {
-            const int64_t step = a.step_ptr ? *a.step_ptr : 0;
-            if (a.loss_out) a.loss_out[step] = part[0];
-            if (a.step_ptr) *a.step_ptr = step + 1;  // no other thread of this launch reads the counter
+            if (a.blk) {
+                const int64_t step = a.blk->step;
+                float* out = a.blk->loss_out;
+                if (out) out[step] = part[0];
+                a.blk->step = step + 1;  // no other thread of this launch reads the counter
+            } else if (a.loss_out) {
+                a.loss_out[0] = part[0];
+            }
         }
         return;
     }
@@ -255,7 +261,7 @@ void kge_launch_update(kge_ctx* c, float* E, float* SE, float* R, float* SR, con
     UpdateArgs a;
     const int b = ids.b, n_ent_keys = 2 * ids.b + ids.n_neg, n_rel_keys = ids.b;
     float* loss_out = ids.loss_out;
-    a.step_ptr = const_cast<int64_t*>(ids.step_ptr);
+    a.blk = ids.blk;
     a.T[0] = E; a.T[1] = R; a.St[0] = SE; a.St[1] = SR;
     a.G[0] = c->Gent; a.G[1] = c->Grel;
     a.key[0] = c->ekey[c->ebuf]; a.key[1] = c->rkey[c->rbuf];

@@ -46,9 +46,12 @@ StepIds direct_ids(const int64_t* h, const int64_t* r, const int64_t* t, int b, 
                    float* loss_out) {
     StepIds ids;
     ids.h = h; ids.r = r; ids.t = t; ids.neg = neg; ids.b = b; ids.n_neg = n_neg; ids.side = side;
-    ids.step_ptr = nullptr; ids.sides = nullptr; ids.loss_out = loss_out;
+    ids.blk = nullptr; ids.loss_out = loss_out;
     return ids;
 }
+
+// Fills the step block of a kge_train_steps call (replay mode): one thread, the values travel as kernel arguments.
+__global__ void k_set_step_block(StepBlock* blk, StepBlock value) { *blk = value; }
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -219,32 +222,34 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
     return KGE_OK;
 }
 
-// ---- replay: kge_train_steps captures UNROLL consecutive steps (and one single step for the remainder) into HIP
-// graphs whose kernels take the step number from device memory, so the same two graphs serve every step of every
-// call with the same arguments.  A graph launch costs the host about as much as one kernel launch.
-constexpr int REPLAY_UNROLL = 8;
+// ---- replay: kge_train_steps captures 1, 2, 4 and 8 consecutive steps into HIP graphs whose kernels take the step
+// number and the id arrays from device memory (the step block), so the same graphs serve every step of every call
+// of the same shape.  Launching a graph costs the host about 2 us per kernel in it plus a fixed part, and the
+// device starts on a graph only once the whole of it is enqueued: a call therefore starts with the short graphs
+// (1, 2, 4 steps: the device is busy after one step's worth of enqueueing and the host stays ahead of it from
+// there), goes on with graphs of 8 and ends with the remainder.
+constexpr int REPLAY_SIZES = 4;  // graphs of 1 << i steps, i < REPLAY_SIZES
 
+// What a captured graph depends on.  The id arrays, the per-step sides and the loss array are not part of it: the
+// kernels find them through the step block.
 struct ReplayKey {
     void *ent, *ent_state, *rel, *rel_state;
-    const void *h, *r, *t, *neg;
     int64_t b, k, chunk;
     float gamma, lr;
-    float* loss_out;
-    bool has_sides;
     bool operator==(const ReplayKey& o) const { return memcmp(this, &o, sizeof(ReplayKey)) == 0; }
 };
 
 struct ReplayCache {
     bool valid = false;
     ReplayKey key;
-    hipGraphExec_t many = nullptr;  // REPLAY_UNROLL steps
-    hipGraphExec_t one = nullptr;   // one step
+    hipGraphExec_t exec[REPLAY_SIZES] = {};  // exec[i] runs 1 << i steps
 };
 
 void replay_drop(ReplayCache* rc) {
-    if (rc->many) (void)hipGraphExecDestroy(rc->many);
-    if (rc->one) (void)hipGraphExecDestroy(rc->one);
-    rc->many = rc->one = nullptr;
+    for (int i = 0; i < REPLAY_SIZES; ++i) {
+        if (rc->exec[i]) (void)hipGraphExecDestroy(rc->exec[i]);
+        rc->exec[i] = nullptr;
+    }
     rc->valid = false;
 }
 
@@ -263,6 +268,8 @@ int capture_steps(kge_ctx* c, float* ent, float* ent_state, float* rel, float* r
     e = hipGraphInstantiate(out, graph, nullptr, nullptr, 0);
     (void)hipGraphDestroy(graph);
     if (e != hipSuccess) return fail(c, KGE_ERR_DEVICE, "hipGraphInstantiate: %s", hipGetErrorString(e));
+    (void)hipGraphUpload(*out, st);  // so that the first launch does not pay for it; a failure here is not one
+    (void)hipGetLastError();
     return KGE_OK;
 }
 
@@ -324,7 +331,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t o_nlp = take((B / 32 + cfg->max_chunks + 1) * ((size_t)cfg->max_neg_per_chunk / 32 + 1) * 4);
     const size_t o_ek0 = take(EK * 4), o_ek1 = take(EK * 4), o_ep0 = take(EK * 4), o_ep1 = take(EK * 4);
     const size_t o_rk0 = take(B * 4), o_rk1 = take(B * 4), o_rp0 = take(B * 4), o_rp1 = take(B * 4);
-    const size_t o_flags = take(256), o_step = take(256);
+    const size_t o_flags = take(256), o_step = take(256), o_sides = take(sizeof(int32_t) * KGE_SIDES_CAP);
     c->ld_bf = (cfg->ent_dim + 7) / 8 * 8;
     const bool bf = cfg->gemm_input == 1;
     const size_t o_Obf = take(bf ? B * c->ld_bf * 2 + 64 : 0), o_Nbf = take(bf ? NR * c->ld_bf * 2 + 64 : 0);
@@ -361,7 +368,8 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->pair_part_n = pair_model ? (float*)(base + o_ppn) : nullptr;
     c->sort_counts = (uint32_t*)(base + o_sc);
     c->flags = (int*)(base + o_flags);
-    c->step_counter = (int64_t*)(base + o_step);
+    c->step_block = (StepBlock*)(base + o_step);
+    c->sides_dev = (int32_t*)(base + o_sides);
 
     bool ok = hipMemset(c->ws_base, 0, off) == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking) == hipSuccess;
@@ -389,7 +397,6 @@ void kge_destroy(kge_ctx* c) {
         replay_drop((ReplayCache*)c->replay);
         delete (ReplayCache*)c->replay;
     }
-    if (c->sides_dev) (void)hipFree(c->sides_dev);
     if (c->ws_base) (void)hipFree(c->ws_base);
     delete c;
 }
@@ -445,48 +452,49 @@ int kge_train_steps(kge_ctx* c, float* ent, float* ent_state, float* rel, float*
         return KGE_OK;
     }
 
-    // replay path
-    if (neg_sides) {
-        if (c->sides_cap < n_steps) {
-            KGE_HIP(c, hipStreamSynchronize(st));
-            if (c->sides_dev) KGE_HIP(c, hipFree(c->sides_dev));
-            c->sides_dev = nullptr;
-            c->sides_cap = 0;
-            KGE_HIP(c, hipMalloc((void**)&c->sides_dev, sizeof(int32_t) * (size_t)n_steps));
-            c->sides_cap = n_steps;
-            if (c->replay) replay_drop((ReplayCache*)c->replay);  // the graphs hold the old pointer
-        }
-        KGE_HIP(c, hipMemcpyAsync(c->sides_dev, neg_sides, sizeof(int32_t) * (size_t)n_steps, hipMemcpyHostToDevice, st));
-    }
-    KGE_HIP(c, hipMemsetAsync(c->step_counter, 0, sizeof(int64_t), st));
-
+    // replay path: nothing here allocates once the two graphs exist
     ReplayKey key;
     memset(&key, 0, sizeof(key));
     key.ent = ent; key.ent_state = ent_state; key.rel = rel; key.rel_state = rel_state;
-    key.h = h; key.r = r; key.t = t; key.neg = neg; key.b = b; key.k = k; key.chunk = chunk;
-    key.gamma = gamma; key.lr = lr; key.loss_out = loss_out; key.has_sides = neg_sides != nullptr;
+    key.b = b; key.k = k; key.chunk = chunk; key.gamma = gamma; key.lr = lr;
     if (!c->replay) c->replay = new (std::nothrow) ReplayCache();
     ReplayCache* cache = (ReplayCache*)c->replay;
     if (!cache) return fail(c, KGE_ERR_DEVICE, "out of host memory%s");
     if (!cache->valid || !(cache->key == key)) {
         replay_drop(cache);
-        StepIds ids = direct_ids(h, r, t, (int)b, neg, (int)n_neg, KGE_NEG_TAIL, loss_out);
-        ids.step_ptr = c->step_counter;
-        ids.sides = neg_sides ? c->sides_dev : nullptr;
-        rc = capture_steps(c, ent, ent_state, rel, rel_state, ids, (int)k, (int)chunk, gamma, lr, st, REPLAY_UNROLL,
-                           &cache->many);
-        if (rc == KGE_OK)
-            rc = capture_steps(c, ent, ent_state, rel, rel_state, ids, (int)k, (int)chunk, gamma, lr, st, 1, &cache->one);
+        StepIds ids = direct_ids(nullptr, nullptr, nullptr, (int)b, nullptr, (int)n_neg, KGE_NEG_TAIL, nullptr);
+        ids.blk = c->step_block;
+        for (int i = 0; i < REPLAY_SIZES && rc == KGE_OK; ++i)
+            rc = capture_steps(c, ent, ent_state, rel, rel_state, ids, (int)k, (int)chunk, gamma, lr, st, 1 << i,
+                               &cache->exec[i]);
         if (rc != KGE_OK) {
             replay_drop(cache);
             return rc;
         }
         cache->key = key;
         cache->valid = true;
+        c->graph_captures += 1;
     }
-    int64_t done = 0;
-    for (; done + REPLAY_UNROLL <= n_steps; done += REPLAY_UNROLL) KGE_HIP(c, hipGraphLaunch(cache->many, st));
-    for (; done < n_steps; ++done) KGE_HIP(c, hipGraphLaunch(cache->one, st));
+    // the per-step sides live in a fixed part of the workspace: a longer call runs in segments of that many steps
+    for (int64_t first = 0; first < n_steps; first += KGE_SIDES_CAP) {
+        const int64_t n = n_steps - first < KGE_SIDES_CAP ? n_steps - first : KGE_SIDES_CAP;
+        if (neg_sides)
+            KGE_HIP(c, hipMemcpyAsync(c->sides_dev, neg_sides + first, sizeof(int32_t) * (size_t)n, hipMemcpyHostToDevice, st));
+        StepBlock blk;
+        blk.step = 0;
+        blk.h = h + first * b; blk.r = r + first * b; blk.t = t + first * b; blk.neg = neg + first * n_neg;
+        blk.sides = neg_sides ? c->sides_dev : nullptr;
+        blk.loss_out = loss_out ? loss_out + first : nullptr;
+        hipLaunchKernelGGL(k_set_step_block, dim3(1), dim3(1), 0, st, c->step_block, blk);
+        int64_t left = n;
+        for (int i = 0; i + 1 < REPLAY_SIZES && left >= ((int64_t)1 << i); ++i) {  // the ramp
+            KGE_HIP(c, hipGraphLaunch(cache->exec[i], st));
+            left -= (int64_t)1 << i;
+        }
+        for (int i = REPLAY_SIZES - 1; i >= 0; --i)  // the long graphs, then the remainder
+            for (; left >= ((int64_t)1 << i); left -= (int64_t)1 << i) KGE_HIP(c, hipGraphLaunch(cache->exec[i], st));
+    }
+    KGE_HIP(c, hipGetLastError());
     return KGE_OK;
 }
 
@@ -613,5 +621,7 @@ int kge_sample_steps(const kge_sampler* sp, int64_t first_step, int64_t n_steps,
 const char* kge_last_error(const kge_ctx* c) { return c ? c->err : g_create_err; }
 
 int64_t kge_workspace_bytes(const kge_ctx* c) { return c ? c->ws_bytes : 0; }
+
+int64_t kge_graph_captures(const kge_ctx* c) { return c ? c->graph_captures : 0; }
 
 }  // extern "C"

@@ -24,6 +24,8 @@ struct PartialRows {
     int64_t n4;      // 16-byte pieces per partial
 };
 
+struct StepBlock;
+
 struct kge_ctx {
     kge_config cfg;
     float eps;
@@ -69,10 +71,10 @@ struct kge_ctx {
     int64_t last_ent_keys, last_rel_keys;  // sizes of the last train step's key lists (0: none yet)
     hipStream_t side_stream;        // runs the key sort beside the forward/backward kernels
     hipEvent_t ev_fork, ev_join;
-    int64_t* step_counter;          // device: the step a replayed graph is at
-    int32_t* sides_dev;             // device: per-step sides of the current kge_train_steps call
-    int64_t sides_cap;
+    StepBlock* step_block;          // device: id arrays and step counter of the running kge_train_steps call
+    int32_t* sides_dev;             // device: per-step sides of the running call, KGE_SIDES_CAP entries
     void* replay;                   // cached graphs of kge_train_steps (ReplayCache in kge_api.hip)
+    int64_t graph_captures;         // how many times they were built
     bool prof_on;                   // kge_profile: bracket every kernel with events
     hipEvent_t prof_ev[KGE_PROF_SLOTS][2];
     double prof_ms[KGE_PROF_SLOTS];
@@ -98,30 +100,40 @@ struct kge_ctx {
 
 // ---------------------------------------------------------------------------------------------------------
 // The ids of one step, as the kernels receive them.
-// Direct mode: step_ptr == nullptr and h, r, t, neg point at this step's ids.
-// Replay mode (one captured HIP graph serves every step of kge_train_steps): h, r, t, neg point at the ids of
-// step 0, consecutive steps lie b (n_neg) entries apart, *step_ptr (device memory, advanced by the last kernel of
-// every step) says which step is running, sides (device, may be null) holds one kge_neg_side per step and
-// loss_out one float per step.
+// Direct mode: blk == nullptr and h, r, t, neg point at this step's ids, side and loss_out are this step's.
+// Replay mode (one captured HIP graph serves every step of every kge_train_steps call of the same shape): blk points
+// at a block in the workspace that a one-thread kernel fills at the start of every call with the call's id arrays
+// (ids of its step 0; consecutive steps lie b (n_neg) entries apart), its per-step sides (may be null: tail
+// corruption throughout) and its loss array (one float per step, may be null), and whose step counter the last
+// kernel of every step advances.  The graphs hold only the block's address, so new id arrays need no new capture.
 // ---------------------------------------------------------------------------------------------------------
+struct StepBlock {
+    int64_t step;
+    const int64_t* h;
+    const int64_t* r;
+    const int64_t* t;
+    const int64_t* neg;
+    const int32_t* sides;
+    float* loss_out;
+};
+
 struct StepIds {
     const int64_t* h;
     const int64_t* r;
     const int64_t* t;
     const int64_t* neg;
     int b, n_neg, side;
-    const int64_t* step_ptr;
-    const int32_t* sides;
+    StepBlock* blk;
     float* loss_out;
 };
 
 // A key list of the duplicate reduction: the concatenation of up to three id arrays (entities: heads | tails |
 // corrupting ids; relations: r), to be brought into (id, position) order.
 struct KeyList {
-    const int64_t* src[3];
+    const int64_t* src[3];   // direct mode
     int n_src[3];
-    int64_t step_stride[3];  // replay mode: src[i] advances by this many entries per step
-    const int64_t* step_ptr;
+    const StepBlock* blk;    // replay mode: the arrays come from the block (which == 0: h | t | neg, 1: r)
+    int which;
     int n;                   // total number of keys
     int passes;              // radix passes needed for ids < n_ids (8 bits each)
     int64_t n_ids;           // ids are clamped into [0, n_ids)
@@ -138,6 +150,7 @@ void kge_make_key_lists(kge_ctx* c, const StepIds& ids, KeyList* ent, KeyList* r
 // KGE_RANK_MAX_KEYS keys; longer lists go through kge_launch_sort)
 void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds& ids, float gamma, float* pos_out,
                        bool with_keys, hipStream_t st);
+constexpr int KGE_SIDES_CAP = 65536;  // steps whose sides fit the workspace: longer kge_train_steps calls run in segments
 constexpr int KGE_SORT_SLICE = 4096;  // keys per workgroup of the radix sort of long key lists
 constexpr int KGE_PAIR_MAX_PARTS = 8;  // partial rows per gradient row in the tiled backward of RotatE / TransE-L1
 constexpr int KGE_RANK_MAX_KEYS = 14336;  // 14 * 1024: positions fit 14 bits, the list and its tables fit 64 KB of LDS
@@ -205,20 +218,47 @@ struct StepView {
 };
 __device__ __forceinline__ StepView step_view(const StepIds& s) {
     StepView v;
-    v.step = s.step_ptr ? *s.step_ptr : 0;
-    v.h = s.h + v.step * s.b;
-    v.r = s.r + v.step * s.b;
-    v.t = s.t + v.step * s.b;
-    v.neg = s.neg + v.step * s.n_neg;
-    v.side = s.sides ? s.sides[v.step] : s.side;
+    if (s.blk) {
+        const StepBlock* k = s.blk;  // uniform address: these are scalar loads of one cache line
+        v.step = k->step;
+        v.h = k->h + v.step * s.b;
+        v.r = k->r + v.step * s.b;
+        v.t = k->t + v.step * s.b;
+        v.neg = k->neg + v.step * s.n_neg;
+        const int32_t* sides = k->sides;
+        v.side = sides ? sides[v.step] : KGE_NEG_TAIL;
+    } else {
+        v.step = 0;
+        v.h = s.h; v.r = s.r; v.t = s.t; v.neg = s.neg;
+        v.side = s.side;
+    }
     return v;
 }
+// The (up to three) id arrays of a key list for the running step.
+struct KeySources { const int64_t* p[3]; };
+__device__ __forceinline__ KeySources key_sources(const KeyList& l) {
+    KeySources s;
+    if (l.blk) {
+        const StepBlock* k = l.blk;
+        const int64_t step = k->step;
+        if (l.which == 0) {
+            s.p[0] = k->h + step * l.n_src[0];
+            s.p[1] = k->t + step * l.n_src[1];
+            s.p[2] = k->neg + step * l.n_src[2];
+        } else {
+            s.p[0] = s.p[1] = s.p[2] = k->r + step * l.n_src[0];
+        }
+    } else {
+        s.p[0] = l.src[0]; s.p[1] = l.src[1]; s.p[2] = l.src[2];
+    }
+    return s;
+}
 // Address of entry idx of a key list (branch-free, so that a thread can have many of these loads in flight).
-__device__ __forceinline__ const int64_t* key_address(const KeyList& l, int64_t step, int idx) {
+__device__ __forceinline__ const int64_t* key_address(const KeyList& l, const KeySources& s, int idx) {
     const int a = l.n_src[0], ab = a + l.n_src[1];
-    const int64_t* p0 = l.src[0] + step * l.step_stride[0] + idx;
-    const int64_t* p1 = l.src[1] + step * l.step_stride[1] + (idx - a);
-    const int64_t* p2 = l.src[2] + step * l.step_stride[2] + (idx - ab);
+    const int64_t* p0 = s.p[0] + idx;
+    const int64_t* p1 = s.p[1] + (idx - a);
+    const int64_t* p2 = s.p[2] + (idx - ab);
     return idx < a ? p0 : (idx < ab ? p1 : p2);
 }
 __device__ __forceinline__ uint32_t clamp_key(const KeyList& l, int64_t id) {
@@ -226,8 +266,7 @@ __device__ __forceinline__ uint32_t clamp_key(const KeyList& l, int64_t id) {
     return (uint32_t)id;
 }
 __device__ __forceinline__ uint32_t fetch_key(const KeyList& l, int idx) {
-    const int64_t step = l.step_ptr ? *l.step_ptr : 0;
-    return clamp_key(l, *key_address(l, step, idx));
+    return clamp_key(l, *key_address(l, key_sources(l), idx));
 }
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -613,8 +613,9 @@ REPLAY_VARIANTS = {
 @pytest.mark.parametrize("variant", list(REPLAY_VARIANTS), ids=list(REPLAY_VARIANTS))
 def test_train_steps_graph_replay_equals_step_by_step(kge, variant):
     """kge_train_steps replays captured graphs; the result must equal kge_train_step called once per step, bit for
-    bit, on every replay: first use (capture), reuse with new ids in the same buffers, a step count that is not a
-    multiple of the unroll factor, with eager work and synchronisation in between.  The variants take every kernel
+    bit, on every replay: first use (capture), reuse with new ids in the same buffers, reuse with id and loss arrays at
+    other addresses (no new capture: the graphs reach them through the step block), a call without sides or loss
+    array, a step count that is not a multiple of the unroll factor, with eager work and synchronisation in between.  The variants take every kernel
     of the library through a replayed graph once (fused and separate loss / chain kernels, pair kernels, the RESCAL
     kernels, the bf16 products, the sort of long key lists)."""
     w = configs.TINY.scaled(name="tiny-replay", side_mode="alternate", **REPLAY_VARIANTS[variant])
@@ -644,7 +645,8 @@ def test_train_steps_graph_replay_equals_step_by_step(kge, variant):
             stream.synchronize()
     ctx.close()
 
-    # replayed: the same device buffers are refilled for every call, so the second and third call reuse the graphs
+    # replayed.  Round 0 captures the graphs; round 1 refills the same device buffers; round 2 passes id, side-less
+    # ... and loss arrays that live elsewhere: the graphs find them through the step block, so nothing is captured again
     ctx = make_ctx()
     bE, bSE, bR, bSR = fresh()
     loss_b = torch.zeros(n_per_call, device="cuda")
@@ -654,6 +656,11 @@ def test_train_steps_graph_replay_equals_step_by_step(kge, variant):
     scratch = torch.zeros(1000, device="cuda")
     for rd in range(rounds):
         h, r, t, neg, sides = bs.steps(rd * n_per_call, n_per_call)
+        if rd == 2:  # other arrays, at other addresses, offset into a larger allocation
+            big = torch.zeros((4, n_per_call + 3, w.batch), dtype=torch.int64, device="cuda")
+            H, Rr, T = big[0, 3:], big[1, 2:2 + n_per_call], big[2, 1:1 + n_per_call]
+            N = torch.zeros((n_per_call + 1, w.n_chunks * w.neg_per_chunk), dtype=torch.int64, device="cuda")[1:]
+            loss_b = torch.zeros(n_per_call + 5, device="cuda")[5:]
         H.copy_(torch.from_numpy(h)); Rr.copy_(torch.from_numpy(r)); T.copy_(torch.from_numpy(t))
         N.copy_(torch.from_numpy(neg.reshape(n_per_call, -1)))
         torch.cuda.synchronize()
@@ -664,5 +671,20 @@ def test_train_steps_graph_replay_equals_step_by_step(kge, variant):
         scratch.add_(1.0)  # unrelated eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(loss_b, loss_a[rd * n_per_call:(rd + 1) * n_per_call]), rd
+        assert ctx.graph_captures() == 1, rd
     assert torch.equal(aE, bE) and torch.equal(aSE, bSE) and torch.equal(aR, bR) and torch.equal(aSR, bSR)
+    # a call without sides and without a loss array replays the same graphs too (tail corruption throughout)
+    h, r, t, neg, _ = bs.steps(rounds * n_per_call, 9)
+    dh, dr, dt, dn = dev(h), dev(r), dev(t), dev(neg.reshape(9, -1))
+    with torch.cuda.stream(stream):
+        ctx.train_steps(bE, bSE, bR, bSR, dh, dr, dt, dn, w.neg_per_chunk, w.chunk, None, w.gamma, w.lr)
+    stream.synchronize()
+    assert ctx.graph_captures() == 1
     ctx.close()
+    ctx = make_ctx()
+    with torch.cuda.stream(stream):
+        for s in range(9):
+            ctx.train_step(aE, aSE, aR, aSR, dh[s], dr[s], dt[s], dn[s], w.neg_per_chunk, w.chunk, 0, w.gamma, w.lr)
+    stream.synchronize()
+    ctx.close()
+    assert torch.equal(aE, bE) and torch.equal(aSE, bSE) and torch.equal(aR, bR) and torch.equal(aSR, bSR)
