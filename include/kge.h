@@ -149,6 +149,25 @@ int kge_score(kge_ctx* ctx, const float* ent, const float* rel,
               void* hip_stream, float* pos_out, float* neg_out);
 
 /*
+ * kge_score for callers that cannot allocate device memory: code that runs while a stream is being captured into a
+ * HIP graph, tight serving loops, harnesses that forbid hipMalloc.  There is no context: (host) cfg carries model,
+ * device, num_entities, num_relations, ent_dim and rel_dim (gemm_input must be 0; the other fields are ignored), and
+ * the staging that kge_score keeps in a context's workspace (the o rows, the gathered corrupting rows, norms) lives
+ * in a fixed 8 MiB array inside the library's device image, of which every GPU that runs the library holds a copy
+ * until the process ends.  The call makes no hipMalloc / hipFree and calls no allocating library routine; its first
+ * use on a device looks the array's address up (and, like any first launch, loads the kernels), so make one call
+ * before a capture begins.  Other arguments, outputs and results exactly as for kge_score.
+ * Limits: TransE-L2, TransE-L1, DistMult, ComplEx, RotatE; 4 * ent_dim * (b + (b/chunk) * k) + 24 * (b + (b/chunk) * k)
+ * bytes (each piece rounded up to 256) must fit the 8 MiB, else KGE_ERR_WORKSPACE and nothing is enqueued; ids are
+ * clamped into their tables (no validate_indices).  Every call on a GPU uses that GPU's one array: calls that overlap
+ * on one GPU, on whatever streams, race; calls on one stream are ordered.  Errors: kge_last_error(NULL) has the text.
+ */
+int kge_score_noalloc(const kge_config* cfg, const float* ent, const float* rel,
+                      const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,
+                      const int64_t* neg, int64_t k, int64_t chunk, int32_t neg_side, float gamma,
+                      void* hip_stream, float* pos_out, float* neg_out);
+
+/*
  * Test hook for the duplicate reduction of the last kge_train_step on this context (Sec. 2: mini-batches
  * touch few rows, and one row may be touched many times).  which = 0: entity rows (the multiset
  * {h_i} + {t_i} + {neg}); which = 1: relation rows ({r_i}).  uniq_out receives the distinct ids in ascending

@@ -26,7 +26,7 @@ MODEL_IDS = {"transe_l2": KGE_TRANSE_L2, "transe_l1": KGE_TRANSE_L1, "distmult":
 
 EXPORTS = ("kge_create", "kge_destroy", "kge_train_step", "kge_train_steps", "kge_score", "kge_get_dedup",
            "kge_check_indices", "kge_last_error", "kge_workspace_bytes", "kge_profile", "kge_profile_read",
-           "kge_profile_slot_name", "kge_sample_steps", "kge_rank", "kge_rank_metrics", "kge_graph_captures")
+           "kge_profile_slot_name", "kge_sample_steps", "kge_rank", "kge_rank_metrics", "kge_graph_captures", "kge_score_noalloc")
 KGE_PROF_SLOTS = 9
 
 
@@ -77,6 +77,8 @@ def _load() -> ctypes.CDLL:
     lib.kge_profile_slot_name.argtypes = [i32]
     lib.kge_score.restype = ctypes.c_int
     lib.kge_score.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp, i64, i64, i32, f32, vp, vp, vp]
+    lib.kge_score_noalloc.restype = ctypes.c_int
+    lib.kge_score_noalloc.argtypes = [ctypes.POINTER(kge_config), vp, vp, vp, vp, vp, i64, vp, i64, i64, i32, f32, vp, vp, vp]
     lib.kge_get_dedup.restype = ctypes.c_int
     lib.kge_get_dedup.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.kge_check_indices.restype = ctypes.c_int
@@ -220,6 +222,16 @@ def kge_score(ctx, ent, rel, h, r, t, b, neg, k, chunk, neg_side, gamma, hip_str
                         int(neg_side), float(gamma), _stream(hip_stream), _dev_ptr(pos_out, f, "pos_out"),
                         _dev_ptr(neg_out, f, "neg_out"))
     _check(ctx, rc)
+
+
+def kge_score_noalloc(cfg: kge_config, ent, rel, h, r, t, b, neg, k, chunk, neg_side, gamma, hip_stream=None,
+                      pos_out=None, neg_out=None) -> None:
+    f, i = torch.float32, torch.int64
+    rc = _lib.kge_score_noalloc(ctypes.byref(cfg), _dev_ptr(ent, f, "ent"), _dev_ptr(rel, f, "rel"),
+                                _dev_ptr(h, i, "h"), _dev_ptr(r, i, "r"), _dev_ptr(t, i, "t"), int(b),
+                                _dev_ptr(neg, i, "neg"), int(k), int(chunk), int(neg_side), float(gamma),
+                                _stream(hip_stream), _dev_ptr(pos_out, f, "pos_out"), _dev_ptr(neg_out, f, "neg_out"))
+    _check(None, rc)
 
 
 def kge_get_dedup(ctx, which, uniq_out, count_out, n_unique_out, hip_stream=None) -> None:

@@ -4,11 +4,37 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "kge_common.h"
 
+// Scratch memory of kge_score_noalloc, the one entry point that allocates nothing: a fixed array in the library's
+// device image (every GPU that runs the library holds its own copy until the process ends).  In host code the name
+// below is only a handle for hipGetSymbolAddress; the address the kernels get is the one that call returns.
+constexpr size_t KGE_NOALLOC_SCRATCH_BYTES = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[KGE_NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int KGE_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[KGE_MAX_DEVICES] = {};  // per device: where that GPU's copy of `scratch` lives
+
+// Address of the current device's scratch array (resolved once per device, with that device current).
+hipError_t scratch_address(int device, void** out) {
+    if (device < 0 || device >= KGE_MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 thread_local char g_create_err[512] = "";
 
@@ -511,6 +537,66 @@ int kge_score(kge_ctx* c, const float* ent, const float* rel,
     const StepIds ids = direct_ids(h, r, t, (int)b, neg, (int)((b / chunk) * kk), neg_side, nullptr);
     forward(c, ent, rel, ids, kk, (int)chunk, gamma, pos_out, neg_out, (int)k, 0, (hipStream_t)hip_stream);
     KGE_HIP(c, hipGetLastError());
+    return KGE_OK;
+}
+
+int kge_score_noalloc(const kge_config* cfg, const float* ent, const float* rel,
+                      const int64_t* h, const int64_t* r, const int64_t* t, int64_t b,
+                      const int64_t* neg, int64_t k, int64_t chunk, int32_t neg_side, float gamma,
+                      void* hip_stream, float* pos_out, float* neg_out) {
+    if (!cfg) return fail(nullptr, KGE_ERR_INVALID_ARG, "null configuration%s");
+    const int m = cfg->model;
+    if (m != KGE_TRANSE_L2 && m != KGE_TRANSE_L1 && m != KGE_DISTMULT && m != KGE_COMPLEX && m != KGE_ROTATE)
+        return fail(nullptr, KGE_ERR_UNSUPPORTED, "kge_score_noalloc serves TransE-L1/L2, DistMult, ComplEx and RotatE%s");
+    if (cfg->gemm_input != 0) return fail(nullptr, KGE_ERR_UNSUPPORTED, "kge_score_noalloc takes fp32 operands only%s");
+    const bool cplx = m == KGE_COMPLEX || m == KGE_ROTATE;
+    if (cfg->ent_dim <= 0 || cfg->ent_dim > 1024 || cfg->ent_dim % (cplx ? 8 : 4) != 0)
+        return fail(nullptr, KGE_ERR_INVALID_ARG, "ent_dim must be a multiple of 4 (8 for ComplEx/RotatE), at most 1024%s");
+    if (cfg->rel_dim != (m == KGE_ROTATE ? cfg->ent_dim / 2 : cfg->ent_dim))
+        return fail(nullptr, KGE_ERR_INVALID_ARG, "rel_dim must be ent_dim (ent_dim/2 for RotatE)%s");
+    if (cfg->num_entities <= 0 || cfg->num_relations <= 0 || cfg->num_entities >= (1ll << 32) ||
+        cfg->num_relations >= (1ll << 32))
+        return fail(nullptr, KGE_ERR_INVALID_ARG, "table row counts must be in [1, 2^32)%s");
+    if (!ent || !rel || !h || !r || !t) return fail(nullptr, KGE_ERR_INVALID_ARG, "null table or id pointer%s");
+    if (b <= 0 || chunk <= 0 || b % chunk != 0) return fail(nullptr, KGE_ERR_INVALID_ARG, "b must be a positive multiple of chunk%s");
+    if (k < 0 || (neg_out && k == 0)) return fail(nullptr, KGE_ERR_INVALID_ARG, "k out of range%s");
+    if (neg_out && !neg) return fail(nullptr, KGE_ERR_INVALID_ARG, "neg is null%s");
+    if (neg_side != KGE_NEG_TAIL && neg_side != KGE_NEG_HEAD) return fail(nullptr, KGE_ERR_INVALID_ARG, "neg_side must be 0 or 1%s");
+    const int64_t kk = neg_out ? k : 0, n_neg = (b / chunk) * kk;
+    if (b > (1 << 24) || n_neg > (1 << 24) || kk > (1 << 24)) return fail(nullptr, KGE_ERR_WORKSPACE, "b or (b/chunk)*k beyond 2^24%s");
+    // layout of the scratch array for this call: o rows | staged corrupting rows | six small vectors
+    const size_t D = (size_t)cfg->ent_dim, B = (size_t)b, NR = (size_t)(n_neg > 0 ? n_neg : 1);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    const size_t o_O = take(B * D * 4), o_N = take(NR * D * 4), o_fpos = take(B * 4), o_on2 = take(B * 4);
+    const size_t o_nn2 = take(NR * 4), o_cpos = take(B * 4), o_idp = take(B * 4), o_rl = take(B * 4);
+    if (off > KGE_NOALLOC_SCRATCH_BYTES)
+        return fail(nullptr, KGE_ERR_WORKSPACE, "kge_score_noalloc: 4 * ent_dim * (b + (b/chunk)*k) bytes of rows (plus 24 bytes per row) exceed its 8 MiB of scratch memory%s");
+
+    int ndev = 0;
+    KGE_HIP(nullptr, hipGetDeviceCount(&ndev));
+    if (cfg->device < 0 || cfg->device >= ndev) return fail(nullptr, KGE_ERR_INVALID_ARG, "no such device%s");
+    KGE_HIP(nullptr, hipSetDevice(cfg->device));
+    void* base_v = nullptr;
+    KGE_HIP(nullptr, scratch_address(cfg->device, &base_v));
+    char* base = (char*)base_v;
+
+    // a context that lives on this call's stack and owns nothing: its buffers are pieces of the scratch array.
+    // Every piece that a kernel of this call reads has been written by an earlier kernel of the same call (the gather
+    // launch fills all of them), so nothing has to be cleared between calls.
+    kge_ctx c;
+    memset(&c, 0, sizeof(c));
+    c.cfg = *cfg;
+    c.cfg.validate_indices = 0;  // there is no context to report to: ids are clamped into their tables, as always
+    c.cfg.adagrad_mode = 0; c.cfg.loss = KGE_LOSS_LOGISTIC; c.cfg.adv_temperature = 0.f;
+    c.cfg.max_batch = (int32_t)b; c.cfg.max_neg_per_chunk = (int32_t)kk; c.cfg.max_chunks = (int32_t)(b / chunk);
+    c.ld_s = (int)kk;
+    c.O = (float*)(base + o_O); c.Nst = (float*)(base + o_N); c.fpos = (float*)(base + o_fpos);
+    c.o_n2 = (float*)(base + o_on2); c.n_n2 = (float*)(base + o_nn2); c.cpos = (float*)(base + o_cpos);
+    c.inv_dpos = (float*)(base + o_idp); c.row_loss = (float*)(base + o_rl);
+    const StepIds ids = direct_ids(h, r, t, (int)b, neg, (int)n_neg, neg_side, nullptr);
+    forward(&c, ent, rel, ids, (int)kk, (int)chunk, gamma, pos_out, neg_out, (int)k, 0, (hipStream_t)hip_stream);
+    KGE_HIP(nullptr, hipGetLastError());
     return KGE_OK;
 }
 
