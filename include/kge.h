@@ -10,7 +10,8 @@
  *   - Every data pointer is a DEVICE pointer on the context's device unless it is marked (host).  Tables,
  *     optimizer state, id arrays and outputs are owned by the caller and must stay alive and unmodified
  *     until the stream has finished the work the call enqueued.  The library owns only its workspace, which
- *     is allocated in kge_create and never grows.
+ *     is allocated in kge_create and never grows; no other entry point allocates device memory (the first
+ *     kge_train_steps call of a shape creates HIP graph objects, see there).
  *   - Calls that take a stream ENQUEUE work and return; they do not synchronise.
  *   - Return value: KGE_OK (0) or a negative kge_status.  When an error is detected on the host nothing has
  *     been enqueued and no caller memory has been touched.  No C++ exception crosses this boundary.
@@ -84,11 +85,13 @@ typedef struct {
 } kge_config;
 
 /* Create a context and its workspace on cfg->device.  (host) cfg, (host) out.  The workspace is sized from
- * max_batch, max_neg_per_chunk, max_chunks and ent_dim and stays allocated until kge_destroy. */
+ * max_batch, max_neg_per_chunk, max_chunks and ent_dim and stays allocated until kge_destroy; it holds what Sec. 3.1
+ * step 2 fetches for one mini-batch (the rows, their gradients) and never the tables.  (Library lifecycle: the
+ * paper has no passage for it.) */
 int kge_create(const kge_config* cfg, kge_ctx** out);
 
 /* Free the workspace and the context.  kge_destroy(NULL) does nothing.  The caller must have synchronised
- * every stream that still runs work of this context. */
+ * every stream that still runs work of this context.  (Library lifecycle, no passage.) */
 void kge_destroy(kge_ctx* ctx);
 
 /*
@@ -178,8 +181,12 @@ int kge_get_dedup(kge_ctx* ctx, int32_t which, int64_t* uniq_out, int32_t* count
                   void* hip_stream);
 
 /* Synchronises hip_stream and returns KGE_ERR_INDEX_RANGE if any call since the last check saw an id outside
- * its table (contexts created with validate_indices), else KGE_OK.  Rows with a bad id are skipped by the
- * kernels, never dereferenced. */
+ * its table (contexts created with validate_indices), else KGE_OK; the flag is cleared by the call that reports it.
+ * What the kernels do with such an id, validated or not: they clamp it into its table (an id below 0 becomes row 0,
+ * an id of num_entities / num_relations or more becomes the last row), so nothing outside the tables is ever read
+ * or written, and the call computes exactly what it would with the clamped ids: in a training step the clamped
+ * row is read, takes the bad position's gradient and is updated.  A caller that must not train on such a batch
+ * checks before it uses the tables again.  (No passage of the paper: input validation.) */
 int kge_check_indices(kge_ctx* ctx, void* hip_stream);
 
 /*
@@ -258,7 +265,8 @@ int kge_sample_steps(const kge_sampler* sampler, int64_t first_step, int64_t n_s
                      int64_t* t, int64_t* neg, int32_t* sides, void* stream);
 
 /* (host) Text of the last error on this context ("" if none); valid until the next call on the context.
- * kge_last_error(NULL) returns the text of the last failed kge_create on this thread. */
+ * kge_last_error(NULL) returns the text of the last failed context-free call (kge_create, kge_sample_steps,
+ * kge_rank_metrics, kge_score_noalloc) on this thread.  (Error reporting, no passage.) */
 const char* kge_last_error(const kge_ctx* ctx);
 
 /* Bytes of device workspace the context holds.  (No passage of the paper: library bookkeeping.) */

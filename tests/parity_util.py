@@ -12,7 +12,8 @@ includes cancellation inside one contribution, e.g. h + r - t) and rho * A the f
 lr * g / (sqrt(S + g^2) + eps) can differ by |U(g +- rho A) - U(g)|.  The per-step check therefore allows
         1e-4 * max(|x|, floor)  +  max |U(g +- rho A) - U(g)|,      rho = 2^-20 (16 fp32 roundoffs)
 per element, with g, A and S taken from the oracle.  For ordinarily conditioned elements the second term is
-far below the first; the tests report how many elements needed it.
+far below the first; the tests count how many elements needed it and assert that their share stays within twice
+what was measured for that family of tests (ALLOWANCE_SHARE), so that a kernel cannot lean on the allowance.
 """
 from __future__ import annotations
 
@@ -25,6 +26,15 @@ from harness import configs, graphs
 SCORE_TOL = 1e-5
 EMB_TOL = 1e-4
 RHO = 2.0 ** -20
+
+# Share of the compared elements whose error exceeds the plain 1e-4 bound, i.e. that pass only thanks to the
+# condition-measure allowance: twice the largest share measured on an MI355X in each family of tests.
+ALLOWANCE_SHARE = {
+    "default": 2e-4,          # measured <= 7.6e-5 (FB15k-sized DistMult / ComplEx); most tests have none at all
+    "ranking-transe_l1": 5e-2,  # measured 2.5e-2: sums of equal +-w terms cancel exactly in many elements, and one
+                                # pair on the other side of the kink then decides the element's sign
+    "ranking-complex": 3e-3,    # measured 1.3e-3
+}
 
 
 def rel_err(got: np.ndarray, want: np.ndarray, floor: float) -> float:
@@ -160,6 +170,11 @@ class Pair:
             # re-synchronise the touched rows so that the next step starts from identical tables
             devt[idx] = torch.from_numpy(host[ids]).cuda()
             devs[idx] = torch.from_numpy(host_s[ids]).cuda()
+
+    def assert_allowance_share(self, family="default"):
+        """At most max(4 elements, share) of everything compared so far needed the rounding allowance."""
+        limit = max(4, ALLOWANCE_SHARE[family] * self.stats["elements"])
+        assert self.stats["needed_allowance"] <= limit, (family, self.stats)
 
     def table_error_profile(self):
         """Distribution of the embedding error after free-running steps (no re-synchronisation)."""

@@ -1,5 +1,7 @@
-"""Parity at the size and in the launch configuration that bench.py times: the Freebase-scale TransE-L2 step with the
-full 86,054,151 x 400 entity table and its Adagrad state resident in HBM (256.5 GiB).
+"""Parity at the size and in the launch configuration that bench.py times, for every named configuration at its full
+entity count: the Freebase-scale TransE-L2 and ComplEx steps with the full 86,054,151 x 400 entity table and its
+Adagrad state resident in HBM (256.5 GiB), 'medium' (2.5 M entities, RotatE, in-batch degree negatives,
+self-adversarial weights) and 'large' (5 M entities, TransE-L2 with bf16 operands).
 
 The oracle cannot hold these tables, and does not need to: a step reads and writes only the rows its ids name.  For
 every checked step the rows of the distinct ids are copied from the device into a compact host table, the ids are
@@ -7,7 +9,8 @@ renumbered by their rank among the distinct ids (which keeps their order, so the
 runs), and the oracle performs the step on the compact table.  Every element of every touched row is then compared
 as in the small-size tests.  The rest of the table is covered by a property: rows outside the batch keep their bits.
 
-Launch configuration: bench.py drives kge_train_steps on a side stream, which replays HIP graphs of eight steps.  The
+Launch configuration: bench.py drives kge_train_steps on a side stream, which replays HIP graphs of 1, 2, 4 and 8
+steps.  The
 same steps are therefore run a second time through kge_train_steps from the same rows, and must reproduce the
 step-by-step result bit for bit.
 """
@@ -17,12 +20,12 @@ import torch
 
 import oracle
 from harness import configs, graphs
-from parity_util import EMB_TOL, SCORE_TOL, rounding_allowance
+from parity_util import ALLOWANCE_SHARE, EMB_TOL, SCORE_TOL, rounding_allowance
 
 pytestmark = pytest.mark.gpu
 
 N_CHECKED = 3   # steps checked one by one against the oracle
-N_REPLAY = 12   # steps run again through kge_train_steps (one replayed graph of eight steps + four single ones)
+N_REPLAY = 27   # steps run again through kge_train_steps (replayed graphs of 1, 2, 4, 8, 8, 4 steps)
 
 
 def _compact(ids_list):
@@ -35,10 +38,11 @@ def _rows(t: torch.Tensor, ids: np.ndarray) -> np.ndarray:
     return t[torch.from_numpy(ids).cuda()].cpu().numpy()
 
 
-def test_freebase_scale_step_with_the_full_table_resident():
+@pytest.mark.parametrize("w", [configs.FREEBASE_TRANSE, configs.FREEBASE_COMPLEX, configs.MEDIUM, configs.LARGE],
+                         ids=lambda w: w.name)
+def test_full_size_step_with_the_whole_table_resident(w):
     import paper_2004_08532_amd as kge
 
-    w = configs.FREEBASE_TRANSE
     dev = torch.device("cuda", 0)
     need = 2 * (w.n_entities * w.ent_dim + w.n_relations * w.rel_dim) * 4
     torch.cuda.empty_cache()  # give back what earlier tests left in the allocator's cache
@@ -46,6 +50,8 @@ def test_freebase_scale_step_with_the_full_table_resident():
     if need + (4 << 30) > free:
         pytest.skip(f"needs {need / 2**30:.1f} GiB of HBM, {free / 2**30:.1f} GiB free")
 
+    # positives straight from the generating distribution (an i.i.d. triple list sampled with replacement is the same
+    # thing), so that the 16 M / 20 M triples of 'medium' / 'large' need not be drawn on the host first
     bs = configs.BatchStream(w, materialise=False)
     n_steps = N_CHECKED + N_REPLAY
     h, r, t, neg, sides = bs.steps(0, n_steps)
@@ -53,7 +59,8 @@ def test_freebase_scale_step_with_the_full_table_resident():
     E, R = configs.init_tables(w, device=dev)
     SE, SR = torch.zeros_like(E), torch.zeros_like(R)
     ctx = kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
-                         max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks)
+                         max_neg_per_chunk=w.neg_per_chunk, max_chunks=w.n_chunks, gemm_input=int(w.bf16_inputs),
+                         adv_temperature=w.adv_temperature)
     floor = graphs.init_bound(w.gamma, w.ent_dim)
     loss = torch.zeros(1, dtype=torch.float32, device=dev)
     dh, dr, dt, dn = (torch.from_numpy(x).to(dev) for x in (h, r, t, neg))
@@ -78,20 +85,21 @@ def test_freebase_scale_step_with_the_full_table_resident():
             torch.cuda.synchronize()
             want_loss, rep = oracle.train_step(w.model, Ec, SEc, Rh, SRh, renum(h[s]), r[s], renum(t[s]),
                                                renum(neg[s]).reshape(w.n_chunks, -1), w.neg_per_chunk, w.chunk,
-                                               int(sides[s]), w.gamma, w.lr, report=True)
+                                               int(sides[s]), w.gamma, w.lr, report=True,
+                                               adv_temperature=w.adv_temperature, bf16_inputs=w.bf16_inputs)
             got_loss = float(loss.item())
             assert abs(got_loss - want_loss) <= SCORE_TOL * max(1.0, abs(want_loss)), (s, got_loss, want_loss)
             assert np.array_equal(rep["ent_ids"], np.arange(ent_ids.shape[0])) and np.array_equal(rep["rel_ids"], rel_ids)
             uniq, cnt = ctx.get_dedup(0, 2 * w.batch + neg.shape[1])
             ou, oc = oracle.dedup(np.concatenate([h[s], t[s], neg[s]]))
             assert np.array_equal(uniq.cpu().numpy(), ou) and np.array_equal(cnt.cpu().numpy().astype(np.int64), oc)
-            for name, ids, want, want_s, devt, devs, g, A in (
-                    ("E", ent_ids, Ec, SEc, E, SE, rep["dE"], rep["absE"]),
-                    ("R", rel_ids, Rh[rel_ids], SRh[rel_ids], R, SR, rep["dR"], rep["absR"])):
+            for name, ids, want, want_s, devt, devs, g, A, M in (
+                    ("E", ent_ids, Ec, SEc, E, SE, rep["dE"], rep["absE"], rep["maxE"]),
+                    ("R", rel_ids, Rh[rel_ids], SRh[rel_ids], R, SR, rep["dR"], rep["absR"], rep["maxR"])):
                 got = _rows(devt, ids).astype(np.float64)
                 got_s = _rows(devs, ids).astype(np.float64)
                 want, want_s = want.astype(np.float64), want_s.astype(np.float64)
-                du, ds = rounding_allowance(g, A, S_prev[name], w.lr, 1e-10)
+                du, ds = rounding_allowance(g, A, S_prev[name], w.lr, 1e-10, M if w.bf16_inputs else None)
                 base = EMB_TOL * np.maximum(np.abs(want), floor)
                 ratio = np.abs(got - want) / (base + du)
                 stats["elements"] += ratio.size
@@ -100,7 +108,8 @@ def test_freebase_scale_step_with_the_full_table_resident():
                 assert ratio.max() <= 1.0, (s, name, float(ratio.max()))
                 s_ratio = np.abs(got_s - want_s) / (1e-5 * want_s + ds + 1e-30)
                 assert s_ratio.max() <= 1.0, (s, name + " state", float(s_ratio.max()))
-        print("\n[parity] freebase-scale, full table", stats)
+        print("\n[parity]", w.name, "full table", stats)
+        assert stats["needed_allowance"] <= max(4, ALLOWANCE_SHARE["default"] * stats["elements"]), stats
 
         # ---- the launch configuration of the benchmark: kge_train_steps on a side stream (replayed graphs) must give
         # the bits of step-by-step calls.  Rows named by these steps are saved, the steps run one by one, the results
@@ -132,3 +141,5 @@ def test_freebase_scale_step_with_the_full_table_resident():
         assert float(SE[torch.from_numpy(probe).cuda()].abs().max()) == 0.0
     finally:
         ctx.close()
+        del E, SE, R, SR
+        torch.cuda.empty_cache()

@@ -34,9 +34,10 @@ def check_scores(p: Pair, h, r, t, neg, side):
     assert rel_err(ng, oneg, 1.0) <= SCORE_TOL
 
 
-def run_steps(p: Pair, bs: configs.BatchStream, n_steps, check_dedup_at=(0,), first=0):
+def run_steps(p: Pair, bs: configs.BatchStream, n_steps, check_dedup_at=(0,), first=0, family="default"):
     """Each step: scores, then one training step, both from tables identical on the two sides; every touched
-    element of tables and optimizer state is compared, then the device rows are re-synchronised."""
+    element of tables and optimizer state is compared, then the device rows are re-synchronised.  At the end the
+    share of elements that needed the rounding allowance is held to the family's limit."""
     for s in range(first, first + n_steps):
         h, r, t, neg, side = bs.step(s)
         check_scores(p, h, r, t, neg, side)
@@ -49,6 +50,7 @@ def run_steps(p: Pair, bs: configs.BatchStream, n_steps, check_dedup_at=(0,), fi
                 assert np.array_equal(uniq.cpu().numpy(), ou)
                 assert np.array_equal(cnt.cpu().numpy().astype(np.int64), oc)
     print("\n[parity]", p.w.name, p.stats)
+    p.assert_allowance_share(family)
 
 
 def free_run(p: Pair, bs: configs.BatchStream, n_steps):
@@ -62,16 +64,30 @@ def free_run(p: Pair, bs: configs.BatchStream, n_steps):
     return prof
 
 
-def assert_trajectory(prof, frac_allowed):
+# Share of table elements (entity table, relation table) that differ by more than 1e-4 (relative, with the
+# initialisation bound as floor) after 10 free-running steps from the same seed: twice what an MI355X run measured
+# (with a floor of 1e-5, i.e. a few hundred elements, where the measured share is a handful of elements).  The
+# shares are over the whole tables, untouched rows included.
+TRAJECTORY_OUTLIERS = {
+    "tiny": (1e-4, 1e-5),                  # measured 4.7e-5 / 0
+    "small-distmult": (1e-2, 5e-3),        # measured 4.7e-3 / 2.5e-3
+    "small-complex": (5.4e-2, 2.8e-2),     # measured 2.7e-2 / 1.4e-2
+    "medium": (2.6e-5, 1.3e-4),            # measured 1.3e-5 / 6.3e-5   (50,000 entities)
+    "freebase-transe_l2": (1e-5, 1e-5),    # measured 1.5e-6 / 6.7e-7   (200,003 entities)
+    "freebase-complex": (7.3e-5, 4.6e-4),  # measured 3.6e-5 / 2.3e-4   (200,003 entities)
+}
+
+
+def assert_trajectory(prof, name):
     """After free-running steps the bulk of the tables agrees far better than 1e-4 (median), and the share of
-    elements beyond 1e-4 stays below frac_allowed.  Those outliers are inherent to comparing an fp32 and an fp64
-    run of Adagrad at lr = 0.1: the first update of an element is lr * sign(g), so an element whose gradient is
-    below the fp32 rounding of its terms can move the other way, and later steps, whose size does not depend on
-    the size of g, pass such differences on to the rows that meet it.  The per-step tests above are the exact
-    element-wise check; this one shows that nothing systematic accumulates."""
-    for name in ("E", "R"):
-        assert prof[name]["median_nonzero"] <= 1e-5, prof
-        assert prof[name]["frac_over_tol"] <= frac_allowed, prof
+    elements beyond 1e-4 stays within twice the share measured for this configuration.  Those outliers are inherent
+    to comparing an fp32 and an fp64 run of Adagrad at lr = 0.1: the first update of an element is lr * sign(g), so
+    an element whose gradient is below the fp32 rounding of its terms can move the other way, and later steps, whose
+    size does not depend on the size of g, pass such differences on to the rows that meet it.  The per-step tests
+    above are the exact element-wise check; this one shows that nothing systematic accumulates."""
+    for table, limit in zip(("E", "R"), TRAJECTORY_OUTLIERS[name]):
+        assert prof[table]["median_nonzero"] <= 1e-5, prof
+        assert prof[table]["frac_over_tol"] <= limit, (name, table, prof)
 
 
 @pytest.mark.parametrize("alpha", [0.0, 1.0])
@@ -105,7 +121,7 @@ def test_pairwise_ranking_loss_every_model(kge, model, alpha):
         opos, oneg = oracle.scores(model, p.E, p.R, h, r, t, neg, w.neg_per_chunk, w.chunk, side, w.gamma)
         active = (w.gamma - opos[:, None] + oneg > 0).mean()
         assert 0.1 < active < 0.9, active  # the test means to exercise both branches
-        run_steps(p, bs, w.steps)
+        run_steps(p, bs, w.steps, family={"transe_l1": "ranking-transe_l1", "complex": "ranking-complex"}.get(model, "default"))
     finally:
         p.close()
 
@@ -208,8 +224,8 @@ def test_tiny_config_20_steps(kge):
         p.close()
     p = Pair(w, kge)
     try:
-        assert_trajectory(free_run(p, bs, 10), 1e-3)   # TransE-L2: 1e-4 holds for all but a few in 10^5 elements
-        assert_trajectory(free_run(p, bs, 10), 1e-3)
+        assert_trajectory(free_run(p, bs, 10), "tiny")   # TransE-L2: 1e-4 holds for all but a few in 10^5 elements
+        assert_trajectory(free_run(p, bs, 10), "tiny")
     finally:
         p.close()
 
@@ -225,7 +241,7 @@ def test_small_config_10_steps(kge, w):
         p.close()
     p = Pair(w, kge)
     try:
-        assert_trajectory(free_run(p, bs, 10), 0.05)  # bilinear scores near 0 at initialisation: chaotic sooner
+        assert_trajectory(free_run(p, bs, 10), w.name)  # bilinear scores near 0 at initialisation: chaotic sooner
     finally:
         p.close()
 
@@ -234,9 +250,15 @@ def test_medium_shape_reduced_entities(kge):
     """Configuration 'medium' (RotatE dim 200 complex, b 1024, g 128, k 256, in-batch degree negatives,
     self-adversarial temperature 1) with the entity count cut to 50,000 so the oracle's tables stay small."""
     w = configs.MEDIUM.scaled(n_entities=50_000, n_triples=400_000)
+    bs = configs.BatchStream(w)
     p = Pair(w, kge)
     try:
-        run_steps(p, configs.BatchStream(w), 3)
+        run_steps(p, bs, 3)
+    finally:
+        p.close()
+    p = Pair(w, kge)
+    try:
+        assert_trajectory(free_run(p, bs, 10), "medium")
     finally:
         p.close()
 
@@ -295,9 +317,15 @@ def test_freebase_batch_shape_reduced_entities(kge):
     entities; the full-size table is covered by test_gpu_fullsize.py."""
     for w0 in (configs.FREEBASE_TRANSE, configs.FREEBASE_COMPLEX):
         w = w0.scaled(n_entities=200_003, n_relations=14_824)
+        bs = configs.BatchStream(w)
         p = Pair(w, kge)
         try:
-            run_steps(p, configs.BatchStream(w), 3)
+            run_steps(p, bs, 3)
+        finally:
+            p.close()
+        p = Pair(w, kge)
+        try:
+            assert_trajectory(free_run(p, bs, 10), w0.name)
         finally:
             p.close()
 
@@ -406,6 +434,24 @@ def test_key_lists_of_medium_length_take_the_bucketed_ranking(kge, n_entities):
         p.close()
 
 
+def check_ranks(p: Pair, h, r, t, neg, side, got):
+    """A rank is an integer decided by comparing fp32 scores, so both sides take that decision in the kernels'
+    precision: (1) the library's fp32 scores of the same call agree with the oracle's to the score tolerance, (2) the
+    oracle's rank definition applied to those fp32 scores gives EVERY device rank exactly, and (3) against the
+    oracle's own fp64 scores a rank lies between the counts with the candidates inside the score tolerance of the
+    positive excluded and included, and is the oracle's rank where there are none."""
+    w = p.w
+    pos, ng, opos, oneg = p.score_both(h, r, t, neg, side)
+    assert rel_err(pos, opos, 1.0) <= SCORE_TOL and rel_err(ng, oneg, 1.0) <= SCORE_TOL
+    assert np.array_equal(got, oracle.ranks(pos, ng))
+    tol = SCORE_TOL * np.maximum(np.abs(opos), 1.0)[:, None]
+    lo = 1 + (oneg > opos[:, None] + tol).sum(axis=1)
+    hi = 1 + (oneg > opos[:, None] - tol).sum(axis=1)
+    assert np.all((got >= lo) & (got <= hi))
+    clear = lo == hi
+    assert np.array_equal(got[clear], oracle.ranks(opos, oneg)[clear])
+
+
 EVAL_SHAPES = {  # "wide": a thousand candidates per positive, two chunks, ragged tiles
     "narrow": dict(batch=180, chunk=60, neg_per_chunk=150),
     "wide": dict(batch=1000, chunk=500, neg_per_chunk=1030),
@@ -416,19 +462,21 @@ EVAL_SHAPES = {  # "wide": a thousand candidates per positive, two chunks, ragge
 @pytest.mark.parametrize("model", MODELS)
 def test_evaluation_ranks_and_metrics(kge, model, shape):
     """Link-prediction evaluation: the rank of every positive among sampled candidates (both sides), then
-    Hit@k / MR / MRR.  A rank is an integer decided by comparing fp32 scores; candidates whose oracle score lies
-    within the score tolerance of the positive's could fall on either side, so the rank must lie between the
-    counts with those candidates excluded and included, and equals the oracle's rank when there are none.  The
-    metrics kernel is checked exactly against the oracle's formulas on the device's own ranks."""
+    Hit@k / MR / MRR; see check_ranks for how an integer decided by fp32 comparisons is compared.  The metrics kernel
+    is checked exactly against the oracle's formulas on the device's own ranks."""
+    kw = dict(EVAL_SHAPES[shape])
     if shape == "wide" and model in ("rescal", "transr"):
-        pytest.skip("the oracle needs minutes for a million pairs of 72 x 72 matrices")
-    w = ragged(model, n_entities=2003, name="eval-" + model, **EVAL_SHAPES[shape])
+        # a million pairs of 72 x 72 matrices would take the oracle minutes: rows of 16 floats, 16 x 16 matrices
+        kw.update(ent_dim=16, rel_dim=16 * 16 + (16 if model == "transr" else 0))
+    w = ragged(model, n_entities=2003, name="eval-" + model, **kw)
     # tables eight times the initialisation range: scores of an untrained model at the usual range lie so close
     # together that most ranks would hinge on differences below the score tolerance
+    # (rows of 16 floats start from a range 4.5 times wider already: (gamma + 2) / dim)
     E, R = configs.init_tables(w)
-    E = E * 8.0
+    scale = 8.0 if w.ent_dim > 16 else 1.0
+    E = E * scale
     if model != "rotate":
-        R = R * 8.0
+        R = R * scale
     p = Pair(w, kge, E=E, R=R)
     try:
         bs = configs.BatchStream(w)
@@ -439,13 +487,10 @@ def test_evaluation_ranks_and_metrics(kge, model, shape):
                             w.gamma)
             torch.cuda.synchronize()
             got = dr.cpu().numpy().astype(np.int64)
+            check_ranks(p, h, r, t, neg, side, got)
             opos, oneg = oracle.scores(w.model, p.E, p.R, h, r, t, neg, w.neg_per_chunk, w.chunk, side, w.gamma)
             tol = SCORE_TOL * np.maximum(np.abs(opos), 1.0)[:, None]
-            lo = 1 + (oneg > opos[:, None] + tol).sum(axis=1)
-            hi = 1 + (oneg > opos[:, None] - tol).sum(axis=1)
-            assert np.all((got >= lo) & (got <= hi))
-            clear = lo == hi
-            assert np.array_equal(got[clear], oracle.ranks(opos, oneg)[clear])
+            clear = (1 + (oneg > opos[:, None] + tol).sum(axis=1)) == (1 + (oneg > opos[:, None] - tol).sum(axis=1))
             unambiguous += int(clear.sum())
             all_ranks.append(dr)
         # (with a thousand candidates per positive more ranks have a candidate within the tolerance of the positive)
@@ -519,6 +564,79 @@ def test_training_from_device_sampled_ids_equals_training_from_host_ids(kge):
             ctx.close()
     for a, b_ in zip(*tables):
         assert torch.equal(a, b_)
+
+
+@pytest.mark.parametrize("model", ["transe_l2", "complex", "rotate"])
+def test_evaluation_protocol_with_uniform_and_degree_proportional_candidates(kge, model):
+    """The paper's second evaluation protocol (Sec. 5): every test triple is ranked among candidates of which one half
+    is drawn uniformly and the other half in proportion to the entities' degrees, without filtering.  The candidate
+    sets come from kge_sample_steps (degree-proportional = the corrupted-side entities of the evaluation batch itself,
+    as in Sec. 3.3; ids bit-exact against the host sampler) and go through kge_rank, both sides."""
+    from harness import graphs, sampler
+    n_ent, b, k, seed = 5003, 500, 200, 77
+    w = ragged(model, n_entities=n_ent, name="eval2-" + model, batch=b, chunk=b, neg_per_chunk=k, side_mode="alternate")
+    E, R = configs.init_tables(w)
+    E = E * 8.0
+    if model != "rotate":
+        R = R * 8.0
+    p = Pair(w, kge, E=E, R=R)
+    try:
+        triples = graphs.TripleSource(n_ent, w.n_relations, 1.0, None).draw(20_000, np.random.default_rng(3))
+        n_steps = 2
+        h = torch.empty((n_steps, b), dtype=torch.int64, device="cuda")
+        r, t = torch.empty_like(h), torch.empty_like(h)
+        neg = torch.empty((n_steps, k), dtype=torch.int64, device="cuda")
+        sides = torch.empty(n_steps, dtype=torch.int32, device="cuda")
+        kge.kge_sample_steps(seed, dev(triples), n_ent, b, 1, k, k // 2, "alternate", 0, n_steps, h, r, t, neg, sides)
+        torch.cuda.synchronize()
+        for s in range(n_steps):
+            side = sampler.side_of_step("alternate", s)
+            pos = triples[sampler.batch_positions(seed, s, b, triples.shape[0])]
+            want_neg = sampler.mixed_negatives(seed, s, 1, k, k // 2, n_ent, pos[:, 0], pos[:, 2], side)
+            hs, rs, ts, ns = (x[s].cpu().numpy() for x in (h, r, t, neg))
+            assert np.array_equal(hs, pos[:, 0]) and np.array_equal(ts, pos[:, 2]) and np.array_equal(ns, want_neg.reshape(-1))
+            # the first half of the candidates are entities of the batch (its tails, or its heads on the head side)
+            assert np.isin(ns[:k // 2], pos[:, 2] if side == 0 else pos[:, 0]).all()
+            dr = p.ctx.rank(p.dE, p.dR, h[s], r[s], t[s], neg[s], k, b, side, w.gamma)
+            torch.cuda.synchronize()
+            check_ranks(p, hs, rs, ts, ns.reshape(1, k), side, dr.cpu().numpy().astype(np.int64))
+    finally:
+        p.close()
+
+
+def test_training_step_with_ids_outside_the_tables_clamps_and_reports(kge):
+    """A head id beyond the table, a negative relation id and a corrupting id beyond the table in one training step:
+    nothing outside the tables is touched, the step is the step of the ids clamped into their tables (bit for bit:
+    row N-1 or row 0 takes the place of the bad id), and kge_check_indices reports KGE_ERR_INDEX_RANGE once."""
+    w = ragged("transe_l2")
+    h, r, t, neg, side = configs.BatchStream(w).step(0)
+    bad_h, bad_r, bad_n = h.copy(), r.copy(), neg.copy()
+    bad_h[3] = w.n_entities + 5
+    bad_r[7] = -2
+    bad_n[1, 4] = 1 << 40
+    cl_h, cl_r, cl_n = bad_h.copy(), bad_r.copy(), bad_n.copy()
+    cl_h[3], cl_r[7], cl_n[1, 4] = w.n_entities - 1, 0, w.n_entities - 1
+    outs = []
+    for hh, rr, nn, validate in ((bad_h, bad_r, bad_n, True), (cl_h, cl_r, cl_n, True)):
+        p = Pair(w, kge, validate=validate)
+        try:
+            p.ctx.train_step(p.dE, p.dSE, p.dR, p.dSR, dev(hh), dev(rr), dev(t), dev(nn.reshape(-1)), w.neg_per_chunk,
+                             w.chunk, side, w.gamma, w.lr, loss_out=p.loss)
+            torch.cuda.synchronize()
+            if hh is bad_h:
+                with pytest.raises(kge.KgeError) as e:
+                    p.ctx.check_indices()
+                assert e.value.code == kge.KGE_ERR_INDEX_RANGE
+                p.ctx.check_indices()  # reported once
+            else:
+                p.ctx.check_indices()
+            uniq, cnt = p.ctx.get_dedup(0, 2 * w.batch + w.n_chunks * w.neg_per_chunk)
+            outs.append((p.dE.clone(), p.dSE.clone(), p.dR.clone(), p.dSR.clone(), p.loss.clone(), uniq, cnt))
+        finally:
+            p.close()
+    for a, b_ in zip(*outs):
+        assert torch.equal(a, b_)
+    assert torch.isfinite(outs[0][0]).all()
 
 
 # ------------------------------------------------------------------------------------------------------------
