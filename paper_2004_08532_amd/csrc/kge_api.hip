@@ -397,7 +397,11 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->step_block = (StepBlock*)(base + o_step);
     c->sides_dev = (int32_t*)(base + o_sides);
 
+    // hipMemset on device memory returns before the fill has run (it is queued on the null stream, behind whatever
+    // the caller has there), and the streams that callers pass are not ordered against the null stream: without the
+    // wait below the fill could land after the first call has written its step block into the workspace.
     bool ok = hipMemset(c->ws_base, 0, off) == hipSuccess;
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
     ok = ok && hipStreamCreateWithFlags(&c->side_stream, hipStreamNonBlocking) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) == hipSuccess;

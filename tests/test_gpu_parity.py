@@ -744,7 +744,9 @@ def test_train_steps_graph_replay_equals_step_by_step(kge, variant):
 
     def fresh():
         dE, dR = dev(E0), dev(R0)
-        return dE, torch.zeros_like(dE), dR, torch.zeros_like(dR)
+        out = dE, torch.zeros_like(dE), dR, torch.zeros_like(dR)
+        torch.cuda.synchronize()  # filled on the default stream, used on `stream`
+        return out
 
     def make_ctx():
         return kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=w.batch,
