@@ -8,8 +8,7 @@
 // corrupting rows of every chunk into staging (the O(bkd/g) rows of Sec. 3.3) and compute |n|^2 for TransE-L2.
 // In a training step the same launch carries extra blocks that bring the step's key lists into (id, position)
 // order for the duplicate reduction (rank_block below): that work needs only the ids, so it rides along here.
-#include "k_rank.h"
-#include "k_stage.h"
+#include "kge_common.h"
 
 namespace {
 
@@ -38,6 +37,176 @@ struct GatherArgs {
     uint64_t bucket_mul;     // long entity lists: bucket of an id = (id * bucket_mul) >> 32 (0: brute-force blocks)
     KeyList ent, rel;
 };
+
+// One block size for both kinds of block in a launch: THREADS = 256 for short key lists, 1024 for long ones.  The
+// rank blocks keep the whole key list in (dynamic) LDS, and every block of a launch is given the same amount; with
+// a long list the blocks are large, so that the LDS of a gather block is spread over 16 row-gathering waves and
+// does not limit how many of them a CU holds, and so that fewer blocks load the list.
+constexpr int RANK_LONG_LIST = 6144;  // keys from which on the 1024-thread blocks are used (measured: lists of 2,200 and 4,096 keys are 4-5 us faster with the small brute-force blocks)
+template <int THREADS> struct RankShape {
+    static constexpr int R = THREADS == 256 ? 1 : 2;     // keys ranked by one 32-thread group
+    static constexpr int ITEMS = (THREADS / 32) * R;     // keys ranked per block
+    static constexpr int LOADS = THREADS == 256 ? 16 : 4;  // key loads in flight per thread
+};
+
+// Orders a key list by brute-force ranking: rank(i) = #{j : key_j < key_i} + #{j < i : key_j == key_i}.  The lists
+// are a few thousand keys, so the n^2 comparisons, spread over n/8 (n/64) blocks that run beside the gather blocks of
+// the same launch, cost less than one pass of a single-workgroup sort, need no other kernel and no other stream,
+// and give exactly the order a stable sort by id would (equal ids in position order).  Every block holds the whole
+// list in LDS.  A group of 32 threads ranks RANK_R consecutive keys: each thread scans every 32nd 16-byte chunk of
+// the list and compares it with all RANK_R keys, so a chunk read from LDS serves 4 * RANK_R comparisons.  The tie
+// rule costs nothing away from the group's own keys: for entries before them "key_j <= key_i" counts, i.e.
+// key_j < key_i + 1, for entries after them key_j < key_i, so the scan is three loops over one comparison each.
+template <int THREADS>
+__device__ __forceinline__ void rank_block(const KeyList& l, int blk, uint32_t* keys) {
+    constexpr int RANK_R = RankShape<THREADS>::R, RANK_ITEMS = RankShape<THREADS>::ITEMS;
+    constexpr int RANK_LOADS = RankShape<THREADS>::LOADS, GATHER_THREADS = THREADS;
+    const int tid = threadIdx.x, n = l.n;
+    const int n4 = (n + 3) & ~3;  // the tail is padded with 0xffffffff, which is larger than any id
+    // independent loads are issued before the first is used: one round of memory latency per 4096 keys
+    const KeySources ks = key_sources(l);
+    for (int base = 0; base < n4; base += RANK_LOADS * GATHER_THREADS) {
+        int64_t raw[RANK_LOADS];
+#pragma unroll
+        for (int u = 0; u < RANK_LOADS; ++u) {
+            const int i = base + u * GATHER_THREADS + tid;
+            raw[u] = *key_address(l, ks, i < n ? i : 0);  // unconditional: all loads go out together
+        }
+#pragma unroll
+        for (int u = 0; u < RANK_LOADS; ++u) {
+            const int i = base + u * GATHER_THREADS + tid;
+            if (i < n4) keys[i] = i < n ? clamp_key(l, raw[u]) : 0xffffffffu;
+        }
+    }
+    __syncthreads();
+    const int it0 = blk * RANK_ITEMS + (tid >> 5) * RANK_R, t = tid & 31;
+    if (it0 >= n) return;
+    uint32_t ki[RANK_R];
+    int cnt[RANK_R];
+#pragma unroll
+    for (int r = 0; r < RANK_R; ++r) {
+        ki[r] = keys[it0 + r < n4 ? it0 + r : n4 - 1];  // ids are below 2^31, so ki + 1 does not wrap for real keys
+        cnt[r] = 0;
+    }
+    int j = 4 * t;
+    // entries wholly before the group's keys: key_j <= key_i
+#pragma unroll 2
+    for (; j + 3 < it0; j += 128) {
+        const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
+#pragma unroll
+        for (int r = 0; r < RANK_R; ++r) {
+            const uint32_t thr = ki[r] + 1u;
+            cnt[r] += (kj.x < thr) + (kj.y < thr) + (kj.z < thr) + (kj.w < thr);
+        }
+    }
+    // the chunk(s) that hold the group's own keys: the full rule
+    for (; j < it0 + RANK_R && j < n4; j += 128) {
+        const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
+        const uint32_t kv[4] = {kj.x, kj.y, kj.z, kj.w};
+#pragma unroll
+        for (int r = 0; r < RANK_R; ++r) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) cnt[r] += (kv[e] < ki[r] || (kv[e] == ki[r] && j + e < it0 + r)) ? 1 : 0;
+        }
+    }
+    // entries after them: key_j < key_i
+#pragma unroll 2
+    for (; j < n4; j += 128) {
+        const uint4 kj = *reinterpret_cast<const uint4*>(keys + j);
+#pragma unroll
+        for (int r = 0; r < RANK_R; ++r) cnt[r] += (kj.x < ki[r]) + (kj.y < ki[r]) + (kj.z < ki[r]) + (kj.w < ki[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < RANK_R; ++r) {
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) cnt[r] += __shfl_xor(cnt[r], o, 32);
+        if (t == 0 && it0 + r < n) {
+            l.key[0][cnt[r]] = ki[r];
+            l.pos[0][cnt[r]] = (uint32_t)(it0 + r);
+        }
+    }
+}
+
+// Long lists (RANK_LONG_LIST keys and more): brute force would compare every key with every other (1.5e8 comparisons
+// for 12,288 keys, which set the duration of the whole launch).  Here a block of 1024 threads ranks 1024 keys with
+// work linear in the list.  The id range [0, n_ids) is cut into RANK_BUCKETS equal slices, so buckets are ordered
+// like the ids they hold.  Every block (1) counts the keys per bucket with LDS atomics, (2) turns the counts into
+// offsets, (3) drops one word per key into its bucket's stretch of LDS, in whatever order the atomics hand out:
+// (id - first id of the bucket) << 14 | position, so that the words of a bucket compare like (id, position) pairs,
+// and (4) ranks its own 1024 keys: offset of the key's bucket + the number of smaller words in that bucket.  The
+// result does not depend on the order inside the buckets.  Needs positions below 2^14 (lists end at 14,336 keys) and
+// buckets narrower than 2^18 ids (tables of up to 134 M rows; larger ones keep the brute-force blocks).
+constexpr int RANK_BUCKETS = 512;
+constexpr int RANK_POS_BITS = 14;
+__host__ __device__ constexpr size_t bucketed_lds_words(int n) { return (size_t)n + 3 * RANK_BUCKETS + 16; }
+inline bool bucketed_ranking_fits(int64_t n_ids) { return n_ids / RANK_BUCKETS + 2 < (1 << (32 - RANK_POS_BITS)); }
+
+__device__ __forceinline__ void rank_block_bucketed(const KeyList& l, int blk, uint64_t bucket_mul, uint32_t* lds) {
+    constexpr int T = 1024, MAXK = KGE_RANK_MAX_KEYS / T;  // keys per thread: position u * T + tid
+    const int tid = threadIdx.x, n = l.n;
+    uint32_t* word = lds;                               // [n] one word per key, bucket after bucket
+    int* cnt = reinterpret_cast<int*>(lds + n);         // [RANK_BUCKETS]
+    int* off = cnt + RANK_BUCKETS;                      // [RANK_BUCKETS] exclusive prefix of cnt
+    uint32_t* first = reinterpret_cast<uint32_t*>(off + RANK_BUCKETS);  // [RANK_BUCKETS] smallest id of the bucket
+    int* wave_tot = reinterpret_cast<int*>(first + RANK_BUCKETS);       // [8]
+    if (tid < RANK_BUCKETS) {
+        cnt[tid] = 0;
+        // bucket(id) = (id * bucket_mul) >> 32 >= tid  <=>  id >= ceil((tid << 32) / bucket_mul)
+        first[tid] = (uint32_t)((((uint64_t)tid << 32) + bucket_mul - 1) / bucket_mul);
+    }
+    const KeySources ks = key_sources(l);
+    int64_t raw[MAXK];
+#pragma unroll
+    for (int u = 0; u < MAXK; ++u) {
+        const int p = u * T + tid;
+        raw[u] = *key_address(l, ks, p < n ? p : 0);
+    }
+    __syncthreads();
+    uint32_t key[MAXK];
+    int bucket[MAXK], slot[MAXK];
+#pragma unroll
+    for (int u = 0; u < MAXK; ++u) {
+        key[u] = clamp_key(l, raw[u]);
+        bucket[u] = (int)(((uint64_t)key[u] * bucket_mul) >> 32);
+        slot[u] = u * T + tid < n ? atomicAdd(&cnt[bucket[u]], 1) : 0;
+    }
+    __syncthreads();
+    if (tid < RANK_BUCKETS) {  // exclusive prefix over the bucket counts: scan inside the 8 waves, then across them
+        const int c = cnt[tid];
+        int inc = c;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(inc, o, 64);
+            if ((tid & 63) >= o) inc += v;
+        }
+        if ((tid & 63) == 63) wave_tot[tid >> 6] = inc;
+        off[tid] = inc - c;
+    }
+    __syncthreads();
+    if (tid < RANK_BUCKETS) {
+        int before = 0;
+        for (int w = 0; w < (tid >> 6); ++w) before += wave_tot[w];
+        off[tid] += before;
+    }
+    __syncthreads();
+    uint32_t mine_word = 0;
+    int mine_bucket = 0;
+#pragma unroll
+    for (int u = 0; u < MAXK; ++u) {
+        const uint32_t wd = ((key[u] - first[bucket[u]]) << RANK_POS_BITS) | (uint32_t)(u * T + tid);
+        if (u * T + tid < n) word[off[bucket[u]] + slot[u]] = wd;
+        if (u == blk) { mine_word = wd; mine_bucket = bucket[u]; }  // this block ranks positions blk * T + tid
+    }
+    __syncthreads();
+    const int mine = blk * T + tid;
+    if (mine >= n) return;
+    const int lo = off[mine_bucket], hi = lo + cnt[mine_bucket];
+    int before = lo;
+#pragma unroll 4
+    for (int j = lo; j < hi; ++j) before += word[j] < mine_word ? 1 : 0;
+    l.key[0][before] = (mine_word >> RANK_POS_BITS) + first[mine_bucket];
+    l.pos[0][before] = (uint32_t)mine;
+}
 
 __device__ __forceinline__ int64_t clamp_id(int64_t id, int64_t n) { return id < 0 ? 0 : (id >= n ? n - 1 : id); }
 
@@ -282,72 +451,7 @@ void launch_model(kge_ctx* c, GatherArgs& a, int nv, int rows, bool with_keys, c
     }
 }
 
-// ---- staged-rows path: the rank blocks and one wave per row of the step's row list, copying it as it is
-struct StageLaunch {
-    StageArgs s;
-    StepIds ids;
-    int rank_blocks, ent_rank_blocks;
-    uint64_t bucket_mul;
-    KeyList ent, rel;
-};
-
-template <int THREADS>
-__global__ __launch_bounds__(THREADS) void k_stage(StageLaunch a) {
-    extern __shared__ uint32_t rank_keys[];
-    if ((int)blockIdx.x < a.rank_blocks) {
-        const int rb = blockIdx.x;
-        if (rb < a.ent_rank_blocks) {
-            if (THREADS == 1024 && a.bucket_mul != 0) rank_block_bucketed(a.ent, rb, a.bucket_mul, rank_keys);
-            else rank_block<THREADS>(a.ent, rb, rank_keys);
-        } else {
-            rank_block<THREADS>(a.rel, rb - a.ent_rank_blocks, rank_keys);
-        }
-        return;
-    }
-    const int p = (blockIdx.x - a.rank_blocks) * (THREADS / 64) + (threadIdx.x >> 6);
-    stage_row(a.s, step_view(a.ids), p, threadIdx.x & 63, nullptr, 0, nullptr, 0);
-}
-
-template <int THREADS>
-void launch_stage(kge_ctx* c, StageLaunch& a, const StepIds& ids, hipStream_t st) {
-    constexpr int ITEMS = RankShape<THREADS>::ITEMS;
-    kge_make_key_lists(c, ids, &a.ent, &a.rel);
-    a.bucket_mul = 0;
-    size_t lds;
-    if (THREADS == 1024 && bucketed_ranking_fits(a.ent.n_ids)) {
-        a.ent_rank_blocks = (a.ent.n + 1023) / 1024;
-        a.bucket_mul = ((uint64_t)RANK_BUCKETS << 32) / (uint64_t)a.ent.n_ids;
-        lds = sizeof(uint32_t) * bucketed_lds_words(a.ent.n);
-        const size_t rel_lds = sizeof(uint32_t) * (size_t)((a.rel.n + 3) & ~3);
-        if (rel_lds > lds) lds = rel_lds;
-    } else {
-        a.ent_rank_blocks = (a.ent.n + ITEMS - 1) / ITEMS;
-        lds = sizeof(uint32_t) * (size_t)((a.ent.n + 3) & ~3);
-    }
-    a.rank_blocks = a.ent_rank_blocks + (a.rel.n + ITEMS - 1) / ITEMS;
-    c->ebuf = 0;
-    c->rbuf = 0;
-    const int rows = 3 * ids.b + ids.n_neg;
-    const dim3 grid(a.rank_blocks + (rows + THREADS / 64 - 1) / (THREADS / 64));
-    KGE_LAUNCH(c, k_stage<THREADS>, grid, dim3(THREADS), lds, st, a);
-}
-
 }  // namespace
-
-void kge_fill_stage_args(const kge_ctx* c, const float* E, const float* R, const StepIds& ids, void* out) {
-    StageArgs& s = *static_cast<StageArgs*>(out);
-    s.E = E; s.R = R; s.Hs = c->Hs; s.Rs = c->Rs; s.Ts = c->Ts; s.Nst = c->Nst;
-    s.b = ids.b; s.n_neg = ids.n_neg; s.D = c->cfg.ent_dim; s.Dr = c->cfg.rel_dim;
-    s.n_ent = c->cfg.num_entities; s.n_rel = c->cfg.num_relations;
-}
-
-void kge_launch_stage(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st) {
-    StageLaunch a;
-    kge_fill_stage_args(c, E, R, ids, &a.s);
-    a.ids = ids;
-    if (2 * ids.b + ids.n_neg >= RANK_LONG_LIST) launch_stage<1024>(c, a, ids, st);
-    else launch_stage<256>(c, a, ids, st);
-}
 
 void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds& ids, float gamma, float* pos_out,
                        bool with_keys, hipStream_t st) {

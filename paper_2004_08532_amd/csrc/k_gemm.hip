@@ -58,11 +58,12 @@ struct BlockLoader {
         K = K_;
         p0_safe = base;
         if (KC) {
-            // the lane's four rows lie 8 rows apart: one pointer (kept in p[0]) and a stride instead of four pointers;
-            // a row outside the matrix is read from row 0, which is always there
 #pragma unroll
-            for (int it = 0; it < 4; ++it) ok[it] = r0 + major0 + 8 * it < rows;
-            p[0] = base + (int64_t)(r0 + major0) * ld;
+            for (int it = 0; it < 4; ++it) {
+                const int gr = r0 + major0 + 8 * it;
+                ok[it] = gr < rows;
+                p[it] = base + (int64_t)(ok[it] ? gr : 0) * ld;  // start of the row: always readable
+            }
             any = true; m1 = m2 = m3 = true;
         } else {
             init_rows_at(base, r0 + minor, rows);
@@ -84,7 +85,7 @@ struct BlockLoader {
             const int gk = k0 + minor;
             const int koff = gk < K ? gk : 0;  // the first 16 bytes of a row are always there
 #pragma unroll
-            for (int it = 0; it < 4; ++it) reg[it] = ld4((ok[it] ? p[0] + (int64_t)(8 * it) * ld : p0_safe) + shift + koff);
+            for (int it = 0; it < 4; ++it) reg[it] = ld4(p[it] + shift + koff);
         } else {
 #pragma unroll
             for (int it = 0; it < 4; ++it)
@@ -135,13 +136,7 @@ __device__ __forceinline__ void lds_frag(const float* region, int lane, int q, f
 }
 
 // One 32x32 output tile: K loop, cross-wave sum, epilogue.
-// FUSE (forward only, staged-rows path): the A operand does not exist in memory; block by block it is formed from the
-// staged rows of the kept entity and the relation, o = a + r / a - r (FUSE_TRANSE, tail / head corrupted) or
-// o = a * r (FUSE_DISTMULT).  The sums of squares that the TransE-L2 epilogue needs (|o_i|^2, |n_j|^2) are taken
-// from the blocks as they pass.  The positives' part of the step (o_i written out for the backward launch, f+_i, its
-// loss term and dL/df+_i) is done by extra workgroups of the same launch, one wave per positive (positive_rows).
-enum { FUSE_NONE = 0, FUSE_TRANSE = 1, FUSE_DISTMULT = 2 };
-template <int NW, bool A_KC, bool B_KC, int EPI, bool IS_DO, int IND = IND_NONE, int FUSE = FUSE_NONE>
+template <int NW, bool A_KC, bool B_KC, int EPI, bool IS_DO, int IND = IND_NONE>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*lds)[2][REGION]) {
     constexpr bool CHAIN = EPI == EPI_CHAIN_L2 || EPI == EPI_CHAIN_DM || EPI == EPI_CHAIN_CX;
     constexpr bool CX = EPI == EPI_CHAIN_CX;
@@ -161,15 +156,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     if (IND == IND_CHUNK_SUM) B = g.B + g.b_off;  // relation 0's matrix; a block is shifted to its positive's relation
     float* As = lds[w][0];
     float* Bs = lds[w][1];
-    int64_t shift_r = 0;  // FUSE: floats from the kept entity's staged rows to the relation's
-    bool fuse_minus = false;
-    if (FUSE != FUSE_NONE) {
-        const bool head = step_view(g.ids).side == KGE_NEG_HEAD;
-        const float* kept = head ? g.Ts : g.Hs;
-        A = kept + c * g.sA;
-        shift_r = g.Rs - kept;
-        fuse_minus = head;
-    }
     // ComplEx chain rule: the real and the imaginary part of a coordinate have to meet in one tile, so the tile's
     // 32 columns are 16 consecutive real parts (columns c0 .. of the [re | im] rows) and the 16 imaginary parts
     // that belong to them (columns N/2 + c0 ..); the tile index along N counts groups of 16 coordinates.
@@ -190,22 +176,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             const bool in = gm < g.M && col_in(e & 31);
             const int i = c * g.M + (in ? gm : 0);  // index of the positive in the mini-batch
             const int d = in ? col_of(e & 31) : 0;
-            e_o[it] = g.X[(int64_t)i * g.ldx + d];
-            e_cp[it] = g.cpos[i];
-            e_a[it] = 0.f; e_r[it] = 0.f; e_inv[it] = 0.f;
-            if (g.staged) {  // the rows as they were staged for this step (no ids, no table)
-                e_c[it] = (e_head ? g.Hs : g.Ts)[(int64_t)i * g.D + d];
-                if (EPI == EPI_CHAIN_DM || CX) {
-                    e_a[it] = (e_head ? g.Ts : g.Hs)[(int64_t)i * g.D + d];
-                    e_r[it] = g.Rs[(int64_t)i * g.D + d];
-                } else {
-                    e_inv[it] = g.inv_dpos[i];
-                }
-                continue;
-            }
             const int64_t hid = clamp_id(sv.h[i], g.n_ent), tid = clamp_id(sv.t[i], g.n_ent);
             const int64_t aid = e_head ? tid : hid, cid = e_head ? hid : tid;
+            e_o[it] = g.X[(int64_t)i * g.ldx + d];
             e_c[it] = g.E[cid * g.D + d];
+            e_cp[it] = g.cpos[i];
+            e_a[it] = 0.f; e_r[it] = 0.f; e_inv[it] = 0.f;
             if (EPI == EPI_CHAIN_DM || CX) {
                 const int64_t rid = clamp_id(sv.r[i], g.n_rel);
                 e_a[it] = g.E[aid * g.D + d];
@@ -246,26 +222,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     };
     int kb = w, kl = 0, kl_n = 0;
     int64_t sa = 0, sb = 0, sa_n = 0, sb_n = 0;
-    float4 rr[4];  // FUSE: the relation rows' block
-    float so = 0.f, sn = 0.f;  // FUSE: sums of squares of row / column lane % 32 over this lane's half of the K values
     if (kb < nblk) {
         place(kb, kl, sa, sb);
         la.issue(kl, ra, sa);
-        if (FUSE != FUSE_NONE) la.issue(kl, rr, shift_r);
         lb.issue(kl, rb, sb);
         if (kb + NW < nblk) place(kb + NW, kl_n, sa_n, sb_n);
     }
     while (kb < nblk) {
-        if (FUSE != FUSE_NONE) {
-            // o from the staged rows; the loader's lane holds 4 consecutive K values of rows lane/8 + 8 it
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const float4 a4 = ra[it], r4 = rr[it];
-                if (FUSE == FUSE_DISTMULT) ra[it] = make_float4(a4.x * r4.x, a4.y * r4.y, a4.z * r4.z, a4.w * r4.w);
-                else if (fuse_minus) ra[it] = make_float4(a4.x - r4.x, a4.y - r4.y, a4.z - r4.z, a4.w - r4.w);
-                else ra[it] = make_float4(a4.x + r4.x, a4.y + r4.y, a4.z + r4.z, a4.w + r4.w);
-            }
-        }
         la.mask(kl, ra);
         lb.mask(kl, rb);
         lds_store<A_KC>(As, lane, ra);
@@ -273,7 +236,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         const int nxt = kb + NW;
         if (nxt < nblk) {  // next block's global loads fly while this block is multiplied
             la.issue(kl_n, ra, sa_n);
-            if (FUSE != FUSE_NONE) la.issue(kl_n, rr, shift_r);
             lb.issue(kl_n, rb, sb_n);
             kl = kl_n;
             if (nxt + NW < nblk) place(nxt + NW, kl_n, sa_n, sb_n);
@@ -290,7 +252,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
             for (int t = 0; t < 4; ++t) {
                 acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[t], fb[t], acc, 0, 0, 0);
                 if (WANT_ASUM) a_sum += fa[t];
-                if (FUSE != FUSE_NONE) { so = fmaf(fa[t], fa[t], so); sn = fmaf(fb[t], fb[t], sn); }
             }
         }
         __builtin_amdgcn_wave_barrier();
@@ -307,13 +268,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     if (WANT_ASUM) {
         a_sum += __shfl_xor(a_sum, 32, 64);
         if (lane < 32) Bs[lane] = a_sum;
-    }
-    if (FUSE != FUSE_NONE) {
-        // this wave's sums of squares, one word per row / column in the wave's B region ([0, 32) |o|^2, [32, 64)
-        // |n|^2); a wave without a K block leaves zeros
-        so += __shfl_xor(so, 32, 64);
-        sn += __shfl_xor(sn, 32, 64);
-        if (lane < 32) { Bs[lane] = so; Bs[32 + lane] = sn; }
     }
     __syncthreads();
     float* C = g.C + c * g.sC;
@@ -353,16 +307,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
         if (EPI == EPI_PLAIN) {
             C[(int64_t)gm * g.ldc + gn] = (IS_FWD && g.out_mode == OUT_W) ? w_and_loss<true>(s, g.wk, loss) : s;
         } else if (EPI == EPI_L2_FWD) {
-            float rown, coln;
-            if (FUSE != FUSE_NONE) {
-                rown = 0.f; coln = 0.f;
-#pragma unroll
-                for (int ww = 0; ww < NW; ++ww) { rown += lds[ww][1][i]; coln += lds[ww][1][32 + j]; }
-            } else {
-                rown = g.rowv[c * g.s_rowv + gm];
-                coln = g.colv[c * g.s_colv + gn];
-            }
-            const float d2 = rown + coln - 2.f * s;
+            const float d2 = g.rowv[c * g.s_rowv + gm] + g.colv[c * g.s_colv + gn] - 2.f * s;
             const float d = sqrtf(fmaxf(d2, 0.f));
             float out = g.out_mode == OUT_DIST ? d : g.gamma - d;
             if (g.out_mode == OUT_W) {  // W = w sigmoid(f) / |o - n|, 0 where the distance is 0
@@ -420,68 +365,12 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, int tile, float (*l
     }
 }
 
-// Staged-rows path, the positives (Table 1; Sec. 2 for the loss): one wave per positive i reads its three staged rows,
-// writes o_i = phi(a_i, r_i) for the backward launch, f+_i = gamma - |o_i - c_i| (TransE-L2) or o_i . c_i (DistMult),
-// softplus(-f+_i) / b and dL/df+_i = -sigmoid(-f+_i) / b.
-template <int FUSE>
-__device__ __forceinline__ void positive_rows(const GemmArgs& g, int i, int lane) {
-    if (i >= g.b) return;
-    const bool head = step_view(g.ids).side == KGE_NEG_HEAD;
-    const int D = g.D, n4 = D / 4;
-    const float* pa = (head ? g.Ts : g.Hs) + (int64_t)i * D;
-    const float* pc = (head ? g.Hs : g.Ts) + (int64_t)i * D;
-    const float* pr = g.Rs + (int64_t)i * D;
-    float4 A4[4], R4[4], C4[4];  // rows are at most 1024 floats: every piece is asked for before the first is used
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int v = lane + it * 64 < n4 ? lane + it * 64 : 0;
-        A4[it] = ld4(pa + 4 * v); R4[it] = ld4(pr + 4 * v); C4[it] = ld4(pc + 4 * v);
-    }
-    float acc = 0.f;
-#pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int v = lane + it * 64;
-        if (v >= n4) continue;
-        const float av[4] = {A4[it].x, A4[it].y, A4[it].z, A4[it].w}, rv[4] = {R4[it].x, R4[it].y, R4[it].z, R4[it].w};
-        const float cv[4] = {C4[it].x, C4[it].y, C4[it].z, C4[it].w};
-        float ov[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (FUSE == FUSE_DISTMULT) ov[e] = av[e] * rv[e];
-            else ov[e] = head ? av[e] - rv[e] : av[e] + rv[e];
-            if (FUSE == FUSE_DISTMULT) acc += ov[e] * cv[e];
-            else { const float u = ov[e] - cv[e]; acc += u * u; }
-        }
-        st4(g.O_out + (int64_t)i * D + 4 * v, make_float4(ov[0], ov[1], ov[2], ov[3]));
-    }
-    acc = wave_sum(acc);
-    if (lane == 0) {
-        const float f = FUSE == FUSE_DISTMULT ? acc : g.gamma - __builtin_amdgcn_sqrtf(acc);
-        g.fpos_out[i] = f;
-        if (FUSE == FUSE_TRANSE) g.inv_dpos_out[i] = acc > 0.f ? __builtin_amdgcn_rsqf(acc) : 0.f;
-        // softplus(-f) / b and its derivative -sigmoid(-f) / b from one hardware exponential, like the negatives' W
-        const float invb = 1.f / (float)g.b;
-        float sp = 0.f;
-        const float sg = w_and_loss<true>(-f, invb, sp);
-        g.row_loss_out[i] = sp * invb;
-        g.cpos_out[i] = -sg;
-    }
-}
-
-// pos_wgs (FUSE only; a multiple of 8, so that a tile's XCD stays blockIdx.x % 8): workgroups at the front of the
-// grid that take the positives, pos_per_wave of them per wave
-template <int NW, int EPI, int FUSE = FUSE_NONE>
-__global__ __launch_bounds__(NW * 64) void k_gemm_fwd(GemmArgs g, int pos_wgs, int pos_per_wave) {
+template <int NW, int EPI>
+__global__ __launch_bounds__(NW * 64) void k_gemm_fwd(GemmArgs g) {
     __shared__ __attribute__((aligned(16))) float lds[NW][2][REGION];
-    if (FUSE != FUSE_NONE && (int)blockIdx.x < pos_wgs) {
-        const int wave = blockIdx.x * NW + (threadIdx.x >> 6);
-        for (int u = 0; u < pos_per_wave; ++u) positive_rows<FUSE>(g, wave * pos_per_wave + u, threadIdx.x & 63);
-        return;
-    }
-    const int bx = blockIdx.x - pos_wgs;
-    const int tile = (bx & 7) * ((gridDim.x - pos_wgs) >> 3) + (bx >> 3);  // see xcd_tile
+    const int tile = xcd_tile(blockIdx.x >> 3, gridDim.x >> 3);
     if (tile >= g.tiles) return;
-    gemm_tile<NW, true, true, EPI, false, IND_NONE, FUSE>(g, tile, lds);
+    gemm_tile<NW, true, true, EPI, false>(g, tile, lds);
 }
 
 // The tiles with the longer K loop first (dN: K is the chunk size; dO: K is the number of corrupting rows per chunk),
@@ -528,26 +417,14 @@ void set_tiling(GemmArgs& g, int chunks, bool coordinate_tiles = false) {
     g.tiles = g.gx * g.gy * chunks;
 }
 
-template <int EPI, int FUSE = FUSE_NONE>
+template <int EPI>
 void launch_fwd(kge_ctx* c, GemmArgs g, int chunks, hipStream_t st) {
     set_tiling(g, chunks);
+    const dim3 grid(8 * ((g.tiles + 7) / 8));
     const int nw = pick_nw(g.tiles, (g.K + TILE - 1) / TILE, 16);
-    const int tile_wgs = 8 * ((g.tiles + 7) / 8);
-    int pos_wgs = 0, pos_per_wave = 0;
-    if (FUSE != FUSE_NONE) {
-        // the positives: as many workgroups as the CUs that the tiles leave free (a 16-wave workgroup takes a CU's
-        // staging memory for itself), at least enough for eight positives per wave
-        const int free_cus = nw == 16 ? 256 - tile_wgs : 0;
-        pos_wgs = free_cus >= 8 ? free_cus & ~7 : 8;
-        const int cap = ((g.b + nw - 1) / nw + 7) & ~7;  // one positive per wave
-        if (pos_wgs > cap) pos_wgs = cap;
-        if (pos_wgs * nw * 8 < g.b) pos_wgs = ((g.b + nw * 8 - 1) / (nw * 8) + 7) & ~7;
-        pos_per_wave = (g.b + pos_wgs * nw - 1) / (pos_wgs * nw);
-    }
-    const dim3 grid(pos_wgs + tile_wgs);
-    if (nw == 4) KGE_LAUNCH(c, (k_gemm_fwd<4, EPI, FUSE>), grid, dim3(256), 0, st, g, pos_wgs, pos_per_wave);
-    else if (nw == 8) KGE_LAUNCH(c, (k_gemm_fwd<8, EPI, FUSE>), grid, dim3(512), 0, st, g, pos_wgs, pos_per_wave);
-    else KGE_LAUNCH(c, (k_gemm_fwd<16, EPI, FUSE>), grid, dim3(1024), 0, st, g, pos_wgs, pos_per_wave);
+    if (nw == 4) KGE_LAUNCH(c, (k_gemm_fwd<4, EPI>), grid, dim3(256), 0, st, g);
+    else if (nw == 8) KGE_LAUNCH(c, (k_gemm_fwd<8, EPI>), grid, dim3(512), 0, st, g);
+    else KGE_LAUNCH(c, (k_gemm_fwd<16, EPI>), grid, dim3(1024), 0, st, g);
 }
 
 template <bool A_KC, bool B_KC, int IND>
@@ -611,24 +488,6 @@ void kge_gemm_neg_score(kge_ctx* c, int b, int k, int gsz, float gamma, float* o
     else launch_fwd<EPI_PLAIN>(c, g, chunks, st);
 }
 
-// The forward launch of the staged-rows path (training, uniform weights): o formed from the staged rows, W and the
-// loss sums left behind as with out_mode 2, the positives done by the first tile column.
-void kge_gemm_neg_score_staged(kge_ctx* c, const StepIds& ids, int k, int gsz, float gamma, hipStream_t st) {
-    const int D = c->cfg.ent_dim, b = ids.b;
-    GemmArgs g = {};
-    g.A = c->Hs; g.B = c->Nst; g.C = c->S;
-    g.M = gsz; g.N = k; g.K = D;
-    g.lda = D; g.ldb = D; g.ldc = c->ld_s;
-    g.sA = (int64_t)gsz * D; g.sB = (int64_t)k * D; g.sC = (int64_t)gsz * c->ld_s;
-    g.gamma = gamma; g.out_mode = OUT_W;
-    g.wk = 1.f / ((float)k * (float)b); g.neg_loss_part = c->neg_loss_part;
-    g.ids = ids; g.b = b; g.D = D;
-    g.Hs = c->Hs; g.Rs = c->Rs; g.Ts = c->Ts;
-    g.O_out = c->O; g.fpos_out = c->fpos; g.cpos_out = c->cpos; g.inv_dpos_out = c->inv_dpos; g.row_loss_out = c->row_loss;
-    if (c->cfg.model == KGE_TRANSE_L2) launch_fwd<EPI_L2_FWD, FUSE_TRANSE>(c, g, b / gsz, st);
-    else launch_fwd<EPI_PLAIN, FUSE_DISTMULT>(c, g, b / gsz, st);
-}
-
 // Evaluation: can the forward launch count the ranks itself (out_mode 3) instead of storing the scores?
 bool kge_gemm_forward_can_rank(const kge_ctx* c) { return c->cfg.gemm_input == 0; }
 
@@ -663,8 +522,6 @@ void kge_gemm_neg_backward(kge_ctx* c, const float* E, const float* R, const Ste
     g.gamma = gamma;
     g.ids = ids; g.E = E; g.R = R; g.cpos = c->cpos; g.inv_dpos = c->inv_dpos; g.Gent = c->Gent; g.Grel = c->Grel;
     g.b = b; g.D = D; g.n_ent = c->cfg.num_entities; g.n_rel = c->cfg.num_relations;
-    g.Hs = c->Hs; g.Rs = c->Rs; g.Ts = c->Ts;
-    g.staged = c->staged_now ? 1 : 0;
 
     GemmArgs q = g;
     q.A = c->S; q.B = c->O; q.C = c->Gent + (int64_t)2 * b * D;

@@ -47,17 +47,6 @@ struct GemmArgs {
     int ind_g;       // positives per chunk: item i uses chunk i / ind_g of the operand that is stored per chunk
     int64_t sA_item; // IND_CHUNK_SUM: floats from one positive's A block to the next one's
     int64_t b_off;   // offset of the matrix inside a relation row
-    // staged-rows path (kge_staged_path): the step's head / relation / tail rows as the tables held them, [b x D] each
-    const float* Hs;
-    const float* Rs;
-    const float* Ts;
-    int staged;          // chain-rule epilogues take their inputs from the staged rows instead of the tables
-    // forward with o formed on the way in: what its first column of tiles writes for the positives
-    float* O_out;        // [b x D] o_i
-    float* fpos_out;     // [b] f+_i
-    float* cpos_out;     // [b] dL/df+_i
-    float* inv_dpos_out; // [b] 1 / |o_i - c_i| (TransE-L2)
-    float* row_loss_out; // [b] softplus(-f+_i) / b
 };
 // how the operands of batch item i are found (IND of gemm_tile)
 enum { IND_NONE = 0,      // A + i sA, B + i sB

@@ -213,14 +213,14 @@ void kge_make_key_lists(kge_ctx* c, const StepIds& ids, KeyList* ent, KeyList* r
     const int b = ids.b, n_neg = ids.n_neg;
     e.src[0] = ids.h; e.src[1] = ids.t; e.src[2] = ids.neg;
     e.n_src[0] = b; e.n_src[1] = b; e.n_src[2] = n_neg;
-    e.blk = ids.blk; e.which = 0; e.ahead = 0; e.parity_halves = 0;
+    e.blk = ids.blk; e.which = 0;
     e.n = 2 * b + n_neg;
     e.passes = passes_for(c->cfg.num_entities);
     e.n_ids = c->cfg.num_entities;
     e.key[0] = c->ekey[0]; e.key[1] = c->ekey[1]; e.pos[0] = c->epos[0]; e.pos[1] = c->epos[1];
     rl.src[0] = ids.r; rl.src[1] = ids.r; rl.src[2] = ids.r;
     rl.n_src[0] = b; rl.n_src[1] = 0; rl.n_src[2] = 0;
-    rl.blk = ids.blk; rl.which = 1; rl.ahead = 0; rl.parity_halves = 0;
+    rl.blk = ids.blk; rl.which = 1;
     rl.n = b;
     rl.passes = passes_for(c->cfg.num_relations);
     rl.n_ids = c->cfg.num_relations;

@@ -50,12 +50,6 @@ int fail(kge_ctx* c, int code, const char* fmt, const char* detail = "") {
         if (e_ != hipSuccess) return fail((c), KGE_ERR_DEVICE, #call ": %s", hipGetErrorString(e_)); \
     } while (0)
 
-// KGE_STAGED_PATH=1 switches the staged-rows step on (under construction: off by default)
-const bool g_staged_enabled = []() {
-    const char* e = getenv("KGE_STAGED_PATH");
-    return e && e[0] == '1';
-}();
-
 bool is_gemm_model(int m) { return m == KGE_TRANSE_L2 || m == KGE_DISTMULT || m == KGE_COMPLEX || m == KGE_RESCAL; }
 
 __global__ void k_validate(StepIds ids, int64_t n_ent, int64_t n_rel, int* flag) {
@@ -175,46 +169,9 @@ int enqueue_transr_rest(kge_ctx* c, float* ent, float* ent_state, float* rel, fl
     return KGE_OK;
 }
 
-// The staged-rows step (see kge_staged_path): staging + key order, forward with o formed on the way in, backward with
-// staged chain-rule inputs, update.
-int enqueue_staged_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state, const StepIds& ids,
-                        int K, int G, float gamma, float lr, hipStream_t st) {
-    c->staged_now = true;
-    if (c->cfg.validate_indices) launch_validate(c, ids, st);
-    {
-        ProfScope p(c, KGE_PROF_GATHER);
-        kge_launch_stage(c, ent, rel, ids, st);
-    }
-    {
-        ProfScope p(c, KGE_PROF_SCORE);
-        kge_gemm_neg_score_staged(c, ids, K, G, gamma, st);
-    }
-    {
-        ProfScope p(c, KGE_PROF_BACKWARD);
-        kge_gemm_neg_backward(c, ent, rel, ids, K, G, gamma, st);
-    }
-    {
-        ProfScope p(c, KGE_PROF_UPDATE);
-        kge_launch_update(c, ent, ent_state, rel, rel_state, ids, lr, kge_gemm_loss_parts(c, ids.b, K, G), st);
-    }
-    c->staged_now = false;
-    KGE_HIP(c, hipGetLastError());
-    if (c->prof_on) {
-        KGE_HIP(c, hipStreamSynchronize(st));
-        for (int s : {KGE_PROF_GATHER, KGE_PROF_SCORE, KGE_PROF_BACKWARD, KGE_PROF_UPDATE}) {
-            float ms = 0.f;
-            if (hipEventElapsedTime(&ms, c->prof_ev[s][0], c->prof_ev[s][1]) == hipSuccess) c->prof_ms[s] += ms;
-        }
-        c->prof_steps += 1;
-    }
-    return KGE_OK;
-}
-
 int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* rel_state, const StepIds& ids, int K,
                  int G, float gamma, float lr, hipStream_t st) {
     const int B = ids.b;
-    if (kge_staged_path(c, 2 * B + ids.n_neg))
-        return enqueue_staged_step(c, ent, ent_state, rel, rel_state, ids, K, G, gamma, lr, st);
     // Ordering the key lists needs only the ids.  Short lists are ordered by extra blocks of the gather launch;
     // long ones by a radix sort on a second stream that joins before the update.
     const bool long_lists = 2 * B + ids.n_neg > KGE_RANK_MAX_KEYS;
@@ -344,11 +301,6 @@ int capture_steps(kge_ctx* c, float* ent, float* ent_state, float* rel, float* r
 
 }  // namespace
 
-bool kge_staged_path(const kge_ctx* c, int n_ent_keys) {
-    return g_staged_enabled && c->Hs != nullptr && c->cfg.adv_temperature == 0.f && c->cfg.loss == KGE_LOSS_LOGISTIC &&
-           n_ent_keys <= KGE_RANK_MAX_KEYS;
-}
-
 extern "C" {
 
 int kge_create(const kge_config* cfg, kge_ctx** out) {
@@ -415,8 +367,6 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t sort_slices = (EK + KGE_SORT_SLICE - 1) / KGE_SORT_SLICE + (B + KGE_SORT_SLICE - 1) / KGE_SORT_SLICE;
     const size_t o_sc = take(sort_slices * 17 * 256 * 4 + 2 * 256 * 4);  // digit counts per wave and per slice + the two lists' digit bases
     const bool pair_model = m == KGE_ROTATE || m == KGE_TRANSE_L1;
-    const bool stageable = (m == KGE_TRANSE_L2 || m == KGE_DISTMULT) && cfg->gemm_input == 0;
-    const size_t o_Hs = take(stageable ? B * D * 4 : 0), o_Rs = take(stageable ? B * D * 4 : 0), o_Ts = take(stageable ? B * D * 4 : 0);
     const size_t o_ppo = take(pair_model ? KGE_PAIR_MAX_PARTS * B * D * 4 : 0), o_ppn = take(pair_model ? KGE_PAIR_MAX_PARTS * NR * D * 4 : 0);
     c->ws_bytes = (int64_t)off;
 
@@ -442,9 +392,6 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     c->P3 = transr ? (float*)(base + o_P3) : nullptr;
     c->pair_part_o = pair_model ? (float*)(base + o_ppo) : nullptr;
     c->pair_part_n = pair_model ? (float*)(base + o_ppn) : nullptr;
-    c->Hs = stageable ? (float*)(base + o_Hs) : nullptr;
-    c->Rs = stageable ? (float*)(base + o_Rs) : nullptr;
-    c->Ts = stageable ? (float*)(base + o_Ts) : nullptr;
     c->sort_counts = (uint32_t*)(base + o_sc);
     c->flags = (int*)(base + o_flags);
     c->step_block = (StepBlock*)(base + o_step);

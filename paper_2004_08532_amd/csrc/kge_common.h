@@ -38,10 +38,6 @@ struct kge_ctx {
     int64_t ws_bytes;
 
     float* O;        // [max_batch x D]      o_i
-    float* Hs;       // staged-rows path (see kge_staged_path): [max_batch x D] head rows of the step's positives,
-    float* Rs;       //   [max_batch x D] their relation rows, [max_batch x D] their tail rows, as they are in the tables
-    float* Ts;       //   when the step starts (null where the path does not exist)
-    bool staged_now; //   the step that is being enqueued takes the staged-rows path
     float* Nst;      // [max_neg_rows x D]   gathered corrupting rows, chunk after chunk
     uint16_t* Obf;   // bf16 operands only: o_i and the corrupting rows rounded to bf16, row pitch ld_bf (the products
     uint16_t* Nbf;   // read these; Nst is then not written)
@@ -113,7 +109,6 @@ struct kge_ctx {
 // ---------------------------------------------------------------------------------------------------------
 struct StepBlock {
     int64_t step;
-    int64_t n_steps;         // steps of the running call (segment): step + 1 < n_steps says that a next step exists
     const int64_t* h;
     const int64_t* r;
     const int64_t* t;
@@ -139,9 +134,6 @@ struct KeyList {
     int n_src[3];
     const StepBlock* blk;    // replay mode: the arrays come from the block (which == 0: h | t | neg, 1: r)
     int which;
-    int parity_halves;       // see ahead
-    int ahead;               // replay mode: the list is that of step blk->step + ahead (0, or 1: the step after the
-                             // running one), and the ordered result goes to half (step + ahead) & 1 of key / pos
     int n;                   // total number of keys
     int passes;              // radix passes needed for ids < n_ids (8 bits each)
     int64_t n_ids;           // ids are clamped into [0, n_ids)
@@ -158,17 +150,6 @@ void kge_make_key_lists(kge_ctx* c, const StepIds& ids, KeyList* ent, KeyList* r
 // KGE_RANK_MAX_KEYS keys; longer lists go through kge_launch_sort)
 void kge_launch_gather(kge_ctx* c, const float* E, const float* R, const StepIds& ids, float gamma, float* pos_out,
                        bool with_keys, hipStream_t st);
-// Staged-rows path of the training step (TransE-L2 and DistMult, fp32 operands, logistic loss with uniform weights,
-// key lists short enough for the rank blocks).  The rows a step needs are copied as they are ("staged": head, relation,
-// tail and corrupting rows), the forward launch forms o_i from them on the way into its tiles and scores the
-// positives in its first column of tiles, the backward launch takes its chain-rule inputs from the staged rows.  The
-// point: staging needs no arithmetic, so in kge_train_steps the staging of step s + 1 rides in the update launch of
-// step s (rows that step s updates are pushed by the update itself, the others copied beside it), its key ordering
-// in the backward launch of step s, and a step is three dependent launches instead of four.
-bool kge_staged_path(const kge_ctx* c, int n_ent_keys);
-// rank blocks + staging of the running step's rows (the first step of a call; every step of kge_train_step)
-void kge_launch_stage(kge_ctx* c, const float* E, const float* R, const StepIds& ids, hipStream_t st);
-void kge_gemm_neg_score_staged(kge_ctx* c, const StepIds& ids, int k, int g, float gamma, hipStream_t st);
 constexpr int KGE_SIDES_CAP = 65536;  // steps whose sides fit the workspace: longer kge_train_steps calls run in segments
 constexpr int KGE_SORT_SLICE = 4096;  // keys per workgroup of the radix sort of long key lists
 constexpr int KGE_PAIR_MAX_PARTS = 8;  // partial rows per gradient row in the tiled backward of RotatE / TransE-L1
@@ -235,11 +216,11 @@ struct StepView {
     int side;
     int64_t step;
 };
-__device__ __forceinline__ StepView step_view(const StepIds& s, int ahead = 0) {
+__device__ __forceinline__ StepView step_view(const StepIds& s) {
     StepView v;
     if (s.blk) {
         const StepBlock* k = s.blk;  // uniform address: these are scalar loads of one cache line
-        v.step = k->step + ahead;
+        v.step = k->step;
         v.h = k->h + v.step * s.b;
         v.r = k->r + v.step * s.b;
         v.t = k->t + v.step * s.b;
@@ -259,7 +240,7 @@ __device__ __forceinline__ KeySources key_sources(const KeyList& l) {
     KeySources s;
     if (l.blk) {
         const StepBlock* k = l.blk;
-        const int64_t step = k->step + l.ahead;
+        const int64_t step = k->step;
         if (l.which == 0) {
             s.p[0] = k->h + step * l.n_src[0];
             s.p[1] = k->t + step * l.n_src[1];
@@ -279,11 +260,6 @@ __device__ __forceinline__ const int64_t* key_address(const KeyList& l, const Ke
     const int64_t* p1 = s.p[1] + (idx - a);
     const int64_t* p2 = s.p[2] + (idx - ab);
     return idx < a ? p0 : (idx < ab ? p1 : p2);
-}
-// Which half of key / pos receives the ordered list: half 0, or, for lists that are ordered a step ahead (the halves
-// then alternate between consecutive steps), the parity of the list's step.
-__device__ __forceinline__ int key_out_half(const KeyList& l) {
-    return (l.blk && l.parity_halves) ? (int)((l.blk->step + l.ahead) & 1) : 0;
 }
 __device__ __forceinline__ uint32_t clamp_key(const KeyList& l, int64_t id) {
     id = id < 0 ? 0 : (id >= l.n_ids ? l.n_ids - 1 : id);
