@@ -58,10 +58,15 @@ struct Stager {
                      // row (of 4 consecutive ones)
     int k;           // KC: first of its 4 K values; MC: first of its two K pairs (2 * kp; the second is 32 + 2 * kp)
     bool okr[4];
+    bool full;       // all 64 rows of the tile lie inside the matrix
     struct Reg { float4 v[4]; };
+    // A block that lies inside the matrix as a whole (the common case) is loaded and stored without the clamps and
+    // masks: they cost several times the instructions of the copy itself.
+    __device__ __forceinline__ bool inside(int kb) const { return full && kb * BK + BK <= K; }
     // KC: 16 consecutive lanes read 256 consecutive bytes of one row (whole cache lines per request)
     __device__ __forceinline__ void init(const float* base_, int ld_, int r0, int R_, int K_, int t) {
         base = base_; ld = ld_; K = K_; R = R_;
+        full = r0 + BT <= R_;
         if (KC) {
             r = t >> 4;
             k = 4 * (t & 15);
@@ -82,6 +87,19 @@ struct Stager {
     __device__ __forceinline__ void issue(int kb, Reg& rg) const {
         float4 (&reg)[4] = rg.v;
         const int k0 = kb * BK + k;
+        if (inside(kb)) {
+            if (KC) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) reg[q] = ld4(pr[q] + k0);
+            } else {
+                const float* b = p + (int64_t)k0 * ld;
+                reg[0] = ld4(b);
+                reg[1] = ld4(b + ld);
+                reg[2] = ld4(b + 32 * ld);
+                reg[3] = ld4(b + 33 * ld);
+            }
+            return;
+        }
         if (KC) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) reg[q] = ld4(pr[q] + (k0 < K ? k0 : 0));
@@ -96,6 +114,25 @@ struct Stager {
     __device__ __forceinline__ void store(int kb, const Reg& rg, __bf16* lds) const {
         const float4 (&reg)[4] = rg.v;
         const int k0 = kb * BK + k;
+        if (inside(kb)) {
+            uint32_t* l32 = reinterpret_cast<uint32_t*>(lds);
+            if (KC) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<uint2*>(l32 + lds_word(r + 16 * q, k >> 1)) =
+                        make_uint2(pack2(reg[q].x, reg[q].y), pack2(reg[q].z, reg[q].w));
+            } else {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const float4 lo = reg[2 * h], hi = reg[2 * h + 1];
+                    l32[lds_word(r + 0, (k >> 1) + 16 * h)] = pack2(lo.x, hi.x);
+                    l32[lds_word(r + 1, (k >> 1) + 16 * h)] = pack2(lo.y, hi.y);
+                    l32[lds_word(r + 2, (k >> 1) + 16 * h)] = pack2(lo.z, hi.z);
+                    l32[lds_word(r + 3, (k >> 1) + 16 * h)] = pack2(lo.w, hi.w);
+                }
+            }
+            return;
+        }
         if (KC) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -135,9 +172,12 @@ struct StagerBF {
     const uint16_t* pr[2];
     int ld, K, R, r, k;
     bool okr[4];
+    bool full;
     struct Reg { uint4 v[2]; };  // KC: two rows x 8 K values; MC: (v[0].xy, v[0].zw, v[1].xy, v[1].zw) = 4 K rows x 4 columns
+    __device__ __forceinline__ bool inside(int kb) const { return full && kb * BK + BK <= K; }
     __device__ __forceinline__ void init(const float* base_, int ld_, int r0, int R_, int K_, int t) {
         base = reinterpret_cast<const uint16_t*>(base_); ld = ld_; K = K_; R = R_;
+        full = r0 + BT <= R_;
         if (KC) {
             r = t >> 3;
             k = 8 * (t & 7);
@@ -157,6 +197,20 @@ struct StagerBF {
     }
     __device__ __forceinline__ void issue(int kb, Reg& rg) const {
         const int k0 = kb * BK + k;
+        if (inside(kb)) {
+            if (KC) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) rg.v[q] = *reinterpret_cast<const uint4*>(pr[q] + k0);
+            } else {
+                const uint16_t* b = p + (int64_t)k0 * ld;
+                const uint2 x0 = *reinterpret_cast<const uint2*>(b), x1 = *reinterpret_cast<const uint2*>(b + ld);
+                const uint2 x2 = *reinterpret_cast<const uint2*>(b + 32 * ld);
+                const uint2 x3 = *reinterpret_cast<const uint2*>(b + 33 * ld);
+                rg.v[0] = make_uint4(x0.x, x0.y, x1.x, x1.y);
+                rg.v[1] = make_uint4(x2.x, x2.y, x3.x, x3.y);
+            }
+            return;
+        }
         if (KC) {
 #pragma unroll
             for (int q = 0; q < 2; ++q) rg.v[q] = *reinterpret_cast<const uint4*>(pr[q] + (k0 < K ? k0 : 0));
@@ -173,6 +227,24 @@ struct StagerBF {
     }
     __device__ __forceinline__ void store(int kb, const Reg& rg, __bf16* lds) const {
         const int k0 = kb * BK + k;
+        if (inside(kb)) {
+            uint32_t* l32 = reinterpret_cast<uint32_t*>(lds);
+            if (KC) {
+#pragma unroll
+                for (int q = 0; q < 2; ++q) *reinterpret_cast<uint4*>(l32 + lds_word(r + 32 * q, k >> 1)) = rg.v[q];
+            } else {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    // lo: K row kk, hi: K row kk + 1; each holds columns (0, 1) in .x / .z and (2, 3) in .y / .w
+                    const uint32_t lo01 = rg.v[h].x, lo23 = rg.v[h].y, hi01 = rg.v[h].z, hi23 = rg.v[h].w;
+                    l32[lds_word(r + 0, (k >> 1) + 16 * h)] = (lo01 & 0xffffu) | (hi01 << 16);
+                    l32[lds_word(r + 1, (k >> 1) + 16 * h)] = (lo01 >> 16) | (hi01 & 0xffff0000u);
+                    l32[lds_word(r + 2, (k >> 1) + 16 * h)] = (lo23 & 0xffffu) | (hi23 << 16);
+                    l32[lds_word(r + 3, (k >> 1) + 16 * h)] = (lo23 >> 16) | (hi23 & 0xffff0000u);
+                }
+            }
+            return;
+        }
         if (KC) {
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
@@ -239,9 +311,10 @@ __device__ __forceinline__ void bf_tile(const GemmArgs& g, int tile, __bf16 (*ld
     const int nblk = (g.K + BK - 1) / BK, last = nblk - 1;
     // Two K blocks of loads are in flight: while block kb is multiplied, kb + 1 is on its way in one register set
     // and kb + 2 in the other.  Blocks past the end are clamped to the last one (loaded again, never stored) rather
-    // than branched around.  (Splitting the K range over two groups of waves that add their partial tiles at the end
-    // was measured and is slower: the launches are bound by what a CU can pull and convert per unit of time, not by
-    // the length of a tile's loop.)
+    // than branched around.  (Measured and slower: the K range split over two groups of waves that add their partial
+    // tiles at the end; four blocks of loads in flight; all eight operand reads of a block issued before its first
+    // matrix instruction.  The last two cost registers, and the launch loses more from fewer resident waves than it
+    // gains.)
     typename SA::Reg ra0, ra1;
     typename SB::Reg rb0, rb1;
     sa.issue(0, ra0);
@@ -257,7 +330,7 @@ __device__ __forceinline__ void bf_tile(const GemmArgs& g, int tile, __bf16 (*ld
         for (int s = 0; s < BK / 16; ++s) {
             const bf16x8 pa = *reinterpret_cast<const bf16x8*>(a32 + lds_word(ra, w0 + 8 * s));
             const bf16x8 pb = *reinterpret_cast<const bf16x8*>(b32 + lds_word(rb, w0 + 8 * s));
-            if (WANT_ASUM) {
+            if (WANT_ASUM && (w & 1) == 0) {  // the two waves of a row block hold the same A rows: one of them sums
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a_sum += (float)pa[e];
             }
@@ -282,11 +355,11 @@ __device__ __forceinline__ void bf_tile(const GemmArgs& g, int tile, __bf16 (*ld
 
     // ---- epilogue, straight from the accumulators: register v of lane l holds C[8 (v/4) + 4 (l/32) + v%4][l%32]
     // of the wave's quarter
-    float* rs_lds = reinterpret_cast<float*>(lds[0][0]) + 32 * w;  // row sums of A for the quarter's 32 rows
+    float* rs_lds = reinterpret_cast<float*>(lds[0][0]) + 32 * (w >> 1);  // row sums of A for the quarter's 32 rows
     if (WANT_ASUM) {
         a_sum += __shfl_xor(a_sum, 32, 64);
         lds_barrier();  // every wave is done reading the operand blocks
-        if (lane < 32) rs_lds[lane] = a_sum;
+        if (lane < 32 && (w & 1) == 0) rs_lds[lane] = a_sum;
         lds_barrier();
     }
     StepView sv;
@@ -298,51 +371,97 @@ __device__ __forceinline__ void bf_tile(const GemmArgs& g, int tile, __bf16 (*ld
     float* C = g.C + c * g.sC;
     float loss = 0.f;
     const int gn = n0 + wn + (lane & 31);
+    const int gnc = gn < g.N ? gn : g.N - 1;
+    // Everything the epilogue reads is fetched before its first store: a lane has 16 elements, and a load that follows
+    // a store which may alias it cannot be moved up by the compiler, so loads written next to their stores would be 16
+    // dependent round trips (table rows: to HBM) instead of one.  Addresses of elements outside the matrix are clamped.
+    auto row_of = [&](int v) { return m0 + wm + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); };
+    float in0[16], in1[16], in2[16], in3[16];
+    if (EPI == EPI_L2_FWD) {
+        const float cv = g.colv[c * g.s_colv + gnc];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int i = 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int gm = m0 + wm + i;
-        if (gm >= g.M || gn >= g.N) continue;
-        const float s = acc[v];
-        const float rs = WANT_ASUM ? rs_lds[i] : 0.f;
-        const int bi = c * g.M + gm;  // index of the positive in the mini-batch (chain epilogues)
-        if (EPI == EPI_PLAIN) {
-            C[(int64_t)gm * g.ldc + gn] = (IS_FWD && g.out_mode == OUT_W) ? w_and_loss<false>(s, g.wk, loss) : s;
-        } else if (EPI == EPI_L2_FWD) {
-            const float d2 = g.rowv[c * g.s_rowv + gm] + g.colv[c * g.s_colv + gn] - 2.f * s;
-            const float d = __builtin_amdgcn_sqrtf(fmaxf(d2, 0.f));  // 1 ulp
-            float out = g.out_mode == OUT_DIST ? d : g.gamma - d;
-            if (g.out_mode == OUT_W) {  // W = w sigmoid(f) / |o - n|, 0 where the distance is 0
-                const float coef = w_and_loss<false>(g.gamma - d, g.wk, loss);
-                out = d > 0.f ? coef * rcp_refined(d) : 0.f;
-            }
-            C[(int64_t)gm * g.ldc + gn] = out;
-        } else if (EPI == EPI_L2_DN) {
-            // the rows of the correction term are the bf16 rows that went into the products
-            const uint16_t xb = reinterpret_cast<const uint16_t*>(g.X)[c * g.sX + (int64_t)gm * g.ldx + gn];
-            C[(int64_t)gm * g.ldc + gn] = s - rs * __builtin_bit_cast(float, (uint32_t)xb << 16);
-        } else {
+        for (int v = 0; v < 16; ++v) {
+            const int gm = row_of(v) < g.M ? row_of(v) : g.M - 1;
+            in0[v] = g.rowv[c * g.s_rowv + gm] + cv;
+        }
+    } else if (EPI == EPI_L2_DN) {
+        // the rows of the correction term are the bf16 rows that went into the products
+        const uint16_t* xb = reinterpret_cast<const uint16_t*>(g.X) + c * g.sX + gnc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int gm = row_of(v) < g.M ? row_of(v) : g.M - 1;
+            in0[v] = __builtin_bit_cast(float, (uint32_t)xb[(int64_t)gm * g.ldx] << 16);
+        }
+    } else if (CHAIN) {
+        int64_t cid[16], aid[16], rid[16];  // the replaced entity; DistMult: also the kept entity and the relation
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int bi = c * g.M + (row_of(v) < g.M ? row_of(v) : g.M - 1);
             const int64_t hid = clamp_id(sv.h[bi], g.n_ent), tid = clamp_id(sv.t[bi], g.n_ent);
-            const int64_t aid = head ? tid : hid, cid = head ? hid : tid;
-            const float e_o = g.X[(int64_t)bi * g.ldx + gn];
-            const float e_c = g.E[cid * g.D + gn];
-            const float e_cp = g.cpos[bi];
+            cid[v] = head ? hid : tid;
+            aid[v] = head ? tid : hid;
+            rid[v] = EPI == EPI_CHAIN_DM ? clamp_id(sv.r[bi], g.n_rel) : 0;
+        }
+        float in4[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int bi = c * g.M + (row_of(v) < g.M ? row_of(v) : g.M - 1);
+            in0[v] = g.X[(int64_t)bi * g.ldx + gnc];   // o
+            in1[v] = g.E[cid[v] * g.D + gnc];           // the replaced entity's row
+            in2[v] = g.cpos[bi];                        // dL/df+
+            if (EPI == EPI_CHAIN_L2) {
+                in3[v] = g.inv_dpos[bi];
+            } else {
+                in3[v] = g.E[aid[v] * g.D + gnc];       // the kept entity's row
+                in4[v] = g.R[rid[v] * g.D + gnc];       // the relation's row
+            }
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int gm = row_of(v);
+            if (gm >= g.M || gn >= g.N) continue;
+            const float s = acc[v];
+            const float rs = WANT_ASUM ? rs_lds[8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] : 0.f;
+            const int bi = c * g.M + gm;  // index of the positive in the mini-batch
+            const float e_o = in0[v], e_c = in1[v], e_cp = in2[v];
             float* ga = g.Gent + (int64_t)(head ? g.b + bi : bi) * g.D + gn;
             float* gc = g.Gent + (int64_t)(head ? bi : g.b + bi) * g.D + gn;
             float* gr = g.Grel + (int64_t)bi * g.D + gn;
             if (EPI == EPI_CHAIN_L2) {
                 // dL/do = W n - rowsum(W) o  +  dL/df+ * d(gamma - |o - c|)/do
-                const float dir = (e_o - e_c) * g.inv_dpos[bi];
+                const float dir = (e_o - e_c) * in3[v];
                 const float go = s - rs * round_bf16(e_o) - e_cp * dir;
                 *ga = go;
                 *gc = e_cp * dir;
                 *gr = head ? -go : go;
             } else {  // EPI_CHAIN_DM: o = a * r, psi = o . x
-                const int64_t rid = clamp_id(sv.r[bi], g.n_rel);
                 const float go = s + e_cp * e_c;
-                *ga = go * g.R[rid * g.D + gn];
+                *ga = go * in4[v];
                 *gc = e_cp * e_o;
-                *gr = go * g.E[aid * g.D + gn];
+                *gr = go * in3[v];
+            }
+        }
+    }
+    if (!CHAIN) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int gm = row_of(v);
+            if (gm >= g.M || gn >= g.N) continue;
+            const float s = acc[v];
+            const float rs = WANT_ASUM ? rs_lds[8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)] : 0.f;
+            if (EPI == EPI_PLAIN) {
+                C[(int64_t)gm * g.ldc + gn] = (IS_FWD && g.out_mode == OUT_W) ? w_and_loss<false>(s, g.wk, loss) : s;
+            } else if (EPI == EPI_L2_FWD) {
+                const float d2 = in0[v] - 2.f * s;
+                const float d = __builtin_amdgcn_sqrtf(fmaxf(d2, 0.f));  // 1 ulp
+                float out = g.out_mode == OUT_DIST ? d : g.gamma - d;
+                if (g.out_mode == OUT_W) {  // W = w sigmoid(f) / |o - n|, 0 where the distance is 0
+                    const float coef = w_and_loss<false>(g.gamma - d, g.wk, loss);
+                    out = d > 0.f ? coef * rcp_refined(d) : 0.f;
+                }
+                C[(int64_t)gm * g.ldc + gn] = out;
+            } else {  // EPI_L2_DN
+                C[(int64_t)gm * g.ldc + gn] = s - rs * in0[v];
             }
         }
     }
