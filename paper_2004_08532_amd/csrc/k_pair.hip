@@ -55,7 +55,9 @@ __global__ __launch_bounds__(512) void k_pair_fwd(PairArgs a) {
     __shared__ __attribute__((aligned(16))) float Ns[CPLX ? 2 : 1][PT][PPITCH];
     __shared__ float halves[256][4];
     const int half = threadIdx.x >> 8, tid = threadIdx.x & 255;
-    const int tj = tid & 15, ti = tid >> 4;  // pairs (2 ti + {0,1}, 2 tj + {0,1}) of the tile
+    // pairs (ti + {0,16}, tj + {0,16}) of the tile: the 16 lanes with consecutive tj read consecutive staged rows,
+    // which the row pitch spreads over all banks (rows 2 tj + {0,1} would fall on half of them)
+    const int tj = tid & 15, ti = tid >> 4;
     const int j0 = blockIdx.x * PT, i0 = blockIdx.y * PT, c = blockIdx.z;
     const int NC = CPLX ? a.D / 2 : a.D;  // coordinates
     const float* Oc = a.O + (int64_t)c * a.g * a.D;
@@ -93,11 +95,11 @@ __global__ __launch_bounds__(512) void k_pair_fwd(PairArgs a) {
             float o_re[2][4], o_im[2][4], n_re[2][4], n_im[2][4];
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const float4 vo = ld4(&Os[0][2 * ti + u][cc]), vn = ld4(&Ns[0][2 * tj + u][cc]);
+                const float4 vo = ld4(&Os[0][ti + 16 * u][cc]), vn = ld4(&Ns[0][tj + 16 * u][cc]);
                 o_re[u][0] = vo.x; o_re[u][1] = vo.y; o_re[u][2] = vo.z; o_re[u][3] = vo.w;
                 n_re[u][0] = vn.x; n_re[u][1] = vn.y; n_re[u][2] = vn.z; n_re[u][3] = vn.w;
                 if (CPLX) {
-                    const float4 wo = ld4(&Os[CPLX ? 1 : 0][2 * ti + u][cc]), wn = ld4(&Ns[CPLX ? 1 : 0][2 * tj + u][cc]);
+                    const float4 wo = ld4(&Os[CPLX ? 1 : 0][ti + 16 * u][cc]), wn = ld4(&Ns[CPLX ? 1 : 0][tj + 16 * u][cc]);
                     o_im[u][0] = wo.x; o_im[u][1] = wo.y; o_im[u][2] = wo.z; o_im[u][3] = wo.w;
                     n_im[u][0] = wn.x; n_im[u][1] = wn.y; n_im[u][2] = wn.z; n_im[u][3] = wn.w;
                 } else {
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(512) void k_pair_fwd(PairArgs a) {
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-            const int i = i0 + 2 * ti + u, j = j0 + 2 * tj + q;
+            const int i = i0 + ti + 16 * u, j = j0 + tj + 16 * q;
             if (i < a.g && j < a.k) a.S[((int64_t)c * a.g + i) * a.ld_s + j] = a.gamma - acc[u][q];
         }
     }
