@@ -358,7 +358,7 @@ int kge_create(const kge_config* cfg, kge_ctx** out) {
     const size_t o_ek0 = take(EK * 4), o_ek1 = take(EK * 4), o_ep0 = take(EK * 4), o_ep1 = take(EK * 4);
     const size_t o_rk0 = take(B * 4), o_rk1 = take(B * 4), o_rp0 = take(B * 4), o_rp1 = take(B * 4);
     const size_t o_flags = take(256), o_step = take(256), o_sides = take(sizeof(int32_t) * KGE_SIDES_CAP);
-    c->ld_bf = (cfg->ent_dim + 7) / 8 * 8;
+    c->ld_bf = (cfg->ent_dim + 63) / 64 * 64;  // rows start on 128-byte lines: a K block of a row is one line, not two
     const bool bf = cfg->gemm_input == 1;
     const size_t o_Obf = take(bf ? B * c->ld_bf * 2 + 64 : 0), o_Nbf = take(bf ? NR * c->ld_bf * 2 + 64 : 0);
     const bool transr = m == KGE_TRANSR;

@@ -41,7 +41,7 @@ struct kge_ctx {
     float* Nst;      // [max_neg_rows x D]   gathered corrupting rows, chunk after chunk
     uint16_t* Obf;   // bf16 operands only: o_i and the corrupting rows rounded to bf16, row pitch ld_bf (the products
     uint16_t* Nbf;   // read these; Nst is then not written)
-    int ld_bf;       // D rounded up to 8
+    int ld_bf;       // D rounded up to 64 (rows of whole 128-byte lines)
     float* S;        // [max_batch x ld_s]   negative scores, then backward coefficients W
     float* PP;       // TransR: [max_batch x D] p_i = M_i c_i
     float* P3;       // TransR: [max_batch x max_neg_per_chunk x D] projections of the corrupting rows, then dL/dP
