@@ -765,8 +765,8 @@ def test_train_steps_graph_replay_equals_step_by_step(kge, variant):
             stream.synchronize()
     ctx.close()
 
-    # replayed.  Round 0 captures the graphs; round 1 refills the same device buffers; round 2 passes id, side-less
-    # ... and loss arrays that live elsewhere: the graphs find them through the step block, so nothing is captured again
+    # replayed.  The first call captures the graphs; the second refills the same device buffers; the third passes id
+    # and loss arrays that live elsewhere: the graphs find them through the step block, so nothing is captured again
     ctx = make_ctx()
     bE, bSE, bR, bSR = fresh()
     loss_b = torch.zeros(n_per_call, device="cuda")
