@@ -2,9 +2,9 @@
 // accumulation: S_c = O_c N_c^T, dO_c = W_c N_c, dN_c = W_c^T O_c with the same epilogues as the fp32 path.
 //
 // Shapes here are the large ones (thousands of positives and corrupting rows per step), where a 32x32 tile per
-// workgroup pulls every operand row from L2 into a CU once per 32 columns of output, and that path is the limit.  A
-// workgroup therefore owns a 64x64 output tile over the whole K range (no split over K, no cross-wave sum); its four
-// waves hold one 32x32 quarter each.  Per K block of 64 the 256 threads load the two 64x64 operand blocks (whole
+// workgroup pulls every operand row from L2 into a CU once per 32 columns of output and spends as long on the
+// cross-wave sum of its K split as on the product.  A workgroup therefore owns a 64x64 output tile over the whole K
+// range (no split over K, no cross-wave sum, half the pulls per output); its four waves hold one 32x32 quarter each.  Per K block of 64 the 256 threads load the two 64x64 operand blocks (whole
 // cache lines per request, the next two blocks in flight while this one is multiplied) and lay them out in LDS as
 // bf16, K-contiguous whatever their
 // orientation in memory, so that every v_mfma_f32_32x32x16_bf16 operand is one 16-byte LDS read.  The o rows and the

@@ -418,11 +418,12 @@ def test_long_key_lists_take_the_radix_sort_path(kge):
         p.close()
 
 
-@pytest.mark.parametrize("n_entities", [401, 200_003])
+@pytest.mark.parametrize("n_entities", [53, 401, 200_003])
 def test_key_lists_of_medium_length_take_the_bucketed_ranking(kge, n_entities):
     """Between 6,144 and 14,336 entity keys the gather launch ranks them bucket by bucket.  With 401 entities every id
-    occurs about 20 times (ties are broken by position, buckets hold one id each and some are empty); with 200,003
-    most ids are distinct and a bucket holds a few hundred different ids."""
+    occurs about 20 times (ties are broken by position, buckets hold one id each and some are empty); with 53 every
+    bucket that is not empty holds 150 copies of one id or more, the length that a wave scans together instead of
+    lane by lane; with 200,003 most ids are distinct and a bucket holds ids from a range of 390."""
     # (one of the two with self-adversarial weights: rows of 550 scores, 9 per lane of the loss kernel)
     w = ragged("distmult", n_entities=n_entities, ent_dim=16, rel_dim=16, batch=768, chunk=64, neg_per_chunk=550,
                steps=2, adv_temperature=1.0 if n_entities == 401 else 0.0)
