@@ -435,6 +435,43 @@ def test_key_lists_of_medium_length_take_the_bucketed_ranking(kge, n_entities):
         p.close()
 
 
+def test_train_steps_call_longer_than_the_sides_buffer(kge):
+    """kge_train_steps keeps the per-step sides in a fixed buffer of 65,536 entries and runs a longer call in segments
+    of that many steps.  One call of 65,536 + 57 steps with a side pattern of period three (so that the second segment
+    does not start where the pattern does) must leave the bits of the same steps run as two calls cut elsewhere, and
+    the same losses.  Ids are uniform random numbers: this is a property of the call's bookkeeping, not of the data."""
+    n_steps, b, chunk, k = 65_536 + 57, 32, 16, 8
+    w = configs.TINY.scaled(name="tiny-long", batch=b, chunk=chunk, neg_per_chunk=k, lr=0.01)
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    ids = lambda hi, n: torch.randint(0, hi, (n_steps, n), dtype=torch.int64, device="cuda", generator=gen)
+    H, Rr, T, N = ids(w.n_entities, b), ids(w.n_relations, b), ids(w.n_entities, b), ids(w.n_entities, (b // chunk) * k)
+    sides = [(s % 3 == 1) * 1 for s in range(n_steps)]
+    E0, R0 = configs.init_tables(w)
+    stream = torch.cuda.Stream()
+
+    def run(cuts):
+        ctx = kge.KgeContext(w.model, w.n_entities, w.n_relations, w.ent_dim, w.rel_dim, max_batch=b,
+                             max_neg_per_chunk=k, max_chunks=b // chunk)
+        E, R = dev(E0), dev(R0)
+        SE, SR = torch.zeros_like(E), torch.zeros_like(R)
+        loss = torch.zeros(n_steps, device="cuda")
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            for lo, hi in zip(cuts[:-1], cuts[1:]):
+                ctx.train_steps(E, SE, R, SR, H[lo:hi], Rr[lo:hi], T[lo:hi], N[lo:hi], k, chunk, sides[lo:hi], w.gamma,
+                                w.lr, loss_out=loss[lo:hi])
+        stream.synchronize()
+        assert ctx.graph_captures() == 1
+        ctx.close()
+        return E, SE, R, SR, loss
+
+    one = run([0, n_steps])
+    two = run([0, 30_001, n_steps])
+    for a, b_ in zip(one, two):
+        assert torch.isfinite(a).all() and torch.equal(a, b_)
+    assert float(one[4][-1]) != 0.0 and float(one[4][65_536]) != 0.0  # the second segment wrote its losses
+
+
 def check_ranks(p: Pair, h, r, t, neg, side, got):
     """A rank is an integer decided by comparing fp32 scores, so both sides take that decision in the kernels'
     precision: (1) the library's fp32 scores of the same call agree with the oracle's to the score tolerance, (2) the
