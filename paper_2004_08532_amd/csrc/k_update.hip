@@ -3,7 +3,7 @@
 //     S += g^2 ;  theta -= lr * g / (sqrt(S) + eps)
 // Table rows that are not in the batch are never touched.
 //
-// Work is cut by POSITION in the sorted key list, not by row id: every workgroup gets a tile of 8 consecutive
+// Work is cut by POSITION in the sorted key list, not by row id: every workgroup gets a tile of 4 consecutive
 // sorted positions, and a run of equal keys (one distinct row) belongs to the tile in which it ENDS.  One row
 // group of the workgroup (one thread per 16 bytes of a row: the "walkers") asks for the table / state rows of the
 // runs that end in the tile and for the tile's gradient rows, then walks the tile in sorted order.  If the tile's
@@ -18,7 +18,7 @@
 
 namespace {
 
-constexpr int TILE_R = 8;
+constexpr int TILE_R = 4;   // sorted positions per workgroup (measured: 2, 3, 6, 8 and 16 are slower on every configuration)
 constexpr int UPD_THREADS = 512;
 constexpr int LOOKBACK_U = 16;  // gradient rows in flight per thread while summing the earlier part of a run
 
