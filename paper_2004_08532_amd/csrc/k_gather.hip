@@ -202,8 +202,16 @@ __device__ __forceinline__ void rank_block_bucketed(const KeyList& l, int blk, u
     if (mine >= n) return;
     const int lo = off[mine_bucket], hi = lo + cnt[mine_bucket];
     int before = lo;
+    // a bucket holds 24 words on average, the bucket of a hub entity hundreds, and the wave waits for its longest
+    // scan: four words per LDS read once the position is a multiple of four
+    int j = lo;
+    for (; j < hi && (j & 3) != 0; ++j) before += word[j] < mine_word ? 1 : 0;
 #pragma unroll 4
-    for (int j = lo; j < hi; ++j) before += word[j] < mine_word ? 1 : 0;
+    for (; j + 3 < hi; j += 4) {
+        const uint4 w4 = *reinterpret_cast<const uint4*>(word + j);
+        before += (w4.x < mine_word) + (w4.y < mine_word) + (w4.z < mine_word) + (w4.w < mine_word);
+    }
+    for (; j < hi; ++j) before += word[j] < mine_word ? 1 : 0;
     l.key[0][before] = (mine_word >> RANK_POS_BITS) + first[mine_bucket];
     l.pos[0][before] = (uint32_t)mine;
 }
@@ -222,7 +230,7 @@ __device__ __forceinline__ void st4_bf16(uint16_t* p, float x0, float x1, float 
 template <int MODEL, int NV, int THREADS>
 __global__ __launch_bounds__(THREADS) void k_gather(GatherArgs a) {
     constexpr int ROWS_PER_BLOCK = THREADS / 64;
-    extern __shared__ uint32_t rank_keys[];
+    extern __shared__ __attribute__((aligned(16))) uint32_t rank_keys[];  // (read 16 bytes at a time)
     // the rank blocks come first: they run longest and need nothing but the ids
     if ((int)blockIdx.x < a.rank_blocks) {
         const int rb = blockIdx.x;
