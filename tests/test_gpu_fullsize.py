@@ -9,8 +9,8 @@ renumbered by their rank among the distinct ids (which keeps their order, so the
 runs), and the oracle performs the step on the compact table.  Every element of every touched row is then compared
 as in the small-size tests.  The rest of the table is covered by a property: rows outside the batch keep their bits.
 
-Launch configuration: bench.py drives kge_train_steps on a side stream, which replays HIP graphs of 1, 2, 4 and 8
-steps.  The
+Launch configuration: bench.py drives kge_train_steps on a side stream, which replays HIP graphs of 1, 2, 4, 8,
+16 and 32 steps.  The
 same steps are therefore run a second time through kge_train_steps from the same rows, and must reproduce the
 step-by-step result bit for bit.
 """
@@ -25,7 +25,7 @@ from parity_util import ALLOWANCE_SHARE, EMB_TOL, SCORE_TOL, rounding_allowance
 pytestmark = pytest.mark.gpu
 
 N_CHECKED = 3   # steps checked one by one against the oracle
-N_REPLAY = 27   # steps run again through kge_train_steps (replayed graphs of 1, 2, 4, 8, 8, 4 steps)
+N_REPLAY = 91   # steps run again through kge_train_steps (replayed graphs of 1, 2, 4, 8, 16, 32, 16, 8, 4 steps)
 
 
 def _compact(ids_list):
