@@ -251,11 +251,28 @@ int enqueue_step(kge_ctx* c, float* ent, float* ent_state, float* rel, float* re
 // ---- replay: kge_train_steps captures 1, 2, 4, ... 32 consecutive steps into HIP graphs whose kernels take the step
 // number and the id arrays from device memory (the step block), so the same graphs serve every step of every call
 // of the same shape.  Launching a graph costs the host about 2 us per kernel in it plus a fixed part, and the
-// device starts on a graph only once the whole of it is enqueued: a call therefore starts with the short graphs
-// (1, 2, 4 steps: the device is busy after one step's worth of enqueueing and the host stays ahead of it from
-// there), goes on with graphs of 8 and ends with the remainder.
+// device starts on a graph only once the whole of it is enqueued, and every graph start costs the device about 8 us
+// of idling: a call therefore starts with a graph of one step (the device is busy after one step's worth of
+// enqueueing), lets the graphs grow as fast as the host can stay ahead, and otherwise uses as few graphs as the step
+// count allows (20 steps: 1, 1, 2, 16).
 constexpr int REPLAY_SIZES = 6;  // graphs of 1 << i steps, i < REPLAY_SIZES (measured per Freebase-scale step in a
                                  // 10,000-step call: longest graph 8 steps 38.2 us, 16: 37.9, 32: 37.8, 64: 38.4)
+
+// Launches exec[i] (1 << i steps), or, if that graph is too long for its place in the call, its two halves.  Too long:
+// more than RAMP times the steps already enqueued by this call (the first graph of a call is one step).  Enqueueing
+// costs the host about 8 us per step, a step takes the device four times that or more, so the host stays ahead.
+constexpr int64_t RAMP = 4;
+void launch_graphs(hipGraphExec_t* exec, int i, int64_t* done, hipStream_t st, hipError_t* err) {
+    const int64_t len = (int64_t)1 << i, cap = *done > 0 ? RAMP * *done : 1;
+    if (i > 0 && len > cap) {
+        launch_graphs(exec, i - 1, done, st, err);
+        launch_graphs(exec, i - 1, done, st, err);
+        return;
+    }
+    const hipError_t e = hipGraphLaunch(exec[i], st);
+    if (*err == hipSuccess) *err = e;
+    *done += len;
+}
 
 // What a captured graph depends on.  The id arrays, the per-step sides and the loss array are not part of it: the
 // kernels find them through the step block.
@@ -517,13 +534,15 @@ int kge_train_steps(kge_ctx* c, float* ent, float* ent_state, float* rel, float*
         blk.sides = neg_sides ? c->sides_dev : nullptr;
         blk.loss_out = loss_out ? loss_out + first : nullptr;
         hipLaunchKernelGGL(k_set_step_block, dim3(1), dim3(1), 0, st, c->step_block, blk);
-        int64_t left = n;
-        for (int i = 0; i + 1 < REPLAY_SIZES && left >= ((int64_t)1 << i); ++i) {  // the ramp
-            KGE_HIP(c, hipGraphLaunch(cache->exec[i], st));
-            left -= (int64_t)1 << i;
-        }
-        for (int i = REPLAY_SIZES - 1; i >= 0; --i)  // the long graphs, then the remainder
-            for (; left >= ((int64_t)1 << i); left -= (int64_t)1 << i) KGE_HIP(c, hipGraphLaunch(cache->exec[i], st));
+        // As few graphs as possible: the binary digits of n below the longest graph, smallest first, then the
+        // longest graph for the rest.  A graph that is too long for its place in the call (see launch_graphs) is cut
+        // into halves.
+        int64_t done = 0;
+        hipError_t herr = hipSuccess;
+        for (int i = 0; i + 1 < REPLAY_SIZES; ++i)
+            if (n & ((int64_t)1 << i)) launch_graphs(cache->exec, i, &done, st, &herr);
+        for (int64_t q = n >> (REPLAY_SIZES - 1); q > 0; --q) launch_graphs(cache->exec, REPLAY_SIZES - 1, &done, st, &herr);
+        KGE_HIP(c, herr);
     }
     KGE_HIP(c, hipGetLastError());
     return KGE_OK;
